@@ -1,0 +1,192 @@
+/*
+ * tmac.h -- C ABI of the MI355X (gfx950) LUT-based mixed-precision GEMV/GEMM library.
+ *
+ * The library computes R[N,M] = A[N,K] x W[M,K]^T for b-bit (b = 1..4) group-quantised
+ * weights W without ever de-quantising them, by the table-lookup method of T-MAC
+ * (arxiv 2407.00088): weights are split into b one-bit planes (Eq. 1), every g = 4
+ * consecutive bits of a plane along K form a 4-bit index (Algorithm 1,
+ * PreprocessWeights), every group of g activations is expanded into a table of 2^g
+ * signed partial sums (Algorithm 1, Precompute; Section 3.1), and the product is the
+ * sum of looked-up table entries, shifted by the plane's weight 2^i, plus a bias term
+ * (Algorithm 1, main loop; Section 4 "Bit-serial linear transformation" with
+ * s0 = -1, s1 = +1, i.e. alpha_i = beta_i = 1/2).
+ *
+ * De-quantisation convention (the paper only speaks of "quantization scales"; the
+ * zero point is this library's reading): w[m,k] = s[m,k/G] * (q[m,k] - z[m,k/G]),
+ * q an unsigned b-bit code, s and z fp16, z real-valued in code units.
+ *
+ * Result:  R[n,m] = sum_G s[m,G] * ( 1/2 * sum_i 2^i L_i[n,m,G] + ((2^b-1)/2 - z[m,G]) * S[n,G] )
+ *   L_i[n,m,G] = sum over the LUT groups kg of quantisation group G of T[n,kg,idx_i[m,kg]]
+ *   S[n,G]     = sum of the activations of quantisation group G.
+ *
+ * General rules
+ *   - The library allocates no memory and keeps no mutable global state; the caller owns
+ *     every buffer.  Pointers named *_host are host memory, *_dev are device memory of the
+ *     current HIP device.  Device pointers must be 16-byte aligned (256 recommended).
+ *   - Device entry points only enqueue work on `stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and never synchronise.
+ *   - Every failure is reported through the returned tmac_status; arguments are checked on
+ *     the host before anything is launched, and nothing is launched when a check fails.
+ *   - Only gfx950 code objects are built into the library.
+ */
+#ifndef TMAC_H_
+#define TMAC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TMAC_OK = 0,
+  TMAC_EINVAL = 1,        /* null/misaligned pointer, bad enum, shape constraint violated   */
+  TMAC_EUNSUPPORTED = 2,  /* valid request that this build has no kernel for                 */
+  TMAC_ESIZE = 3,         /* a caller-provided buffer is too small                           */
+  TMAC_EHIP = 4           /* the HIP runtime reported an error while enqueuing               */
+} tmac_status;
+
+typedef enum { TMAC_ACT_F16 = 0, TMAC_ACT_I8 = 1 } tmac_act_t;
+
+/* Table entry type.
+ *   TMAC_LUT_F16: entries are the fp32 signed sums of fp16 activations rounded once to fp16
+ *                 (results within 2e-3 relative Frobenius error of the fp64 product).
+ *   TMAC_LUT_I16: entries are exact int16 sums of int8 activations (|T| <= 4*127); all
+ *                 aggregation is int32 and the result is bit-exact. */
+typedef enum { TMAC_LUT_F16 = 0, TMAC_LUT_I16 = 1 } tmac_lut_t;
+
+/* TMAC_OUT_I32 (raw integer dot products) is available with TMAC_LUT_I16 and a
+ * per-tensor scale (group == 0) with an integer zero point only. */
+typedef enum { TMAC_OUT_F32 = 0, TMAC_OUT_F16 = 1, TMAC_OUT_I32 = 2 } tmac_out_t;
+
+/* Weight matrix description (Algorithm 1: W has shape [M, K]).
+ *   bits   1..4, weight bit-width b
+ *   g      LUT group size; must be 4 (one 16-entry table per 4 activations)
+ *   group  quantisation group G along K: a multiple of 128, or 32, or 64, or == K
+ *          (one scale per row); 0 = one scale and zero for the whole tensor
+ *   layout TMAC_LAYOUT_*
+ *   zero_point  per-tensor zero in code units (group == 0 only), e.g. 1 for ternary
+ *          weights stored as q = t+1 (Section 5.1: ternary weights run as 2-bit) */
+typedef struct {
+  int32_t M, K, bits, g, group, layout;
+  float   zero_point;   /* zero point of the whole tensor, used when group == 0 */
+  int32_t reserved;     /* must be 0 */
+} tmac_wdesc;
+
+/* Packed layout 1 ("tile 16 rows x 128 k"; Section 3.2 weight permutation + interleaving):
+ *
+ *   header   256 bytes (struct tmac_blob_header below)
+ *   indices  u32 idx[n_tiles][n_chunks][64][bits]
+ *            tile t = rows 16t..16t+15, chunk c = k in [128c, 128c+128), lane = 16*phi + r
+ *            (r = row in tile, phi = 0..3).  The dword [t][c][16*phi+r][i] holds the eight
+ *            4-bit indices of bit plane i of row 16t+r for LUT groups kg = 32c + 4j + phi,
+ *            j = 0..7; index j sits in nibble position 2j (j < 4) or 2(j-4)+1 (j >= 4), so
+ *            that (x<<1)&0x1E1E1E1E and (x>>3)&0x1E1E1E1E yield byte-aligned table offsets
+ *            in order.  Bit (k % 4) of an index belongs to element k (lowest k = LSB).
+ *            Rows >= M and k >= K are padded with index 0.
+ *   scales   u16 sz[n_tiles][n_qgroups][16][2]  = {fp16 scale, fp16 zero} per row and
+ *            quantisation group (n_qgroups = K/G, 1 when group == K, absent when group == 0)
+ *   One wavefront reads 64*4*bits contiguous bytes per (tile, chunk).
+ */
+enum { TMAC_LAYOUT_T16K128 = 1 };
+
+typedef struct {
+  uint32_t magic;        /* 0x43414D54 "TMAC" */
+  uint32_t layout;
+  int32_t  M, K, bits, g, group;
+  int32_t  Mp, Kp;       /* M rounded up to 16, K rounded up to 128 */
+  int32_t  n_tiles, n_chunks, n_qgroups;
+  float    zero_point;   /* per-tensor zero (group == 0) */
+  uint32_t reserved0;
+  uint64_t idx_off, idx_bytes, sz_off, sz_bytes, total_bytes;
+  uint8_t  pad[256 - 14 * 4 - 5 * 8];
+} tmac_blob_header;
+
+/* Size in bytes of the packed blob for `desc`, header included; 0 if `desc` is invalid. */
+size_t tmac_packed_bytes(const tmac_wdesc* desc);
+
+/* Offline weight preparation (Algorithm 1 PreprocessWeights; Section 3.2 permutation and
+ * interleaving).  Host to host; the caller uploads the blob to the device afterwards.
+ *   q_host       [M,K] row-major, one unsigned code per byte, each < 2^bits
+ *   scales_host  fp16 bits, [M, K/G] row-major (ignored when group == 0: the per-tensor
+ *                scale is given to tmac_mpgemm)
+ *   zeros_host   fp16 bits, [M, K/G] row-major; NULL means z = (2^b-1)/2 (symmetric
+ *                levels, the bias term vanishes); ignored when group == 0 (the zero of
+ *                the whole tensor is desc->zero_point)
+ *   packed_host  output, packed_bytes >= tmac_packed_bytes(desc)
+ * The blob cannot be checked against `desc` once it is in device memory: passing a blob
+ * packed for a different desc to tmac_mpgemm is undefined.
+ * Errors: TMAC_EINVAL (null pointer, bad desc, code out of range), TMAC_ESIZE. */
+tmac_status tmac_pack_weights(const tmac_wdesc* desc, const uint8_t* q_host,
+                              const uint16_t* scales_host, const uint16_t* zeros_host,
+                              void* packed_host, size_t packed_bytes);
+
+/* Bytes of the LUT buffer for N activation rows: tables [N][Kp/4][16] (2 bytes each, k
+ * padded to 128 with all-zero tables) followed by the group sums S[N][n_qgroups]
+ * (fp32 for TMAC_LUT_F16, int32 for TMAC_LUT_I16), 256-byte aligned.  0 on bad arguments. */
+size_t tmac_lut_bytes(int32_t N, int32_t K, int32_t g, int32_t group, tmac_lut_t lut);
+
+/* Online table precompute (Algorithm 1 Precompute; Section 3.1; mirror consolidation of
+ * Section 3.3 is used to compute half of the entries and negate them for the rest):
+ *   T[n,kg,p] = sum_{j<4} (bit j of p ? +a : -a)[n, 4kg+j],  S[n,G] = sum_{k in G} a[n,k].
+ *   A_dev  [N,K] row-major with leading dimension lda (elements): fp16 or int8
+ *   TMAC_ACT_F16 requires TMAC_LUT_F16, TMAC_ACT_I8 requires TMAC_LUT_I16.
+ * Errors: TMAC_EINVAL, TMAC_ESIZE, TMAC_EHIP. */
+tmac_status tmac_precompute_lut(const void* A_dev, tmac_act_t act, int32_t N, int32_t K,
+                                int64_t lda, int32_t g, int32_t group, tmac_lut_t lut,
+                                void* lut_dev, size_t lut_bytes, void* stream);
+
+/* Bytes of workspace tmac_mpgemm needs (split-K partial sums and arrival counters).
+ * The workspace must be zero-filled once before its first use; every call leaves the
+ * counters at zero again.  Calls that share a workspace must not overlap in time. */
+size_t tmac_workspace_bytes(const tmac_wdesc* desc, int32_t N);
+
+/* Look-up, bit-plane shift-accumulate, scale/zero, reduce (Algorithm 1 main loop, Eq. 1,
+ * Section 4 bit-serial linear transformation).
+ *   packed_dev     blob written by tmac_pack_weights, uploaded unchanged
+ *   lut_dev        buffer filled by tmac_precompute_lut with the same N, K, group, lut
+ *   act_scale_dev  fp32 [N] per-row activation scale, multiplied into the result
+ *                  (TMAC_LUT_I16 path); NULL = 1
+ *   weight_scale   per-tensor weight scale, used when desc->group == 0
+ *   out_dev        R[N,M] row-major with leading dimension ldo (elements)
+ * Integer path result (group == 0, integer zero): R_int = sum_k a_q[n,k]*(q[m,k]-z) exactly;
+ * TMAC_OUT_I32 stores R_int, TMAC_OUT_F32 stores fl(fl(float(R_int)*act_scale[n])*weight_scale).
+ * The fp reduction order is fixed, so results are reproducible run to run.
+ * Errors: TMAC_EINVAL, TMAC_EUNSUPPORTED, TMAC_ESIZE, TMAC_EHIP. */
+tmac_status tmac_mpgemm(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev,
+                        tmac_lut_t lut, int32_t N, const float* act_scale_dev,
+                        float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
+                        void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/* Launch-shape knobs for benchmarking sweeps; 0 = library default.
+ *   kernel           1 = K-sliced kernel (tables of a K-slice in LDS, split-K reduction through
+ *                    the workspace), 2 = full-K decode kernel (all tables of one activation row
+ *                    in LDS, one 16-row tile per workgroup; needs K <= 20416 and a group size
+ *                    that is 0, K or a multiple of 128; TMAC_EUNSUPPORTED otherwise)
+ *   chunks_per_wave  K-sliced kernel: 128-k chunks one wavefront covers: 2, 4 or 8
+ *   n_tile           K-sliced kernel: activation rows handled per workgroup pass: 1 or 4 */
+typedef struct {
+  int32_t chunks_per_wave, n_tile, kernel, reserved[5];
+} tmac_tuning;
+
+/* Same as tmac_mpgemm with explicit launch-shape knobs (NULL = defaults). */
+tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev,
+                           tmac_lut_t lut, int32_t N, const float* act_scale_dev,
+                           float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
+                           void* workspace_dev, size_t workspace_bytes, void* stream,
+                           const tmac_tuning* tuning);
+
+const char* tmac_status_str(tmac_status s);
+
+/* Text of the last HIP error this thread met inside the library ("" if none); diagnostics
+ * for a TMAC_EHIP return. */
+const char* tmac_last_error_detail(void);
+
+/* Library version: 1000*major + minor. */
+int32_t tmac_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TMAC_H_ */

@@ -1,0 +1,192 @@
+"""Thin ctypes binding of libtmac_hip.so: argument marshalling only.
+
+Every step of the path (table precompute, lookup, accumulate, scale, reduce) runs in
+the library's HIP kernels; the offline packer runs in the library's host code.  torch
+is used for device memory and streams only.  There is no fallback: if the shared
+library is missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libtmac_hip.so")
+
+TMAC_OK, TMAC_EINVAL, TMAC_EUNSUPPORTED, TMAC_ESIZE, TMAC_EHIP = range(5)
+TMAC_ACT_F16, TMAC_ACT_I8 = 0, 1
+TMAC_LUT_F16, TMAC_LUT_I16 = 0, 1
+TMAC_OUT_F32, TMAC_OUT_F16, TMAC_OUT_I32 = 0, 1, 2
+TMAC_LAYOUT_T16K128 = 1
+
+EXPORTS = [
+    "tmac_packed_bytes", "tmac_pack_weights", "tmac_lut_bytes", "tmac_precompute_lut",
+    "tmac_workspace_bytes", "tmac_mpgemm", "tmac_mpgemm_ex", "tmac_status_str", "tmac_version",
+    "tmac_last_error_detail",
+]
+
+
+class tmac_wdesc(C.Structure):
+    _fields_ = [("M", C.c_int32), ("K", C.c_int32), ("bits", C.c_int32), ("g", C.c_int32),
+                ("group", C.c_int32), ("layout", C.c_int32), ("zero_point", C.c_float),
+                ("reserved", C.c_int32)]
+
+
+class tmac_tuning(C.Structure):
+    _fields_ = [("chunks_per_wave", C.c_int32), ("n_tile", C.c_int32), ("kernel", C.c_int32),
+                ("reserved", C.c_int32 * 5)]
+
+
+class TmacError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        detail = lib.tmac_last_error_detail().decode() if status == TMAC_EHIP else ""
+        super().__init__(f"{where}: {status_str(status)} (status {status}) {detail}".rstrip())
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(there is no CPU or PyTorch fallback for the HIP path)")
+    # torch bundles its own HIP runtime (same soname as ROCm's).  Import torch first so that the
+    # library binds to that one runtime instead of pulling a second copy from /opt/rocm: two
+    # runtimes in one process do not share streams or devices.
+    import torch  # noqa: F401
+    lib = C.CDLL(LIB_PATH)
+    P, I32, I64, SZ, F = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float
+    D = C.POINTER(tmac_wdesc)
+    lib.tmac_packed_bytes.restype, lib.tmac_packed_bytes.argtypes = SZ, [D]
+    lib.tmac_pack_weights.restype = C.c_int
+    lib.tmac_pack_weights.argtypes = [D, P, P, P, P, SZ]
+    lib.tmac_lut_bytes.restype, lib.tmac_lut_bytes.argtypes = SZ, [I32, I32, I32, I32, C.c_int]
+    lib.tmac_precompute_lut.restype = C.c_int
+    lib.tmac_precompute_lut.argtypes = [P, C.c_int, I32, I32, I64, I32, I32, C.c_int, P, SZ, P]
+    lib.tmac_workspace_bytes.restype, lib.tmac_workspace_bytes.argtypes = SZ, [D, I32]
+    lib.tmac_mpgemm.restype = C.c_int
+    lib.tmac_mpgemm.argtypes = [D, P, P, C.c_int, I32, P, F, P, C.c_int, I64, P, SZ, P]
+    lib.tmac_mpgemm_ex.restype = C.c_int
+    lib.tmac_mpgemm_ex.argtypes = [D, P, P, C.c_int, I32, P, F, P, C.c_int, I64, P, SZ, P,
+                                   C.POINTER(tmac_tuning)]
+    lib.tmac_status_str.restype, lib.tmac_status_str.argtypes = C.c_char_p, [C.c_int]
+    lib.tmac_version.restype, lib.tmac_version.argtypes = I32, []
+    lib.tmac_last_error_detail.restype, lib.tmac_last_error_detail.argtypes = C.c_char_p, []
+    return lib
+
+
+lib = _load()
+
+
+def status_str(status: int) -> str:
+    return lib.tmac_status_str(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != TMAC_OK:
+        raise TmacError(status, where)
+
+
+def wdesc(M: int, K: int, bits: int, group: int, zero_point: float = 0.0, g: int = 4,
+          layout: int = TMAC_LAYOUT_T16K128) -> tmac_wdesc:
+    return tmac_wdesc(M, K, bits, g, group, layout, float(zero_point), 0)
+
+
+def tmac_version() -> int:
+    return int(lib.tmac_version())
+
+
+def tmac_packed_bytes(desc: tmac_wdesc) -> int:
+    return int(lib.tmac_packed_bytes(C.byref(desc)))
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def tmac_pack_weights(desc: tmac_wdesc, q: np.ndarray, scales: Optional[np.ndarray] = None,
+                      zeros: Optional[np.ndarray] = None) -> np.ndarray:
+    """Host-side offline packing; returns the blob as a uint8 numpy array."""
+    q = np.ascontiguousarray(q, dtype=np.uint8)
+    if q.shape != (desc.M, desc.K):
+        raise ValueError("q must be [M, K]")
+    s16 = None if scales is None else np.ascontiguousarray(scales, dtype=np.float16).view(np.uint16)
+    z16 = None if zeros is None else np.ascontiguousarray(zeros, dtype=np.float16).view(np.uint16)
+    if desc.group > 0:
+        ng = desc.K // desc.group if desc.K % desc.group == 0 else -1
+        for a in (s16, z16):
+            if a is not None and a.shape != (desc.M, ng):
+                raise ValueError("scales/zeros must be [M, K/group]")
+    nbytes = tmac_packed_bytes(desc)
+    if nbytes == 0:
+        raise TmacError(TMAC_EINVAL, "tmac_packed_bytes")
+    blob = np.empty(nbytes, dtype=np.uint8)
+    _check(lib.tmac_pack_weights(C.byref(desc), _np_ptr(q), _np_ptr(s16), _np_ptr(z16),
+                                 _np_ptr(blob), nbytes), "tmac_pack_weights")
+    return blob
+
+
+def tmac_lut_bytes(N: int, K: int, group: int, lut: int, g: int = 4) -> int:
+    return int(lib.tmac_lut_bytes(N, K, g, group, lut))
+
+
+def tmac_workspace_bytes(desc: tmac_wdesc, N: int) -> int:
+    return int(lib.tmac_workspace_bytes(C.byref(desc), N))
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def tmac_precompute_lut(A, N: int, K: int, group: int, lut: int, lut_buf, act: Optional[int] = None,
+                        lda: Optional[int] = None, g: int = 4, stream=None) -> None:
+    """A: device tensor (fp16 or int8) [N, K]; lut_buf: device uint8 tensor of tmac_lut_bytes."""
+    import torch
+    if act is None:
+        act = TMAC_ACT_I8 if A.dtype == torch.int8 else TMAC_ACT_F16
+    if lda is None:
+        lda = A.stride(0) if A.dim() == 2 else K
+    _check(lib.tmac_precompute_lut(C.c_void_p(A.data_ptr()), act, N, K, lda, g, group, lut,
+                                   C.c_void_p(lut_buf.data_ptr()), lut_buf.numel() * lut_buf.element_size(),
+                                   _stream_ptr(stream)), "tmac_precompute_lut")
+
+
+def tmac_mpgemm(desc: tmac_wdesc, packed, lut_buf, lut: int, N: int, out, out_t: int,
+                workspace=None, act_scale=None, weight_scale: float = 1.0, ldo: Optional[int] = None,
+                stream=None, tuning: Optional[tmac_tuning] = None) -> None:
+    """packed / lut_buf / out / workspace / act_scale: device tensors."""
+    if ldo is None:
+        ldo = out.stride(0) if out.dim() == 2 else desc.M
+    ws_ptr = C.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    as_ptr = C.c_void_p(act_scale.data_ptr()) if act_scale is not None else None
+    args = [C.byref(desc), C.c_void_p(packed.data_ptr()), C.c_void_p(lut_buf.data_ptr()), lut, N, as_ptr,
+            C.c_float(weight_scale), C.c_void_p(out.data_ptr()), out_t, ldo, ws_ptr, ws_bytes,
+            _stream_ptr(stream)]
+    if tuning is None:
+        _check(lib.tmac_mpgemm(*args), "tmac_mpgemm")
+    else:
+        _check(lib.tmac_mpgemm_ex(*args, C.byref(tuning)), "tmac_mpgemm_ex")
+
+
+# ---------------------------------------------------------------------------------------
+# Convenience holder for device-resident state (allocation only; no arithmetic)
+# ---------------------------------------------------------------------------------------
+@dataclass
+class DeviceWeights:
+    desc: tmac_wdesc
+    packed: "object"   # torch uint8 tensor on the device
+    nbytes: int
+
+
+def upload_weights(desc: tmac_wdesc, q, scales=None, zeros=None, device="cuda") -> DeviceWeights:
+    import torch
+    blob = tmac_pack_weights(desc, q, scales, zeros)
+    t = torch.from_numpy(blob).to(device)
+    return DeviceWeights(desc, t, blob.size)

@@ -1,0 +1,60 @@
+"""Device-resident state for one weight matrix: buffers and call order only (no arithmetic)."""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+
+from . import binding as B
+
+
+class LinearLUT:
+    """Holds the packed weights of one [M, K] matrix on the device together with the LUT,
+    workspace and output buffers for up to ``max_N`` activation rows, and issues
+    tmac_precompute_lut + tmac_mpgemm on the current torch stream."""
+
+    def __init__(self, M: int, K: int, bits: int, group: int, q: np.ndarray,
+                 scales: Optional[np.ndarray] = None, zeros: Optional[np.ndarray] = None,
+                 zero_point: float = 0.0, weight_scale: float = 1.0, int_path: bool = False,
+                 max_N: int = 1, device: str = "cuda", packed_host: Optional[np.ndarray] = None):
+        import torch
+        self.torch = torch
+        self.device = device
+        self.desc = B.wdesc(M, K, bits, group, zero_point)
+        self.M, self.K, self.bits, self.group = M, K, bits, group
+        self.weight_scale = float(weight_scale)
+        self.lut_t = B.TMAC_LUT_I16 if int_path else B.TMAC_LUT_F16
+        self.max_N = max_N
+        blob = packed_host if packed_host is not None else B.tmac_pack_weights(self.desc, q, scales, zeros)
+        self.packed_bytes = int(blob.size)
+        self.packed = torch.from_numpy(blob).to(device)
+        self.lut = torch.empty(B.tmac_lut_bytes(max_N, K, group, self.lut_t), dtype=torch.uint8, device=device)
+        self.workspace = torch.zeros(max(B.tmac_workspace_bytes(self.desc, max_N), 256), dtype=torch.uint8,
+                                     device=device)
+
+    def precompute(self, A, N: Optional[int] = None, stream=None):
+        N = A.shape[0] if N is None else N
+        B.tmac_precompute_lut(A, N, self.K, self.group, self.lut_t, self.lut, stream=stream)
+
+    def mpgemm(self, N: int, out, out_t: int = B.TMAC_OUT_F32, act_scale=None, stream=None, tuning=None,
+               packed=None):
+        B.tmac_mpgemm(self.desc, self.packed if packed is None else packed, self.lut, self.lut_t, N, out,
+                      out_t, workspace=self.workspace, act_scale=act_scale, weight_scale=self.weight_scale,
+                      stream=stream, tuning=tuning)
+
+    def forward(self, A, out_t: int = B.TMAC_OUT_F32, act_scale=None, tuning=None):
+        torch = self.torch
+        N = A.shape[0]
+        assert N <= self.max_N
+        dt = {B.TMAC_OUT_F32: torch.float32, B.TMAC_OUT_F16: torch.float16, B.TMAC_OUT_I32: torch.int32}[out_t]
+        out = torch.empty((N, self.M), dtype=dt, device=self.device)
+        self.precompute(A, N)
+        self.mpgemm(N, out, out_t, act_scale=act_scale, tuning=tuning)
+        return out
+
+
+def from_problem(p, max_N: Optional[int] = None, device: str = "cuda") -> LinearLUT:
+    """Build a LinearLUT from a workload description object with fields M, K, bits, group, q,
+    scales, zeros, zero_point, weight_scale and int_path."""
+    return LinearLUT(p.M, p.K, p.bits, p.group, p.q, p.scales, p.zeros, zero_point=p.zero_point,
+                     weight_scale=p.weight_scale, int_path=p.int_path, max_N=max_N or p.N, device=device)
