@@ -89,7 +89,33 @@ typedef struct {
  *            quantisation group (n_qgroups = K/G, 1 when group == K, absent when group == 0)
  *   One wavefront reads 64*4*bits contiguous bytes per (tile, chunk).
  */
-enum { TMAC_LAYOUT_T16K128 = 1 };
+/* Packed layout 2 ("tile 8 rows x units of 16 k", for the register-table decode kernel;
+ * Section 3.2 permutation + interleaving, Section 3.3 mirror consolidation folded into
+ * the stored indices):
+ *
+ *   header   as layout 1 (Mp = M rounded up to 8, n_tiles = Mp/8, n_chunks = Kp/16 units)
+ *   indices  per tile t (rows 8t..8t+7) the records of its n_units units, 4*bits dwords each:
+ *            record[tb][d], unit u = k in [16u, 16u+16), table tb = LUT group kg = 4u + tb.
+ *            One lane of the kernel owns one unit (four tables held in registers).  The units
+ *            are split into nB = ceil(n_units/64) blocks, block j = units [floor(j*n_units/nB),
+ *            floor((j+1)*n_units/nB)), one block per wavefront pass.  Inside a block of nu units
+ *            the records are stored piece-major: the 16-byte piece i (dwords 4i..4i+3 of the
+ *            flattened record) of the block's l-th unit sits at dword offset
+ *            (t*n_units + u0)*4*bits + (i*nu + l)*4, so that each of the `bits` load
+ *            instructions of a wavefront reads one contiguous run.
+ *            Stored 4-bit code of an index p:  p < 8 ? p : 8 | (15 - p)   (bit 3 = negate,
+ *            bits 0..2 = entry of the stored half table, because T[p] = -T[15-p]).
+ *            Byte y of a dword holds two codes of the same table, the low nibble for the
+ *            "low" row and the high nibble for the "high" row (r = row in tile):
+ *              bits = 4: dword d = 0..3:  low = (r = 2d, plane y), high = (r = 2d+1, plane y)
+ *              bits = 2: dword d = 0..1:  low = (r = 4d + y/2, plane y%2),
+ *                                         high = (r = 4d + 2 + y/2, plane y%2)
+ *              bits = 1: dword 0:         low = (r = y, plane 0), high = (r = 4 + y, plane 0)
+ *              bits = 3: dwords 0,1 as bits = 2 (planes 0,1); dword 2 as bits = 1 with plane 2
+ *   scales   u16 sz[n_tiles][n_qgroups][8][2] = {fp16 scale, fp16 zero}
+ *   Group sizes: any multiple of 16, or K, or 0 (per tensor).
+ */
+enum { TMAC_LAYOUT_T16K128 = 1, TMAC_LAYOUT_R8U16 = 2 };
 
 typedef struct {
   uint32_t magic;        /* 0x43414D54 "TMAC" */
@@ -123,8 +149,9 @@ tmac_status tmac_pack_weights(const tmac_wdesc* desc, const uint8_t* q_host,
                               void* packed_host, size_t packed_bytes);
 
 /* Bytes of the LUT buffer for N activation rows: tables [N][Kp/4][16] (2 bytes each, k
- * padded to 128 with all-zero tables) followed by the group sums S[N][n_qgroups]
- * (fp32 for TMAC_LUT_F16, int32 for TMAC_LUT_I16), 256-byte aligned.  0 on bad arguments. */
+ * padded to 128 with all-zero tables), then the group sums S[N][n_qgroups], then the sums
+ * of every 16 consecutive activations S16[N][Kp/16] (both fp32 for TMAC_LUT_F16, int32 for
+ * TMAC_LUT_I16), each region 256-byte aligned.  0 on bad arguments. */
 size_t tmac_lut_bytes(int32_t N, int32_t K, int32_t g, int32_t group, tmac_lut_t lut);
 
 /* Online table precompute (Algorithm 1 Precompute; Section 3.1; mirror consolidation of
@@ -176,6 +203,14 @@ tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed_dev, const
                            float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
                            void* workspace_dev, size_t workspace_bytes, void* stream,
                            const tmac_tuning* tuning);
+
+/* Measurement helper, not part of the mpGEMM path (Section 5.2 notes that multi-threaded mpGEMV
+ * is bound by memory bandwidth: this is the plain streaming read the lookup kernels are compared
+ * with).  Reads `bytes` bytes from src_dev with 16-byte loads, `per_thread` (1, 4 or 8) loads in
+ * flight per lane, optionally non-temporal; sink_dev needs 256 writable bytes.
+ * Errors: TMAC_EINVAL, TMAC_EUNSUPPORTED, TMAC_EHIP. */
+tmac_status tmac_stream_read(const void* src_dev, size_t bytes, void* sink_dev, int32_t per_thread,
+                             int32_t nontemporal, void* stream);
 
 const char* tmac_status_str(tmac_status s);
 

@@ -21,12 +21,13 @@ TMAC_OK, TMAC_EINVAL, TMAC_EUNSUPPORTED, TMAC_ESIZE, TMAC_EHIP = range(5)
 TMAC_ACT_F16, TMAC_ACT_I8 = 0, 1
 TMAC_LUT_F16, TMAC_LUT_I16 = 0, 1
 TMAC_OUT_F32, TMAC_OUT_F16, TMAC_OUT_I32 = 0, 1, 2
-TMAC_LAYOUT_T16K128 = 1
+TMAC_LAYOUT_T16K128 = 1   # LDS-table kernels (any N)
+TMAC_LAYOUT_R8U16 = 2     # register-table decode kernel (small N)
 
 EXPORTS = [
     "tmac_packed_bytes", "tmac_pack_weights", "tmac_lut_bytes", "tmac_precompute_lut",
     "tmac_workspace_bytes", "tmac_mpgemm", "tmac_mpgemm_ex", "tmac_status_str", "tmac_version",
-    "tmac_last_error_detail",
+    "tmac_last_error_detail", "tmac_stream_read",
 ]
 
 
@@ -75,6 +76,8 @@ def _load() -> C.CDLL:
     lib.tmac_status_str.restype, lib.tmac_status_str.argtypes = C.c_char_p, [C.c_int]
     lib.tmac_version.restype, lib.tmac_version.argtypes = I32, []
     lib.tmac_last_error_detail.restype, lib.tmac_last_error_detail.argtypes = C.c_char_p, []
+    lib.tmac_stream_read.restype = C.c_int
+    lib.tmac_stream_read.argtypes = [P, SZ, P, I32, I32, P]
     return lib
 
 
@@ -127,6 +130,14 @@ def tmac_pack_weights(desc: tmac_wdesc, q: np.ndarray, scales: Optional[np.ndarr
     _check(lib.tmac_pack_weights(C.byref(desc), _np_ptr(q), _np_ptr(s16), _np_ptr(z16),
                                  _np_ptr(blob), nbytes), "tmac_pack_weights")
     return blob
+
+
+def tmac_stream_read(src, sink, per_thread: int = 4, nontemporal: bool = False, nbytes: Optional[int] = None,
+                     stream=None) -> None:
+    """Plain streaming read of a device tensor (measurement helper)."""
+    n = src.numel() * src.element_size() if nbytes is None else nbytes
+    _check(lib.tmac_stream_read(C.c_void_p(src.data_ptr()), n, C.c_void_p(sink.data_ptr()), per_thread,
+                                1 if nontemporal else 0, _stream_ptr(stream)), "tmac_stream_read")
 
 
 def tmac_lut_bytes(N: int, K: int, group: int, lut: int, g: int = 4) -> int:

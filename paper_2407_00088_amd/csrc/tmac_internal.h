@@ -2,6 +2,7 @@
 #ifndef TMAC_INTERNAL_H_
 #define TMAC_INTERNAL_H_
 
+#include <cstddef>
 #include <cstdint>
 
 #include "tmac.h"
@@ -10,8 +11,16 @@ namespace tmac {
 
 constexpr uint32_t TMAC_MAGIC = 0x43414D54u;  // "TMAC"
 
+inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// Geometry of a packed weight blob (both layouts).
+//   layout 1: row tiles of 16, k chunks of 128;  layout 2: row tiles of 8, lane-units of 16 k.
 struct Geometry {
-  int Mp, Kp, n_tiles, n_chunks, n_qgroups;
+  int Mp, Kp;          // padded M and K
+  int n_tiles;         // row tiles (16 rows in layout 1, 8 rows in layout 2)
+  int n_chunks;        // layout 1: 128-k chunks; layout 2: 16-k lane-units
+  int n_qgroups;       // scale groups per row stored in the blob (0 when per-tensor)
+  int tile_rows;       // 16 or 8
   uint64_t idx_off, idx_bytes, sz_off, sz_bytes, total_bytes;
 };
 
@@ -19,7 +28,41 @@ bool desc_valid(const tmac_wdesc* d);
 bool group_supported(const tmac_wdesc* d);
 Geometry geometry(const tmac_wdesc* d);
 
-inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+// Geometry of the LUT buffer written by tmac_precompute_lut.
+struct LutGeom {
+  int Kp, KG, nq;       // K padded to 128, tables per row, quantisation groups per row (>= 1)
+  int Geff;             // elements per quantisation group (K when one group per row/tensor)
+  int U;                // 16-k units per row (Kp / 16)
+  size_t s_off;         // byte offset of the group sums S[N][nq]
+  size_t s16_off;       // byte offset of the unit sums S16[N][U]
+  size_t ht_off;        // byte offset of the fp16 half tables HT[N][U][4][8], piece-major per block
+  size_t total;
+};
+
+inline bool lut_geom(int N, int K, int g, int group, LutGeom* lg) {
+  if (N <= 0 || K <= 0 || g != 4 || K % 4 != 0 || group < 0) return false;
+  if (group > 0 && (K % group != 0 || group % 4 != 0)) return false;
+  lg->Kp = round_up(K, 128);
+  lg->KG = lg->Kp / 4;
+  lg->U = lg->Kp / 16;
+  lg->Geff = (group == 0) ? K : group;
+  lg->nq = K / lg->Geff;
+  const size_t tab = (size_t)N * lg->KG * 16 * 2;
+  lg->s_off = (tab + 255) / 256 * 256;
+  lg->s16_off = (lg->s_off + (size_t)N * lg->nq * 4 + 255) / 256 * 256;
+  lg->ht_off = (lg->s16_off + (size_t)N * lg->U * 4 + 255) / 256 * 256;
+  lg->total = (lg->ht_off + (size_t)N * lg->U * 64 + 255) / 256 * 256;
+  return true;
+}
+
+// Register-table decode kernel (layout 2); defined in tmac_perm.hip.  Arguments are those of
+// tmac_mpgemm after validation; returns a tmac_status value.
+int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, int lut_is_int,
+                     int N, const float* act_scale_dev, float weight_scale, void* out_dev, int out_t,
+                     int64_t ldo, void* stream);
+
+// Records the last HIP error of this thread (diagnostics for TMAC_EHIP).
+void note_hip_error(int hip_error);
 
 }  // namespace tmac
 #endif

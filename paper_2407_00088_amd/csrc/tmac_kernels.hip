@@ -41,24 +41,7 @@ typedef __attribute__((address_space(3))) __half lds_f16;
 // ------------------------------------------------------------------------------------------
 // LUT buffer geometry
 // ------------------------------------------------------------------------------------------
-struct LutGeom {
-  int Kp, KG, nq;       // padded K, tables per row, quantisation groups per row (>= 1)
-  int Geff;             // elements per quantisation group (K when one group per row/tensor)
-  size_t s_off, total;  // byte offset of the sums, total bytes
-};
-
-static bool lut_geom(int N, int K, int g, int group, LutGeom* lg) {
-  if (N <= 0 || K <= 0 || g != 4 || K % 4 != 0 || group < 0) return false;
-  if (group > 0 && (K % group != 0 || group % 4 != 0)) return false;
-  lg->Kp = round_up(K, 128);
-  lg->KG = lg->Kp / 4;
-  lg->Geff = (group == 0) ? K : group;
-  lg->nq = K / lg->Geff;
-  const size_t tab = (size_t)N * lg->KG * 16 * 2;
-  lg->s_off = (tab + 255) / 256 * 256;
-  lg->total = (lg->s_off + (size_t)N * lg->nq * 4 + 255) / 256 * 256;
-  return true;
-}
+// (LutGeom / lut_geom live in tmac_internal.h)
 
 // ------------------------------------------------------------------------------------------
 // Table precompute
@@ -67,19 +50,23 @@ template <bool IS_INT>
 __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict__ A_, int N, int K,
                                                          int64_t lda, int KG,
                                                          uint4* __restrict__ tables,
-                                                         void* __restrict__ S_, int Geff, int nq,
+                                                         void* __restrict__ S_, void* __restrict__ S16_,
+                                                         uint4* __restrict__ HT, int U, int Geff, int nq,
                                                          int n_tab_blocks) {
   if ((int)blockIdx.x < n_tab_blocks) {
     const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (tid >= (int64_t)N * KG) return;
     const int n = (int)(tid / KG), kg = (int)(tid % KG);
     uint32_t packed[8];
+    float sum4f = 0.f;  // sum of this table's four activations (for the per-16 unit sums)
+    int sum4i = 0;
     if (4 * kg >= K) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) packed[i] = 0;  // k padding: all-zero table
     } else if constexpr (IS_INT) {
       const int8_t* a = static_cast<const int8_t*>(A_) + n * lda + 4 * kg;
       const int a0 = a[0], a1 = a[1], a2 = a[2], a3 = a[3];
+      sum4i = a0 + a1 + a2 + a3;
       int e[16];
 #pragma unroll
       for (int p = 0; p < 8; ++p) {
@@ -94,6 +81,7 @@ __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict_
       const __half* a = static_cast<const __half*>(A_) + n * lda + 4 * kg;
       const float a0 = __half2float(a[0]), a1 = __half2float(a[1]);
       const float a2 = __half2float(a[2]), a3 = __half2float(a[3]);
+      sum4f = ((a0 + a1) + a2) + a3;
       uint16_t e[16];
 #pragma unroll
       for (int p = 0; p < 8; ++p) {
@@ -108,6 +96,41 @@ __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict_
     uint4* dst = tables + tid * 2;
     dst[0] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
     dst[1] = make_uint4(packed[4], packed[5], packed[6], packed[7]);
+    // Mirror-consolidated copy for the register-table kernel: entries 0..7 as fp16 (int16 entries
+    // are at most 508 in magnitude, exact in fp16).  Units are grouped in nB blocks; inside a block
+    // of nu units, table tb of the block's l-th unit sits at 16-byte slot tb*nu + l, so that 64
+    // lanes loading "their" table tb read one contiguous run.
+    {
+      uint4 half;
+      if constexpr (IS_INT) {
+        uint32_t h[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int lo = (int)(short)(packed[i] & 0xffffu), hi = (int)(short)(packed[i] >> 16);
+          h[i] = (uint32_t)__half_as_ushort(__int2half_rn(lo)) | ((uint32_t)__half_as_ushort(__int2half_rn(hi)) << 16);
+        }
+        half = make_uint4(h[0], h[1], h[2], h[3]);
+      } else {
+        half = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+      }
+      const int u = kg >> 2, tb = kg & 3;
+      const int nB = (U + 63) >> 6;
+      int blk = (int)(((int64_t)u * nB) / U);
+      while ((int)(((int64_t)(blk + 1) * U) / nB) <= u) ++blk;
+      while ((int)(((int64_t)blk * U) / nB) > u) --blk;
+      const int u0 = (int)(((int64_t)blk * U) / nB), u1 = (int)(((int64_t)(blk + 1) * U) / nB);
+      HT[((size_t)n * U + u0) * 4 + (size_t)tb * (u1 - u0) + (u - u0)] = half;
+    }
+    // unit sums S16[n][kg / 4]: the four tables of a unit sit in four adjacent lanes
+    if constexpr (IS_INT) {
+      sum4i += __shfl_xor(sum4i, 1);
+      sum4i += __shfl_xor(sum4i, 2);
+      if ((kg & 3) == 0) static_cast<int*>(S16_)[tid >> 2] = sum4i;
+    } else {
+      sum4f += __shfl_xor(sum4f, 1);
+      sum4f += __shfl_xor(sum4f, 2);
+      if ((kg & 3) == 0) static_cast<float*>(S16_)[tid >> 2] = sum4f;
+    }
   } else {
     // one wavefront per (n, quantisation group): strided partial sums, then a butterfly
     const int wave = ((int)blockIdx.x - n_tab_blocks) * 4 + (threadIdx.x >> 6);
@@ -613,6 +636,7 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 // Last HIP error seen by this thread while enqueuing (diagnostics only).
 static thread_local hipError_t g_last_hip_error = hipSuccess;
+void note_hip_error(int hip_error) { g_last_hip_error = static_cast<hipError_t>(hip_error); }
 
 // Launch through hipLaunchKernel so that the status is this launch's own and not a stale
 // error left behind by some other user of the runtime in the same process.
@@ -742,19 +766,22 @@ extern "C" tmac_status tmac_precompute_lut(const void* A_dev, tmac_act_t act, in
   const int n_sum_blocks = (N * lg.nq + 3) / 4;
   uint4* tables = static_cast<uint4*>(lut_dev);
   void* S = static_cast<char*>(lut_dev) + lg.s_off;
+  void* S16 = static_cast<char*>(lut_dev) + lg.s16_off;
+  uint4* HT = reinterpret_cast<uint4*>(static_cast<char*>(lut_dev) + lg.ht_off);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const dim3 grid(n_tab_blocks + n_sum_blocks), block(256);
   const hipError_t e =
       (act == TMAC_ACT_F16)
-          ? launch(precompute_kernel<false>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S, lg.Geff,
-                   lg.nq, n_tab_blocks)
-          : launch(precompute_kernel<true>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S, lg.Geff,
-                   lg.nq, n_tab_blocks);
+          ? launch(precompute_kernel<false>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S, S16, HT,
+                   lg.U, lg.Geff, lg.nq, n_tab_blocks)
+          : launch(precompute_kernel<true>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S, S16, HT,
+                   lg.U, lg.Geff, lg.nq, n_tab_blocks);
   return e == hipSuccess ? TMAC_OK : TMAC_EHIP;
 }
 
 extern "C" size_t tmac_workspace_bytes(const tmac_wdesc* desc, int32_t N) {
   if (!desc_valid(desc) || N <= 0) return 0;
+  if (desc->layout == TMAC_LAYOUT_R8U16) return 256;  // the register-table kernel uses none
   const Geometry ge = geometry(desc);
   const size_t max_slices = (ge.n_chunks + KS_MAX_SLICES_CHUNKS - 1) / KS_MAX_SLICES_CHUNKS;
   const size_t part = (max_slices * (size_t)N * ge.Mp * 4 + 255) / 256 * 256;
@@ -784,6 +811,14 @@ extern "C" tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed
   if (!lut_geom(N, desc->K, desc->g, desc->group, &lg)) return TMAC_EINVAL;
   const bool is_int = (lut == TMAC_LUT_I16);
   const bool one_group = (desc->group == 0 || desc->group == desc->K);
+  if (desc->layout == TMAC_LAYOUT_R8U16) {
+    // register-table decode kernel; it needs no workspace and has no launch-shape knobs
+    if (tuning && (tuning->kernel != 0 || tuning->chunks_per_wave != 0 || tuning->n_tile != 0))
+      return TMAC_EUNSUPPORTED;
+    return static_cast<tmac_status>(launch_perm_gemv(desc, packed_dev, lut_dev, is_int ? 1 : 0, N,
+                                                      act_scale_dev, weight_scale, out_dev, (int)out, ldo,
+                                                      stream));
+  }
   // int32 accumulators: |L| <= 508 * (2^b - 1) * K/4 must stay below 2^31
   if (is_int && (double)508.0 * ((1 << desc->bits) - 1) * (desc->K / 4) >= 2147483647.0) return TMAC_EUNSUPPORTED;
 

@@ -5,11 +5,10 @@
 // belonging to element k.  Section 3.2 "Weight permutation": the indices are stored tile by
 // tile in exactly the order the lookup kernel walks them, so that one wavefront reads one
 // contiguous run per step.  Section 3.2 "Weight interleaving": inside a dword the eight
-// indices are placed so that two mask-and-shift operations leave byte-aligned table offsets
-// in processing order.
-#include <cmath>
+// indices are placed so that the kernel's mask-and-shift unpacking leaves them in processing
+// order.  Section 3.3 "Mirror consolidation" (layout 2 only): an index p >= 8 is stored as a
+// sign bit plus the 3-bit selector of its mirror entry 15 - p, because T[p] = -T[15 - p].
 #include <cstring>
-#include <vector>
 
 #include "tmac.h"
 #include "tmac_internal.h"
@@ -21,7 +20,7 @@ bool desc_valid(const tmac_wdesc* d) {
   if (d->M <= 0 || d->K <= 0) return false;
   if (d->bits < 1 || d->bits > 4) return false;
   if (d->g != 4) return false;
-  if (d->layout != TMAC_LAYOUT_T16K128) return false;
+  if (d->layout != TMAC_LAYOUT_T16K128 && d->layout != TMAC_LAYOUT_R8U16) return false;
   if (d->K % d->g != 0) return false;
   if (d->group < 0 || d->reserved != 0) return false;
   if (!(d->zero_point == d->zero_point)) return false;  // NaN
@@ -31,26 +30,125 @@ bool desc_valid(const tmac_wdesc* d) {
   return true;
 }
 
-// Group sizes the lookup kernels can apply scales for: whole chunks (multiples of 128),
-// the two sub-chunk sizes 32 and 64, one group per row, or one per tensor.
+// Group sizes the lookup kernels can apply scales for.
+//   layout 1: whole chunks (multiples of 128), the sub-chunk sizes 32 and 64, one group per
+//             row, or one per tensor.
+//   layout 2: any multiple of 16 (a lane's four tables must share one group), one group per
+//             row, or one per tensor.
 bool group_supported(const tmac_wdesc* d) {
   const int G = d->group;
-  return G == 0 || G == d->K || G == 32 || G == 64 || (G % 128 == 0);
+  if (G == 0 || G == d->K) return true;
+  if (d->layout == TMAC_LAYOUT_R8U16) return G % 16 == 0;
+  return G == 32 || G == 64 || (G % 128 == 0);
 }
 
 Geometry geometry(const tmac_wdesc* d) {
   Geometry ge;
-  ge.Mp = (d->M + 15) / 16 * 16;
-  ge.Kp = (d->K + 127) / 128 * 128;
-  ge.n_tiles = ge.Mp / 16;
-  ge.n_chunks = ge.Kp / 128;
+  ge.Kp = round_up(d->K, 128);
   ge.n_qgroups = d->group == 0 ? 0 : d->K / d->group;
   ge.idx_off = sizeof(tmac_blob_header);
-  ge.idx_bytes = (uint64_t)ge.n_tiles * ge.n_chunks * 64 * d->bits * 4;
+  if (d->layout == TMAC_LAYOUT_R8U16) {
+    ge.tile_rows = 8;
+    ge.Mp = round_up(d->M, 8);
+    ge.n_tiles = ge.Mp / 8;
+    ge.n_chunks = ge.Kp / 16;
+    ge.idx_bytes = (uint64_t)ge.n_tiles * ge.n_chunks * 16 * d->bits;
+  } else {
+    ge.tile_rows = 16;
+    ge.Mp = round_up(d->M, 16);
+    ge.n_tiles = ge.Mp / 16;
+    ge.n_chunks = ge.Kp / 128;
+    ge.idx_bytes = (uint64_t)ge.n_tiles * ge.n_chunks * 64 * d->bits * 4;
+  }
   ge.sz_off = (ge.idx_off + ge.idx_bytes + 255) / 256 * 256;
-  ge.sz_bytes = (uint64_t)ge.n_tiles * ge.n_qgroups * 16 * 4;
+  ge.sz_bytes = (uint64_t)ge.n_tiles * ge.n_qgroups * ge.tile_rows * 4;
   ge.total_bytes = (ge.sz_off + ge.sz_bytes + 255) / 256 * 256;
   return ge;
+}
+
+// 4-bit index of bit plane `plane` of row `row` (length K) for LUT group kg; 0 past the end of K.
+static inline uint32_t index_of(const uint8_t* row, int K, int kg, int plane) {
+  const int k0 = 4 * kg;
+  if (k0 >= K) return 0;
+  uint32_t nib = 0;
+  for (int e = 0; e < 4; ++e) nib |= (uint32_t)((row[k0 + e] >> plane) & 1) << e;
+  return nib;
+}
+
+// Mirror-consolidated form of an index: sign bit 3, selector of the stored half in bits 0..2.
+static inline uint32_t mirror_fold(uint32_t p) { return p < 8 ? p : (8u | (15u - p)); }
+
+static void pack_indices_layout1(const tmac_wdesc* d, const Geometry& ge, const uint8_t* q, uint32_t* idx) {
+  const int M = d->M, K = d->K, b = d->bits;
+  for (int t = 0; t < ge.n_tiles; ++t)
+    for (int c = 0; c < ge.n_chunks; ++c)
+      for (int lane = 0; lane < 64; ++lane) {
+        const int r = lane & 15, phi = lane >> 4;
+        const int m = 16 * t + r;
+        if (m >= M) continue;
+        uint32_t* dst = idx + (((size_t)t * ge.n_chunks + c) * 64 + lane) * b;
+        const uint8_t* row = q + (size_t)m * K;
+        for (int i = 0; i < b; ++i) {
+          uint32_t word = 0;
+          for (int j = 0; j < 8; ++j) {
+            const int pos = (j < 4) ? 2 * j : 2 * (j - 4) + 1;
+            word |= index_of(row, K, 32 * c + 4 * j + phi, i) << (4 * pos);
+          }
+          dst[i] = word;
+        }
+      }
+}
+
+// Layout 2: per (8-row tile, 16-k unit) four tables, each with `bits` dwords.  Byte y of a dword
+// carries two indices of the same table: the low nibble belongs to the "low" row set and the
+// high nibble to the "high" row set; which (row, plane) a byte stands for depends on how many
+// planes share the dword (see tmac.h).
+static void pack_indices_layout2(const tmac_wdesc* d, const Geometry& ge, const uint8_t* q, uint32_t* idx) {
+  const int M = d->M, K = d->K, b = d->bits;
+  auto nib = [&](int m, int kg, int plane) -> uint32_t {
+    if (m >= M) return 0;
+    return mirror_fold(index_of(q + (size_t)m * K, K, kg, plane));
+  };
+  const int U = ge.n_chunks, nB = (U + 63) / 64;
+  for (int t = 0; t < ge.n_tiles; ++t)
+    for (int blk = 0; blk < nB; ++blk) {
+     const int u0 = (int)(((int64_t)blk * U) / nB), u1 = (int)(((int64_t)(blk + 1) * U) / nB), nu = u1 - u0;
+     for (int u = u0; u < u1; ++u) {
+      uint32_t rec[16];  // the unit's record: [table][dword]
+      for (int tb = 0; tb < 4; ++tb) {
+        const int kg = 4 * u + tb, m0 = 8 * t;
+        uint32_t* dst = rec + tb * b;
+        int nd = 0;
+        auto quad = [&](int dw) {  // four planes of rows 2dw (low) and 2dw+1 (high)
+          uint32_t w = 0;
+          for (int y = 0; y < 4; ++y)
+            w |= (nib(m0 + 2 * dw, kg, y) | (nib(m0 + 2 * dw + 1, kg, y) << 4)) << (8 * y);
+          return w;
+        };
+        auto pair = [&](int dw, int p0) {  // planes p0, p0+1 of rows 4dw, 4dw+1 (low), 4dw+2, 4dw+3 (high)
+          uint32_t w = 0;
+          for (int y = 0; y < 4; ++y)
+            w |= (nib(m0 + 4 * dw + y / 2, kg, p0 + y % 2) | (nib(m0 + 4 * dw + 2 + y / 2, kg, p0 + y % 2) << 4))
+                 << (8 * y);
+          return w;
+        };
+        auto single = [&](int p0) {  // plane p0 of rows 0..3 (low) and 4..7 (high)
+          uint32_t w = 0;
+          for (int y = 0; y < 4; ++y) w |= (nib(m0 + y, kg, p0) | (nib(m0 + 4 + y, kg, p0) << 4)) << (8 * y);
+          return w;
+        };
+        if (b == 4) { for (int dw = 0; dw < 4; ++dw) dst[nd++] = quad(dw); }
+        else if (b == 2) { dst[nd++] = pair(0, 0); dst[nd++] = pair(1, 0); }
+        else if (b == 1) { dst[nd++] = single(0); }
+        else { dst[nd++] = pair(0, 0); dst[nd++] = pair(1, 0); dst[nd++] = single(2); }
+      }
+      // 16-byte piece i of the record goes to slot (i, lane) of the block, so that the 64 lanes
+      // of a wavefront read one contiguous run per load instruction
+      uint32_t* blk_base = idx + ((size_t)t * U + u0) * (4 * b);
+      for (int i = 0; i < b; ++i)
+        for (int e = 0; e < 4; ++e) blk_base[((size_t)i * nu + (u - u0)) * 4 + e] = rec[4 * i + e];
+     }
+    }
 }
 
 }  // namespace tmac
@@ -88,44 +186,21 @@ extern "C" tmac_status tmac_pack_weights(const tmac_wdesc* desc, const uint8_t* 
   h.sz_off = ge.sz_off; h.sz_bytes = ge.sz_bytes; h.total_bytes = ge.total_bytes;
   std::memcpy(out, &h, sizeof(h));
 
-  // indices
   uint32_t* idx = reinterpret_cast<uint32_t*>(out + ge.idx_off);
-  for (int t = 0; t < ge.n_tiles; ++t) {
-    for (int c = 0; c < ge.n_chunks; ++c) {
-      for (int lane = 0; lane < 64; ++lane) {
-        const int r = lane & 15, phi = lane >> 4;
-        const int m = 16 * t + r;
-        uint32_t* dst = idx + (((size_t)t * ge.n_chunks + c) * 64 + lane) * b;
-        if (m >= M) continue;
-        const uint8_t* row = q + (size_t)m * K;
-        for (int i = 0; i < b; ++i) {
-          uint32_t word = 0;
-          for (int j = 0; j < 8; ++j) {
-            const int kg = 32 * c + 4 * j + phi;   // LUT group
-            const int k0 = 4 * kg;
-            if (k0 >= K) continue;
-            uint32_t nib = 0;
-            for (int e = 0; e < 4; ++e) nib |= (uint32_t)((row[k0 + e] >> i) & 1) << e;
-            const int pos = (j < 4) ? 2 * j : 2 * (j - 4) + 1;
-            word |= nib << (4 * pos);
-          }
-          dst[i] = word;
-        }
-      }
-    }
-  }
+  if (desc->layout == TMAC_LAYOUT_R8U16) pack_indices_layout2(desc, ge, q, idx);
+  else pack_indices_layout1(desc, ge, q, idx);
 
-  // scales and zeros, {s, z} per (tile, quantisation group, row)
+  // scales and zeros, {s, z} per (row tile, quantisation group, row in tile)
   if (G > 0) {
     uint16_t* sz = reinterpret_cast<uint16_t*>(out + ge.sz_off);
-    const int nq = ge.n_qgroups;
+    const int nq = ge.n_qgroups, R = ge.tile_rows;
     // fp16 bits of (2^b-1)/2: 0.5, 1.5, 3.5, 7.5
     static const uint16_t mid_bits[5] = {0, 0x3800, 0x3E00, 0x4300, 0x4780};
     for (int t = 0; t < ge.n_tiles; ++t)
       for (int gq = 0; gq < nq; ++gq)
-        for (int r = 0; r < 16; ++r) {
-          const int m = 16 * t + r;
-          uint16_t* dst = sz + (((size_t)t * nq + gq) * 16 + r) * 2;
+        for (int r = 0; r < R; ++r) {
+          const int m = R * t + r;
+          uint16_t* dst = sz + (((size_t)t * nq + gq) * R + r) * 2;
           if (m >= M) { dst[0] = 0; dst[1] = 0; continue; }
           dst[0] = scales[(size_t)m * nq + gq];
           dst[1] = zeros ? zeros[(size_t)m * nq + gq] : mid_bits[b];
@@ -145,4 +220,4 @@ extern "C" const char* tmac_status_str(tmac_status s) {
   return "unknown status";
 }
 
-extern "C" int32_t tmac_version(void) { return 1000 * 0 + 1; }
+extern "C" int32_t tmac_version(void) { return 1000 * 0 + 2; }

@@ -7,6 +7,12 @@ import numpy as np
 
 from . import binding as B
 
+DECODE_MAX_N = 8  # up to this many activation rows the register-table layout is the default
+
+
+def default_layout(max_N: int) -> int:
+    return B.TMAC_LAYOUT_R8U16 if max_N <= DECODE_MAX_N else B.TMAC_LAYOUT_T16K128
+
 
 class LinearLUT:
     """Holds the packed weights of one [M, K] matrix on the device together with the LUT,
@@ -16,11 +22,13 @@ class LinearLUT:
     def __init__(self, M: int, K: int, bits: int, group: int, q: np.ndarray,
                  scales: Optional[np.ndarray] = None, zeros: Optional[np.ndarray] = None,
                  zero_point: float = 0.0, weight_scale: float = 1.0, int_path: bool = False,
-                 max_N: int = 1, device: str = "cuda", packed_host: Optional[np.ndarray] = None):
+                 max_N: int = 1, device: str = "cuda", packed_host: Optional[np.ndarray] = None,
+                 layout: Optional[int] = None):
         import torch
         self.torch = torch
         self.device = device
-        self.desc = B.wdesc(M, K, bits, group, zero_point)
+        self.layout = default_layout(max_N) if layout is None else layout
+        self.desc = B.wdesc(M, K, bits, group, zero_point, layout=self.layout)
         self.M, self.K, self.bits, self.group = M, K, bits, group
         self.weight_scale = float(weight_scale)
         self.lut_t = B.TMAC_LUT_I16 if int_path else B.TMAC_LUT_F16
@@ -53,8 +61,18 @@ class LinearLUT:
         return out
 
 
-def from_problem(p, max_N: Optional[int] = None, device: str = "cuda") -> LinearLUT:
+def layout_supports_group(layout: int, K: int, group: int) -> bool:
+    """Mirror of the library's rule for which group sizes a layout's kernels can apply."""
+    if group == 0 or group == K:
+        return True
+    if layout == B.TMAC_LAYOUT_R8U16:
+        return group % 16 == 0
+    return group in (32, 64) or group % 128 == 0
+
+
+def from_problem(p, max_N: Optional[int] = None, device: str = "cuda", layout: Optional[int] = None) -> LinearLUT:
     """Build a LinearLUT from a workload description object with fields M, K, bits, group, q,
     scales, zeros, zero_point, weight_scale and int_path."""
     return LinearLUT(p.M, p.K, p.bits, p.group, p.q, p.scales, p.zeros, zero_point=p.zero_point,
-                     weight_scale=p.weight_scale, int_path=p.int_path, max_N=max_N or p.N, device=device)
+                     weight_scale=p.weight_scale, int_path=p.int_path, max_N=max_N or p.N, device=device,
+                     layout=layout)

@@ -2,7 +2,10 @@
 element on the same seeded inputs.
 
 Bars: integer path bit-exact; fp16-table path within 2e-3 relative Frobenius error of the
-fp64 product (the rounding of table entries to fp16 alone costs a few 1e-4)."""
+fp64 product (the rounding of table entries to fp16 alone costs a few 1e-4).
+
+Every case runs in both packed layouts where both apply: layout 1 feeds the LDS-table kernels
+(K-sliced and full-K), layout 2 the register-table decode kernel."""
 import numpy as np
 import pytest
 
@@ -12,6 +15,7 @@ from oracle import tmac_oracle as orc
 pytestmark = pytest.mark.gpu
 
 FP_TOL = 2e-3
+L1, L2 = 1, 2
 
 
 @pytest.fixture(scope="module")
@@ -27,9 +31,20 @@ def torch():
     return torch
 
 
-def run_fp(T, torch, p, out_t=None, tuning=None):
-    from paper_2407_00088_amd.runner import from_problem
-    lin = from_problem(p)
+@pytest.fixture(params=[L1, L2], ids=["lds", "regs"])
+def layout(request):
+    return request.param
+
+
+def make_lin(p, layout):
+    from paper_2407_00088_amd.runner import from_problem, layout_supports_group
+    if not layout_supports_group(layout, p.K, p.group):
+        pytest.skip(f"group {p.group} not supported by layout {layout}")
+    return from_problem(p, layout=layout)
+
+
+def run_fp(T, torch, p, out_t=None, tuning=None, layout=L1):
+    lin = make_lin(p, layout)
     A = torch.from_numpy(p.act).cuda()
     out = lin.forward(A, out_t=T.TMAC_OUT_F32 if out_t is None else out_t, tuning=tuning)
     torch.cuda.synchronize()
@@ -40,20 +55,19 @@ def oracle_fp(p):
     return orc.mpgemm_definition(p.act, p.q, p.scales, p.zeros, p.group, p.weight_scale, p.zero_point)
 
 
-def check_fp(T, torch, p, tuning=None, tol=FP_TOL):
-    got = run_fp(T, torch, p, tuning=tuning)
+def check_fp(T, torch, p, tuning=None, tol=FP_TOL, layout=L1):
+    got = run_fp(T, torch, p, tuning=tuning, layout=layout)
     ref = oracle_fp(p)
     assert got.shape == ref.shape and got.dtype == np.float32
     assert np.all(np.isfinite(got))
     err = orc.rel_frobenius(got, ref)
-    print(f"{p.name}: rel_frobenius={err:.3e}", flush=True)
-    assert err <= tol, (p.name, err)
+    print(f"{p.name} layout{layout}: rel_frobenius={err:.3e}", flush=True)
+    assert err <= tol, (p.name, layout, err)
     return err
 
 
-def run_int(T, torch, p, out_t, tuning=None):
-    from paper_2407_00088_amd.runner import from_problem
-    lin = from_problem(p)
+def run_int(T, torch, p, out_t, tuning=None, layout=L1):
+    lin = make_lin(p, layout)
     A = torch.from_numpy(p.act_q).cuda()
     s_a = torch.from_numpy(p.act_scale).cuda()
     out = lin.forward(A, out_t=out_t, act_scale=s_a, tuning=tuning)
@@ -61,28 +75,28 @@ def run_int(T, torch, p, out_t, tuning=None):
     return out.cpu().numpy()
 
 
-def check_int(T, torch, p, tuning=None):
+def check_int(T, torch, p, tuning=None, layout=L1):
     ref_i = orc.ternary_int_matmul(p.act_q, p.q, int(p.zero_point))
-    got_i = run_int(T, torch, p, T.TMAC_OUT_I32, tuning)
+    got_i = run_int(T, torch, p, T.TMAC_OUT_I32, tuning, layout)
     assert got_i.dtype == np.int32
-    assert np.array_equal(got_i.astype(np.int64), ref_i), p.name
+    assert np.array_equal(got_i.astype(np.int64), ref_i), (p.name, layout)
     ref_f = orc.int_path_output_f32(ref_i, p.act_scale, p.weight_scale)
-    got_f = run_int(T, torch, p, T.TMAC_OUT_F32, tuning)
-    assert np.array_equal(got_f.view(np.uint32), ref_f.view(np.uint32)), p.name
+    got_f = run_int(T, torch, p, T.TMAC_OUT_F32, tuning, layout)
+    assert np.array_equal(got_f.view(np.uint32), ref_f.view(np.uint32)), (p.name, layout)
 
 
 # ------------------------------------------------------------- small cases ----
 
-def test_config1_tiny(T, torch):
-    err = check_fp(T, torch, wl.config1())
+def test_config1_tiny(T, torch, layout):
+    err = check_fp(T, torch, wl.config1(), layout=layout)
     assert err < 1e-3
 
 
 @pytest.mark.parametrize("bits", [1, 2, 3, 4])
-@pytest.mark.parametrize("group", [32, 64, 128, 384, 0])
-def test_small_ragged_all_bits_all_groupings(T, torch, bits, group):
-    """Several 16-row tiles with a ragged last tile, three 128-chunks; every supported
-    grouping (sub-chunk, chunk, multi-chunk, per row == K, per tensor)."""
+@pytest.mark.parametrize("group", [16, 32, 48, 64, 128, 192, 384, 0])
+def test_small_ragged_all_bits_all_groupings(T, torch, bits, group, layout):
+    """Several row tiles with a ragged last tile, three 128-chunks; every supported grouping
+    (sub-chunk, chunk, multi-chunk, per row == K, per tensor)."""
     M, K = 100, 384
     if group == 0:
         rng = np.random.default_rng(7 + bits)
@@ -90,16 +104,16 @@ def test_small_ragged_all_bits_all_groupings(T, torch, bits, group):
                        weight_scale=0.037, zero_point=1.25, act=wl.gaussian_act(rng, 1, K))
     else:
         p = wl.make_grouped(0, 10 * bits + group % 7, 1, M, K, bits, group, name=f"small_w{bits}_g{group}")
-    check_fp(T, torch, p)
+    check_fp(T, torch, p, layout=layout)
 
 
-@pytest.mark.parametrize("K", [4, 64, 192, 8640 // 5])
-def test_ragged_k_padding(T, torch, K):
-    """K not a multiple of the 128-wide chunk: padded tables are all-zero."""
+@pytest.mark.parametrize("K", [4, 24, 64, 192, 8640 // 5])
+def test_ragged_k_padding(T, torch, K, layout):
+    """K not a multiple of the 128-wide chunk (nor of the 16-wide unit): padded tables are all-zero."""
     p = wl.make_grouped(0, 50 + K % 13, 2, 40, K, 4, K, name=f"ragk_{K}")
-    check_fp(T, torch, p)
+    check_fp(T, torch, p, layout=layout)
     if K % 64 == 0:
-        check_fp(T, torch, wl.make_grouped(0, 51, 1, 40, K, 2, 32, name=f"ragk32_{K}"))
+        check_fp(T, torch, wl.make_grouped(0, 51, 1, 40, K, 2, 32, name=f"ragk32_{K}"), layout=layout)
 
 
 @pytest.mark.parametrize("ks", [2, 4, 8])
@@ -107,37 +121,45 @@ def test_ragged_k_padding(T, torch, K):
 def test_launch_shapes_agree(T, torch, ks, nt):
     from paper_2407_00088_amd.binding import tmac_tuning
     p = wl.make_grouped(0, 60, 6, 200, 1280, 4, 128, name=f"tune_ks{ks}_nt{nt}")
-    tun = tmac_tuning(ks, nt)
-    check_fp(T, torch, p, tuning=tun)
+    check_fp(T, torch, p, tuning=tmac_tuning(ks, nt))
 
 
 @pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 9])
-def test_small_batches(T, torch, N):
+def test_small_batches(T, torch, N, layout):
     p = wl.make_grouped(0, 70 + N, N, 64, 512, 3, 128, name=f"batch_{N}")
-    check_fp(T, torch, p)
+    check_fp(T, torch, p, layout=layout)
 
 
-def test_single_row_and_single_tile(T, torch):
-    check_fp(T, torch, wl.make_grouped(0, 80, 1, 1, 128, 4, 128, name="m1"))
-    check_fp(T, torch, wl.make_grouped(0, 81, 1, 16, 4096, 2, 128, name="one_tile_longk"))
+def test_single_row_and_single_tile(T, torch, layout):
+    check_fp(T, torch, wl.make_grouped(0, 80, 1, 1, 128, 4, 128, name="m1"), layout=layout)
+    check_fp(T, torch, wl.make_grouped(0, 81, 1, 16, 4096, 2, 128, name="one_tile_longk"), layout=layout)
 
 
-def test_fp16_output_is_rounded_fp32(T, torch):
+def test_long_k_multi_pass(T, torch):
+    """K beyond 16 waves x 64 units x 16: the register-table kernel walks several blocks per wave;
+    K beyond the LDS capacity of the full-K kernel falls back to the K-sliced kernel."""
+    p = wl.make_grouped(0, 85, 1, 24, 20480, 4, 128, name="k20480")
+    check_fp(T, torch, p, layout=L2)
+    check_fp(T, torch, wl.make_grouped(0, 86, 2, 24, 24576, 2, 0 + 256, name="k24576"), layout=L2)
+    check_fp(T, torch, wl.make_grouped(0, 86, 1, 24, 24576, 2, 256, name="k24576_lds"), layout=L1)
+
+
+def test_fp16_output_is_rounded_fp32(T, torch, layout):
     p = wl.make_grouped(0, 82, 2, 48, 256, 4, 128, name="f16out")
-    f32 = run_fp(T, torch, p)
-    f16 = run_fp(T, torch, p, out_t=T.TMAC_OUT_F16)
+    f32 = run_fp(T, torch, p, layout=layout)
+    f16 = run_fp(T, torch, p, out_t=T.TMAC_OUT_F16, layout=layout)
     assert f16.dtype == np.float16
     assert np.array_equal(f16, f32.astype(np.float16))
 
 
-def test_results_are_reproducible(T, torch):
+def test_results_are_reproducible(T, torch, layout):
     p = wl.make_grouped(0, 83, 1, 512, 4096, 4, 128, name="repro")
-    a = run_fp(T, torch, p)
+    a = run_fp(T, torch, p, layout=layout)
     for _ in range(3):
-        assert np.array_equal(run_fp(T, torch, p).view(np.uint32), a.view(np.uint32))
+        assert np.array_equal(run_fp(T, torch, p, layout=layout).view(np.uint32), a.view(np.uint32))
 
 
-def test_closed_forms_on_device(T, torch):
+def test_closed_forms_on_device(T, torch, layout):
     """All-zero codes: R = -sum_G s z S; zero point at mid level and 1-bit: flipping all bits negates R."""
     rng = np.random.default_rng(84)
     M, K, G, b = 32, 256, 128, 4
@@ -149,22 +171,29 @@ def test_closed_forms_on_device(T, torch):
     expect = -np.einsum("ng,mg->nm", S, s.astype(np.float64) * z.astype(np.float64))
     # the look-up term and the bias term cancel to first order here, which amplifies the fp16
     # rounding of the table entries: a few 1e-4 is expected
-    assert orc.rel_frobenius(run_fp(T, torch, p), expect) < 1e-3
+    assert orc.rel_frobenius(run_fp(T, torch, p, layout=layout), expect) < 1e-3
     q = wl.uniform_codes(rng, M, K, 1)
     half = np.full((M, K // G), 0.5, np.float16)
     p1 = wl.Problem("sign", 0, 1, M, K, 1, G, q, s, half, act=a)
     p2 = wl.Problem("sign_flipped", 0, 1, M, K, 1, G, 1 - q, s, half, act=a)
-    assert np.array_equal(run_fp(T, torch, p1), -run_fp(T, torch, p2))
+    assert np.array_equal(run_fp(T, torch, p1, layout=layout), -run_fp(T, torch, p2, layout=layout))
+
+
+def test_small_magnitude_activations(T, torch, layout):
+    """Activations of magnitude 1e-2: table entries stay normal fp16 numbers; the error bar holds."""
+    p = wl.make_grouped(0, 87, 1, 64, 1024, 4, 128, name="small_act")
+    p.act = (p.act.astype(np.float32) * np.float32(1e-2)).astype(np.float16)
+    check_fp(T, torch, p, layout=layout)
 
 
 # ------------------------------------------------------------ integer path ----
 
 @pytest.mark.parametrize("M,K,N", [(48, 256, 1), (100, 192, 3), (16, 8640, 1), (130, 3200, 5)])
-def test_ternary_int_path_bit_exact_small(T, torch, M, K, N):
-    check_int(T, torch, wl.make_ternary(0, M + K + N, N, M, K))
+def test_ternary_int_path_bit_exact_small(T, torch, M, K, N, layout):
+    check_int(T, torch, wl.make_ternary(0, M + K + N, N, M, K), layout=layout)
 
 
-def test_int_path_extreme_values(T, torch):
+def test_int_path_extreme_values(T, torch, layout):
     """Largest table entries (+-508) and code 3 (= +2): still exact."""
     M, K = 32, 512
     q = np.full((M, K), 3, np.uint8)
@@ -173,7 +202,24 @@ def test_int_path_extreme_values(T, torch):
     a_q[1] = -127
     p = wl.Problem("extreme", 0, 2, M, K, 2, 0, q, None, None, weight_scale=0.5, zero_point=1.0,
                    act_q=a_q, act_scale=np.array([0.25, 2.0], np.float32))
-    check_int(T, torch, p)
+    check_int(T, torch, p, layout=layout)
+
+
+def test_int_path_extreme_values_four_bit_long_k(T, torch):
+    """4-bit codes against +-127 activations over K = 16384: the register-table kernel carries
+    integer sums in fp32 inside a wave (below 2^24) and in int32 across waves."""
+    M, K = 16, 16384
+    rng = np.random.default_rng(88)
+    q = rng.integers(0, 16, size=(M, K), dtype=np.uint8)
+    q[0] = 15
+    q[1] = 0
+    a_q = np.full((1, K), 127, np.int8)
+    p = wl.Problem("extreme4", 0, 1, M, K, 4, 0, q, None, None, weight_scale=1.0, zero_point=0.0,
+                   act_q=a_q, act_scale=np.array([1.0], np.float32))
+    ref = orc.ternary_int_matmul(a_q, q, 0)
+    for layout in (L1, L2):
+        got = run_int(T, torch, p, T.TMAC_OUT_I32, layout=layout)
+        assert np.array_equal(got.astype(np.int64), ref), layout
 
 
 @pytest.mark.parametrize("ks", [2, 8])
@@ -182,8 +228,8 @@ def test_int_path_launch_shapes(T, torch, ks):
     check_int(T, torch, wl.make_ternary(0, 90 + ks, 2, 144, 1664), tuning=tmac_tuning(ks, 1))
 
 
-def test_int_tables_with_group_scales(T, torch):
-    """int8 activations against group-quantised 4-bit weights (W4A8): exact int32 group sums,
+def test_int_tables_with_group_scales(T, torch, layout):
+    """int8 activations against group-quantised 4-bit weights (W4A8): exact integer group sums,
     fp32 scale application; compared with the fp64 product of the de-quantised operands."""
     rng = np.random.default_rng(95)
     N, M, K, G, b = 2, 64, 512, 128, 4
@@ -191,7 +237,7 @@ def test_int_tables_with_group_scales(T, torch):
     q = wl.uniform_codes(rng, M, K, b)
     s, z = wl.group_scales(rng, M, K // G), wl.group_zeros(rng, M, K // G, b)
     p = wl.Problem("w4a8", 0, N, M, K, b, G, q, s, z, act_q=a_q, act_scale=s_a)
-    got = run_int(T, torch, p, T.TMAC_OUT_F32)
+    got = run_int(T, torch, p, T.TMAC_OUT_F32, layout=layout)
     ref = orc.mpgemm_definition(a_q.astype(np.float64) * s_a[:, None].astype(np.float64), q, s, z, G)
     assert orc.rel_frobenius(got, ref) < 1e-5
 
@@ -199,32 +245,32 @@ def test_int_tables_with_group_scales(T, torch):
 # ------------------------------------------- full-size configurations ----
 
 @pytest.mark.parametrize("i", [0, 1, 2])
-def test_config2_llama7b_w4(T, torch, i):
-    err = check_fp(T, torch, wl.config2(i))
+def test_config2_llama7b_w4(T, torch, i, layout):
+    err = check_fp(T, torch, wl.config2(i), layout=layout)
     assert err < 1e-3
 
 
 @pytest.mark.parametrize("bits", [1, 2, 3, 4])
-def test_config3_bit_sweep(T, torch, bits):
-    check_fp(T, torch, wl.config3(bits))
+def test_config3_bit_sweep(T, torch, bits, layout):
+    check_fp(T, torch, wl.config3(bits), layout=layout)
 
 
 @pytest.mark.parametrize("i", [0, 1, 2])
-def test_config4_bitnet_ternary(T, torch, i):
-    check_int(T, torch, wl.config4(i))
+def test_config4_bitnet_ternary(T, torch, i, layout):
+    check_int(T, torch, wl.config4(i), layout=layout)
 
 
 @pytest.mark.parametrize("bits", [2, 4])
 @pytest.mark.parametrize("i", [0, 1, 2])
 def test_config5_llama13b_prefill(T, torch, i, bits):
-    check_fp(T, torch, wl.config5(i, bits))
+    check_fp(T, torch, wl.config5(i, bits), layout=L1)
 
 
-# ------------------------------------------------ both lookup kernels ----
+# ------------------------------------------------ both LDS lookup kernels ----
 
 @pytest.mark.parametrize("kernel", [1, 2])
 @pytest.mark.parametrize("bits,group,K", [(4, 128, 1408), (2, 256, 1024), (3, 0, 640), (1, 896, 896)])
-def test_both_kernels_fp(T, torch, kernel, bits, group, K):
+def test_both_lds_kernels_fp(T, torch, kernel, bits, group, K):
     """kernel 1 = K-sliced with split-K reduction, kernel 2 = full-K decode kernel
     (K = 1408 gives 11 chunks: a ragged last batch for the 8 waves)."""
     from paper_2407_00088_amd.binding import tmac_tuning
@@ -239,7 +285,7 @@ def test_both_kernels_fp(T, torch, kernel, bits, group, K):
 
 
 @pytest.mark.parametrize("kernel", [1, 2])
-def test_both_kernels_int(T, torch, kernel):
+def test_both_lds_kernels_int(T, torch, kernel):
     from paper_2407_00088_amd.binding import tmac_tuning
     check_int(T, torch, wl.make_ternary(0, 320 + kernel, 3, 200, 2240), tuning=tmac_tuning(0, 0, kernel))
 
