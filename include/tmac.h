@@ -97,8 +97,9 @@ typedef struct {
  *   indices  per tile t (rows 8t..8t+7) the records of its n_units units, 4*bits dwords each:
  *            record[tb][d], unit u = k in [16u, 16u+16), table tb = LUT group kg = 4u + tb.
  *            One lane of the kernel owns one unit (four tables held in registers).  The units
- *            are split into nB = ceil(n_units/64) blocks, block j = units [floor(j*n_units/nB),
- *            floor((j+1)*n_units/nB)), one block per wavefront pass.  Inside a block of nu units
+ *            are split into nB = ceil(n_units/64) consecutive blocks, the first n_units % nB of
+ *            them with floor(n_units/nB) + 1 units, the others with floor(n_units/nB); one
+ *            block per wavefront pass.  Inside a block of nu units starting at unit u0
  *            the records are stored piece-major: the 16-byte piece i (dwords 4i..4i+3 of the
  *            flattened record) of the block's l-th unit sits at dword offset
  *            (t*n_units + u0)*4*bits + (i*nu + l)*4, so that each of the `bits` load
@@ -192,9 +193,11 @@ tmac_status tmac_mpgemm(const tmac_wdesc* desc, const void* packed_dev, const vo
  *                    in LDS, one 16-row tile per workgroup; needs K <= 20416 and a group size
  *                    that is 0, K or a multiple of 128; TMAC_EUNSUPPORTED otherwise)
  *   chunks_per_wave  K-sliced kernel: 128-k chunks one wavefront covers: 2, 4 or 8
- *   n_tile           K-sliced kernel: activation rows handled per workgroup pass: 1 or 4 */
+ *   n_tile           K-sliced kernel: activation rows handled per workgroup pass: 1 or 4
+ *   rows_per_group   register-table kernel (layout 2, which takes none of the knobs above):
+ *                    weight rows per workgroup, 8 or 16 */
 typedef struct {
-  int32_t chunks_per_wave, n_tile, kernel, reserved[5];
+  int32_t chunks_per_wave, n_tile, kernel, rows_per_group, reserved[4];
 } tmac_tuning;
 
 /* Same as tmac_mpgemm with explicit launch-shape knobs (NULL = defaults). */

@@ -39,7 +39,7 @@ class tmac_wdesc(C.Structure):
 
 class tmac_tuning(C.Structure):
     _fields_ = [("chunks_per_wave", C.c_int32), ("n_tile", C.c_int32), ("kernel", C.c_int32),
-                ("reserved", C.c_int32 * 5)]
+                ("rows_per_group", C.c_int32), ("reserved", C.c_int32 * 4)]
 
 
 class TmacError(RuntimeError):

@@ -51,15 +51,40 @@ inline bool lut_geom(int N, int K, int g, int group, LutGeom* lg) {
   lg->s_off = (tab + 255) / 256 * 256;
   lg->s16_off = (lg->s_off + (size_t)N * lg->nq * 4 + 255) / 256 * 256;
   lg->ht_off = (lg->s16_off + (size_t)N * lg->U * 4 + 255) / 256 * 256;
-  lg->total = (lg->ht_off + (size_t)N * lg->U * 64 + 255) / 256 * 256;
+  // one extra all-zero 16-byte slot (in a 256-byte tail) for lanes that own no unit
+  lg->total = (lg->ht_off + (size_t)N * lg->U * 64 + 256 + 255) / 256 * 256;
   return true;
+}
+
+// Split of the U 16-k units of a row into nB = ceil(U/64) blocks of at most 64 units (one block
+// per wavefront pass of the register-table kernel): the first r blocks have q+1 units, the
+// others q.  Shared by the packer, the precompute kernel and the lookup kernel.
+#if defined(__HIPCC__)
+#define TMAC_HD __host__ __device__
+#else
+#define TMAC_HD
+#endif
+struct BlockSplit {
+  int nB, q, r;
+};
+TMAC_HD inline BlockSplit block_split(int U) {
+  BlockSplit b;
+  b.nB = (U + 63) / 64;
+  b.q = U / b.nB;
+  b.r = U % b.nB;
+  return b;
+}
+TMAC_HD inline int block_start(const BlockSplit& b, int blk) { return blk * b.q + (blk < b.r ? blk : b.r); }
+TMAC_HD inline int block_of(const BlockSplit& b, int u) {
+  const int big = b.r * (b.q + 1);
+  return u < big ? u / (b.q + 1) : b.r + (u - big) / b.q;
 }
 
 // Register-table decode kernel (layout 2); defined in tmac_perm.hip.  Arguments are those of
 // tmac_mpgemm after validation; returns a tmac_status value.
 int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, int lut_is_int,
                      int N, const float* act_scale_dev, float weight_scale, void* out_dev, int out_t,
-                     int64_t ldo, void* stream);
+                     int64_t ldo, void* stream, int rows_per_group);
 
 // Records the last HIP error of this thread (diagnostics for TMAC_EHIP).
 void note_hip_error(int hip_error);

@@ -113,13 +113,18 @@ __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict_
       } else {
         half = make_uint4(packed[0], packed[1], packed[2], packed[3]);
       }
+      // split into the two 8-byte byte-permute sources (Section 4: an fp16 table as two 8-bit
+      // tables): low bytes of entries 0..3, 4..7, then high bytes of entries 0..3, 4..7
+      const uint4 split = make_uint4(__builtin_amdgcn_perm(half.y, half.x, 0x06040200u),
+                                     __builtin_amdgcn_perm(half.w, half.z, 0x06040200u),
+                                     __builtin_amdgcn_perm(half.y, half.x, 0x07050301u),
+                                     __builtin_amdgcn_perm(half.w, half.z, 0x07050301u));
       const int u = kg >> 2, tb = kg & 3;
-      const int nB = (U + 63) >> 6;
-      int blk = (int)(((int64_t)u * nB) / U);
-      while ((int)(((int64_t)(blk + 1) * U) / nB) <= u) ++blk;
-      while ((int)(((int64_t)blk * U) / nB) > u) --blk;
-      const int u0 = (int)(((int64_t)blk * U) / nB), u1 = (int)(((int64_t)(blk + 1) * U) / nB);
-      HT[((size_t)n * U + u0) * 4 + (size_t)tb * (u1 - u0) + (u - u0)] = half;
+      const BlockSplit bs = block_split(U);
+      const int blk = block_of(bs, u);
+      const int u0 = block_start(bs, blk), nu = block_start(bs, blk + 1) - u0;
+      HT[((size_t)n * U + u0) * 4 + (size_t)tb * nu + (u - u0)] = split;
+      if (tid == 0) HT[(size_t)N * U * 4] = make_uint4(0, 0, 0, 0);  // the all-zero slot
     }
     // unit sums S16[n][kg / 4]: the four tables of a unit sit in four adjacent lanes
     if constexpr (IS_INT) {
@@ -812,12 +817,14 @@ extern "C" tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed
   const bool is_int = (lut == TMAC_LUT_I16);
   const bool one_group = (desc->group == 0 || desc->group == desc->K);
   if (desc->layout == TMAC_LAYOUT_R8U16) {
-    // register-table decode kernel; it needs no workspace and has no launch-shape knobs
+    // register-table decode kernel; it needs no workspace and takes none of the LDS kernels' knobs
     if (tuning && (tuning->kernel != 0 || tuning->chunks_per_wave != 0 || tuning->n_tile != 0))
       return TMAC_EUNSUPPORTED;
+    const int rpg = tuning ? tuning->rows_per_group : 0;
+    if (rpg != 0 && rpg != 8 && rpg != 16) return TMAC_EINVAL;
     return static_cast<tmac_status>(launch_perm_gemv(desc, packed_dev, lut_dev, is_int ? 1 : 0, N,
                                                       act_scale_dev, weight_scale, out_dev, (int)out, ldo,
-                                                      stream));
+                                                      stream, rpg));
   }
   // int32 accumulators: |L| <= 508 * (2^b - 1) * K/4 must stay below 2^31
   if (is_int && (double)508.0 * ((1 << desc->bits) - 1) * (desc->K / 4) >= 2147483647.0) return TMAC_EUNSUPPORTED;

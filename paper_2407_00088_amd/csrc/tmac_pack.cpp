@@ -109,10 +109,11 @@ static void pack_indices_layout2(const tmac_wdesc* d, const Geometry& ge, const 
     if (m >= M) return 0;
     return mirror_fold(index_of(q + (size_t)m * K, K, kg, plane));
   };
-  const int U = ge.n_chunks, nB = (U + 63) / 64;
+  const int U = ge.n_chunks;
+  const BlockSplit bs = block_split(U);
   for (int t = 0; t < ge.n_tiles; ++t)
-    for (int blk = 0; blk < nB; ++blk) {
-     const int u0 = (int)(((int64_t)blk * U) / nB), u1 = (int)(((int64_t)(blk + 1) * U) / nB), nu = u1 - u0;
+    for (int blk = 0; blk < bs.nB; ++blk) {
+     const int u0 = block_start(bs, blk), u1 = block_start(bs, blk + 1), nu = u1 - u0;
      for (int u = u0; u < u1; ++u) {
       uint32_t rec[16];  // the unit's record: [table][dword]
       for (int tb = 0; tb < 4; ++tb) {

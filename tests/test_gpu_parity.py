@@ -296,3 +296,40 @@ def test_full_k_kernel_rejects_what_it_cannot_do(T, torch):
     with pytest.raises(T.TmacError) as ei:
         run_fp(T, torch, p, tuning=tmac_tuning(0, 0, 2))
     assert ei.value.status == T.TMAC_EUNSUPPORTED
+
+
+# ------------------------------------- register-table kernel launch shapes ----
+
+@pytest.mark.parametrize("rows", [8, 16])
+@pytest.mark.parametrize("bits,group,M,K", [(4, 128, 200, 1408), (2, 64, 72, 1024), (3, 0, 41, 640),
+                                            (1, 1040, 24, 1040), (4, 128, 8, 17408)])
+def test_register_kernel_rows_per_group(T, torch, rows, bits, group, M, K):
+    """8 or 16 weight rows per workgroup (an odd number of 8-row tiles leaves the second tile of
+    the last workgroup empty); K = 17408 walks two blocks of units per wave."""
+    from paper_2407_00088_amd.binding import tmac_tuning
+
+    def run(p, tun):
+        lin = make_lin(p, L2)
+        out = lin.forward(torch.from_numpy(p.act).cuda(), tuning=tun)
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+
+    N = 2
+    if group == 0:
+        rng = np.random.default_rng(400 + bits)
+        p = wl.Problem("rpg_pt", 0, N, M, K, bits, 0, wl.uniform_codes(rng, M, K, bits), None, None,
+                       weight_scale=0.05, zero_point=2.0, act=wl.gaussian_act(rng, N, K))
+    else:
+        p = wl.make_grouped(0, 410 + bits, N, M, K, bits, group, name=f"rpg{rows}_w{bits}")
+    got = run(p, tmac_tuning(0, 0, 0, rows))
+    err = orc.rel_frobenius(got, oracle_fp(p))
+    assert err <= FP_TOL, err
+    # both launch shapes add the same terms in the same order
+    other = run(p, tmac_tuning(0, 0, 0, 24 - rows))
+    assert np.array_equal(got.view(np.uint32), other.view(np.uint32))
+
+
+@pytest.mark.parametrize("rows", [8, 16])
+def test_register_kernel_rows_per_group_int(T, torch, rows):
+    from paper_2407_00088_amd.binding import tmac_tuning
+    check_int(T, torch, wl.make_ternary(0, 420 + rows, 3, 200, 2240), tuning=tmac_tuning(0, 0, 0, rows), layout=L2)

@@ -37,9 +37,11 @@ def unpack_layout2(blob: np.ndarray):
     # of the record of unit u0 + lane
     rec = np.zeros((n_tiles, n_units, 4 * bits), dtype=np.uint32)
     nB = (n_units + 63) // 64
+    qq, rr = divmod(n_units, nB)
     for blk in range(nB):
-        u0, u1 = blk * n_units // nB, (blk + 1) * n_units // nB
-        nu = u1 - u0
+        u0 = blk * qq + min(blk, rr)
+        nu = qq + 1 if blk < rr else qq
+        u1 = u0 + nu
         span = flat[:, u0 * 4 * bits: u1 * 4 * bits].reshape(n_tiles, bits, nu, 4)
         rec[:, u0:u1, :] = span.transpose(0, 2, 1, 3).reshape(n_tiles, nu, 4 * bits)
     idx = rec.reshape(n_tiles, n_units, 4, bits)
@@ -142,7 +144,7 @@ def test_layout2_sizes_and_group_rules():
     assert T.tmac_packed_bytes(d) == 256 + 4096 * 4096 // 2 + 4096 * 32 * 4
     assert T.tmac_workspace_bytes(d, 1) == 256
     # LUT buffer: tables, group sums, per-16 sums
-    assert T.tmac_lut_bytes(1, 4096, 128, B.TMAC_LUT_F16) == 4096 * 8 + 256 + 1024 + 4096 * 4
+    assert T.tmac_lut_bytes(1, 4096, 128, B.TMAC_LUT_F16) == 4096 * 8 + 256 + 1024 + 4096 * 4 + 256
     import ctypes as C
     fake = C.c_void_p(0x1000)
     g24 = desc2(16, 192, 2, 24)      # valid (24 % 4 == 0) but not a multiple of 16
