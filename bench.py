@@ -45,8 +45,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--ring-mb", type=int, default=RING_MB)
-    ap.add_argument("--kernel", type=int, default=0, help="tmac_tuning.kernel override (0 = default)")
-    ap.add_argument("--ks", type=int, default=0, help="tmac_tuning.chunks_per_wave override")
+    ap.add_argument("--layout", type=int, default=2, help="packed layout: 2 = register-table kernel, 1 = LDS kernels")
+    ap.add_argument("--rows", type=int, default=0, help="layout 2: tmac_tuning.rows_per_group override (8 or 16)")
+    ap.add_argument("--kernel", type=int, default=0, help="layout 1: tmac_tuning.kernel override (0 = default)")
+    ap.add_argument("--ks", type=int, default=0, help="layout 1: tmac_tuning.chunks_per_wave override")
     ap.add_argument("--sweep", action="store_true", help="also time the W1..W4 and BitNet shapes")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead of graph replay")
     args = ap.parse_args()
@@ -66,13 +68,18 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda"
-    tuning = tmac_tuning(args.ks, 0, args.kernel) if (args.ks or args.kernel) else None
+    tuning = None
+    if args.layout == 1 and (args.ks or args.kernel):
+        tuning = tmac_tuning(args.ks, 0, args.kernel)
+    elif args.layout == 2 and args.rows:
+        tuning = tmac_tuning(0, 0, 0, args.rows)
     stream = torch.cuda.Stream()
+    sink = torch.zeros(256, dtype=torch.uint8, device=dev)
 
     class Case:
         def __init__(self, p):
             self.p = p
-            self.lin = from_problem(p)
+            self.lin = from_problem(p, layout=args.layout)
             self.bytes = algorithmic_bytes(p.M, p.K, p.bits, p.group, p.N, act_bytes=1 if p.int_path else 2)
             n_copies = max(2, (args.ring_mb << 20) // self.lin.packed_bytes + 1)
             self.ring = [self.lin.packed] + [self.lin.packed.clone() for _ in range(n_copies - 1)]
@@ -88,6 +95,12 @@ def main():
             packed = self.ring[self.i % len(self.ring)]
             self.i += 1
             self.lin.mpgemm(self.p.N, self.out, T.TMAC_OUT_F32, act_scale=self.s_a, tuning=tuning, packed=packed)
+
+        def stream_read(self):
+            """Plain read of the same packed bytes: what a read-only kernel reaches on this ring."""
+            packed = self.ring[self.i % len(self.ring)]
+            self.i += 1
+            T.tmac_stream_read(packed, sink, 1, True)
 
     class Replay:
         """`body` issued `reps` times per launch, either eagerly or as one captured HIP graph."""
@@ -127,10 +140,10 @@ def main():
     def ring_len(c):
         return len(c.ring)
 
-    def measure_kernel(c, total):
+    def measure_kernel(c, total, body=None):
         reps = ring_len(c)
         launches = max(1, total // reps)
-        return timed(Replay(c.mpgemm, reps), launches, max(1, launches // 10))
+        return timed(Replay(body or c.mpgemm, reps), launches, max(1, launches // 10))
 
     cases = [Case(wl.config2(i)) for i in range(3)]
     step_bytes = sum(c.bytes for c in cases)
@@ -151,12 +164,14 @@ def main():
     per_us = [measure_kernel(c, args.steps) for c in cases]
     achieved = sum(c.bytes for c in cases) / (sum(per_us) * 1e-6) / 1e9
     pre_us = [timed(Replay(c.precompute, 50), max(1, args.steps // 50), 2) for c in cases]
+    read_us = [measure_kernel(c, args.steps, c.stream_read) for c in cases]
     detail = {"shapes": []}
-    for c, us, pu in zip(cases, per_us, pre_us):
+    for c, us, pu, ru in zip(cases, per_us, pre_us, read_us):
         detail["shapes"].append({"M": c.p.M, "K": c.p.K, "bits": c.p.bits, "mpgemm_us": round(us, 3),
                                  "precompute_us": round(pu, 3), "bytes": c.bytes,
                                  "GBps": round(c.bytes / us / 1e3, 1),
-                                 "frac_hbm_peak": round(c.bytes / us / 1e3 / HBM_PEAK_GBPS, 4)})
+                                 "frac_hbm_peak": round(c.bytes / us / 1e3 / HBM_PEAK_GBPS, 4),
+                                 "plain_read_of_same_bytes_us": round(ru, 3)})
 
     if args.sweep:
         sweep = []
@@ -222,7 +237,8 @@ def main():
                    "frac_hbm_peak_whole_step": round(value / HBM_PEAK_GBPS, 4)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                     "kernel": "mpgemv_fullk_kernel<f16 tables, 4 bit, group scales>",
+                     "kernel": ("mpgemv_perm_kernel<f16 tables, 4 bit, group scales>" if args.layout == 2
+                                else "mpgemv_fullk_kernel<f16 tables, 4 bit, group scales>"),
                      "launch_us": [round(u, 3) for u in per_us]},
         "cpu_baseline": cpu,
         "detail": detail,
