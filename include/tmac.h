@@ -96,14 +96,17 @@ typedef struct {
  *   header   as layout 1 (Mp = M rounded up to 8, n_tiles = Mp/8, n_chunks = Kp/16 units)
  *   indices  per tile t (rows 8t..8t+7) the records of its n_units units, 4*bits dwords each:
  *            record[tb][d], unit u = k in [16u, 16u+16), table tb = LUT group kg = 4u + tb.
- *            One lane of the kernel owns one unit (four tables held in registers).  The units
- *            are split into nB = ceil(n_units/64) consecutive blocks, the first n_units % nB of
- *            them with floor(n_units/nB) + 1 units, the others with floor(n_units/nB); one
- *            block per wavefront pass.  Inside a block of nu units starting at unit u0
- *            the records are stored piece-major: the 16-byte piece i (dwords 4i..4i+3 of the
- *            flattened record) of the block's l-th unit sits at dword offset
- *            (t*n_units + u0)*4*bits + (i*nu + l)*4, so that each of the `bits` load
- *            instructions of a wavefront reads one contiguous run.
+ *            One lane of the kernel owns one unit (four tables held in registers).  Eight
+ *            consecutive units form a chunk of 128 k; the n_units/8 chunks of a row are split
+ *            into nB = ceil(chunks/8) consecutive blocks, the first chunks % nB of them with
+ *            floor(chunks/nB) + 1 chunks, the others with floor(chunks/nB); one block per
+ *            wavefront pass.  Inside a block of ng chunks starting at chunk c0, unit
+ *            8*(c0 + j) + pos (j < ng, pos < 8) belongs to lane 8*pos + j and sits in slot
+ *            s = pos*ng + j; the records are stored piece-major: the 16-byte piece i (dwords
+ *            4i..4i+3 of the flattened record) of slot s sits at dword offset
+ *            (t*n_units + 8*c0)*4*bits + (i*8*ng + s)*4, so that each of the `bits` load
+ *            instructions of a wavefront reads one contiguous run, and the eight lanes that
+ *            share (lane & 7) cover one chunk.
  *            Stored 4-bit code of an index p:  p < 8 ? p : 8 | (15 - p)   (bit 3 = negate,
  *            bits 0..2 = entry of the stored half table, because T[p] = -T[15-p]).
  *            Byte y of a dword holds two codes of the same table, the low nibble for the
@@ -152,7 +155,9 @@ tmac_status tmac_pack_weights(const tmac_wdesc* desc, const uint8_t* q_host,
 /* Bytes of the LUT buffer for N activation rows: tables [N][Kp/4][16] (2 bytes each, k
  * padded to 128 with all-zero tables), then the group sums S[N][n_qgroups], then the sums
  * of every 16 consecutive activations S16[N][Kp/16] (both fp32 for TMAC_LUT_F16, int32 for
- * TMAC_LUT_I16), each region 256-byte aligned.  0 on bad arguments. */
+ * TMAC_LUT_I16), the sums of every 128 consecutive activations S128[N][Kp/128] (same type) and
+ * the mirror-consolidated byte-split half tables of the register-table kernel, each region
+ * 256-byte aligned.  0 on bad arguments. */
 size_t tmac_lut_bytes(int32_t N, int32_t K, int32_t g, int32_t group, tmac_lut_t lut);
 
 /* Online table precompute (Algorithm 1 Precompute; Section 3.1; mirror consolidation of

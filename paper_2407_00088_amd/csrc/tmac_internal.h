@@ -35,6 +35,7 @@ struct LutGeom {
   int U;                // 16-k units per row (Kp / 16)
   size_t s_off;         // byte offset of the group sums S[N][nq]
   size_t s16_off;       // byte offset of the unit sums S16[N][U]
+  size_t s128_off;      // byte offset of the 128-k chunk sums S128[N][U/8]
   size_t ht_off;        // byte offset of the fp16 half tables HT[N][U][4][8], piece-major per block
   size_t total;
 };
@@ -50,15 +51,20 @@ inline bool lut_geom(int N, int K, int g, int group, LutGeom* lg) {
   const size_t tab = (size_t)N * lg->KG * 16 * 2;
   lg->s_off = (tab + 255) / 256 * 256;
   lg->s16_off = (lg->s_off + (size_t)N * lg->nq * 4 + 255) / 256 * 256;
-  lg->ht_off = (lg->s16_off + (size_t)N * lg->U * 4 + 255) / 256 * 256;
+  lg->s128_off = (lg->s16_off + (size_t)N * lg->U * 4 + 255) / 256 * 256;
+  lg->ht_off = (lg->s128_off + (size_t)N * (lg->U / 8) * 4 + 255) / 256 * 256;
   // one extra all-zero 16-byte slot (in a 256-byte tail) for lanes that own no unit
   lg->total = (lg->ht_off + (size_t)N * lg->U * 64 + 256 + 255) / 256 * 256;
   return true;
 }
 
-// Split of the U 16-k units of a row into nB = ceil(U/64) blocks of at most 64 units (one block
-// per wavefront pass of the register-table kernel): the first r blocks have q+1 units, the
-// others q.  Shared by the packer, the precompute kernel and the lookup kernel.
+// Split of a row's C = U/8 chunks (128 k = 8 units of 16 k each) into nB = ceil(C/8) blocks of at
+// most 8 chunks, one block per wavefront pass of the register-table kernel: the first r blocks
+// have q+1 chunks, the others q.  Inside a block of ng chunks starting at chunk c0, lane l of the
+// wavefront owns unit 8*(c0 + (l & 7)) + (l >> 3), i.e. the eight lanes with equal l & 7 cover
+// one 128-k chunk; lanes with (l & 7) >= ng own nothing.  The lane's data sits at slot
+// (l >> 3) * ng + (l & 7) of the block.  Shared by the packer, the precompute kernel and the
+// lookup kernel.
 #if defined(__HIPCC__)
 #define TMAC_HD __host__ __device__
 #else
@@ -68,17 +74,22 @@ struct BlockSplit {
   int nB, q, r;
 };
 TMAC_HD inline BlockSplit block_split(int U) {
+  const int C = U / 8;
   BlockSplit b;
-  b.nB = (U + 63) / 64;
-  b.q = U / b.nB;
-  b.r = U % b.nB;
+  b.nB = (C + 7) / 8;
+  b.q = C / b.nB;
+  b.r = C % b.nB;
   return b;
 }
+// first chunk of block blk
 TMAC_HD inline int block_start(const BlockSplit& b, int blk) { return blk * b.q + (blk < b.r ? blk : b.r); }
-TMAC_HD inline int block_of(const BlockSplit& b, int u) {
+// block that holds chunk c
+TMAC_HD inline int block_of(const BlockSplit& b, int c) {
   const int big = b.r * (b.q + 1);
-  return u < big ? u / (b.q + 1) : b.r + (u - big) / b.q;
+  return c < big ? c / (b.q + 1) : b.r + (c - big) / b.q;
 }
+// slot of unit u inside its block (c0 = first chunk, ng = chunks of the block)
+TMAC_HD inline int block_slot(int u, int c0, int ng) { return (u & 7) * ng + ((u >> 3) - c0); }
 
 // Register-table decode kernel (layout 2); defined in tmac_perm.hip.  Arguments are those of
 // tmac_mpgemm after validation; returns a tmac_status value.

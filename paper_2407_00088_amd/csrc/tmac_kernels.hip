@@ -51,6 +51,7 @@ __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict_
                                                          int64_t lda, int KG,
                                                          uint4* __restrict__ tables,
                                                          void* __restrict__ S_, void* __restrict__ S16_,
+                                                         void* __restrict__ S128_,
                                                          uint4* __restrict__ HT, int U, int Geff, int nq,
                                                          int n_tab_blocks) {
   if ((int)blockIdx.x < n_tab_blocks) {
@@ -98,7 +99,7 @@ __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict_
     dst[1] = make_uint4(packed[4], packed[5], packed[6], packed[7]);
     // Mirror-consolidated copy for the register-table kernel: entries 0..7 as fp16 (int16 entries
     // are at most 508 in magnitude, exact in fp16).  Units are grouped in nB blocks; inside a block
-    // of nu units, table tb of the block's l-th unit sits at 16-byte slot tb*nu + l, so that 64
+    // of nu units, table tb of the unit in slot s sits at 16-byte slot tb*nu + s, so that the
     // lanes loading "their" table tb read one contiguous run.
     {
       uint4 half;
@@ -121,20 +122,30 @@ __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict_
                                      __builtin_amdgcn_perm(half.w, half.z, 0x07050301u));
       const int u = kg >> 2, tb = kg & 3;
       const BlockSplit bs = block_split(U);
-      const int blk = block_of(bs, u);
-      const int u0 = block_start(bs, blk), nu = block_start(bs, blk + 1) - u0;
-      HT[((size_t)n * U + u0) * 4 + (size_t)tb * nu + (u - u0)] = split;
+      const int blk = block_of(bs, u >> 3);
+      const int c0 = block_start(bs, blk), ng = block_start(bs, blk + 1) - c0;
+      HT[((size_t)n * U + 8 * c0) * 4 + (size_t)tb * (8 * ng) + block_slot(u, c0, ng)] = split;
       if (tid == 0) HT[(size_t)N * U * 4] = make_uint4(0, 0, 0, 0);  // the all-zero slot
     }
-    // unit sums S16[n][kg / 4]: the four tables of a unit sit in four adjacent lanes
+    // unit sums S16[n][kg / 4] and chunk sums S128[n][kg / 32]: the tables of a unit sit in four
+    // adjacent lanes, those of a 128-k chunk in 32 adjacent lanes (KG is a multiple of 32 and the
+    // workgroup size a multiple of 64, so a chunk never straddles a wavefront); fixed tree order
     if constexpr (IS_INT) {
       sum4i += __shfl_xor(sum4i, 1);
       sum4i += __shfl_xor(sum4i, 2);
       if ((kg & 3) == 0) static_cast<int*>(S16_)[tid >> 2] = sum4i;
+      sum4i += __shfl_xor(sum4i, 4);
+      sum4i += __shfl_xor(sum4i, 8);
+      sum4i += __shfl_xor(sum4i, 16);
+      if ((kg & 31) == 0) static_cast<int*>(S128_)[tid >> 5] = sum4i;
     } else {
       sum4f += __shfl_xor(sum4f, 1);
       sum4f += __shfl_xor(sum4f, 2);
       if ((kg & 3) == 0) static_cast<float*>(S16_)[tid >> 2] = sum4f;
+      sum4f += __shfl_xor(sum4f, 4);
+      sum4f += __shfl_xor(sum4f, 8);
+      sum4f += __shfl_xor(sum4f, 16);
+      if ((kg & 31) == 0) static_cast<float*>(S128_)[tid >> 5] = sum4f;
     }
   } else {
     // one wavefront per (n, quantisation group): strided partial sums, then a butterfly
@@ -772,14 +783,15 @@ extern "C" tmac_status tmac_precompute_lut(const void* A_dev, tmac_act_t act, in
   uint4* tables = static_cast<uint4*>(lut_dev);
   void* S = static_cast<char*>(lut_dev) + lg.s_off;
   void* S16 = static_cast<char*>(lut_dev) + lg.s16_off;
+  void* S128 = static_cast<char*>(lut_dev) + lg.s128_off;
   uint4* HT = reinterpret_cast<uint4*>(static_cast<char*>(lut_dev) + lg.ht_off);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const dim3 grid(n_tab_blocks + n_sum_blocks), block(256);
   const hipError_t e =
       (act == TMAC_ACT_F16)
-          ? launch(precompute_kernel<false>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S, S16, HT,
+          ? launch(precompute_kernel<false>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S, S16, S128, HT,
                    lg.U, lg.Geff, lg.nq, n_tab_blocks)
-          : launch(precompute_kernel<true>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S, S16, HT,
+          : launch(precompute_kernel<true>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S, S16, S128, HT,
                    lg.U, lg.Geff, lg.nq, n_tab_blocks);
   return e == hipSuccess ? TMAC_OK : TMAC_EHIP;
 }

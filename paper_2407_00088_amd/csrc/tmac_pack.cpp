@@ -113,7 +113,8 @@ static void pack_indices_layout2(const tmac_wdesc* d, const Geometry& ge, const 
   const BlockSplit bs = block_split(U);
   for (int t = 0; t < ge.n_tiles; ++t)
     for (int blk = 0; blk < bs.nB; ++blk) {
-     const int u0 = block_start(bs, blk), u1 = block_start(bs, blk + 1), nu = u1 - u0;
+     const int c0 = block_start(bs, blk), ng = block_start(bs, blk + 1) - c0;
+     const int u0 = 8 * c0, u1 = u0 + 8 * ng, nu = 8 * ng;
      for (int u = u0; u < u1; ++u) {
       uint32_t rec[16];  // the unit's record: [table][dword]
       for (int tb = 0; tb < 4; ++tb) {
@@ -143,11 +144,12 @@ static void pack_indices_layout2(const tmac_wdesc* d, const Geometry& ge, const 
         else if (b == 1) { dst[nd++] = single(0); }
         else { dst[nd++] = pair(0, 0); dst[nd++] = pair(1, 0); dst[nd++] = single(2); }
       }
-      // 16-byte piece i of the record goes to slot (i, lane) of the block, so that the 64 lanes
-      // of a wavefront read one contiguous run per load instruction
+      // 16-byte piece i of the record goes to (piece i, slot of the unit's lane) of the block, so
+      // that the lanes of a wavefront read one contiguous run per load instruction
       uint32_t* blk_base = idx + ((size_t)t * U + u0) * (4 * b);
+      const int slot = block_slot(u, c0, ng);
       for (int i = 0; i < b; ++i)
-        for (int e = 0; e < 4; ++e) blk_base[((size_t)i * nu + (u - u0)) * 4 + e] = rec[4 * i + e];
+        for (int e = 0; e < 4; ++e) blk_base[((size_t)i * nu + slot) * 4 + e] = rec[4 * i + e];
      }
     }
 }
@@ -221,4 +223,4 @@ extern "C" const char* tmac_status_str(tmac_status s) {
   return "unknown status";
 }
 
-extern "C" int32_t tmac_version(void) { return 1000 * 0 + 2; }
+extern "C" int32_t tmac_version(void) { return 1000 * 0 + 3; }

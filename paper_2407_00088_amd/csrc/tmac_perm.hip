@@ -22,11 +22,16 @@
 //     all partial sums are integers below 2^24 and therefore exact in fp32; sums across waves
 //     are taken in int32.
 //
-// Work split: one workgroup = RT tiles of 8 rows over the whole K; wave w owns a contiguous run
-// of 16-k units (one per lane), so each wave streams contiguous pieces of the tiles' packed
-// indices with 16-byte loads, all issued before the first lookup.  Cross-lane reduction of 8 row
-// sums is a transposing butterfly (v_permlane32_swap, v_permlane16_swap, DPP), cross-wave
-// reduction goes through LDS in wave order: the summation order is fixed.
+// Work split: one workgroup = RT tiles of 8 rows over the whole K; wave w owns one block of at
+// most 8 chunks of 128 k (one 16-k unit per lane), so each wave streams contiguous pieces of the
+// tiles' packed indices with 16-byte loads.  The eight lanes with equal (lane & 7) cover one
+// 128-k chunk.  When the quantisation group is a multiple of 128 the 8 row sums of a lane are
+// first reduced over those eight lanes with a transposing butterfly (v_permlane32_swap,
+// v_permlane16_swap, DPP), which leaves one (row, chunk) sum per lane; scale, zero and bias are
+// then applied once per (row, chunk) with a 4-byte scale/zero load per lane, and the chunks are
+// summed with three DPP steps.  Other group sizes (multiples of 16) scale per (row, lane) before
+// the same butterfly.  Cross-wave reduction goes through LDS and is finished by one wave with a
+// fixed summation tree: results do not depend on timing.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -47,12 +52,14 @@ struct PermParams {
   const pu32x4* ht;        // split fp16 half tables, [N][U][4] 16-byte slots, piece-major per block
   const void* S;           // [N][nq] fp32 / int32 group sums
   const void* S16;         // [N][U]  fp32 / int32 unit sums
+  const void* S128;        // [N][U/8] fp32 / int32 sums of every 128 consecutive activations
   void* out;
   const float* act_scale;
   int64_t ldo;
   int M, N, U, n_tiles, nq;
   int G, g_shift;  // elements per quantisation group; log2(G) if G is a power of two, else -1
-  BlockSplit bs;   // split of the U units into blocks of at most 64
+  int cpg;         // group mode 2: 128-k chunks per quantisation group
+  BlockSplit bs;   // split of the U/8 chunks into blocks of at most 8
   uint32_t ht_zero;  // slot index of the all-zero table
   int per_tensor, int_exact, icoef;
   float wscale, zero_point, mid;
@@ -72,12 +79,12 @@ __device__ __forceinline__ float dpp_add_t(float v) {
   return v + __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), CTRL, 0xf, 0xf, false));
 }
 
-// Sum 8 per-lane values over the 64 lanes with a transposing butterfly; afterwards every lane
-// holds the full sum of row (lane >> 3) & 7.
+// Sum 8 per-lane values over lane bits 5, 4, 3 with a transposing butterfly; afterwards every
+// lane holds row (lane >> 3), summed over the eight lanes with the same (lane & 7).
 //   v_permlane32_swap exchanges lanes 32..63 of its first operand with lanes 0..31 of the second,
 //   v_permlane16_swap does the same for the odd/even 16-lane rows; after each exchange the two
 //   operands hold, in every lane, two partial sums of the same row.
-__device__ __forceinline__ float butterfly8(const float (&t)[8], int lane) {
+__device__ __forceinline__ float reduce_hi3(const float* t, int lane) {
   float v4[4], v2[2];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -91,7 +98,11 @@ __device__ __forceinline__ float butterfly8(const float (&t)[8], int lane) {
   }
   const bool up = (lane & 8) != 0;
   const float keep = up ? v2[1] : v2[0], send = up ? v2[0] : v2[1];
-  float v = keep + __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(send), 0x128, 0xf, 0xf, false));  // row_ror:8
+  return keep + __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(send), 0x128, 0xf, 0xf, false));  // row_ror:8
+}
+
+// Sum over lane bits 0, 1, 2 (all lanes of a group of 8 end with the total).
+__device__ __forceinline__ float reduce_lo3(float v) {
   v = dpp_add_t<0xB1>(v);   // quad_perm [1,0,3,2]
   v = dpp_add_t<0x4E>(v);   // quad_perm [2,3,0,1]
   v = dpp_add_t<0x141>(v);  // row_half_mirror
@@ -102,6 +113,9 @@ __device__ __forceinline__ float butterfly8(const float (&t)[8], int lane) {
 constexpr uint32_t h2pack(uint16_t lo, uint16_t hi) { return (uint32_t)lo | ((uint32_t)hi << 16); }
 constexpr uint16_t H_0 = 0x0000, H_05 = 0x3800, H_1 = 0x3C00, H_2 = 0x4000, H_4 = 0x4400, H_8 = 0x4800;
 
+// GM: 0 = one scale per row or per tensor (raw sums, finished at the end), 1 = group scales applied
+// per (row, lane) (any group size that is a multiple of 16), 2 = group scales applied per
+// (row, 128-k chunk) after the in-chunk reduction (group sizes that are multiples of 128).
 template <bool IS_INT, int BITS, int GM, int RT>
 __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
   constexpr int NR = 8 * RT;
@@ -110,6 +124,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int NW = blockDim.x >> 6;
   const int n = blockIdx.y;
+  const uint32_t jl = (uint32_t)lane & 7u, pos = (uint32_t)lane >> 3;  // chunk in block, unit in chunk
   uint32_t tile[RT];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
@@ -117,26 +132,38 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
     tile[rt] = t < (uint32_t)p.n_tiles ? t : (uint32_t)p.n_tiles - 1;  // clamped; stores are masked
   }
 
-  // plane weights: halved in group-scale mode, where acc = bias + 1/2 * sum_i 2^i L_i
+  // plane weights: halved in the group-scale modes, where acc = bias + 1/2 * sum_i 2^i L_i
   constexpr uint32_t W01 = GM ? h2pack(H_05, H_1) : h2pack(H_1, H_2);
   constexpr uint32_t W23 = GM ? h2pack(H_2, H_4) : h2pack(H_4, H_8);
   constexpr uint16_t WS0 = GM ? H_05 : H_1;  // single plane 0
   constexpr uint16_t WS2 = GM ? H_2 : H_4;   // single plane 2
 
-  float tot[NR];  // group-scale mode: scaled sums; otherwise the raw sums
+  // GM 0: raw sums, GM 1: scaled sums per (row, lane); GM 2: one scaled (row, chunk) sum per tile
+  float tot[GM == 2 ? RT : NR];
 #pragma unroll
-  for (int r = 0; r < NR; ++r) tot[r] = 0.f;
+  for (int r = 0; r < (GM == 2 ? RT : NR); ++r) tot[r] = 0.f;
 
   for (int blk = wave; blk < p.bs.nB; blk += NW) {
-    const uint32_t u0 = (uint32_t)block_start(p.bs, blk);
-    const uint32_t nu = (uint32_t)(blk < p.bs.r ? p.bs.q + 1 : p.bs.q);
-    const bool valid = (uint32_t)lane < nu;
-    const uint32_t l = valid ? (uint32_t)lane : 0u;  // lanes without a unit re-read unit u0, with zero tables
-    const uint32_t u = u0 + l;
+    const uint32_t c0 = (uint32_t)block_start(p.bs, blk);
+    const uint32_t ng = (uint32_t)(blk < p.bs.r ? p.bs.q + 1 : p.bs.q);
+    const uint32_t u0 = 8u * c0, nu = 8u * ng;
+    const bool valid = jl < ng;
+    const uint32_t l = valid ? pos * ng + jl : 0u;  // lanes without a unit re-read slot 0, with zero tables
+    const uint32_t c = valid ? c0 + jl : c0;        // 128-k chunk of this lane
+    const uint32_t u = 8u * c + pos;                // 16-k unit of this lane
 
-    // 1. packed indices of this lane: 16*BITS bytes per tile, issued first.  The block's records
-    // are stored piece-major: 16-byte piece i of lane l sits at slot i*nu + l, so every load
-    // instruction of the wavefront reads one contiguous run.
+    // 1. the lane's four tables, already split into low-byte and high-byte permute sources
+    uint32_t lo0[4], lo1[4], hi0[4], hi1[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const uint32_t slot = valid ? ((uint32_t)n * (uint32_t)p.U + u0) * 4 + (uint32_t)t * nu + l : p.ht_zero;
+      const pu32x4 d = p.ht[slot];
+      lo0[t] = d.x; lo1[t] = d.y; hi0[t] = d.z; hi1[t] = d.w;
+    }
+
+    // 2. packed indices of this lane: 16*BITS bytes per tile.  The block's records are stored
+    // piece-major: 16-byte piece i of slot l sits at i*nu + l, so every load instruction of the
+    // wavefront reads one contiguous run.
     uint32_t w[RT][4 * BITS];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
@@ -148,8 +175,9 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
       }
     }
 
-    // 2. scale and zero of the lane's quantisation group for the rows
-    uint32_t szr[NR];
+    // 3. scale and zero, and the activation sum the bias term needs
+    uint32_t szr[GM == 1 ? NR : RT];
+    float Sl = 0.f;
     if constexpr (GM == 1) {
       uint32_t gq = p.g_shift >= 0 ? (16u * u) >> p.g_shift : (16u * u) / (uint32_t)p.G;
       gq = gq < (uint32_t)p.nq ? gq : (uint32_t)p.nq - 1;  // units in the K padding: tables and S16 are zero
@@ -160,140 +188,158 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
         szr[8 * rt + 0] = a.x; szr[8 * rt + 1] = a.y; szr[8 * rt + 2] = a.z; szr[8 * rt + 3] = a.w;
         szr[8 * rt + 4] = b.x; szr[8 * rt + 5] = b.y; szr[8 * rt + 6] = b.z; szr[8 * rt + 7] = b.w;
       }
+      if constexpr (IS_INT) Sl = (float)static_cast<const int*>(p.S16)[(uint32_t)n * (uint32_t)p.U + u];
+      else Sl = static_cast<const float*>(p.S16)[(uint32_t)n * (uint32_t)p.U + u];
+      Sl = valid ? Sl : 0.f;
+    } else if constexpr (GM == 2) {
+      // one {scale, zero} per lane: row pos of the tile, quantisation group of chunk c
+      const uint32_t gq = p.cpg == 1 ? c : c / (uint32_t)p.cpg;
+      const uint32_t* szw = reinterpret_cast<const uint32_t*>(p.sz);
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) szr[rt] = szw[(tile[rt] * (uint32_t)p.nq + gq) * 8 + pos];
+      if constexpr (IS_INT) Sl = (float)static_cast<const int*>(p.S128)[(uint32_t)n * ((uint32_t)p.U >> 3) + c];
+      else Sl = static_cast<const float*>(p.S128)[(uint32_t)n * ((uint32_t)p.U >> 3) + c];
+      Sl = valid ? Sl : 0.f;
     }
 
-    // 3. the lane's four tables, already split into low-byte and high-byte permute sources
-    uint32_t lo0[4], lo1[4], hi0[4], hi1[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const uint32_t slot = valid ? ((uint32_t)n * (uint32_t)p.U + u0) * 4 + (uint32_t)t * nu + l : p.ht_zero;
-      const pu32x4 d = p.ht[slot];
-      lo0[t] = d.x; lo1[t] = d.y; hi0[t] = d.z; hi1[t] = d.w;
-    }
-    float Sl;
-    if constexpr (IS_INT) Sl = (float)static_cast<const int*>(p.S16)[(uint32_t)n * (uint32_t)p.U + u];
-    else Sl = static_cast<const float*>(p.S16)[(uint32_t)n * (uint32_t)p.U + u];
-    Sl = valid ? Sl : 0.f;
-
-    // 4. accumulators start at the bias term (group-scale mode)
-    float acc[NR];
+    for (int rt = 0; rt < RT; ++rt) {
+      // 4. accumulators: GM 1 starts at the bias term, GM 0 continues the raw sums
+      float acc[8];
 #pragma unroll
-    for (int r = 0; r < NR; ++r) {
-      if constexpr (GM == 1) {
-        const float z = __half2float(__ushort_as_half((uint16_t)(szr[r] >> 16)));
-        acc[r] = fmaf(-z, Sl, p.mid * Sl);
-      } else {
-        acc[r] = tot[r];
-      }
-    }
-
-    // 5. lookups
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      // four lookups of table t: selector bytes `sel` (0..7 each), sign bits `sgn` at bit 7 of each byte
-      auto look = [&](uint32_t sel, uint32_t sgn, uint32_t& p01, uint32_t& p23) {
-        const uint32_t lo = bperm(lo1[t], lo0[t], sel);
-        const uint32_t hi = bperm(hi1[t], hi0[t], sel) ^ sgn;
-        p01 = bperm(hi, lo, 0x05010400u);  // fp16 pair of bytes 0 and 1
-        p23 = bperm(hi, lo, 0x07030602u);  // fp16 pair of bytes 2 and 3
-      };
-      auto quad = [&](uint32_t x, float& a_lo, float& a_hi) {  // 4 planes of one row (low nibbles), one (high)
-        uint32_t a, b;
-        look(x & 0x07070707u, (x << 4) & 0x80808080u, a, b);
-        a_lo = dot2(a, W01, a_lo);
-        a_lo = dot2(b, W23, a_lo);
-        look((x >> 4) & 0x07070707u, x & 0x80808080u, a, b);
-        a_hi = dot2(a, W01, a_hi);
-        a_hi = dot2(b, W23, a_hi);
-      };
-      auto pair = [&](uint32_t x, float* a4) {  // planes 0,1 of rows 0,1 (low) and 2,3 (high) of a4
-        uint32_t a, b;
-        look(x & 0x07070707u, (x << 4) & 0x80808080u, a, b);
-        a4[0] = dot2(a, W01, a4[0]);
-        a4[1] = dot2(b, W01, a4[1]);
-        look((x >> 4) & 0x07070707u, x & 0x80808080u, a, b);
-        a4[2] = dot2(a, W01, a4[2]);
-        a4[3] = dot2(b, W01, a4[3]);
-      };
-      auto single = [&](uint32_t x, uint16_t wgt, float* a8) {  // one plane of rows 0..3 (low), 4..7 (high)
-        const uint32_t wl = h2pack(wgt, H_0), wh = h2pack(H_0, wgt);
-        uint32_t a, b;
-        look(x & 0x07070707u, (x << 4) & 0x80808080u, a, b);
-        a8[0] = dot2(a, wl, a8[0]);
-        a8[1] = dot2(a, wh, a8[1]);
-        a8[2] = dot2(b, wl, a8[2]);
-        a8[3] = dot2(b, wh, a8[3]);
-        look((x >> 4) & 0x07070707u, x & 0x80808080u, a, b);
-        a8[4] = dot2(a, wl, a8[4]);
-        a8[5] = dot2(a, wh, a8[5]);
-        a8[6] = dot2(b, wl, a8[6]);
-        a8[7] = dot2(b, wh, a8[7]);
-      };
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
-        const uint32_t* wt = &w[rt][t * BITS];
-        float* a8 = &acc[8 * rt];
-        if constexpr (BITS == 4) {
-#pragma unroll
-          for (int d = 0; d < 4; ++d) quad(wt[d], a8[2 * d], a8[2 * d + 1]);
-        } else if constexpr (BITS == 2) {
-          pair(wt[0], a8);
-          pair(wt[1], a8 + 4);
-        } else if constexpr (BITS == 1) {
-          single(wt[0], WS0, a8);
+      for (int r = 0; r < 8; ++r) {
+        if constexpr (GM == 1) {
+          const float z = __half2float(__ushort_as_half((uint16_t)(szr[8 * rt + r] >> 16)));
+          acc[r] = fmaf(-z, Sl, p.mid * Sl);
+        } else if constexpr (GM == 0) {
+          acc[r] = tot[8 * rt + r];
         } else {
-          pair(wt[0], a8);
-          pair(wt[1], a8 + 4);
-          single(wt[2], WS2, a8);
+          acc[r] = 0.f;
         }
       }
-    }
 
-    // 6. scale once per (row, lane)
+      // 5. lookups
 #pragma unroll
-    for (int r = 0; r < NR; ++r) {
+      for (int t = 0; t < 4; ++t) {
+        // four lookups of table t: selector bytes `sel` (0..7 each), sign bits `sgn` at bit 7 of each byte
+        auto look = [&](uint32_t sel, uint32_t sgn, uint32_t& p01, uint32_t& p23) {
+          const uint32_t lo = bperm(lo1[t], lo0[t], sel);
+          const uint32_t hi = bperm(hi1[t], hi0[t], sel) ^ sgn;
+          p01 = bperm(hi, lo, 0x05010400u);  // fp16 pair of bytes 0 and 1
+          p23 = bperm(hi, lo, 0x07030602u);  // fp16 pair of bytes 2 and 3
+        };
+        auto quad = [&](uint32_t x, float& a_lo, float& a_hi) {  // 4 planes of one row (low nibbles), one (high)
+          uint32_t a, b;
+          look(x & 0x07070707u, (x << 4) & 0x80808080u, a, b);
+          a_lo = dot2(a, W01, a_lo);
+          a_lo = dot2(b, W23, a_lo);
+          look((x >> 4) & 0x07070707u, x & 0x80808080u, a, b);
+          a_hi = dot2(a, W01, a_hi);
+          a_hi = dot2(b, W23, a_hi);
+        };
+        auto pair = [&](uint32_t x, float* a4) {  // planes 0,1 of rows 0,1 (low) and 2,3 (high) of a4
+          uint32_t a, b;
+          look(x & 0x07070707u, (x << 4) & 0x80808080u, a, b);
+          a4[0] = dot2(a, W01, a4[0]);
+          a4[1] = dot2(b, W01, a4[1]);
+          look((x >> 4) & 0x07070707u, x & 0x80808080u, a, b);
+          a4[2] = dot2(a, W01, a4[2]);
+          a4[3] = dot2(b, W01, a4[3]);
+        };
+        auto single = [&](uint32_t x, uint16_t wgt, float* a8) {  // one plane of rows 0..3 (low), 4..7 (high)
+          const uint32_t wl = h2pack(wgt, H_0), wh = h2pack(H_0, wgt);
+          uint32_t a, b;
+          look(x & 0x07070707u, (x << 4) & 0x80808080u, a, b);
+          a8[0] = dot2(a, wl, a8[0]);
+          a8[1] = dot2(a, wh, a8[1]);
+          a8[2] = dot2(b, wl, a8[2]);
+          a8[3] = dot2(b, wh, a8[3]);
+          look((x >> 4) & 0x07070707u, x & 0x80808080u, a, b);
+          a8[4] = dot2(a, wl, a8[4]);
+          a8[5] = dot2(a, wh, a8[5]);
+          a8[6] = dot2(b, wl, a8[6]);
+          a8[7] = dot2(b, wh, a8[7]);
+        };
+        const uint32_t* wt = &w[rt][t * BITS];
+        if constexpr (BITS == 4) {
+#pragma unroll
+          for (int d = 0; d < 4; ++d) quad(wt[d], acc[2 * d], acc[2 * d + 1]);
+        } else if constexpr (BITS == 2) {
+          pair(wt[0], acc);
+          pair(wt[1], acc + 4);
+        } else if constexpr (BITS == 1) {
+          single(wt[0], WS0, acc);
+        } else {
+          pair(wt[0], acc);
+          pair(wt[1], acc + 4);
+          single(wt[2], WS2, acc);
+        }
+      }
+
+      // 6. scale: once per (row, lane) in GM 1, once per (row, chunk) in GM 2
       if constexpr (GM == 1) {
-        const float s = __half2float(__ushort_as_half((uint16_t)(szr[r] & 0xffffu)));
-        tot[r] = fmaf(s, acc[r], tot[r]);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+          const float s = __half2float(__ushort_as_half((uint16_t)(szr[8 * rt + r] & 0xffffu)));
+          tot[8 * rt + r] = fmaf(s, acc[r], tot[8 * rt + r]);
+        }
+      } else if constexpr (GM == 0) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) tot[8 * rt + r] = acc[r];
       } else {
-        tot[r] = acc[r];
+        const float v = reduce_hi3(acc, lane);  // row pos, summed over the chunk (sums of this size are exact for ints)
+        const float s = __half2float(__ushort_as_half((uint16_t)(szr[rt] & 0xffffu)));
+        const float z = __half2float(__ushort_as_half((uint16_t)(szr[rt] >> 16)));
+        tot[rt] = fmaf(s, fmaf(p.mid - z, Sl, v), tot[rt]);
       }
     }
   }
 
-  // 7. cross-lane sums; lanes 0, 8, .., 56 publish the 8 rows of each tile
+  // 7. cross-lane sums: lane 8*r publishes row r of each tile
   constexpr bool RAW_INT = (GM == 0 && IS_INT);
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
-    float t8[8];
-#pragma unroll
-    for (int r = 0; r < 8; ++r) t8[r] = tot[8 * rt + r];
-    const float v = butterfly8(t8, lane);
-    if ((lane & 7) == 0) {
-      const int row = 8 * rt + ((lane >> 3) & 7);
+    float v;
+    if constexpr (GM == 2) v = tot[rt];
+    else v = reduce_hi3(&tot[8 * rt], lane);
+    v = reduce_lo3(v);
+    if (jl == 0) {
+      const int row = 8 * rt + (int)pos;
       if constexpr (RAW_INT) red[wave * NR + row] = __int_as_float((int)v);  // exact: integer < 2^24
       else red[wave * NR + row] = v;
     }
   }
   __syncthreads();
 
-  // 8. sum the waves in wave order, finish and store
-  if (threadIdx.x < NR) {
-    const int r = threadIdx.x;
-    const uint32_t t = blockIdx.x * RT + (r >> 3);
-    const int m = (int)t * 8 + (r & 7);
+  // 8. wave 0 sums the waves with a fixed tree (lane = 8*slot + row: waves slot and slot + 8, then
+  // the slots), finishes and stores
+  if (wave != 0) return;
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int r = 8 * rt + (int)jl;   // row of this lane
+    const int ws = (int)pos;          // wave slot
     float sf = 0.f;
     int si = 0;
-    for (int wv = 0; wv < NW; ++wv) {
-      const float x = red[wv * NR + r];
-      if constexpr (RAW_INT) si += __float_as_int(x);
-      else sf += x;
+    if constexpr (RAW_INT) {
+      si = ws < NW ? __float_as_int(red[ws * NR + r]) : 0;
+      if (ws + 8 < NW) si += __float_as_int(red[(ws + 8) * NR + r]);
+      si += __builtin_amdgcn_update_dpp(0, si, 0x128, 0xf, 0xf, false);  // row_ror:8
+      si += __shfl_xor(si, 16);
+      si += __shfl_xor(si, 32);
+    } else {
+      sf = ws < NW ? red[ws * NR + r] : 0.f;
+      if (ws + 8 < NW) sf += red[(ws + 8) * NR + r];
+      sf += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(sf), 0x128, 0xf, 0xf, false));
+      sf += __shfl_xor(sf, 16);
+      sf += __shfl_xor(sf, 32);
     }
-    if (t < (uint32_t)p.n_tiles && m < p.M) {
+    const uint32_t t = blockIdx.x * RT + rt;
+    const int m = (int)t * 8 + (int)jl;
+    if (lane < 8 && t < (uint32_t)p.n_tiles && m < p.M) {
       const float as = p.act_scale ? p.act_scale[n] : 1.0f;
       float res;
       int ires = 0;
-      if constexpr (GM == 1) {
+      if constexpr (GM != 0) {
         res = sf * as;
       } else {
         float s, z;
@@ -301,7 +347,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
           s = p.wscale;
           z = p.zero_point;
         } else {
-          const uint32_t szv = reinterpret_cast<const uint32_t*>(p.sz)[(size_t)t * 8 + (r & 7)];
+          const uint32_t szv = reinterpret_cast<const uint32_t*>(p.sz)[(size_t)t * 8 + jl];
           s = __half2float(__ushort_as_half((uint16_t)(szv & 0xffffu)));
           z = __half2float(__ushort_as_half((uint16_t)(szv >> 16)));
         }
@@ -341,7 +387,11 @@ static hipError_t launch_rt(const PermParams& p, int rt, int NW, hipStream_t st)
 
 template <bool IS_INT, int BITS>
 static hipError_t launch_gm(const PermParams& p, int gm, int rt, int NW, hipStream_t st) {
-  return gm ? launch_rt<IS_INT, BITS, 1>(p, rt, NW, st) : launch_rt<IS_INT, BITS, 0>(p, rt, NW, st);
+  switch (gm) {
+    case 0: return launch_rt<IS_INT, BITS, 0>(p, rt, NW, st);
+    case 1: return launch_rt<IS_INT, BITS, 1>(p, rt, NW, st);
+    default: return launch_rt<IS_INT, BITS, 2>(p, rt, NW, st);
+  }
 }
 
 template <bool IS_INT>
@@ -375,6 +425,7 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
   p.ht_zero = (uint32_t)((size_t)N * lg.U * 4);
   p.S = static_cast<const char*>(lut_dev) + lg.s_off;
   p.S16 = static_cast<const char*>(lut_dev) + lg.s16_off;
+  p.S128 = static_cast<const char*>(lut_dev) + lg.s128_off;
   p.out = out_dev;
   p.act_scale = act_scale_dev;
   p.ldo = ldo;
@@ -405,11 +456,12 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
     const int passes = (p.bs.nB + NW - 1) / NW;
     if ((double)508.0 * ((1 << desc->bits) - 1) * 256.0 * passes >= 16777216.0) return TMAC_EUNSUPPORTED;
   }
-  // two row tiles per workgroup halve the table traffic; kept for matrices with enough tiles to
-  // still fill the chip
-  int rt = rows_per_group == 8 ? 1 : rows_per_group == 16 ? 2 : (ge.n_tiles >= 1024 ? 2 : 1);
+  // two row tiles per workgroup halve the table traffic but also the number of waves; one tile
+  // per workgroup measured faster on every decode shape, so it is the default
+  const int rt = rows_per_group == 16 ? 2 : 1;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int gm = one_group ? 0 : 1;
+  const int gm = one_group ? 0 : (desc->group % 128 == 0 ? 2 : 1);
+  p.cpg = gm == 2 ? desc->group / 128 : 1;
   const hipError_t e = lut_is_int ? launch_bits<true>(p, desc->bits, gm, rt, NW, st)
                                   : launch_bits<false>(p, desc->bits, gm, rt, NW, st);
   if (e != hipSuccess) {

@@ -33,17 +33,23 @@ def unpack_layout2(blob: np.ndarray):
     assert Mp == (M + 7) // 8 * 8 and Kp == (K + 127) // 128 * 128 and n_units == Kp // 16
     assert total == len(raw) and idx_bytes == n_tiles * n_units * 16 * bits
     flat = np.frombuffer(raw, dtype="<u4", count=idx_bytes // 4, offset=idx_off).reshape(n_tiles, n_units * 4 * bits)
-    # undo the piece-major order inside every block of units: slot (i, lane) holds dwords 4i..4i+3
-    # of the record of unit u0 + lane
+    # undo the block order: the n_units / 8 chunks (8 units = 128 k each) are split into
+    # ceil(chunks / 8) blocks; inside a block of ng chunks starting at chunk c0, unit
+    # 8 * (c0 + j) + pos sits in slot pos * ng + j, and 16-byte piece i of the record in slot s
+    # is stored at (i * 8 * ng + s)
     rec = np.zeros((n_tiles, n_units, 4 * bits), dtype=np.uint32)
-    nB = (n_units + 63) // 64
-    qq, rr = divmod(n_units, nB)
+    n_chunks = n_units // 8
+    nB = (n_chunks + 7) // 8
+    qq, rr = divmod(n_chunks, nB)
     for blk in range(nB):
-        u0 = blk * qq + min(blk, rr)
-        nu = qq + 1 if blk < rr else qq
-        u1 = u0 + nu
-        span = flat[:, u0 * 4 * bits: u1 * 4 * bits].reshape(n_tiles, bits, nu, 4)
-        rec[:, u0:u1, :] = span.transpose(0, 2, 1, 3).reshape(n_tiles, nu, 4 * bits)
+        c0 = blk * qq + min(blk, rr)
+        ng = qq + 1 if blk < rr else qq
+        nu = 8 * ng
+        span = flat[:, 8 * c0 * 4 * bits: (8 * c0 + nu) * 4 * bits].reshape(n_tiles, bits, nu, 4)
+        by_slot = span.transpose(0, 2, 1, 3).reshape(n_tiles, nu, 4 * bits)
+        for j in range(ng):
+            for pos in range(8):
+                rec[:, 8 * (c0 + j) + pos, :] = by_slot[:, pos * ng + j, :]
     idx = rec.reshape(n_tiles, n_units, 4, bits)
     q = np.zeros((Mp, Kp), dtype=np.uint8)
     for tb in range(4):
@@ -143,8 +149,8 @@ def test_layout2_sizes_and_group_rules():
     d = desc2(4096, 4096, 4, 128)
     assert T.tmac_packed_bytes(d) == 256 + 4096 * 4096 // 2 + 4096 * 32 * 4
     assert T.tmac_workspace_bytes(d, 1) == 256
-    # LUT buffer: tables, group sums, per-16 sums
-    assert T.tmac_lut_bytes(1, 4096, 128, B.TMAC_LUT_F16) == 4096 * 8 + 256 + 1024 + 4096 * 4 + 256
+    # LUT buffer: tables, group sums, per-16 sums, per-128 sums, half tables, zero slot
+    assert T.tmac_lut_bytes(1, 4096, 128, B.TMAC_LUT_F16) == 4096 * 8 + 256 + 1024 + 256 + 4096 * 4 + 256
     import ctypes as C
     fake = C.c_void_p(0x1000)
     g24 = desc2(16, 192, 2, 24)      # valid (24 % 4 == 0) but not a multiple of 16
