@@ -57,8 +57,8 @@ struct PermParams {
   const float* act_scale;
   int64_t ldo;
   int M, N, U, n_tiles, nq;
-  int G, g_shift;  // elements per quantisation group; log2(G) if G is a power of two, else -1
-  int cpg;         // group mode 2: 128-k chunks per quantisation group
+  int G;           // elements per quantisation group
+  uint32_t q_magic;  // ceil(2^32 / d), d = units (mode 1) or chunks (mode 2) per quantisation group; 0 if d = 1
   BlockSplit bs;   // split of the U/8 chunks into blocks of at most 8
   uint32_t ht_zero;  // slot index of the all-zero table
   int per_tensor, int_exact, icoef;
@@ -132,6 +132,22 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
     tile[rt] = t < (uint32_t)p.n_tiles ? t : (uint32_t)p.n_tiles - 1;  // clamped; stores are masked
   }
 
+  // values the last stage needs, requested now so that their latency is hidden behind the main loop
+  const float as = p.act_scale ? p.act_scale[n] : 1.0f;
+  float fin_s = p.wscale, fin_z = p.zero_point, fin_Sf = 0.f;
+  int fin_Si = 0;
+  if constexpr (GM == 0) {
+    if constexpr (IS_INT) fin_Si = static_cast<const int*>(p.S)[n];
+    else fin_Sf = static_cast<const float*>(p.S)[n];
+  }
+  uint32_t fin_sz[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    fin_sz[rt] = 0;
+    if constexpr (GM == 0)
+      if (!p.per_tensor) fin_sz[rt] = reinterpret_cast<const uint32_t*>(p.sz)[(size_t)tile[rt] * 8 + jl];
+  }
+
   // plane weights: halved in the group-scale modes, where acc = bias + 1/2 * sum_i 2^i L_i
   constexpr uint32_t W01 = GM ? h2pack(H_05, H_1) : h2pack(H_1, H_2);
   constexpr uint32_t W23 = GM ? h2pack(H_2, H_4) : h2pack(H_4, H_8);
@@ -152,34 +168,11 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
     const uint32_t c = valid ? c0 + jl : c0;        // 128-k chunk of this lane
     const uint32_t u = 8u * c + pos;                // 16-k unit of this lane
 
-    // 1. the lane's four tables, already split into low-byte and high-byte permute sources
-    uint32_t lo0[4], lo1[4], hi0[4], hi1[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const uint32_t slot = valid ? ((uint32_t)n * (uint32_t)p.U + u0) * 4 + (uint32_t)t * nu + l : p.ht_zero;
-      const pu32x4 d = p.ht[slot];
-      lo0[t] = d.x; lo1[t] = d.y; hi0[t] = d.z; hi1[t] = d.w;
-    }
-
-    // 2. packed indices of this lane: 16*BITS bytes per tile.  The block's records are stored
-    // piece-major: 16-byte piece i of slot l sits at i*nu + l, so every load instruction of the
-    // wavefront reads one contiguous run.
-    uint32_t w[RT][4 * BITS];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      const pu32x4* src = p.idx + (tile[rt] * (uint32_t)p.U + u0) * BITS + l;
-#pragma unroll
-      for (int i = 0; i < BITS; ++i) {
-        const pu32x4 v = __builtin_nontemporal_load(src + i * nu);
-        w[rt][4 * i + 0] = v.x; w[rt][4 * i + 1] = v.y; w[rt][4 * i + 2] = v.z; w[rt][4 * i + 3] = v.w;
-      }
-    }
-
-    // 3. scale and zero, and the activation sum the bias term needs
+    // 1. scale and zero, and the activation sum the bias term needs
     uint32_t szr[GM == 1 ? NR : RT];
     float Sl = 0.f;
     if constexpr (GM == 1) {
-      uint32_t gq = p.g_shift >= 0 ? (16u * u) >> p.g_shift : (16u * u) / (uint32_t)p.G;
+      uint32_t gq = p.q_magic ? __umulhi(u, p.q_magic) : u;  // u / (units per group), exact for u < 2^16
       gq = gq < (uint32_t)p.nq ? gq : (uint32_t)p.nq - 1;  // units in the K padding: tables and S16 are zero
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
@@ -193,13 +186,36 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
       Sl = valid ? Sl : 0.f;
     } else if constexpr (GM == 2) {
       // one {scale, zero} per lane: row pos of the tile, quantisation group of chunk c
-      const uint32_t gq = p.cpg == 1 ? c : c / (uint32_t)p.cpg;
+      const uint32_t gq = p.q_magic ? __umulhi(c, p.q_magic) : c;  // c / (chunks per group), exact for c < 2^16
       const uint32_t* szw = reinterpret_cast<const uint32_t*>(p.sz);
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) szr[rt] = szw[(tile[rt] * (uint32_t)p.nq + gq) * 8 + pos];
       if constexpr (IS_INT) Sl = (float)static_cast<const int*>(p.S128)[(uint32_t)n * ((uint32_t)p.U >> 3) + c];
       else Sl = static_cast<const float*>(p.S128)[(uint32_t)n * ((uint32_t)p.U >> 3) + c];
       Sl = valid ? Sl : 0.f;
+    }
+
+    // 2. the lane's four tables, already split into low-byte and high-byte permute sources
+    uint32_t lo0[4], lo1[4], hi0[4], hi1[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const uint32_t slot = valid ? ((uint32_t)n * (uint32_t)p.U + u0) * 4 + (uint32_t)t * nu + l : p.ht_zero;
+      const pu32x4 d = p.ht[slot];
+      lo0[t] = d.x; lo1[t] = d.y; hi0[t] = d.z; hi1[t] = d.w;
+    }
+
+    // 3. packed indices of this lane: 16*BITS bytes per tile.  The block's records are stored
+    // piece-major: 16-byte piece i of slot l sits at i*nu + l, so every load instruction of the
+    // wavefront reads one contiguous run.
+    uint32_t w[RT][4 * BITS];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const pu32x4* src = p.idx + (tile[rt] * (uint32_t)p.U + u0) * BITS + l;
+#pragma unroll
+      for (int i = 0; i < BITS; ++i) {
+        const pu32x4 v = __builtin_nontemporal_load(src + i * nu);
+        w[rt][4 * i + 0] = v.x; w[rt][4 * i + 1] = v.y; w[rt][4 * i + 2] = v.z; w[rt][4 * i + 3] = v.w;
+      }
     }
 
 #pragma unroll
@@ -336,32 +352,27 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
     const uint32_t t = blockIdx.x * RT + rt;
     const int m = (int)t * 8 + (int)jl;
     if (lane < 8 && t < (uint32_t)p.n_tiles && m < p.M) {
-      const float as = p.act_scale ? p.act_scale[n] : 1.0f;
       float res;
       int ires = 0;
       if constexpr (GM != 0) {
         res = sf * as;
       } else {
-        float s, z;
-        if (p.per_tensor) {
-          s = p.wscale;
-          z = p.zero_point;
-        } else {
-          const uint32_t szv = reinterpret_cast<const uint32_t*>(p.sz)[(size_t)t * 8 + jl];
-          s = __half2float(__ushort_as_half((uint16_t)(szv & 0xffffu)));
-          z = __half2float(__ushort_as_half((uint16_t)(szv >> 16)));
+        float s = fin_s, z = fin_z;
+        if (!p.per_tensor) {
+          s = __half2float(__ushort_as_half((uint16_t)(fin_sz[rt] & 0xffffu)));
+          z = __half2float(__ushort_as_half((uint16_t)(fin_sz[rt] >> 16)));
         }
         if constexpr (IS_INT) {
-          const int St = static_cast<const int*>(p.S)[n];
+          const int St = fin_Si;
           if (p.int_exact) {
             ires = (si + p.icoef * St) >> 1;  // numerator is always even
             res = ((float)ires * as) * s;     // two roundings, left to right
           } else {
-            res = ((0.5f * (float)si + (p.mid - z) * (float)St) * as) * s;
+            res = (fmaf(p.mid - z, (float)St, 0.5f * (float)si) * as) * s;  // explicit fma: same rounding in every instantiation
           }
         } else {
-          const float St = static_cast<const float*>(p.S)[n];
-          res = (s * (0.5f * sf + (p.mid - z) * St)) * as;
+          const float St = fin_Sf;
+          res = (s * fmaf(p.mid - z, St, 0.5f * sf)) * as;  // explicit fma: same rounding in every instantiation
         }
       }
       const size_t o = (size_t)n * p.ldo + m;
@@ -431,9 +442,6 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
   p.ldo = ldo;
   p.M = desc->M; p.N = N; p.U = lg.U; p.n_tiles = ge.n_tiles; p.nq = lg.nq;
   p.G = lg.Geff;
-  p.g_shift = -1;
-  for (int s = 0; s < 31; ++s)
-    if ((1 << s) == lg.Geff) p.g_shift = s;
   p.bs = block_split(lg.U);
   p.per_tensor = (desc->group == 0);
   p.wscale = weight_scale;
@@ -461,7 +469,12 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
   const int rt = rows_per_group == 16 ? 2 : 1;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int gm = one_group ? 0 : (desc->group % 128 == 0 ? 2 : 1);
-  p.cpg = gm == 2 ? desc->group / 128 : 1;
+  {
+    // divisor of the lane's unit (mode 1) or chunk (mode 2) index that gives its quantisation group
+    const uint32_t d = gm == 2 ? (uint32_t)desc->group / 128u : gm == 1 ? (uint32_t)desc->group / 16u : 1u;
+    if (d >= 65536u || lg.U >= 65536) return TMAC_EUNSUPPORTED;
+    p.q_magic = d == 1 ? 0u : (uint32_t)((4294967296ull + d - 1) / d);
+  }
   const hipError_t e = lut_is_int ? launch_bits<true>(p, desc->bits, gm, rt, NW, st)
                                   : launch_bits<false>(p, desc->bits, gm, rt, NW, st);
   if (e != hipSuccess) {
