@@ -192,6 +192,22 @@ tmac_status tmac_mpgemm(const tmac_wdesc* desc, const void* packed_dev, const vo
                         float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
                         void* workspace_dev, size_t workspace_bytes, void* stream);
 
+/* Decode call with the table precompute fused into the lookup kernel (Algorithm 1 Precompute
+ * and main loop in one launch; Section 3.1: the tables are small and cheap to build, so every
+ * lane rebuilds the four tables of its 16 activations in registers instead of reading them from
+ * a LUT buffer).  Same result as tmac_precompute_lut + tmac_mpgemm on a layout-2 blob: table
+ * entries, chunk sums and summation order are identical for group sizes that are multiples
+ * of 16.
+ *   packed_dev  layout-2 (TMAC_LAYOUT_R8U16) blob; K must be a multiple of 16
+ *   A_dev       [N,K] fp16 (TMAC_ACT_F16: fp16 tables) or int8 (TMAC_ACT_I8: exact integer
+ *               tables), 16-byte aligned, leading dimension lda a multiple of 8 (fp16) or 16 (int8)
+ *   other arguments as tmac_mpgemm; no LUT buffer and no workspace.
+ * Errors: TMAC_EINVAL, TMAC_EUNSUPPORTED (layout 1, K % 16 != 0, unsupported group), TMAC_EHIP. */
+tmac_status tmac_mpgemv_fused(const tmac_wdesc* desc, const void* packed_dev, const void* A_dev,
+                              tmac_act_t act, int32_t N, int64_t lda, const float* act_scale_dev,
+                              float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
+                              void* stream);
+
 /* Launch-shape knobs for benchmarking sweeps; 0 = library default.
  *   kernel           1 = K-sliced kernel (tables of a K-slice in LDS, split-K reduction through
  *                    the workspace), 2 = full-K decode kernel (all tables of one activation row

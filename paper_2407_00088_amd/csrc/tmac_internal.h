@@ -92,10 +92,11 @@ TMAC_HD inline int block_of(const BlockSplit& b, int c) {
 TMAC_HD inline int block_slot(int u, int c0, int ng) { return (u & 7) * ng + ((u >> 3) - c0); }
 
 // Register-table decode kernel (layout 2); defined in tmac_perm.hip.  Arguments are those of
-// tmac_mpgemm after validation; returns a tmac_status value.
-int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, int lut_is_int,
-                     int N, const float* act_scale_dev, float weight_scale, void* out_dev, int out_t,
-                     int64_t ldo, void* stream, int rows_per_group);
+// tmac_mpgemm after validation; with lut_dev == nullptr the kernel builds its tables itself from
+// the activations A_dev (leading dimension lda).  Returns a tmac_status value.
+int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, const void* A_dev,
+                     int64_t lda, int lut_is_int, int N, const float* act_scale_dev, float weight_scale,
+                     void* out_dev, int out_t, int64_t ldo, void* stream, int rows_per_group);
 
 // Records the last HIP error of this thread (diagnostics for TMAC_EHIP).
 void note_hip_error(int hip_error);

@@ -86,7 +86,7 @@ __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict_
       uint16_t e[16];
 #pragma unroll
       for (int p = 0; p < 8; ++p) {
-        const float v = ((((p & 1) ? a0 : -a0) + ((p & 2) ? a1 : -a1)) + ((p & 4) ? a2 : -a2)) - a3;
+        const float v = (((p & 1) ? a0 : -a0) + ((p & 2) ? a1 : -a1)) + (((p & 4) ? a2 : -a2) - a3);
         const __half h = __float2half_rn(v);
         e[p] = __half_as_ushort(h);
         e[15 - p] = e[p] ^ 0x8000u;  // mirror half: exact negation
@@ -834,7 +834,7 @@ extern "C" tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed
       return TMAC_EUNSUPPORTED;
     const int rpg = tuning ? tuning->rows_per_group : 0;
     if (rpg != 0 && rpg != 8 && rpg != 16) return TMAC_EINVAL;
-    return static_cast<tmac_status>(launch_perm_gemv(desc, packed_dev, lut_dev, is_int ? 1 : 0, N,
+    return static_cast<tmac_status>(launch_perm_gemv(desc, packed_dev, lut_dev, nullptr, 0, is_int ? 1 : 0, N,
                                                       act_scale_dev, weight_scale, out_dev, (int)out, ldo,
                                                       stream, rpg));
   }
@@ -899,6 +899,25 @@ extern "C" tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed
 
   const hipError_t e = is_int ? launch_bits<true>(desc->bits, p, ls, st) : launch_bits<false>(desc->bits, p, ls, st);
   return e == hipSuccess ? TMAC_OK : TMAC_EHIP;
+}
+
+extern "C" tmac_status tmac_mpgemv_fused(const tmac_wdesc* desc, const void* packed_dev, const void* A_dev,
+                                         tmac_act_t act, int32_t N, int64_t lda, const float* act_scale_dev,
+                                         float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
+                                         void* stream) {
+  if (!desc_valid(desc) || !packed_dev || !A_dev || !out_dev || N <= 0) return TMAC_EINVAL;
+  if (act != TMAC_ACT_F16 && act != TMAC_ACT_I8) return TMAC_EINVAL;
+  if (out != TMAC_OUT_F32 && out != TMAC_OUT_F16 && out != TMAC_OUT_I32) return TMAC_EINVAL;
+  if (!aligned16(packed_dev) || !aligned16(A_dev)) return TMAC_EINVAL;
+  if (ldo < desc->M || lda < desc->K) return TMAC_EINVAL;
+  // every lane reads the 16 activations of its unit with 16-byte loads
+  const int64_t row_elems_16B = (act == TMAC_ACT_F16) ? 8 : 16;
+  if (lda % row_elems_16B != 0) return TMAC_EINVAL;
+  if (desc->layout != TMAC_LAYOUT_R8U16 || desc->K % 16 != 0) return TMAC_EUNSUPPORTED;
+  if (!group_supported(desc)) return TMAC_EUNSUPPORTED;
+  return static_cast<tmac_status>(launch_perm_gemv(desc, packed_dev, nullptr, A_dev, lda, act == TMAC_ACT_I8 ? 1 : 0,
+                                                    N, act_scale_dev, weight_scale, out_dev, (int)out, ldo,
+                                                    stream, 8));
 }
 
 extern "C" tmac_status tmac_mpgemm(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev,

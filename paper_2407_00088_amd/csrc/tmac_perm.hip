@@ -53,10 +53,12 @@ struct PermParams {
   const void* S;           // [N][nq] fp32 / int32 group sums
   const void* S16;         // [N][U]  fp32 / int32 unit sums
   const void* S128;        // [N][U/8] fp32 / int32 sums of every 128 consecutive activations
+  const void* A;           // fused mode: activations [N][lda], fp16 or int8 (no LUT buffer is read)
+  int64_t lda;
   void* out;
   const float* act_scale;
   int64_t ldo;
-  int M, N, U, n_tiles, nq;
+  int M, N, K, U, n_tiles, nq;
   int G;           // elements per quantisation group
   uint32_t q_magic;  // ceil(2^32 / d), d = units (mode 1) or chunks (mode 2) per quantisation group; 0 if d = 1
   BlockSplit bs;   // split of the U/8 chunks into blocks of at most 8
@@ -116,10 +118,13 @@ constexpr uint16_t H_0 = 0x0000, H_05 = 0x3800, H_1 = 0x3C00, H_2 = 0x4000, H_4 
 // GM: 0 = one scale per row or per tensor (raw sums, finished at the end), 1 = group scales applied
 // per (row, lane) (any group size that is a multiple of 16), 2 = group scales applied per
 // (row, 128-k chunk) after the in-chunk reduction (group sizes that are multiples of 128).
-template <bool IS_INT, int BITS, int GM, int RT>
+// FUSED: the lane builds the four tables of its unit from the activations itself (Algorithm 1
+// Precompute inside the lookup kernel), with the arithmetic of the stand-alone precompute kernel.
+template <bool IS_INT, int BITS, int GM, int RT, bool FUSED>
 __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
   constexpr int NR = 8 * RT;
   __shared__ float red[16 * NR];
+  __shared__ float redS[16];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int NW = blockDim.x >> 6;
@@ -137,8 +142,10 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
   float fin_s = p.wscale, fin_z = p.zero_point, fin_Sf = 0.f;
   int fin_Si = 0;
   if constexpr (GM == 0) {
-    if constexpr (IS_INT) fin_Si = static_cast<const int*>(p.S)[n];
-    else fin_Sf = static_cast<const float*>(p.S)[n];
+    if constexpr (!FUSED) {
+      if constexpr (IS_INT) fin_Si = static_cast<const int*>(p.S)[n];
+      else fin_Sf = static_cast<const float*>(p.S)[n];
+    }
   }
   uint32_t fin_sz[RT];
 #pragma unroll
@@ -159,6 +166,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
 #pragma unroll
   for (int r = 0; r < (GM == 2 ? RT : NR); ++r) tot[r] = 0.f;
 
+  float Stot = 0.f;  // fused mode, GM 0: this lane's share of the sum of all activations
   for (int blk = wave; blk < p.bs.nB; blk += NW) {
     const uint32_t c0 = (uint32_t)block_start(p.bs, blk);
     const uint32_t ng = (uint32_t)(blk < p.bs.r ? p.bs.q + 1 : p.bs.q);
@@ -168,9 +176,54 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
     const uint32_t c = valid ? c0 + jl : c0;        // 128-k chunk of this lane
     const uint32_t u = 8u * c + pos;                // 16-k unit of this lane
 
-    // 1. scale and zero, and the activation sum the bias term needs
+    // 1. in fused mode: the lane's 16 activations (zero past the end of K and for idle lanes)
+    float af[16];
+    int ai[16];
+    if constexpr (FUSED) {
+      const bool have = valid && 16u * u < (uint32_t)p.K;
+      if constexpr (IS_INT) {
+        pu32x4 v = {0u, 0u, 0u, 0u};
+        if (have) v = *reinterpret_cast<const pu32x4*>(static_cast<const int8_t*>(p.A) + (size_t)n * p.lda + 16u * u);
+        const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 16; ++i) ai[i] = (int)(int8_t)(vv[i >> 2] >> (8 * (i & 3)));
+      } else {
+        pu32x4 v0 = {0u, 0u, 0u, 0u}, v1 = {0u, 0u, 0u, 0u};
+        if (have) {
+          const pu32x4* ap = reinterpret_cast<const pu32x4*>(static_cast<const __half*>(p.A) + (size_t)n * p.lda + 16u * u);
+          v0 = ap[0];
+          v1 = ap[1];
+        }
+        const uint32_t vv[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+        for (int i = 0; i < 16; ++i) af[i] = __half2float(__ushort_as_half((uint16_t)(vv[i >> 1] >> (16 * (i & 1)))));
+      }
+    }
+
+    // 2. scale and zero, and the activation sum the bias term needs
     uint32_t szr[GM == 1 ? NR : RT];
     float Sl = 0.f;
+    if constexpr (FUSED) {
+      // sum of the lane's 16 activations, in the order of the precompute kernel's tree
+      if constexpr (IS_INT) {
+        int s16 = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s16 += ai[i];
+        Sl = (float)s16;  // |s16| <= 16 * 128
+      } else {
+        float t4[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) t4[t] = ((af[4 * t] + af[4 * t + 1]) + af[4 * t + 2]) + af[4 * t + 3];
+        Sl = (t4[0] + t4[1]) + (t4[2] + t4[3]);
+      }
+      if constexpr (GM == 0) Stot += Sl;
+      if constexpr (GM == 2) {
+        // sum over the chunk's eight lanes (lane bits 3, 4, 5), pairing units as the precompute kernel does
+        Sl += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(Sl), 0x128, 0xf, 0xf, false));  // row_ror:8
+        Sl += __shfl_xor(Sl, 16);
+        Sl += __shfl_xor(Sl, 32);
+      }
+    }
     if constexpr (GM == 1) {
       uint32_t gq = p.q_magic ? __umulhi(u, p.q_magic) : u;  // u / (units per group), exact for u < 2^16
       gq = gq < (uint32_t)p.nq ? gq : (uint32_t)p.nq - 1;  // units in the K padding: tables and S16 are zero
@@ -181,30 +234,62 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
         szr[8 * rt + 0] = a.x; szr[8 * rt + 1] = a.y; szr[8 * rt + 2] = a.z; szr[8 * rt + 3] = a.w;
         szr[8 * rt + 4] = b.x; szr[8 * rt + 5] = b.y; szr[8 * rt + 6] = b.z; szr[8 * rt + 7] = b.w;
       }
-      if constexpr (IS_INT) Sl = (float)static_cast<const int*>(p.S16)[(uint32_t)n * (uint32_t)p.U + u];
-      else Sl = static_cast<const float*>(p.S16)[(uint32_t)n * (uint32_t)p.U + u];
-      Sl = valid ? Sl : 0.f;
+      if constexpr (!FUSED) {
+        if constexpr (IS_INT) Sl = (float)static_cast<const int*>(p.S16)[(uint32_t)n * (uint32_t)p.U + u];
+        else Sl = static_cast<const float*>(p.S16)[(uint32_t)n * (uint32_t)p.U + u];
+        Sl = valid ? Sl : 0.f;
+      }
     } else if constexpr (GM == 2) {
       // one {scale, zero} per lane: row pos of the tile, quantisation group of chunk c
       const uint32_t gq = p.q_magic ? __umulhi(c, p.q_magic) : c;  // c / (chunks per group), exact for c < 2^16
       const uint32_t* szw = reinterpret_cast<const uint32_t*>(p.sz);
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) szr[rt] = szw[(tile[rt] * (uint32_t)p.nq + gq) * 8 + pos];
-      if constexpr (IS_INT) Sl = (float)static_cast<const int*>(p.S128)[(uint32_t)n * ((uint32_t)p.U >> 3) + c];
-      else Sl = static_cast<const float*>(p.S128)[(uint32_t)n * ((uint32_t)p.U >> 3) + c];
-      Sl = valid ? Sl : 0.f;
+      if constexpr (!FUSED) {
+        if constexpr (IS_INT) Sl = (float)static_cast<const int*>(p.S128)[(uint32_t)n * ((uint32_t)p.U >> 3) + c];
+        else Sl = static_cast<const float*>(p.S128)[(uint32_t)n * ((uint32_t)p.U >> 3) + c];
+        Sl = valid ? Sl : 0.f;
+      }
     }
 
-    // 2. the lane's four tables, already split into low-byte and high-byte permute sources
+    // 3. the lane's four tables as low-byte and high-byte permute sources: read from the LUT
+    // buffer, or built here (mirror half: entries 0..7, i.e. the fourth activation subtracted)
     uint32_t lo0[4], lo1[4], hi0[4], hi1[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      const uint32_t slot = valid ? ((uint32_t)n * (uint32_t)p.U + u0) * 4 + (uint32_t)t * nu + l : p.ht_zero;
-      const pu32x4 d = p.ht[slot];
-      lo0[t] = d.x; lo1[t] = d.y; hi0[t] = d.z; hi1[t] = d.w;
+      if constexpr (!FUSED) {
+        const uint32_t slot = valid ? ((uint32_t)n * (uint32_t)p.U + u0) * 4 + (uint32_t)t * nu + l : p.ht_zero;
+        const pu32x4 d = p.ht[slot];
+        lo0[t] = d.x; lo1[t] = d.y; hi0[t] = d.z; hi1[t] = d.w;
+      } else {
+        float e[8];
+        if constexpr (IS_INT) {
+          const int x0 = ai[4 * t], x1 = ai[4 * t + 1], x2 = ai[4 * t + 2], x3 = ai[4 * t + 3];
+#pragma unroll
+          for (int q = 0; q < 8; ++q)
+            e[q] = (float)((((q & 1) ? x0 : -x0) + ((q & 2) ? x1 : -x1)) + (((q & 4) ? x2 : -x2) - x3));  // exact
+        } else {
+          const float x0 = af[4 * t], x1 = af[4 * t + 1], x2 = af[4 * t + 2], x3 = af[4 * t + 3];
+#pragma unroll
+          for (int q = 0; q < 8; ++q)
+            e[q] = (((q & 1) ? x0 : -x0) + ((q & 2) ? x1 : -x1)) + (((q & 4) ? x2 : -x2) - x3);
+        }
+        uint32_t pk[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          h2 v;
+          v.x = (_Float16)e[2 * i];
+          v.y = (_Float16)e[2 * i + 1];
+          pk[i] = __builtin_bit_cast(uint32_t, v);
+        }
+        lo0[t] = bperm(pk[1], pk[0], 0x06040200u);
+        lo1[t] = bperm(pk[3], pk[2], 0x06040200u);
+        hi0[t] = bperm(pk[1], pk[0], 0x07050301u);
+        hi1[t] = bperm(pk[3], pk[2], 0x07050301u);
+      }
     }
 
-    // 3. packed indices of this lane: 16*BITS bytes per tile.  The block's records are stored
+    // 4. packed indices of this lane: 16*BITS bytes per tile.  The block's records are stored
     // piece-major: 16-byte piece i of slot l sits at i*nu + l, so every load instruction of the
     // wavefront reads one contiguous run.
     uint32_t w[RT][4 * BITS];
@@ -220,7 +305,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
 
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      // 4. accumulators: GM 1 starts at the bias term, GM 0 continues the raw sums
+      // 5. accumulators: GM 1 starts at the bias term, GM 0 continues the raw sums
       float acc[8];
 #pragma unroll
       for (int r = 0; r < 8; ++r) {
@@ -234,7 +319,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
         }
       }
 
-      // 5. lookups
+      // 6. lookups
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         // four lookups of table t: selector bytes `sel` (0..7 each), sign bits `sgn` at bit 7 of each byte
@@ -292,7 +377,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
         }
       }
 
-      // 6. scale: once per (row, lane) in GM 1, once per (row, chunk) in GM 2
+      // 7. scale: once per (row, lane) in GM 1, once per (row, chunk) in GM 2
       if constexpr (GM == 1) {
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
@@ -311,7 +396,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
     }
   }
 
-  // 7. cross-lane sums: lane 8*r publishes row r of each tile
+  // 8. cross-lane sums: lane 8*r publishes row r of each tile
   constexpr bool RAW_INT = (GM == 0 && IS_INT);
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
@@ -325,11 +410,23 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
       else red[wave * NR + row] = v;
     }
   }
+  if constexpr (FUSED && GM == 0) {
+    // the wave's sum of activations (exact for ints: below 2^24)
+    const float t8[8] = {Stot, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const float sw = reduce_lo3(reduce_hi3(t8, lane));  // lanes 0..7 hold the total
+    if (lane == 0) redS[wave] = sw;
+  }
   __syncthreads();
 
-  // 8. wave 0 sums the waves with a fixed tree (lane = 8*slot + row: waves slot and slot + 8, then
+  // 9. wave 0 sums the waves with a fixed tree (lane = 8*slot + row: waves slot and slot + 8, then
   // the slots), finishes and stores
   if (wave != 0) return;
+  if constexpr (FUSED && GM == 0) {
+    float st = 0.f;
+    for (int wv = 0; wv < NW; ++wv) st += redS[wv];  // wave order
+    fin_Sf = st;
+    fin_Si = (int)st;
+  }
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
     const int r = 8 * rt + (int)jl;   // row of this lane
@@ -383,42 +480,45 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
   }
 }
 
-template <bool IS_INT, int BITS, int GM, int RT>
+template <bool IS_INT, int BITS, int GM, int RT, bool FUSED>
 static hipError_t launch_one(const PermParams& p, int NW, hipStream_t st) {
   PermParams local = p;
   void* args[] = {&local};
-  return hipLaunchKernel(reinterpret_cast<const void*>(mpgemv_perm_kernel<IS_INT, BITS, GM, RT>),
+  return hipLaunchKernel(reinterpret_cast<const void*>(mpgemv_perm_kernel<IS_INT, BITS, GM, RT, FUSED>),
                          dim3((p.n_tiles + RT - 1) / RT, p.N), dim3(NW * 64), args, 0, st);
 }
 
+// rt: row tiles per workgroup (1 or 2); the fused kernel is built for one tile per workgroup
 template <bool IS_INT, int BITS, int GM>
-static hipError_t launch_rt(const PermParams& p, int rt, int NW, hipStream_t st) {
-  return rt == 2 ? launch_one<IS_INT, BITS, GM, 2>(p, NW, st) : launch_one<IS_INT, BITS, GM, 1>(p, NW, st);
+static hipError_t launch_rt(const PermParams& p, int rt, bool fused, int NW, hipStream_t st) {
+  if (fused) return launch_one<IS_INT, BITS, GM, 1, true>(p, NW, st);
+  return rt == 2 ? launch_one<IS_INT, BITS, GM, 2, false>(p, NW, st) : launch_one<IS_INT, BITS, GM, 1, false>(p, NW, st);
 }
 
 template <bool IS_INT, int BITS>
-static hipError_t launch_gm(const PermParams& p, int gm, int rt, int NW, hipStream_t st) {
+static hipError_t launch_gm(const PermParams& p, int gm, int rt, bool fused, int NW, hipStream_t st) {
   switch (gm) {
-    case 0: return launch_rt<IS_INT, BITS, 0>(p, rt, NW, st);
-    case 1: return launch_rt<IS_INT, BITS, 1>(p, rt, NW, st);
-    default: return launch_rt<IS_INT, BITS, 2>(p, rt, NW, st);
+    case 0: return launch_rt<IS_INT, BITS, 0>(p, rt, fused, NW, st);
+    case 1: return launch_rt<IS_INT, BITS, 1>(p, rt, fused, NW, st);
+    default: return launch_rt<IS_INT, BITS, 2>(p, rt, fused, NW, st);
   }
 }
 
 template <bool IS_INT>
-static hipError_t launch_bits(const PermParams& p, int bits, int gm, int rt, int NW, hipStream_t st) {
+static hipError_t launch_bits(const PermParams& p, int bits, int gm, int rt, bool fused, int NW, hipStream_t st) {
   switch (bits) {
-    case 1: return launch_gm<IS_INT, 1>(p, gm, rt, NW, st);
-    case 2: return launch_gm<IS_INT, 2>(p, gm, rt, NW, st);
-    case 3: return launch_gm<IS_INT, 3>(p, gm, rt, NW, st);
-    case 4: return launch_gm<IS_INT, 4>(p, gm, rt, NW, st);
+    case 1: return launch_gm<IS_INT, 1>(p, gm, rt, fused, NW, st);
+    case 2: return launch_gm<IS_INT, 2>(p, gm, rt, fused, NW, st);
+    case 3: return launch_gm<IS_INT, 3>(p, gm, rt, fused, NW, st);
+    case 4: return launch_gm<IS_INT, 4>(p, gm, rt, fused, NW, st);
   }
   return hipErrorInvalidValue;
 }
 
-int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, int lut_is_int,
-                     int N, const float* act_scale_dev, float weight_scale, void* out_dev, int out_t,
-                     int64_t ldo, void* stream, int rows_per_group) {
+int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, const void* A_dev,
+                     int64_t lda, int lut_is_int, int N, const float* act_scale_dev, float weight_scale,
+                     void* out_dev, int out_t, int64_t ldo, void* stream, int rows_per_group) {
+  const bool fused = (lut_dev == nullptr);
   const Geometry ge = geometry(desc);
   LutGeom lg;
   if (!lut_geom(N, desc->K, desc->g, desc->group, &lg)) return TMAC_EINVAL;
@@ -432,11 +532,15 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
   const char* blob = static_cast<const char*>(packed_dev);
   p.idx = reinterpret_cast<const pu32x4*>(blob + ge.idx_off);
   p.sz = reinterpret_cast<const pu32x4*>(blob + ge.sz_off);
-  p.ht = reinterpret_cast<const pu32x4*>(static_cast<const char*>(lut_dev) + lg.ht_off);
+  const char* lut = static_cast<const char*>(lut_dev);
+  p.ht = fused ? nullptr : reinterpret_cast<const pu32x4*>(lut + lg.ht_off);
   p.ht_zero = (uint32_t)((size_t)N * lg.U * 4);
-  p.S = static_cast<const char*>(lut_dev) + lg.s_off;
-  p.S16 = static_cast<const char*>(lut_dev) + lg.s16_off;
-  p.S128 = static_cast<const char*>(lut_dev) + lg.s128_off;
+  p.S = fused ? nullptr : lut + lg.s_off;
+  p.S16 = fused ? nullptr : lut + lg.s16_off;
+  p.S128 = fused ? nullptr : lut + lg.s128_off;
+  p.A = A_dev;
+  p.lda = lda;
+  p.K = desc->K;
   p.out = out_dev;
   p.act_scale = act_scale_dev;
   p.ldo = ldo;
@@ -475,8 +579,8 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
     if (d >= 65536u || lg.U >= 65536) return TMAC_EUNSUPPORTED;
     p.q_magic = d == 1 ? 0u : (uint32_t)((4294967296ull + d - 1) / d);
   }
-  const hipError_t e = lut_is_int ? launch_bits<true>(p, desc->bits, gm, rt, NW, st)
-                                  : launch_bits<false>(p, desc->bits, gm, rt, NW, st);
+  const hipError_t e = lut_is_int ? launch_bits<true>(p, desc->bits, gm, rt, fused, NW, st)
+                                  : launch_bits<false>(p, desc->bits, gm, rt, fused, NW, st);
   if (e != hipSuccess) {
     note_hip_error((int)e);
     return TMAC_EHIP;

@@ -5,7 +5,9 @@ Bars: integer path bit-exact; fp16-table path within 2e-3 relative Frobenius err
 fp64 product (the rounding of table entries to fp16 alone costs a few 1e-4).
 
 Every case runs in both packed layouts where both apply: layout 1 feeds the LDS-table kernels
-(K-sliced and full-K), layout 2 the register-table decode kernel."""
+(K-sliced and full-K), layout 2 the register-table decode kernel, called either as
+tmac_precompute_lut + tmac_mpgemm ("regs") or as the single fused launch tmac_mpgemv_fused
+("fused")."""
 import numpy as np
 import pytest
 
@@ -16,6 +18,7 @@ pytestmark = pytest.mark.gpu
 
 FP_TOL = 2e-3
 L1, L2 = 1, 2
+LF = 3   # layout 2 through the fused entry point
 
 
 @pytest.fixture(scope="module")
@@ -31,13 +34,17 @@ def torch():
     return torch
 
 
-@pytest.fixture(params=[L1, L2], ids=["lds", "regs"])
+@pytest.fixture(params=[L1, L2, LF], ids=["lds", "regs", "fused"])
 def layout(request):
     return request.param
 
 
 def make_lin(p, layout):
     from paper_2407_00088_amd.runner import from_problem, layout_supports_group
+    if layout == LF:
+        if p.K % 16 != 0:
+            pytest.skip("the fused entry point needs K % 16 == 0")
+        layout = L2
     if not layout_supports_group(layout, p.K, p.group):
         pytest.skip(f"group {p.group} not supported by layout {layout}")
     return from_problem(p, layout=layout)
@@ -46,7 +53,11 @@ def make_lin(p, layout):
 def run_fp(T, torch, p, out_t=None, tuning=None, layout=L1):
     lin = make_lin(p, layout)
     A = torch.from_numpy(p.act).cuda()
-    out = lin.forward(A, out_t=T.TMAC_OUT_F32 if out_t is None else out_t, tuning=tuning)
+    if layout == LF:
+        assert tuning is None
+        out = lin.forward_fused(A, out_t=T.TMAC_OUT_F32 if out_t is None else out_t)
+    else:
+        out = lin.forward(A, out_t=T.TMAC_OUT_F32 if out_t is None else out_t, tuning=tuning)
     torch.cuda.synchronize()
     return out.cpu().numpy()
 
@@ -70,7 +81,11 @@ def run_int(T, torch, p, out_t, tuning=None, layout=L1):
     lin = make_lin(p, layout)
     A = torch.from_numpy(p.act_q).cuda()
     s_a = torch.from_numpy(p.act_scale).cuda()
-    out = lin.forward(A, out_t=out_t, act_scale=s_a, tuning=tuning)
+    if layout == LF:
+        assert tuning is None
+        out = lin.forward_fused(A, out_t=out_t, act_scale=s_a)
+    else:
+        out = lin.forward(A, out_t=out_t, act_scale=s_a, tuning=tuning)
     torch.cuda.synchronize()
     return out.cpu().numpy()
 
@@ -333,3 +348,31 @@ def test_register_kernel_rows_per_group(T, torch, rows, bits, group, M, K):
 def test_register_kernel_rows_per_group_int(T, torch, rows):
     from paper_2407_00088_amd.binding import tmac_tuning
     check_int(T, torch, wl.make_ternary(0, 420 + rows, 3, 200, 2240), tuning=tmac_tuning(0, 0, 0, rows), layout=L2)
+
+
+# ----------------------------------------------------------- fused entry point ----
+
+@pytest.mark.parametrize("bits,group,M,K,N", [(4, 128, 200, 1408, 2), (2, 64, 72, 1024, 1), (3, 256, 41, 768, 3),
+                                              (1, 16, 24, 1040, 1), (4, 128, 64, 11008, 1)])
+def test_fused_equals_two_call_path_bitwise(T, torch, bits, group, M, K, N):
+    """With group scales the fused kernel builds the same table entries and chunk sums as the
+    precompute kernel and adds in the same order: results are identical bit for bit."""
+    p = wl.make_grouped(0, 500 + bits, N, M, K, bits, group, name=f"fused_w{bits}_g{group}")
+    two = run_fp(T, torch, p, layout=L2)
+    one = run_fp(T, torch, p, layout=LF)
+    assert orc.rel_frobenius(one, oracle_fp(p)) <= FP_TOL
+    assert np.array_equal(one.view(np.uint32), two.view(np.uint32))
+
+
+def test_fused_rejects_what_it_cannot_do(T, torch):
+    from paper_2407_00088_amd import binding as B
+    p = wl.make_grouped(0, 510, 1, 16, 136, 2, 8)
+    A = torch.from_numpy(p.act).cuda()
+    out = torch.empty((1, 16), dtype=torch.float32, device="cuda")
+    for layout, K in ((L1, 128), (L2, 136)):
+        q = p.q[:, :K]
+        d = B.wdesc(16, K, 2, 0, 1.0, layout=layout)
+        packed = torch.from_numpy(B.tmac_pack_weights(d, q)).cuda()
+        with pytest.raises(T.TmacError) as e:
+            B.tmac_mpgemv_fused(d, packed, A, 1, out, B.TMAC_OUT_F32, lda=K)
+        assert e.value.status in (B.TMAC_EUNSUPPORTED, B.TMAC_EINVAL)
