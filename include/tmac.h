@@ -228,6 +228,13 @@ tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed_dev, const
                            void* workspace_dev, size_t workspace_bytes, void* stream,
                            const tmac_tuning* tuning);
 
+/* Same as tmac_mpgemv_fused with explicit launch-shape knobs (NULL = defaults; only
+ * rows_per_group applies). */
+tmac_status tmac_mpgemv_fused_ex(const tmac_wdesc* desc, const void* packed_dev, const void* A_dev,
+                                 tmac_act_t act, int32_t N, int64_t lda, const float* act_scale_dev,
+                                 float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
+                                 void* stream, const tmac_tuning* tuning);
+
 /* Measurement helper, not part of the mpGEMM path (Section 5.2 notes that multi-threaded mpGEMV
  * is bound by memory bandwidth: this is the plain streaming read the lookup kernels are compared
  * with).  Reads `bytes` bytes from src_dev with 16-byte loads, `per_thread` (1, 4 or 8) loads in

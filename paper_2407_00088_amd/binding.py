@@ -27,7 +27,7 @@ TMAC_LAYOUT_R8U16 = 2     # register-table decode kernel (small N)
 EXPORTS = [
     "tmac_packed_bytes", "tmac_pack_weights", "tmac_lut_bytes", "tmac_precompute_lut",
     "tmac_workspace_bytes", "tmac_mpgemm", "tmac_mpgemm_ex", "tmac_status_str", "tmac_version",
-    "tmac_last_error_detail", "tmac_stream_read", "tmac_mpgemv_fused",
+    "tmac_last_error_detail", "tmac_stream_read", "tmac_mpgemv_fused", "tmac_mpgemv_fused_ex",
 ]
 
 
@@ -75,6 +75,8 @@ def _load() -> C.CDLL:
                                    C.POINTER(tmac_tuning)]
     lib.tmac_mpgemv_fused.restype = C.c_int
     lib.tmac_mpgemv_fused.argtypes = [D, P, P, C.c_int, I32, I64, P, F, P, C.c_int, I64, P]
+    lib.tmac_mpgemv_fused_ex.restype = C.c_int
+    lib.tmac_mpgemv_fused_ex.argtypes = [D, P, P, C.c_int, I32, I64, P, F, P, C.c_int, I64, P, C.POINTER(tmac_tuning)]
     lib.tmac_status_str.restype, lib.tmac_status_str.argtypes = C.c_char_p, [C.c_int]
     lib.tmac_version.restype, lib.tmac_version.argtypes = I32, []
     lib.tmac_last_error_detail.restype, lib.tmac_last_error_detail.argtypes = C.c_char_p, []
@@ -190,7 +192,7 @@ def tmac_mpgemm(desc: tmac_wdesc, packed, lut_buf, lut: int, N: int, out, out_t:
 
 def tmac_mpgemv_fused(desc: tmac_wdesc, packed, A, N: int, out, out_t: int, act: Optional[int] = None,
                       lda: Optional[int] = None, act_scale=None, weight_scale: float = 1.0,
-                      ldo: Optional[int] = None, stream=None) -> None:
+                      ldo: Optional[int] = None, stream=None, tuning: Optional[tmac_tuning] = None) -> None:
     """packed / A / out / act_scale: device tensors; A fp16 or int8 [N, K]."""
     import torch
     if act is None:
@@ -200,9 +202,12 @@ def tmac_mpgemv_fused(desc: tmac_wdesc, packed, A, N: int, out, out_t: int, act:
     if ldo is None:
         ldo = out.stride(0) if out.dim() == 2 else desc.M
     as_ptr = C.c_void_p(act_scale.data_ptr()) if act_scale is not None else None
-    _check(lib.tmac_mpgemv_fused(C.byref(desc), C.c_void_p(packed.data_ptr()), C.c_void_p(A.data_ptr()), act, N,
-                                 lda, as_ptr, C.c_float(weight_scale), C.c_void_p(out.data_ptr()), out_t, ldo,
-                                 _stream_ptr(stream)), "tmac_mpgemv_fused")
+    args = [C.byref(desc), C.c_void_p(packed.data_ptr()), C.c_void_p(A.data_ptr()), act, N, lda, as_ptr,
+            C.c_float(weight_scale), C.c_void_p(out.data_ptr()), out_t, ldo, _stream_ptr(stream)]
+    if tuning is None:
+        _check(lib.tmac_mpgemv_fused(*args), "tmac_mpgemv_fused")
+    else:
+        _check(lib.tmac_mpgemv_fused_ex(*args, C.byref(tuning)), "tmac_mpgemv_fused_ex")
 
 
 # ---------------------------------------------------------------------------------------

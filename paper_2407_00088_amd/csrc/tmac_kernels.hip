@@ -901,10 +901,10 @@ extern "C" tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed
   return e == hipSuccess ? TMAC_OK : TMAC_EHIP;
 }
 
-extern "C" tmac_status tmac_mpgemv_fused(const tmac_wdesc* desc, const void* packed_dev, const void* A_dev,
-                                         tmac_act_t act, int32_t N, int64_t lda, const float* act_scale_dev,
-                                         float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
-                                         void* stream) {
+extern "C" tmac_status tmac_mpgemv_fused_ex(const tmac_wdesc* desc, const void* packed_dev, const void* A_dev,
+                                            tmac_act_t act, int32_t N, int64_t lda, const float* act_scale_dev,
+                                            float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
+                                            void* stream, const tmac_tuning* tuning) {
   if (!desc_valid(desc) || !packed_dev || !A_dev || !out_dev || N <= 0) return TMAC_EINVAL;
   if (act != TMAC_ACT_F16 && act != TMAC_ACT_I8) return TMAC_EINVAL;
   if (out != TMAC_OUT_F32 && out != TMAC_OUT_F16 && out != TMAC_OUT_I32) return TMAC_EINVAL;
@@ -915,9 +915,23 @@ extern "C" tmac_status tmac_mpgemv_fused(const tmac_wdesc* desc, const void* pac
   if (lda % row_elems_16B != 0) return TMAC_EINVAL;
   if (desc->layout != TMAC_LAYOUT_R8U16 || desc->K % 16 != 0) return TMAC_EUNSUPPORTED;
   if (!group_supported(desc)) return TMAC_EUNSUPPORTED;
+  int rpg = 0;
+  if (tuning) {
+    if (tuning->kernel != 0 || tuning->chunks_per_wave != 0 || tuning->n_tile != 0) return TMAC_EUNSUPPORTED;
+    rpg = tuning->rows_per_group;
+    if (rpg != 0 && rpg != 8 && rpg != 16) return TMAC_EINVAL;
+  }
   return static_cast<tmac_status>(launch_perm_gemv(desc, packed_dev, nullptr, A_dev, lda, act == TMAC_ACT_I8 ? 1 : 0,
                                                     N, act_scale_dev, weight_scale, out_dev, (int)out, ldo,
-                                                    stream, 8));
+                                                    stream, rpg));
+}
+
+extern "C" tmac_status tmac_mpgemv_fused(const tmac_wdesc* desc, const void* packed_dev, const void* A_dev,
+                                         tmac_act_t act, int32_t N, int64_t lda, const float* act_scale_dev,
+                                         float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
+                                         void* stream) {
+  return tmac_mpgemv_fused_ex(desc, packed_dev, A_dev, act, N, lda, act_scale_dev, weight_scale, out_dev, out, ldo,
+                              stream, nullptr);
 }
 
 extern "C" tmac_status tmac_mpgemm(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev,

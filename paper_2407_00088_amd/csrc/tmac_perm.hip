@@ -176,54 +176,9 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
     const uint32_t c = valid ? c0 + jl : c0;        // 128-k chunk of this lane
     const uint32_t u = 8u * c + pos;                // 16-k unit of this lane
 
-    // 1. in fused mode: the lane's 16 activations (zero past the end of K and for idle lanes)
-    float af[16];
-    int ai[16];
-    if constexpr (FUSED) {
-      const bool have = valid && 16u * u < (uint32_t)p.K;
-      if constexpr (IS_INT) {
-        pu32x4 v = {0u, 0u, 0u, 0u};
-        if (have) v = *reinterpret_cast<const pu32x4*>(static_cast<const int8_t*>(p.A) + (size_t)n * p.lda + 16u * u);
-        const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int i = 0; i < 16; ++i) ai[i] = (int)(int8_t)(vv[i >> 2] >> (8 * (i & 3)));
-      } else {
-        pu32x4 v0 = {0u, 0u, 0u, 0u}, v1 = {0u, 0u, 0u, 0u};
-        if (have) {
-          const pu32x4* ap = reinterpret_cast<const pu32x4*>(static_cast<const __half*>(p.A) + (size_t)n * p.lda + 16u * u);
-          v0 = ap[0];
-          v1 = ap[1];
-        }
-        const uint32_t vv[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-#pragma unroll
-        for (int i = 0; i < 16; ++i) af[i] = __half2float(__ushort_as_half((uint16_t)(vv[i >> 1] >> (16 * (i & 1)))));
-      }
-    }
-
-    // 2. scale and zero, and the activation sum the bias term needs
+    // 1. scale and zero, and (from the LUT buffer) the activation sum the bias term needs
     uint32_t szr[GM == 1 ? NR : RT];
     float Sl = 0.f;
-    if constexpr (FUSED) {
-      // sum of the lane's 16 activations, in the order of the precompute kernel's tree
-      if constexpr (IS_INT) {
-        int s16 = 0;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s16 += ai[i];
-        Sl = (float)s16;  // |s16| <= 16 * 128
-      } else {
-        float t4[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) t4[t] = ((af[4 * t] + af[4 * t + 1]) + af[4 * t + 2]) + af[4 * t + 3];
-        Sl = (t4[0] + t4[1]) + (t4[2] + t4[3]);
-      }
-      if constexpr (GM == 0) Stot += Sl;
-      if constexpr (GM == 2) {
-        // sum over the chunk's eight lanes (lane bits 3, 4, 5), pairing units as the precompute kernel does
-        Sl += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(Sl), 0x128, 0xf, 0xf, false));  // row_ror:8
-        Sl += __shfl_xor(Sl, 16);
-        Sl += __shfl_xor(Sl, 32);
-      }
-    }
     if constexpr (GM == 1) {
       uint32_t gq = p.q_magic ? __umulhi(u, p.q_magic) : u;  // u / (units per group), exact for u < 2^16
       gq = gq < (uint32_t)p.nq ? gq : (uint32_t)p.nq - 1;  // units in the K padding: tables and S16 are zero
@@ -252,27 +207,102 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
       }
     }
 
-    // 3. the lane's four tables as low-byte and high-byte permute sources: read from the LUT
-    // buffer, or built here (mirror half: entries 0..7, i.e. the fourth activation subtracted)
+    // 1b. in fused mode: the lane's 16 activations (zero past the end of K and for idle lanes), raw;
+    // they are unpacked only after the index loads have been requested
+    uint32_t araw[8];  // fp16: two per dword; int8: four per dword (one table each) in araw[0..3]
+    if constexpr (FUSED) {
+      const bool have = valid && 16u * u < (uint32_t)p.K;
+      pu32x4 v0 = {0u, 0u, 0u, 0u}, v1 = {0u, 0u, 0u, 0u};
+      if constexpr (IS_INT) {
+        if (have) v0 = *reinterpret_cast<const pu32x4*>(static_cast<const int8_t*>(p.A) + (size_t)n * p.lda + 16u * u);
+      } else {
+        if (have) {
+          const pu32x4* ap = reinterpret_cast<const pu32x4*>(static_cast<const __half*>(p.A) + (size_t)n * p.lda + 16u * u);
+          v0 = ap[0];
+          v1 = ap[1];
+        }
+      }
+      araw[0] = v0.x; araw[1] = v0.y; araw[2] = v0.z; araw[3] = v0.w;
+      araw[4] = v1.x; araw[5] = v1.y; araw[6] = v1.z; araw[7] = v1.w;
+    }
+
+    // 2. tables from the LUT buffer (requested before the indices: they are needed first)
     uint32_t lo0[4], lo1[4], hi0[4], hi1[4];
+    if constexpr (!FUSED) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      if constexpr (!FUSED) {
+      for (int t = 0; t < 4; ++t) {
         const uint32_t slot = valid ? ((uint32_t)n * (uint32_t)p.U + u0) * 4 + (uint32_t)t * nu + l : p.ht_zero;
         const pu32x4 d = p.ht[slot];
         lo0[t] = d.x; lo1[t] = d.y; hi0[t] = d.z; hi1[t] = d.w;
+      }
+    }
+
+    // 3. packed indices of this lane: 16*BITS bytes per tile.  The block's records are stored
+    // piece-major: 16-byte piece i of slot l sits at i*nu + l, so every load instruction of the
+    // wavefront reads one contiguous run.
+    uint32_t w[RT][4 * BITS];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const pu32x4* src = p.idx + (tile[rt] * (uint32_t)p.U + u0) * BITS + l;
+#pragma unroll
+      for (int i = 0; i < BITS; ++i) {
+        const pu32x4 v = __builtin_nontemporal_load(src + i * nu);
+        w[rt][4 * i + 0] = v.x; w[rt][4 * i + 1] = v.y; w[rt][4 * i + 2] = v.z; w[rt][4 * i + 3] = v.w;
+      }
+    }
+
+    // every load of this block is requested above this line; keep the scheduler from sinking index
+    // loads below the first use of the activations
+    if constexpr (FUSED) __builtin_amdgcn_sched_barrier(0);
+
+    // 4. fused mode: unpack the activations; the activation sum the bias term needs
+    float af[16];
+    if constexpr (FUSED && !IS_INT) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) af[i] = __half2float(__ushort_as_half((uint16_t)(araw[i >> 1] >> (16 * (i & 1)))));
+    }
+    if constexpr (FUSED) {
+      // sum of the lane's 16 activations, in the order of the precompute kernel's tree
+      if constexpr (IS_INT) {
+        int s16 = 0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) s16 = __builtin_amdgcn_sdot4((int)araw[t], 0x01010101, s16, false);
+        Sl = (float)s16;  // |s16| <= 16 * 128
       } else {
+        float t4[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) t4[t] = ((af[4 * t] + af[4 * t + 1]) + af[4 * t + 2]) + af[4 * t + 3];
+        Sl = (t4[0] + t4[1]) + (t4[2] + t4[3]);
+      }
+      if constexpr (GM == 0) Stot += Sl;
+      if constexpr (GM == 2) {
+        // sum over the chunk's eight lanes (lane bits 3, 4, 5), pairing units as the precompute kernel does
+        Sl += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(Sl), 0x128, 0xf, 0xf, false));  // row_ror:8
+        Sl += __shfl_xor(Sl, 16);
+        Sl += __shfl_xor(Sl, 32);
+      }
+    }
+    // 4b. fused mode: build the four tables while the indices are in flight (mirror half: entries
+    // 0..7, i.e. the fourth activation subtracted), as low-byte and high-byte permute sources
+    if constexpr (FUSED) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
         float e[8];
         if constexpr (IS_INT) {
-          const int x0 = ai[4 * t], x1 = ai[4 * t + 1], x2 = ai[4 * t + 2], x3 = ai[4 * t + 3];
+          // entry q = sum_j (bit j of q ? +a_j : -a_j), a_3 subtracted: a signed dot product with +-1 bytes
 #pragma unroll
-          for (int q = 0; q < 8; ++q)
-            e[q] = (float)((((q & 1) ? x0 : -x0) + ((q & 2) ? x1 : -x1)) + (((q & 4) ? x2 : -x2) - x3));  // exact
+          for (int q = 0; q < 8; ++q) {
+            const int sg = (int)(((q & 1) ? 0x01u : 0xFFu) | ((q & 2) ? 0x0100u : 0xFF00u) |
+                                 ((q & 4) ? 0x010000u : 0xFF0000u) | 0xFF000000u);
+            e[q] = (float)__builtin_amdgcn_sdot4((int)araw[t], sg, 0, false);  // exact
+          }
         } else {
+          // (+-x0 +- x1) + (+-x2 - x3): negating a sum negates its rounded value, so four adds give the
+          // pair sums and one add each the entries, with the bits of the stand-alone precompute kernel
           const float x0 = af[4 * t], x1 = af[4 * t + 1], x2 = af[4 * t + 2], x3 = af[4 * t + 3];
-#pragma unroll
-          for (int q = 0; q < 8; ++q)
-            e[q] = (((q & 1) ? x0 : -x0) + ((q & 2) ? x1 : -x1)) + (((q & 4) ? x2 : -x2) - x3);
+          const float sp = x0 + x1, dp = x0 - x1, tq = x2 + x3, wq = x2 - x3;
+          e[0] = -sp - tq; e[1] = dp - tq; e[2] = -dp - tq; e[3] = sp - tq;
+          e[4] = wq - sp;  e[5] = dp + wq; e[6] = wq - dp;  e[7] = sp + wq;
         }
         uint32_t pk[4];
 #pragma unroll
@@ -286,20 +316,6 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
         lo1[t] = bperm(pk[3], pk[2], 0x06040200u);
         hi0[t] = bperm(pk[1], pk[0], 0x07050301u);
         hi1[t] = bperm(pk[3], pk[2], 0x07050301u);
-      }
-    }
-
-    // 4. packed indices of this lane: 16*BITS bytes per tile.  The block's records are stored
-    // piece-major: 16-byte piece i of slot l sits at i*nu + l, so every load instruction of the
-    // wavefront reads one contiguous run.
-    uint32_t w[RT][4 * BITS];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      const pu32x4* src = p.idx + (tile[rt] * (uint32_t)p.U + u0) * BITS + l;
-#pragma unroll
-      for (int i = 0; i < BITS; ++i) {
-        const pu32x4 v = __builtin_nontemporal_load(src + i * nu);
-        w[rt][4 * i + 0] = v.x; w[rt][4 * i + 1] = v.y; w[rt][4 * i + 2] = v.z; w[rt][4 * i + 3] = v.w;
       }
     }
 
@@ -488,10 +504,11 @@ static hipError_t launch_one(const PermParams& p, int NW, hipStream_t st) {
                          dim3((p.n_tiles + RT - 1) / RT, p.N), dim3(NW * 64), args, 0, st);
 }
 
-// rt: row tiles per workgroup (1 or 2); the fused kernel is built for one tile per workgroup
+// rt: row tiles per workgroup (1 or 2)
 template <bool IS_INT, int BITS, int GM>
 static hipError_t launch_rt(const PermParams& p, int rt, bool fused, int NW, hipStream_t st) {
-  if (fused) return launch_one<IS_INT, BITS, GM, 1, true>(p, NW, st);
+  if (fused)
+    return rt == 2 ? launch_one<IS_INT, BITS, GM, 2, true>(p, NW, st) : launch_one<IS_INT, BITS, GM, 1, true>(p, NW, st);
   return rt == 2 ? launch_one<IS_INT, BITS, GM, 2, false>(p, NW, st) : launch_one<IS_INT, BITS, GM, 1, false>(p, NW, st);
 }
 

@@ -50,17 +50,18 @@ class LinearLUT:
                       out_t, workspace=self.workspace, act_scale=act_scale, weight_scale=self.weight_scale,
                       stream=stream, tuning=tuning)
 
-    def mpgemv_fused(self, A, N: int, out, out_t: int = B.TMAC_OUT_F32, act_scale=None, stream=None, packed=None):
+    def mpgemv_fused(self, A, N: int, out, out_t: int = B.TMAC_OUT_F32, act_scale=None, stream=None, packed=None,
+                     tuning=None):
         """One launch: tables built inside the lookup kernel (layout 2 only)."""
         B.tmac_mpgemv_fused(self.desc, self.packed if packed is None else packed, A, N, out, out_t,
-                            act_scale=act_scale, weight_scale=self.weight_scale, stream=stream)
+                            act_scale=act_scale, weight_scale=self.weight_scale, stream=stream, tuning=tuning)
 
-    def forward_fused(self, A, out_t: int = B.TMAC_OUT_F32, act_scale=None):
+    def forward_fused(self, A, out_t: int = B.TMAC_OUT_F32, act_scale=None, tuning=None):
         torch = self.torch
         N = A.shape[0]
         dt = {B.TMAC_OUT_F32: torch.float32, B.TMAC_OUT_F16: torch.float16, B.TMAC_OUT_I32: torch.int32}[out_t]
         out = torch.empty((N, self.M), dtype=dt, device=self.device)
-        self.mpgemv_fused(A, N, out, out_t, act_scale=act_scale)
+        self.mpgemv_fused(A, N, out, out_t, act_scale=act_scale, tuning=tuning)
         return out
 
     def forward(self, A, out_t: int = B.TMAC_OUT_F32, act_scale=None, tuning=None):

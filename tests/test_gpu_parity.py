@@ -54,8 +54,7 @@ def run_fp(T, torch, p, out_t=None, tuning=None, layout=L1):
     lin = make_lin(p, layout)
     A = torch.from_numpy(p.act).cuda()
     if layout == LF:
-        assert tuning is None
-        out = lin.forward_fused(A, out_t=T.TMAC_OUT_F32 if out_t is None else out_t)
+        out = lin.forward_fused(A, out_t=T.TMAC_OUT_F32 if out_t is None else out_t, tuning=tuning)
     else:
         out = lin.forward(A, out_t=T.TMAC_OUT_F32 if out_t is None else out_t, tuning=tuning)
     torch.cuda.synchronize()
@@ -82,8 +81,7 @@ def run_int(T, torch, p, out_t, tuning=None, layout=L1):
     A = torch.from_numpy(p.act_q).cuda()
     s_a = torch.from_numpy(p.act_scale).cuda()
     if layout == LF:
-        assert tuning is None
-        out = lin.forward_fused(A, out_t=out_t, act_scale=s_a)
+        out = lin.forward_fused(A, out_t=out_t, act_scale=s_a, tuning=tuning)
     else:
         out = lin.forward(A, out_t=out_t, act_scale=s_a, tuning=tuning)
     torch.cuda.synchronize()
@@ -315,19 +313,17 @@ def test_full_k_kernel_rejects_what_it_cannot_do(T, torch):
 
 # ------------------------------------- register-table kernel launch shapes ----
 
+@pytest.mark.parametrize("fused", [False, True], ids=["regs", "fused"])
 @pytest.mark.parametrize("rows", [8, 16])
 @pytest.mark.parametrize("bits,group,M,K", [(4, 128, 200, 1408), (2, 64, 72, 1024), (3, 0, 41, 640),
                                             (1, 1040, 24, 1040), (4, 128, 8, 17408)])
-def test_register_kernel_rows_per_group(T, torch, rows, bits, group, M, K):
+def test_register_kernel_rows_per_group(T, torch, rows, bits, group, M, K, fused):
     """8 or 16 weight rows per workgroup (an odd number of 8-row tiles leaves the second tile of
     the last workgroup empty); K = 17408 walks two blocks of units per wave."""
     from paper_2407_00088_amd.binding import tmac_tuning
 
     def run(p, tun):
-        lin = make_lin(p, L2)
-        out = lin.forward(torch.from_numpy(p.act).cuda(), tuning=tun)
-        torch.cuda.synchronize()
-        return out.cpu().numpy()
+        return run_fp(T, torch, p, tuning=tun, layout=LF if fused else L2)
 
     N = 2
     if group == 0:
@@ -344,10 +340,12 @@ def test_register_kernel_rows_per_group(T, torch, rows, bits, group, M, K):
     assert np.array_equal(got.view(np.uint32), other.view(np.uint32))
 
 
+@pytest.mark.parametrize("fused", [False, True], ids=["regs", "fused"])
 @pytest.mark.parametrize("rows", [8, 16])
-def test_register_kernel_rows_per_group_int(T, torch, rows):
+def test_register_kernel_rows_per_group_int(T, torch, rows, fused):
     from paper_2407_00088_amd.binding import tmac_tuning
-    check_int(T, torch, wl.make_ternary(0, 420 + rows, 3, 200, 2240), tuning=tmac_tuning(0, 0, 0, rows), layout=L2)
+    check_int(T, torch, wl.make_ternary(0, 420 + rows, 3, 200, 2240), tuning=tmac_tuning(0, 0, 0, rows),
+              layout=LF if fused else L2)
 
 
 # ----------------------------------------------------------- fused entry point ----
