@@ -1,10 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the LUT mpGEMV hot path on one MI355X.
 
-A step = one pass of the whole hot path (tmac_precompute_lut + tmac_mpgemm) over the three
-Llama-2-7B-shaped W4A16 decode GEMVs (N=1; M x K = 4096x4096, 11008x4096, 4096x11008;
-group 128), inputs resident in HBM.  Every shape cycles through a ring of distinct packed
-weight copies larger than twice the 256 MB Infinity Cache, so weights come from HBM.
+A step = one pass of the whole hot path (table precompute, lookup, bit-plane accumulate, scale
+and zero, reduce, store) over the three Llama-2-7B-shaped W4A16 decode GEMVs (N=1; M x K =
+4096x4096, 11008x4096, 4096x11008; group 128), inputs resident in HBM.  By default every GEMV
+is ONE launch of tmac_mpgemv_fused (tables built inside the lookup kernel); --two-call times
+tmac_precompute_lut + tmac_mpgemm instead.  Every shape cycles through a ring of distinct
+packed weight copies larger than twice the 256 MB Infinity Cache, so weights come from HBM.
 
 Launches are replayed from HIP graphs (captured once, outside the timed region) so that the
 host-side cost of issuing ~3 us kernels from Python does not hide the GPU time; the timed
@@ -29,6 +31,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 RING_MB = 576  # > 2 x 256 MB Infinity Cache
 
+# HBM bytes of the three launches of one step (default configuration: fused kernel, 8 rows per
+# workgroup), from two rocprofv3 --pmc passes (FETCH_SIZE, then WRITE_SIZE), each dispatch's
+# counter scaled by what the same counter reads for the plain read kernel on a blob of the same
+# size (2093 / 2051 bytes per count); summary under profiles/.
+MEASURED_TRAFFIC_BYTES = {"fetch": [9.26e6, 24.14e6, 24.28e6], "write": [16384, 44032, 16384]}
+
 
 def algorithmic_bytes(M, K, bits, group, N=1, act_bytes=2, out_bytes=4):
     """Bytes the method must move per call: packed indices + scales and zeros + activations + output."""
@@ -51,6 +59,8 @@ def main():
     ap.add_argument("--ks", type=int, default=0, help="layout 1: tmac_tuning.chunks_per_wave override")
     ap.add_argument("--sweep", action="store_true", help="also time the W1..W4 and BitNet shapes")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead of graph replay")
+    ap.add_argument("--two-call", action="store_true",
+                    help="step = tmac_precompute_lut + tmac_mpgemm (two launches per GEMV) instead of the fused call")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -77,11 +87,11 @@ def main():
     sink = torch.zeros(256, dtype=torch.uint8, device=dev)
 
     class Case:
-        def __init__(self, p):
+        def __init__(self, p, layout=None, ring_mb=None):
             self.p = p
-            self.lin = from_problem(p, layout=args.layout)
+            self.lin = from_problem(p, layout=args.layout if layout is None else layout)
             self.bytes = algorithmic_bytes(p.M, p.K, p.bits, p.group, p.N, act_bytes=1 if p.int_path else 2)
-            n_copies = max(2, (args.ring_mb << 20) // self.lin.packed_bytes + 1)
+            n_copies = max(2, ((args.ring_mb if ring_mb is None else ring_mb) << 20) // self.lin.packed_bytes + 1)
             self.ring = [self.lin.packed] + [self.lin.packed.clone() for _ in range(n_copies - 1)]
             self.A = torch.from_numpy(p.act_q if p.int_path else p.act).to(dev)
             self.s_a = torch.from_numpy(p.act_scale).to(dev) if p.int_path else None
@@ -95,6 +105,12 @@ def main():
             packed = self.ring[self.i % len(self.ring)]
             self.i += 1
             self.lin.mpgemm(self.p.N, self.out, T.TMAC_OUT_F32, act_scale=self.s_a, tuning=tuning, packed=packed)
+
+        def fused(self):
+            packed = self.ring[self.i % len(self.ring)]
+            self.i += 1
+            self.lin.mpgemv_fused(self.A, self.p.N, self.out, T.TMAC_OUT_F32, act_scale=self.s_a, packed=packed,
+                                  tuning=tuning)
 
         def stream_read(self):
             """Plain read of the same packed bytes: what a read-only kernel reaches on this ring."""
@@ -148,10 +164,15 @@ def main():
     cases = [Case(wl.config2(i)) for i in range(3)]
     step_bytes = sum(c.bytes for c in cases)
 
+    fused = (args.layout == 2 and not args.two_call)
+
     def step():
         for c in cases:
-            c.precompute()
-            c.mpgemm()
+            if fused:
+                c.fused()
+            else:
+                c.precompute()
+                c.mpgemm()
 
     reps = max(ring_len(c) for c in cases)
     launches = max(1, args.steps // reps)
@@ -160,17 +181,22 @@ def main():
     ms_per_step = step_us * 1e-3
     value = step_bytes / (step_us * 1e-6) / 1e9
 
-    # dominant kernel: the lookup kernel alone, back-to-back over the weight ring
-    per_us = [measure_kernel(c, args.steps) for c in cases]
+    # dominant kernel: the lookup kernel alone (the fused one when the step uses it), back-to-back
+    # over the weight ring
+    mp_us = [measure_kernel(c, args.steps) for c in cases]
+    fu_us = [measure_kernel(c, args.steps, c.fused) for c in cases] if args.layout == 2 else [None] * 3
+    per_us = fu_us if fused else mp_us
     achieved = sum(c.bytes for c in cases) / (sum(per_us) * 1e-6) / 1e9
     pre_us = [timed(Replay(c.precompute, 50), max(1, args.steps // 50), 2) for c in cases]
     read_us = [measure_kernel(c, args.steps, c.stream_read) for c in cases]
     detail = {"shapes": []}
-    for c, us, pu, ru in zip(cases, per_us, pre_us, read_us):
+    for c, us, fu, pu, ru in zip(cases, mp_us, fu_us, pre_us, read_us):
+        dom = fu if fused else us
         detail["shapes"].append({"M": c.p.M, "K": c.p.K, "bits": c.p.bits, "mpgemm_us": round(us, 3),
+                                 "fused_us": None if fu is None else round(fu, 3),
                                  "precompute_us": round(pu, 3), "bytes": c.bytes,
-                                 "GBps": round(c.bytes / us / 1e3, 1),
-                                 "frac_hbm_peak": round(c.bytes / us / 1e3 / HBM_PEAK_GBPS, 4),
+                                 "GBps": round(c.bytes / dom / 1e3, 1),
+                                 "frac_hbm_peak": round(c.bytes / dom / 1e3 / HBM_PEAK_GBPS, 4),
                                  "plain_read_of_same_bytes_us": round(ru, 3)})
 
     if args.sweep:
@@ -181,13 +207,37 @@ def main():
         for p in extra:
             c = Case(p)
             us = measure_kernel(c, args.steps)
+            fu = measure_kernel(c, args.steps, c.fused) if args.layout == 2 else None
             pu = timed(Replay(c.precompute, 50), max(1, args.steps // 50), 2)
-            sweep.append({"name": p.name, "bits": p.bits, "mpgemm_us": round(us, 3), "precompute_us": round(pu, 3),
+            ru = measure_kernel(c, args.steps, c.stream_read)
+            sweep.append({"name": p.name, "bits": p.bits, "mpgemm_us": round(us, 3),
+                          "fused_us": None if fu is None else round(fu, 3), "precompute_us": round(pu, 3),
+                          "plain_read_of_same_bytes_us": round(ru, 3),
                           "bytes": c.bytes, "GBps": round(c.bytes / us / 1e3, 1),
                           "frac_hbm_peak": round(c.bytes / us / 1e3 / HBM_PEAK_GBPS, 4)})
             del c
             torch.cuda.empty_cache()
         detail["sweep"] = sweep
+        # prefill mpGEMM, N = 256 (LDS-table kernel, layout 1): precompute + mpgemm per call
+        prefill = []
+        for bits in (2, 4):
+            for i in range(3):
+                p = wl.config5(i, bits)
+                c = Case(p, layout=1, ring_mb=0)
+
+                def both(c=c):
+                    c.precompute()
+                    c.mpgemm()
+                us = timed(Replay(both, 2), 10, 2)
+                pu = timed(Replay(c.precompute, 2), 10, 2)
+                flops = 2.0 * p.N * p.M * p.K
+                prefill.append({"name": p.name, "bits": bits, "N": p.N, "call_us": round(us, 2),
+                                "precompute_us": round(pu, 2),
+                                "TOPS_equiv": round(flops / us / 1e6, 2),
+                                "lookups_per_s": round(p.N * p.M * (p.K / 4) * bits / us * 1e6, -6)})
+                del c
+                torch.cuda.empty_cache()
+        detail["prefill_n256"] = prefill
         xs = np.array([s["bits"] for s in sweep[:4]], dtype=np.float64)
         ys = np.array([s["mpgemm_us"] for s in sweep[:4]], dtype=np.float64)
         cfit, t0fit = np.polyfit(xs, ys, 1)
@@ -230,15 +280,21 @@ def main():
         "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": "configs[1]: Llama-2-7B-shaped W4A16 decode GEMV, N=1, "
-                               "(M,K) in {(4096,4096),(11008,4096),(4096,11008)}, group 128; "
-                               "step = precompute_lut + mpgemm for the three shapes, weights cycled "
-                               f"through a {args.ring_mb} MiB ring per shape",
+                               "(M,K) in {(4096,4096),(11008,4096),(4096,11008)}, group 128; step = "
+                               + ("one fused launch (table precompute + lookup) per shape"
+                                  if fused else "precompute_lut + mpgemm per shape")
+                               + f" for the three shapes, weights cycled through a {args.ring_mb} MiB ring per shape",
                    "launch": "eager" if args.no_graph else "hip graph replay",
                    "frac_hbm_peak_whole_step": round(value / HBM_PEAK_GBPS, 4)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                     "kernel": ("mpgemv_perm_kernel<f16 tables, 4 bit, group scales>" if args.layout == 2
-                                else "mpgemv_fullk_kernel<f16 tables, 4 bit, group scales>"),
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": (sum(MEASURED_TRAFFIC_BYTES["fetch"]) + sum(MEASURED_TRAFFIC_BYTES["write"])
+                                 if (fused and not args.rows) else None),
+                     "traffic_unit": "bytes per step (three launches), rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated",
+                     "algorithmic_bytes": step_bytes,
+                     "kernel": (("mpgemv_perm_kernel<f16 tables, 4 bit, chunk scales, 8 rows, "
+                                 + ("fused table build>" if fused else "tables from the LUT buffer>"))
+                                if args.layout == 2 else "mpgemv_fullk_kernel<f16 tables, 4 bit, group scales>"),
                      "launch_us": [round(u, 3) for u in per_us]},
         "cpu_baseline": cpu,
         "detail": detail,

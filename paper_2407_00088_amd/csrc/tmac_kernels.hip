@@ -154,17 +154,25 @@ __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict_
     if (wave >= N * nq) return;
     const int n = wave / nq, gq = wave % nq;
     const int64_t base = n * lda + (int64_t)gq * Geff;
+    // four elements per lane and step (the row base, lda and the group size are multiples of 4)
     if constexpr (IS_INT) {
-      const int8_t* a = static_cast<const int8_t*>(A_) + base;
+      const uint32_t* a = reinterpret_cast<const uint32_t*>(static_cast<const int8_t*>(A_) + base);
       int s = 0;
-      for (int k = lane; k < Geff; k += 64) s += a[k];
+      for (int k4 = lane; 4 * k4 < Geff; k4 += 64) s = __builtin_amdgcn_sdot4((int)a[k4], 0x01010101, s, false);
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
       if (lane == 0) static_cast<int*>(S_)[wave] = s;
     } else {
-      const __half* a = static_cast<const __half*>(A_) + base;
+      const uint2* a = reinterpret_cast<const uint2*>(static_cast<const __half*>(A_) + base);
       float s = 0.f;
-      for (int k = lane; k < Geff; k += 64) s += __half2float(a[k]);
+      for (int k4 = lane; 4 * k4 < Geff; k4 += 64) {
+        const uint2 v = a[k4];
+        const float a0 = __half2float(__ushort_as_half((uint16_t)(v.x & 0xffffu)));
+        const float a1 = __half2float(__ushort_as_half((uint16_t)(v.x >> 16)));
+        const float a2 = __half2float(__ushort_as_half((uint16_t)(v.y & 0xffffu)));
+        const float a3 = __half2float(__ushort_as_half((uint16_t)(v.y >> 16)));
+        s += (a0 + a1) + (a2 + a3);
+      }
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
       if (lane == 0) static_cast<float*>(S_)[wave] = s;
