@@ -252,8 +252,8 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
     }
 
     // every load of this block is requested above this line; keep the scheduler from sinking index
-    // loads below the first use of the activations
-    if constexpr (FUSED) __builtin_amdgcn_sched_barrier(0);
+    // loads below the first lookups (or, in fused mode, the first use of the activations)
+    __builtin_amdgcn_sched_barrier(0);
 
     // 4. fused mode: unpack the activations; the activation sum the bias term needs
     float af[16];
