@@ -273,3 +273,69 @@ def quantize_tables_int8(lut, lut_groups_per_qgroup):
     scale = np.where(amax > 0, amax / 127.0, 1.0)
     qt = np.clip(np.rint(t / scale[:, :, None]), -127, 127).astype(np.int64)
     return qt.reshape(N, KG, P), scale
+
+
+def quantize_tables_int8_per_unit(lut, tables_per_unit=4):
+    """int8 table quantisation with one dynamic scale per unit of ``tables_per_unit``
+    consecutive tables (16 activations for g = 4): scale = max|T| / 127 over the unit,
+    entries rint(T / scale) clipped to +-127 (Section 3.3 "table quantization": fine-grained,
+    dynamic; the granularity and the rounding are this build's reading).  The tables of a
+    unit share a scale so that their looked-up entries can be added as integers.
+    Returns (int8 tables as int64 [N, KG, P], scales fp64 [N, KG / tables_per_unit]);
+    K/g must be a multiple of tables_per_unit (pad the activations with zeros first)."""
+    N, KG, P = lut.shape
+    assert KG % tables_per_unit == 0
+    nu = KG // tables_per_unit
+    t = lut.astype(np.float64).reshape(N, nu, tables_per_unit * P)
+    amax = np.abs(t).max(axis=2)
+    scale = amax / 127.0
+    safe = np.where(amax > 0, scale, 1.0)
+    qt = np.clip(np.rint(t / safe[:, :, None]), -127, 127).astype(np.int64)
+    return qt.reshape(N, KG, P), scale
+
+
+def lut_mpgemm_tq(act, q, bits, scales=None, zeros=None, group=0, weight_scale=1.0,
+                  zero_point=0.0, g=4, tables_per_unit=4):
+    """LUT route with int8-quantised tables (Section 3.3): as ``lut_mpgemm`` but every table
+    entry is replaced by scale_unit * rint(T / scale_unit); the bias term keeps the exact
+    activation sums.  Look-ups of one unit are added as integers, converted once and
+    multiplied by the unit's scale."""
+    q = np.asarray(q)
+    M, K = q.shape
+    A = np.asarray(act).astype(np.float64)
+    unit = g * tables_per_unit
+    Kp = (K + unit - 1) // unit * unit
+    if Kp != K:                      # zero activations and zero codes: contribute nothing
+        A = np.concatenate([A, np.zeros((A.shape[0], Kp - K))], axis=1)
+        q = np.concatenate([q, np.zeros((M, Kp - K), dtype=q.dtype)], axis=1)
+    G = K if group == 0 else group
+    assert K % G == 0 and G % g == 0
+    nq = K // G
+    if group == 0:
+        s = np.full((M, 1), np.float64(weight_scale))
+        z = np.full((M, 1), np.float64(zero_point))
+    else:
+        s = np.asarray(scales).astype(np.float64)
+        z = np.asarray(zeros).astype(np.float64)
+    lut = precompute_lut(A, g)                                     # exact, fp64
+    qt, usc = quantize_tables_int8_per_unit(lut, tables_per_unit)
+    deq = qt.astype(np.float64) * np.repeat(usc, tables_per_unit, axis=1)[:, :, None]
+    S = group_sums(A[:, :K], G).astype(np.float64)
+    mid = (2.0 ** bits - 1.0) / 2.0
+    N = A.shape[0]
+    # per-LUT-group partial results, then summed per quantisation group (a unit never straddles
+    # a quantisation group when G is a multiple of g * tables_per_unit; otherwise the tables of a
+    # unit are still looked up one by one, so the split is by table)
+    KG = Kp // g
+    contrib = np.zeros((N, M, KG), dtype=np.float64)
+    kg_range = np.arange(KG)
+    for i, plane in enumerate(bit_planes(q, bits)):
+        idx = group_indices(plane, g)                              # [M, KG]
+        for n in range(N):
+            contrib[n] += (2.0 ** i) * deq[n][kg_range[None, :], idx]
+    R = np.zeros((N, M), dtype=np.float64)
+    for gq in range(nq):
+        k0, k1 = gq * G // g, (gq + 1) * G // g
+        L = contrib[:, :, k0:k1].sum(axis=2)
+        R += s[None, :, gq] * (0.5 * L + (mid - z[None, :, gq]) * S[:, gq][:, None])
+    return R
