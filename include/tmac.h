@@ -53,8 +53,13 @@ typedef enum { TMAC_ACT_F16 = 0, TMAC_ACT_I8 = 1 } tmac_act_t;
  *   TMAC_LUT_F16: entries are the fp32 signed sums of fp16 activations rounded once to fp16
  *                 (results within 2e-3 relative Frobenius error of the fp64 product).
  *   TMAC_LUT_I16: entries are exact int16 sums of int8 activations (|T| <= 4*127); all
- *                 aggregation is int32 and the result is bit-exact. */
-typedef enum { TMAC_LUT_F16 = 0, TMAC_LUT_I16 = 1 } tmac_lut_t;
+ *                 aggregation is int32 and the result is bit-exact.
+ *   TMAC_LUT_I8Q: table quantisation (Section 3.3): entries of fp16 activations' tables rounded
+ *                 to int8 with one dynamic scale per 16 activations (four tables),
+ *                 scale = max|T| / 127; the look-ups of those four tables are added as
+ *                 integers and multiplied by the scale once.  Lossy (about 4e-3 relative
+ *                 error on Gaussian data); packed layout 2 only. */
+typedef enum { TMAC_LUT_F16 = 0, TMAC_LUT_I16 = 1, TMAC_LUT_I8Q = 2 } tmac_lut_t;
 
 /* TMAC_OUT_I32 (raw integer dot products) is available with TMAC_LUT_I16 and a
  * per-tensor scale (group == 0) with an integer zero point only. */
@@ -153,7 +158,8 @@ tmac_status tmac_pack_weights(const tmac_wdesc* desc, const uint8_t* q_host,
                               void* packed_host, size_t packed_bytes);
 
 /* Bytes of the LUT buffer for N activation rows: tables [N][Kp/4][16] (2 bytes each, k
- * padded to 128 with all-zero tables), then the group sums S[N][n_qgroups], then the sums
+ * padded to 128 with all-zero tables; absent for TMAC_LUT_I8Q, which has unit scales [N][Kp/16]
+ * and one-byte half tables instead), then the group sums S[N][n_qgroups], then the sums
  * of every 16 consecutive activations S16[N][Kp/16] (both fp32 for TMAC_LUT_F16, int32 for
  * TMAC_LUT_I16), the sums of every 128 consecutive activations S128[N][Kp/128] (same type) and
  * the mirror-consolidated byte-split half tables of the register-table kernel, each region
@@ -164,7 +170,7 @@ size_t tmac_lut_bytes(int32_t N, int32_t K, int32_t g, int32_t group, tmac_lut_t
  * Section 3.3 is used to compute half of the entries and negate them for the rest):
  *   T[n,kg,p] = sum_{j<4} (bit j of p ? +a : -a)[n, 4kg+j],  S[n,G] = sum_{k in G} a[n,k].
  *   A_dev  [N,K] row-major with leading dimension lda (elements): fp16 or int8
- *   TMAC_ACT_F16 requires TMAC_LUT_F16, TMAC_ACT_I8 requires TMAC_LUT_I16.
+ *   TMAC_ACT_F16 goes with TMAC_LUT_F16 or TMAC_LUT_I8Q, TMAC_ACT_I8 with TMAC_LUT_I16.
  * Errors: TMAC_EINVAL, TMAC_ESIZE, TMAC_EHIP. */
 tmac_status tmac_precompute_lut(const void* A_dev, tmac_act_t act, int32_t N, int32_t K,
                                 int64_t lda, int32_t g, int32_t group, tmac_lut_t lut,

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libtmac_hip.so")
 
 TMAC_OK, TMAC_EINVAL, TMAC_EUNSUPPORTED, TMAC_ESIZE, TMAC_EHIP = range(5)
 TMAC_ACT_F16, TMAC_ACT_I8 = 0, 1
-TMAC_LUT_F16, TMAC_LUT_I16 = 0, 1
+TMAC_LUT_F16, TMAC_LUT_I16, TMAC_LUT_I8Q = 0, 1, 2
 TMAC_OUT_F32, TMAC_OUT_F16, TMAC_OUT_I32 = 0, 1, 2
 TMAC_LAYOUT_T16K128 = 1   # LDS-table kernels (any N)
 TMAC_LAYOUT_R8U16 = 2     # register-table decode kernel (small N)

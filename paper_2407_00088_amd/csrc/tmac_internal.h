@@ -33,28 +33,35 @@ struct LutGeom {
   int Kp, KG, nq;       // K padded to 128, tables per row, quantisation groups per row (>= 1)
   int Geff;             // elements per quantisation group (K when one group per row/tensor)
   int U;                // 16-k units per row (Kp / 16)
+  int ht_slots;         // 16-byte slots per unit in the half-table region: 4 (fp16) or 2 (int8)
   size_t s_off;         // byte offset of the group sums S[N][nq]
   size_t s16_off;       // byte offset of the unit sums S16[N][U]
   size_t s128_off;      // byte offset of the 128-k chunk sums S128[N][U/8]
-  size_t ht_off;        // byte offset of the fp16 half tables HT[N][U][4][8], piece-major per block
+  size_t usc_off;       // int8 tables only: byte offset of the unit scales [N][U] (fp32)
+  size_t ht_off;        // byte offset of the half tables, piece-major per block
   size_t total;
 };
 
-inline bool lut_geom(int N, int K, int g, int group, LutGeom* lg) {
+// lut_t: a tmac_lut_t value.  The 16-entry tables [N][KG][16] at offset 0 (read by the LDS
+// kernels) exist for the 16-bit table types only.
+inline bool lut_geom(int N, int K, int g, int group, int lut_t, LutGeom* lg) {
   if (N <= 0 || K <= 0 || g != 4 || K % 4 != 0 || group < 0) return false;
   if (group > 0 && (K % group != 0 || group % 4 != 0)) return false;
+  const bool q8 = (lut_t == TMAC_LUT_I8Q);
   lg->Kp = round_up(K, 128);
   lg->KG = lg->Kp / 4;
   lg->U = lg->Kp / 16;
   lg->Geff = (group == 0) ? K : group;
   lg->nq = K / lg->Geff;
-  const size_t tab = (size_t)N * lg->KG * 16 * 2;
+  lg->ht_slots = q8 ? 2 : 4;
+  const size_t tab = q8 ? 0 : (size_t)N * lg->KG * 16 * 2;
   lg->s_off = (tab + 255) / 256 * 256;
   lg->s16_off = (lg->s_off + (size_t)N * lg->nq * 4 + 255) / 256 * 256;
   lg->s128_off = (lg->s16_off + (size_t)N * lg->U * 4 + 255) / 256 * 256;
-  lg->ht_off = (lg->s128_off + (size_t)N * (lg->U / 8) * 4 + 255) / 256 * 256;
+  lg->usc_off = (lg->s128_off + (size_t)N * (lg->U / 8) * 4 + 255) / 256 * 256;
+  lg->ht_off = q8 ? (lg->usc_off + (size_t)N * lg->U * 4 + 255) / 256 * 256 : lg->usc_off;
   // one extra all-zero 16-byte slot (in a 256-byte tail) for lanes that own no unit
-  lg->total = (lg->ht_off + (size_t)N * lg->U * 64 + 256 + 255) / 256 * 256;
+  lg->total = (lg->ht_off + (size_t)N * lg->U * 16 * lg->ht_slots + 256 + 255) / 256 * 256;
   return true;
 }
 
@@ -93,9 +100,10 @@ TMAC_HD inline int block_slot(int u, int c0, int ng) { return (u & 7) * ng + ((u
 
 // Register-table decode kernel (layout 2); defined in tmac_perm.hip.  Arguments are those of
 // tmac_mpgemm after validation; with lut_dev == nullptr the kernel builds its tables itself from
-// the activations A_dev (leading dimension lda).  Returns a tmac_status value.
+// the activations A_dev (leading dimension lda).  lut_t is a tmac_lut_t value.  Returns a
+// tmac_status value.
 int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, const void* A_dev,
-                     int64_t lda, int lut_is_int, int N, const float* act_scale_dev, float weight_scale,
+                     int64_t lda, int lut_t, int N, const float* act_scale_dev, float weight_scale,
                      void* out_dev, int out_t, int64_t ldo, void* stream, int rows_per_group);
 
 // Records the last HIP error of this thread (diagnostics for TMAC_EHIP).

@@ -46,6 +46,40 @@ typedef __attribute__((address_space(3))) __half lds_f16;
 // ------------------------------------------------------------------------------------------
 // Table precompute
 // ------------------------------------------------------------------------------------------
+// One wavefront per (n, quantisation group): the group sum S[n][gq] = sum of its activations,
+// four elements per lane and step (the row base, lda and the group size are multiples of 4),
+// then a butterfly.
+template <bool IS_INT>
+__device__ __forceinline__ void group_sums_wave(const void* __restrict__ A_, int N, int64_t lda,
+                                                void* __restrict__ S_, int Geff, int nq, int wave) {
+  const int lane = threadIdx.x & 63;
+  if (wave >= N * nq) return;
+  const int n = wave / nq, gq = wave % nq;
+  const int64_t base = n * lda + (int64_t)gq * Geff;
+  if constexpr (IS_INT) {
+    const uint32_t* a = reinterpret_cast<const uint32_t*>(static_cast<const int8_t*>(A_) + base);
+    int s = 0;
+    for (int k4 = lane; 4 * k4 < Geff; k4 += 64) s = __builtin_amdgcn_sdot4((int)a[k4], 0x01010101, s, false);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (lane == 0) static_cast<int*>(S_)[wave] = s;
+  } else {
+    const uint2* a = reinterpret_cast<const uint2*>(static_cast<const __half*>(A_) + base);
+    float s = 0.f;
+    for (int k4 = lane; 4 * k4 < Geff; k4 += 64) {
+      const uint2 v = a[k4];
+      const float a0 = __half2float(__ushort_as_half((uint16_t)(v.x & 0xffffu)));
+      const float a1 = __half2float(__ushort_as_half((uint16_t)(v.x >> 16)));
+      const float a2 = __half2float(__ushort_as_half((uint16_t)(v.y & 0xffffu)));
+      const float a3 = __half2float(__ushort_as_half((uint16_t)(v.y >> 16)));
+      s += (a0 + a1) + (a2 + a3);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (lane == 0) static_cast<float*>(S_)[wave] = s;
+  }
+}
+
 template <bool IS_INT>
 __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict__ A_, int N, int K,
                                                          int64_t lda, int KG,
@@ -148,36 +182,86 @@ __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict_
       if ((kg & 31) == 0) static_cast<float*>(S128_)[tid >> 5] = sum4f;
     }
   } else {
-    // one wavefront per (n, quantisation group): strided partial sums, then a butterfly
-    const int wave = ((int)blockIdx.x - n_tab_blocks) * 4 + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (wave >= N * nq) return;
-    const int n = wave / nq, gq = wave % nq;
-    const int64_t base = n * lda + (int64_t)gq * Geff;
-    // four elements per lane and step (the row base, lda and the group size are multiples of 4)
-    if constexpr (IS_INT) {
-      const uint32_t* a = reinterpret_cast<const uint32_t*>(static_cast<const int8_t*>(A_) + base);
-      int s = 0;
-      for (int k4 = lane; 4 * k4 < Geff; k4 += 64) s = __builtin_amdgcn_sdot4((int)a[k4], 0x01010101, s, false);
+    group_sums_wave<IS_INT>(A_, N, lda, S_, Geff, nq, ((int)blockIdx.x - n_tab_blocks) * 4 + (threadIdx.x >> 6));
+  }
+}
+
+// Table quantisation (Section 3.3): one thread per unit of 16 activations builds the mirror halves
+// of its four tables in fp32 (same sums as above), takes the unit's largest magnitude
+// amax = max_t sum_j |a_j| (attained by the entry whose signs match), and stores
+// rint(T * 127 / amax) as int8 together with the scale amax / 127.  Per unit: two 16-byte pieces
+// (tables 0,1 and 2,3; eight entries of one byte each), laid out like the fp16 half tables.
+__global__ __launch_bounds__(256) void precompute_q8_kernel(const __half* __restrict__ A, int N, int K, int64_t lda,
+                                                            int U, float* __restrict__ S, float* __restrict__ S16,
+                                                            float* __restrict__ S128, float* __restrict__ usc,
+                                                            uint4* __restrict__ HTQ, int Geff, int nq,
+                                                            int n_unit_blocks) {
+  if ((int)blockIdx.x >= n_unit_blocks) {
+    group_sums_wave<false>(A, N, lda, S, Geff, nq, ((int)blockIdx.x - n_unit_blocks) * 4 + (threadIdx.x >> 6));
+    return;
+  }
+  const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (tid >= (int64_t)N * U) return;  // N*U is a multiple of 8: chunks never straddle the cut
+  const int n = (int)(tid / U), u = (int)(tid % U);
+  float a[16];
+  if (16 * u < K) {  // K is a multiple of 4: a unit may end early
+    const __half* ap = A + n * lda + 16 * u;
 #pragma unroll
-      for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
-      if (lane == 0) static_cast<int*>(S_)[wave] = s;
-    } else {
-      const uint2* a = reinterpret_cast<const uint2*>(static_cast<const __half*>(A_) + base);
-      float s = 0.f;
-      for (int k4 = lane; 4 * k4 < Geff; k4 += 64) {
-        const uint2 v = a[k4];
-        const float a0 = __half2float(__ushort_as_half((uint16_t)(v.x & 0xffffu)));
-        const float a1 = __half2float(__ushort_as_half((uint16_t)(v.x >> 16)));
-        const float a2 = __half2float(__ushort_as_half((uint16_t)(v.y & 0xffffu)));
-        const float a3 = __half2float(__ushort_as_half((uint16_t)(v.y >> 16)));
-        s += (a0 + a1) + (a2 + a3);
+    for (int t = 0; t < 4; ++t) {
+      if (16 * u + 4 * t < K) {
+        const uint2 v = *reinterpret_cast<const uint2*>(ap + 4 * t);
+        a[4 * t + 0] = __half2float(__ushort_as_half((uint16_t)(v.x & 0xffffu)));
+        a[4 * t + 1] = __half2float(__ushort_as_half((uint16_t)(v.x >> 16)));
+        a[4 * t + 2] = __half2float(__ushort_as_half((uint16_t)(v.y & 0xffffu)));
+        a[4 * t + 3] = __half2float(__ushort_as_half((uint16_t)(v.y >> 16)));
+      } else {
+        a[4 * t] = a[4 * t + 1] = a[4 * t + 2] = a[4 * t + 3] = 0.f;
       }
+    }
+  } else {
 #pragma unroll
-      for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
-      if (lane == 0) static_cast<float*>(S_)[wave] = s;
+    for (int i = 0; i < 16; ++i) a[i] = 0.f;
+  }
+  float e[4][8], t4[4], amax = 0.f;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const float x0 = a[4 * t], x1 = a[4 * t + 1], x2 = a[4 * t + 2], x3 = a[4 * t + 3];
+    const float sp = x0 + x1, dp = x0 - x1, tq = x2 + x3, wq = x2 - x3;
+    e[t][0] = -sp - tq; e[t][1] = dp - tq; e[t][2] = -dp - tq; e[t][3] = sp - tq;
+    e[t][4] = wq - sp;  e[t][5] = dp + wq; e[t][6] = wq - dp;  e[t][7] = sp + wq;
+    t4[t] = ((x0 + x1) + x2) + x3;
+    amax = fmaxf(amax, (fabsf(x0) + fabsf(x1)) + (fabsf(x2) + fabsf(x3)));
+  }
+  const float inv = amax > 0.f ? 127.0f / amax : 0.f;
+  uint32_t w[8];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      uint32_t word = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        int v = (int)rintf(e[t][4 * h + q] * inv);
+        v = v > 127 ? 127 : (v < -127 ? -127 : v);
+        word |= ((uint32_t)v & 0xffu) << (8 * q);
+      }
+      w[2 * t + h] = word;
     }
   }
+  const BlockSplit bs = block_split(U);
+  const int blk = block_of(bs, u >> 3);
+  const int c0 = block_start(bs, blk), ng = block_start(bs, blk + 1) - c0;
+  uint4* dst = HTQ + ((size_t)n * U + 8 * c0) * 2 + block_slot(u, c0, ng);
+  dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+  dst[8 * ng] = make_uint4(w[4], w[5], w[6], w[7]);
+  if (tid == 0) HTQ[(size_t)N * U * 2] = make_uint4(0, 0, 0, 0);  // the all-zero slot
+  usc[tid] = amax / 127.0f;
+  float s16 = (t4[0] + t4[1]) + (t4[2] + t4[3]);
+  S16[tid] = s16;
+  s16 += __shfl_xor(s16, 1);  // the eight units of a 128-k chunk sit in eight adjacent lanes
+  s16 += __shfl_xor(s16, 2);
+  s16 += __shfl_xor(s16, 4);
+  if ((u & 7) == 0) S128[tid >> 3] = s16;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -766,8 +850,8 @@ using namespace tmac;
 
 extern "C" size_t tmac_lut_bytes(int32_t N, int32_t K, int32_t g, int32_t group, tmac_lut_t lut) {
   LutGeom lg;
-  if (lut != TMAC_LUT_F16 && lut != TMAC_LUT_I16) return 0;
-  if (!lut_geom(N, K, g, group, &lg)) return 0;
+  if (lut != TMAC_LUT_F16 && lut != TMAC_LUT_I16 && lut != TMAC_LUT_I8Q) return 0;
+  if (!lut_geom(N, K, g, group, (int)lut, &lg)) return 0;
   return lg.total;
 }
 
@@ -775,19 +859,30 @@ extern "C" tmac_status tmac_precompute_lut(const void* A_dev, tmac_act_t act, in
                                            int64_t lda, int32_t g, int32_t group, tmac_lut_t lut,
                                            void* lut_dev, size_t lut_bytes, void* stream) {
   if (!A_dev || !lut_dev) return TMAC_EINVAL;
-  if (!((act == TMAC_ACT_F16 && lut == TMAC_LUT_F16) || (act == TMAC_ACT_I8 && lut == TMAC_LUT_I16)))
+  if (!((act == TMAC_ACT_F16 && (lut == TMAC_LUT_F16 || lut == TMAC_LUT_I8Q)) ||
+        (act == TMAC_ACT_I8 && lut == TMAC_LUT_I16)))
     return TMAC_EINVAL;
   LutGeom lg;
-  if (!lut_geom(N, K, g, group, &lg)) return TMAC_EINVAL;
+  if (!lut_geom(N, K, g, group, (int)lut, &lg)) return TMAC_EINVAL;
   if (lda < K) return TMAC_EINVAL;
   if (!aligned16(lut_dev)) return TMAC_EINVAL;
   const uintptr_t a_align = (act == TMAC_ACT_F16) ? 7u : 3u;  // one group of 4 activations per load
   if ((reinterpret_cast<uintptr_t>(A_dev) & a_align) != 0 || (lda % 4) != 0) return TMAC_EINVAL;
   if (lut_bytes < lg.total) return TMAC_ESIZE;
 
+  const int n_sum_blocks = (N * lg.nq + 3) / 4;
+  if (lut == TMAC_LUT_I8Q) {
+    char* base = static_cast<char*>(lut_dev);
+    const int n_unit_blocks = (int)(((int64_t)N * lg.U + 255) / 256);
+    const hipError_t eq = launch(precompute_q8_kernel, dim3(n_unit_blocks + n_sum_blocks), dim3(256), 0,
+                                 static_cast<hipStream_t>(stream), static_cast<const __half*>(A_dev), N, K, lda, lg.U,
+                                 reinterpret_cast<float*>(base + lg.s_off), reinterpret_cast<float*>(base + lg.s16_off),
+                                 reinterpret_cast<float*>(base + lg.s128_off), reinterpret_cast<float*>(base + lg.usc_off),
+                                 reinterpret_cast<uint4*>(base + lg.ht_off), lg.Geff, lg.nq, n_unit_blocks);
+    return eq == hipSuccess ? TMAC_OK : TMAC_EHIP;
+  }
   const int64_t n_items = (int64_t)N * lg.KG;
   const int n_tab_blocks = (int)((n_items + 255) / 256);
-  const int n_sum_blocks = (N * lg.nq + 3) / 4;
   uint4* tables = static_cast<uint4*>(lut_dev);
   void* S = static_cast<char*>(lut_dev) + lg.s_off;
   void* S16 = static_cast<char*>(lut_dev) + lg.s16_off;
@@ -821,9 +916,10 @@ extern "C" tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed
                                       void* workspace_dev, size_t workspace_bytes, void* stream,
                                       const tmac_tuning* tuning) {
   if (!desc_valid(desc) || !packed_dev || !lut_dev || !out_dev || N <= 0) return TMAC_EINVAL;
-  if (lut != TMAC_LUT_F16 && lut != TMAC_LUT_I16) return TMAC_EINVAL;
+  if (lut != TMAC_LUT_F16 && lut != TMAC_LUT_I16 && lut != TMAC_LUT_I8Q) return TMAC_EINVAL;
   if (out != TMAC_OUT_F32 && out != TMAC_OUT_F16 && out != TMAC_OUT_I32) return TMAC_EINVAL;
   if (!aligned16(packed_dev) || !aligned16(lut_dev) || !aligned16(workspace_dev)) return TMAC_EINVAL;
+  if (lut == TMAC_LUT_I8Q && desc->layout != TMAC_LAYOUT_R8U16) return TMAC_EUNSUPPORTED;
   if (ldo < desc->M) return TMAC_EINVAL;
   if (!group_supported(desc)) return TMAC_EUNSUPPORTED;
   if (tuning) {
@@ -833,7 +929,7 @@ extern "C" tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed
   }
   const Geometry ge = geometry(desc);
   LutGeom lg;
-  if (!lut_geom(N, desc->K, desc->g, desc->group, &lg)) return TMAC_EINVAL;
+  if (!lut_geom(N, desc->K, desc->g, desc->group, (int)lut, &lg)) return TMAC_EINVAL;
   const bool is_int = (lut == TMAC_LUT_I16);
   const bool one_group = (desc->group == 0 || desc->group == desc->K);
   if (desc->layout == TMAC_LAYOUT_R8U16) {
@@ -842,7 +938,7 @@ extern "C" tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed
       return TMAC_EUNSUPPORTED;
     const int rpg = tuning ? tuning->rows_per_group : 0;
     if (rpg != 0 && rpg != 8 && rpg != 16) return TMAC_EINVAL;
-    return static_cast<tmac_status>(launch_perm_gemv(desc, packed_dev, lut_dev, nullptr, 0, is_int ? 1 : 0, N,
+    return static_cast<tmac_status>(launch_perm_gemv(desc, packed_dev, lut_dev, nullptr, 0, (int)lut, N,
                                                       act_scale_dev, weight_scale, out_dev, (int)out, ldo,
                                                       stream, rpg));
   }
@@ -929,7 +1025,8 @@ extern "C" tmac_status tmac_mpgemv_fused_ex(const tmac_wdesc* desc, const void* 
     rpg = tuning->rows_per_group;
     if (rpg != 0 && rpg != 8 && rpg != 16) return TMAC_EINVAL;
   }
-  return static_cast<tmac_status>(launch_perm_gemv(desc, packed_dev, nullptr, A_dev, lda, act == TMAC_ACT_I8 ? 1 : 0,
+  return static_cast<tmac_status>(launch_perm_gemv(desc, packed_dev, nullptr, A_dev, lda,
+                                                    act == TMAC_ACT_I8 ? (int)TMAC_LUT_I16 : (int)TMAC_LUT_F16,
                                                     N, act_scale_dev, weight_scale, out_dev, (int)out, ldo,
                                                     stream, rpg));
 }

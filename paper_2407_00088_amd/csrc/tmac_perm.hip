@@ -18,6 +18,10 @@
 //     quantisation group, so acc starts at (mid - z) * S16 (bias term of Section 4's linear
 //     transform, S16 = sum of the lane's 16 activations), collects the half-weighted lookups and
 //     is multiplied by the scale once.
+//   * Table quantisation (Section 3.3, TMAC_LUT_I8Q): one-byte entries need one permute per four
+//     lookups; the negate bits select signed plane weights (+-2^i, again by a byte permute) and
+//     v_dot4_i32_i8 does the shift-accumulate of four planes in integers; the four tables of a
+//     lane share one scale, applied once per (row, lane).
 //   * The integer path reuses the same code: int16 table entries (|T| <= 508) are exact in fp16,
 //     all partial sums are integers below 2^24 and therefore exact in fp32; sums across waves
 //     are taken in int32.
@@ -53,6 +57,7 @@ struct PermParams {
   const void* S;           // [N][nq] fp32 / int32 group sums
   const void* S16;         // [N][U]  fp32 / int32 unit sums
   const void* S128;        // [N][U/8] fp32 / int32 sums of every 128 consecutive activations
+  const float* usc;        // int8 tables: [N][U] scale of the lane's four tables
   const void* A;           // fused mode: activations [N][lda], fp16 or int8 (no LUT buffer is read)
   int64_t lda;
   void* out;
@@ -120,8 +125,10 @@ constexpr uint16_t H_0 = 0x0000, H_05 = 0x3800, H_1 = 0x3C00, H_2 = 0x4000, H_4 
 // (row, 128-k chunk) after the in-chunk reduction (group sizes that are multiples of 128).
 // FUSED: the lane builds the four tables of its unit from the activations itself (Algorithm 1
 // Precompute inside the lookup kernel), with the arithmetic of the stand-alone precompute kernel.
-template <bool IS_INT, int BITS, int GM, int RT, bool FUSED>
+// Q8: int8 tables with one scale per lane-unit (not with IS_INT or FUSED).
+template <bool IS_INT, int BITS, int GM, int RT, bool FUSED, bool Q8>
 __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
+  static_assert(!(Q8 && (IS_INT || FUSED)), "int8 tables: fp16 activations, tables from the LUT buffer");
   constexpr int NR = 8 * RT;
   __shared__ float red[16 * NR];
   __shared__ float redS[16];
@@ -228,7 +235,18 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
 
     // 2. tables from the LUT buffer (requested before the indices: they are needed first)
     uint32_t lo0[4], lo1[4], hi0[4], hi1[4];
-    if constexpr (!FUSED) {
+    float uscale = 0.f;
+    if constexpr (Q8) {
+      // two 16-byte pieces: tables 0,1 and 2,3, eight one-byte entries each (lo0 = entries 0..3,
+      // lo1 = entries 4..7); plus the unit's scale
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const uint32_t slot = valid ? ((uint32_t)n * (uint32_t)p.U + u0) * 2 + (uint32_t)h * nu + l : p.ht_zero;
+        const pu32x4 d = p.ht[slot];
+        lo0[2 * h] = d.x; lo1[2 * h] = d.y; lo0[2 * h + 1] = d.z; lo1[2 * h + 1] = d.w;
+      }
+      uscale = p.usc[(uint32_t)n * (uint32_t)p.U + u];  // idle lanes: an in-range unit; their sums are zero
+    } else if constexpr (!FUSED) {
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         const uint32_t slot = valid ? ((uint32_t)n * (uint32_t)p.U + u0) * 4 + (uint32_t)t * nu + l : p.ht_zero;
@@ -336,6 +354,72 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
       }
 
       // 6. lookups
+      if constexpr (Q8) {
+        // signed plane weights as permute sources: bytes (+1, -1, +2, -2 | +4, -4, +8, -8); the
+        // selector of a byte is 2 * plane + negate
+        constexpr uint32_t WLO = 0xFE02FF01u, WHI = 0xF808FC04u;
+        int ia[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) ia[r] = 0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          auto lookq = [&](uint32_t sel) { return bperm(lo1[t], lo0[t], sel); };
+          // x: a dword of the record; planes: selector base (2 * plane of each byte)
+          auto both = [&](uint32_t x, uint32_t planes, uint32_t& vA, uint32_t& wA, uint32_t& vB, uint32_t& wB) {
+            // the selector base sits in a vector register so that (bits & mask) | base is one
+            // v_and_or_b32 (a VOP3 instruction takes a single literal or scalar operand)
+            uint32_t pv;
+            asm("v_mov_b32 %0, %1" : "=v"(pv) : "s"(planes));
+            vA = lookq(x & 0x07070707u);
+            wA = bperm(WHI, WLO, ((x >> 3) & 0x01010101u) | pv);
+            vB = lookq((x >> 4) & 0x07070707u);
+            wB = bperm(WHI, WLO, ((x >> 7) & 0x01010101u) | pv);
+          };
+          auto dot4 = [&](uint32_t v, uint32_t w, int a) { return __builtin_amdgcn_sdot4((int)v, (int)w, a, false); };
+          auto quadq = [&](uint32_t x, int& a_lo, int& a_hi) {  // 4 planes of one row (low nibbles), one (high)
+            uint32_t vA, wA, vB, wB;
+            both(x, 0x06040200u, vA, wA, vB, wB);
+            a_lo = dot4(vA, wA, a_lo);
+            a_hi = dot4(vB, wB, a_hi);
+          };
+          auto pairq = [&](uint32_t x, int* a4) {  // planes 0,1 of rows 0,1 (low) and 2,3 (high) of a4
+            uint32_t vA, wA, vB, wB;
+            both(x, 0x02000200u, vA, wA, vB, wB);
+            a4[0] = dot4(vA, wA & 0x0000FFFFu, a4[0]);
+            a4[1] = dot4(vA, wA & 0xFFFF0000u, a4[1]);
+            a4[2] = dot4(vB, wB & 0x0000FFFFu, a4[2]);
+            a4[3] = dot4(vB, wB & 0xFFFF0000u, a4[3]);
+          };
+          auto singleq = [&](uint32_t x, uint32_t planes, int* a8) {  // one plane of rows 0..3 (low), 4..7 (high)
+            uint32_t vA, wA, vB, wB;
+            both(x, planes, vA, wA, vB, wB);
+#pragma unroll
+            for (int y = 0; y < 4; ++y) {
+              a8[y] = dot4(vA, wA & (0xFFu << (8 * y)), a8[y]);
+              a8[4 + y] = dot4(vB, wB & (0xFFu << (8 * y)), a8[4 + y]);
+            }
+          };
+          const uint32_t* wt = &w[rt][t * BITS];
+          if constexpr (BITS == 4) {
+#pragma unroll
+            for (int d = 0; d < 4; ++d) quadq(wt[d], ia[2 * d], ia[2 * d + 1]);
+          } else if constexpr (BITS == 2) {
+            pairq(wt[0], ia);
+            pairq(wt[1], ia + 4);
+          } else if constexpr (BITS == 1) {
+            singleq(wt[0], 0x00000000u, ia);
+          } else {
+            pairq(wt[0], ia);
+            pairq(wt[1], ia + 4);
+            singleq(wt[2], 0x04040404u, ia);
+          }
+        }
+        // integer sum of the unit's four tables, converted once and scaled (the scale is halved
+        // together with the plane weights in the group-scale modes)
+        const float us = GM != 0 ? 0.5f * uscale : uscale;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) acc[r] = fmaf((float)ia[r], us, acc[r]);
+      } else {
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         // four lookups of table t: selector bytes `sel` (0..7 each), sign bits `sgn` at bit 7 of each byte
@@ -391,6 +475,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
           pair(wt[1], acc + 4);
           single(wt[2], WS2, acc);
         }
+      }
       }
 
       // 7. scale: once per (row, lane) in GM 1, once per (row, chunk) in GM 2
@@ -496,11 +581,11 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
   }
 }
 
-template <bool IS_INT, int BITS, int GM, int RT, bool FUSED>
+template <bool IS_INT, int BITS, int GM, int RT, bool FUSED, bool Q8 = false>
 static hipError_t launch_one(const PermParams& p, int NW, hipStream_t st) {
   PermParams local = p;
   void* args[] = {&local};
-  return hipLaunchKernel(reinterpret_cast<const void*>(mpgemv_perm_kernel<IS_INT, BITS, GM, RT, FUSED>),
+  return hipLaunchKernel(reinterpret_cast<const void*>(mpgemv_perm_kernel<IS_INT, BITS, GM, RT, FUSED, Q8>),
                          dim3((p.n_tiles + RT - 1) / RT, p.N), dim3(NW * 64), args, 0, st);
 }
 
@@ -510,6 +595,26 @@ static hipError_t launch_rt(const PermParams& p, int rt, bool fused, int NW, hip
   if (fused)
     return rt == 2 ? launch_one<IS_INT, BITS, GM, 2, true>(p, NW, st) : launch_one<IS_INT, BITS, GM, 1, true>(p, NW, st);
   return rt == 2 ? launch_one<IS_INT, BITS, GM, 2, false>(p, NW, st) : launch_one<IS_INT, BITS, GM, 1, false>(p, NW, st);
+}
+
+// int8 tables: one row tile per workgroup, tables from the LUT buffer
+template <int BITS>
+static hipError_t launch_q8(const PermParams& p, int gm, int NW, hipStream_t st) {
+  switch (gm) {
+    case 0: return launch_one<false, BITS, 0, 1, false, true>(p, NW, st);
+    case 1: return launch_one<false, BITS, 1, 1, false, true>(p, NW, st);
+    default: return launch_one<false, BITS, 2, 1, false, true>(p, NW, st);
+  }
+}
+
+static hipError_t launch_q8_bits(const PermParams& p, int bits, int gm, int NW, hipStream_t st) {
+  switch (bits) {
+    case 1: return launch_q8<1>(p, gm, NW, st);
+    case 2: return launch_q8<2>(p, gm, NW, st);
+    case 3: return launch_q8<3>(p, gm, NW, st);
+    case 4: return launch_q8<4>(p, gm, NW, st);
+  }
+  return hipErrorInvalidValue;
 }
 
 template <bool IS_INT, int BITS>
@@ -533,12 +638,15 @@ static hipError_t launch_bits(const PermParams& p, int bits, int gm, int rt, boo
 }
 
 int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, const void* A_dev,
-                     int64_t lda, int lut_is_int, int N, const float* act_scale_dev, float weight_scale,
+                     int64_t lda, int lut_t, int N, const float* act_scale_dev, float weight_scale,
                      void* out_dev, int out_t, int64_t ldo, void* stream, int rows_per_group) {
   const bool fused = (lut_dev == nullptr);
+  const bool q8 = (lut_t == TMAC_LUT_I8Q);
+  const int lut_is_int = (lut_t == TMAC_LUT_I16);
+  if (q8 && (fused || rows_per_group == 16)) return TMAC_EUNSUPPORTED;
   const Geometry ge = geometry(desc);
   LutGeom lg;
-  if (!lut_geom(N, desc->K, desc->g, desc->group, &lg)) return TMAC_EINVAL;
+  if (!lut_geom(N, desc->K, desc->g, desc->group, lut_t, &lg)) return TMAC_EINVAL;
   if (N > 65535) return TMAC_EUNSUPPORTED;
   // 32-bit slot arithmetic inside the kernel
   if ((double)ge.n_tiles * lg.U * desc->bits >= 4294967296.0 || (double)N * lg.U * 4 >= 4294967296.0)
@@ -551,7 +659,8 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
   p.sz = reinterpret_cast<const pu32x4*>(blob + ge.sz_off);
   const char* lut = static_cast<const char*>(lut_dev);
   p.ht = fused ? nullptr : reinterpret_cast<const pu32x4*>(lut + lg.ht_off);
-  p.ht_zero = (uint32_t)((size_t)N * lg.U * 4);
+  p.ht_zero = (uint32_t)((size_t)N * lg.U * lg.ht_slots);
+  p.usc = (fused || !q8) ? nullptr : reinterpret_cast<const float*>(lut + lg.usc_off);
   p.S = fused ? nullptr : lut + lg.s_off;
   p.S16 = fused ? nullptr : lut + lg.s16_off;
   p.S128 = fused ? nullptr : lut + lg.s128_off;
@@ -596,8 +705,9 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
     if (d >= 65536u || lg.U >= 65536) return TMAC_EUNSUPPORTED;
     p.q_magic = d == 1 ? 0u : (uint32_t)((4294967296ull + d - 1) / d);
   }
-  const hipError_t e = lut_is_int ? launch_bits<true>(p, desc->bits, gm, rt, fused, NW, st)
-                                  : launch_bits<false>(p, desc->bits, gm, rt, fused, NW, st);
+  const hipError_t e = q8 ? launch_q8_bits(p, desc->bits, gm, NW, st)
+                          : lut_is_int ? launch_bits<true>(p, desc->bits, gm, rt, fused, NW, st)
+                                       : launch_bits<false>(p, desc->bits, gm, rt, fused, NW, st);
   if (e != hipSuccess) {
     note_hip_error((int)e);
     return TMAC_EHIP;

@@ -23,7 +23,7 @@ class LinearLUT:
                  scales: Optional[np.ndarray] = None, zeros: Optional[np.ndarray] = None,
                  zero_point: float = 0.0, weight_scale: float = 1.0, int_path: bool = False,
                  max_N: int = 1, device: str = "cuda", packed_host: Optional[np.ndarray] = None,
-                 layout: Optional[int] = None):
+                 layout: Optional[int] = None, lut_t: Optional[int] = None):
         import torch
         self.torch = torch
         self.device = device
@@ -31,7 +31,7 @@ class LinearLUT:
         self.desc = B.wdesc(M, K, bits, group, zero_point, layout=self.layout)
         self.M, self.K, self.bits, self.group = M, K, bits, group
         self.weight_scale = float(weight_scale)
-        self.lut_t = B.TMAC_LUT_I16 if int_path else B.TMAC_LUT_F16
+        self.lut_t = (B.TMAC_LUT_I16 if int_path else B.TMAC_LUT_F16) if lut_t is None else lut_t
         self.max_N = max_N
         blob = packed_host if packed_host is not None else B.tmac_pack_weights(self.desc, q, scales, zeros)
         self.packed_bytes = int(blob.size)
@@ -84,9 +84,10 @@ def layout_supports_group(layout: int, K: int, group: int) -> bool:
     return group in (32, 64) or group % 128 == 0
 
 
-def from_problem(p, max_N: Optional[int] = None, device: str = "cuda", layout: Optional[int] = None) -> LinearLUT:
+def from_problem(p, max_N: Optional[int] = None, device: str = "cuda", layout: Optional[int] = None,
+                 lut_t: Optional[int] = None) -> LinearLUT:
     """Build a LinearLUT from a workload description object with fields M, K, bits, group, q,
     scales, zeros, zero_point, weight_scale and int_path."""
     return LinearLUT(p.M, p.K, p.bits, p.group, p.q, p.scales, p.zeros, zero_point=p.zero_point,
                      weight_scale=p.weight_scale, int_path=p.int_path, max_N=max_N or p.N, device=device,
-                     layout=layout)
+                     layout=layout, lut_t=lut_t)

@@ -374,3 +374,82 @@ def test_fused_rejects_what_it_cannot_do(T, torch):
         with pytest.raises(T.TmacError) as e:
             B.tmac_mpgemv_fused(d, packed, A, 1, out, B.TMAC_OUT_F32, lda=K)
         assert e.value.status in (B.TMAC_EUNSUPPORTED, B.TMAC_EINVAL)
+
+
+# ------------------------------------------------- int8 table quantisation ----
+
+TQ_VS_ORACLE_TQ = 2e-4   # same int8 tables on both sides up to rare ties; fp32 vs fp64 sums
+TQ_VS_EXACT = 1.2e-2     # Section 3.3 is lossy: a few 1e-3 on Gaussian data
+
+
+def run_tq(T, torch, p):
+    from paper_2407_00088_amd.runner import from_problem
+    lin = from_problem(p, layout=L2, lut_t=T.TMAC_LUT_I8Q)
+    out = lin.forward(torch.from_numpy(p.act).cuda())
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def oracle_tq(p):
+    return orc.lut_mpgemm_tq(p.act, p.q, p.bits, p.scales, p.zeros, p.group, p.weight_scale, p.zero_point)
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+@pytest.mark.parametrize("group", [16, 64, 128, 384, 0, -1])
+def test_table_quantisation_small(T, torch, bits, group):
+    """int8 tables with one scale per 16 activations: against the oracle's quantised route
+    (tight) and against the exact product (the method's own loss); ragged M, two chunks blocks."""
+    M, K, N = 75, 1152, 2
+    if group == 0:
+        rng = np.random.default_rng(600 + bits)
+        p = wl.Problem("tq_pt", 0, N, M, K, bits, 0, wl.uniform_codes(rng, M, K, bits), None, None,
+                       weight_scale=0.05, zero_point=1.0, act=wl.gaussian_act(rng, N, K))
+    else:
+        p = wl.make_grouped(0, 610 + bits, N, M, K, bits, K if group < 0 else group, name=f"tq_w{bits}_g{group}")
+    got = run_tq(T, torch, p)
+    e_tq = orc.rel_frobenius(got, oracle_tq(p))
+    e_ex = orc.rel_frobenius(got, oracle_fp(p))
+    print(f"{p.name}: vs quantised oracle {e_tq:.2e}, vs exact {e_ex:.2e}", flush=True)
+    assert e_tq <= TQ_VS_ORACLE_TQ, e_tq
+    assert e_ex <= TQ_VS_EXACT, e_ex
+
+
+@pytest.mark.parametrize("K", [16, 24, 200, 1000])
+def test_table_quantisation_ragged_k(T, torch, K):
+    p = wl.make_grouped(0, 620, 1, 40, K, 4, K, name=f"tq_ragk_{K}")   # one group per row
+    got = run_tq(T, torch, p)
+    assert orc.rel_frobenius(got, oracle_tq(p)) <= TQ_VS_ORACLE_TQ
+
+
+@pytest.mark.parametrize("i", [0, 1, 2])
+def test_table_quantisation_config2(T, torch, i):
+    p = wl.config2(i)
+    got = run_tq(T, torch, p)
+    e_tq = orc.rel_frobenius(got, oracle_tq(p))
+    e_ex = orc.rel_frobenius(got, oracle_fp(p))
+    print(f"{p.name}: vs quantised oracle {e_tq:.2e}, vs exact {e_ex:.2e} (NMSE {e_ex ** 2:.2e})", flush=True)
+    assert e_tq <= TQ_VS_ORACLE_TQ and e_ex <= TQ_VS_EXACT
+
+
+def test_table_quantisation_zero_and_tiny_activations(T, torch):
+    p = wl.make_grouped(0, 630, 2, 24, 256, 2, 32)
+    p.act[0, :] = 0
+    p.act[1, 16:48] = 0
+    p.act[1, 64:] = (p.act[1, 64:].astype(np.float32) * 1e-3).astype(np.float16)
+    got = run_tq(T, torch, p)
+    assert np.all(got[0] == 0)
+    assert orc.rel_frobenius(got, oracle_tq(p)) <= 5e-4
+
+
+def test_table_quantisation_rejects_what_it_cannot_do(T, torch):
+    from paper_2407_00088_amd import binding as B
+    from paper_2407_00088_amd.runner import from_problem
+    p = wl.make_grouped(0, 640, 1, 16, 128, 2, 128)
+    with pytest.raises(T.TmacError) as e:
+        from_problem(p, layout=L1, lut_t=B.TMAC_LUT_I8Q).forward(torch.from_numpy(p.act).cuda())
+    assert e.value.status == B.TMAC_EUNSUPPORTED
+    t = wl.make_ternary(0, 641, 1, 16, 128)
+    lut = torch.empty(B.tmac_lut_bytes(1, 128, 0, B.TMAC_LUT_I8Q), dtype=torch.uint8, device="cuda")
+    with pytest.raises(T.TmacError) as e:
+        B.tmac_precompute_lut(torch.from_numpy(t.act_q).cuda(), 1, 128, 0, B.TMAC_LUT_I8Q, lut)
+    assert e.value.status == B.TMAC_EINVAL
