@@ -87,9 +87,9 @@ def main():
     sink = torch.zeros(256, dtype=torch.uint8, device=dev)
 
     class Case:
-        def __init__(self, p, layout=None, ring_mb=None):
+        def __init__(self, p, layout=None, ring_mb=None, lut_t=None):
             self.p = p
-            self.lin = from_problem(p, layout=args.layout if layout is None else layout)
+            self.lin = from_problem(p, layout=args.layout if layout is None else layout, lut_t=lut_t)
             self.bytes = algorithmic_bytes(p.M, p.K, p.bits, p.group, p.N, act_bytes=1 if p.int_path else 2)
             n_copies = max(2, ((args.ring_mb if ring_mb is None else ring_mb) << 20) // self.lin.packed_bytes + 1)
             self.ring = [self.lin.packed] + [self.lin.packed.clone() for _ in range(n_copies - 1)]
@@ -218,6 +218,32 @@ def main():
             del c
             torch.cuda.empty_cache()
         detail["sweep"] = sweep
+        if args.layout == 2:
+            # int8 table quantisation (Section 3.3): lookup kernel with int8 tables, two-call path
+            tq = []
+            for i in range(3):
+                c = Case(wl.config2(i), lut_t=T.TMAC_LUT_I8Q)
+                us = measure_kernel(c, args.steps)
+                pu = timed(Replay(c.precompute, 50), max(1, args.steps // 50), 2)
+                tq.append({"name": c.p.name + "_int8_tables", "mpgemm_us": round(us, 3), "precompute_us": round(pu, 3),
+                           "bytes": c.bytes, "GBps": round(c.bytes / us / 1e3, 1),
+                           "frac_hbm_peak": round(c.bytes / us / 1e3 / HBM_PEAK_GBPS, 4)})
+                del c
+                torch.cuda.empty_cache()
+            detail["table_quantisation"] = tq
+            # stacked projections in one call (Q,K,V and gate,up of Llama-2-7B stacked along M): the
+            # fraction of the roofline the same kernel reaches once a call moves more bytes
+            stacked = []
+            for M, K in ((12288, 4096), (22016, 4096)):
+                c = Case(wl.make_grouped(3, 50 + M // 1000, 1, M, K, 4, 128, name=f"stacked_{M}x{K}_w4_n1"))
+                fu = measure_kernel(c, args.steps, c.fused)
+                ru = measure_kernel(c, args.steps, c.stream_read)
+                stacked.append({"name": c.p.name, "fused_us": round(fu, 3), "plain_read_of_same_bytes_us": round(ru, 3),
+                                "bytes": c.bytes, "GBps": round(c.bytes / fu / 1e3, 1),
+                                "frac_hbm_peak": round(c.bytes / fu / 1e3 / HBM_PEAK_GBPS, 4)})
+                del c
+                torch.cuda.empty_cache()
+            detail["stacked_projections"] = stacked
         # prefill mpGEMM, N = 256 (LDS-table kernel, layout 1): precompute + mpgemm per call
         prefill = []
         for bits in (2, 4):

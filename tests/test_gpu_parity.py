@@ -453,3 +453,36 @@ def test_table_quantisation_rejects_what_it_cannot_do(T, torch):
     with pytest.raises(T.TmacError) as e:
         B.tmac_precompute_lut(torch.from_numpy(t.act_q).cuda(), 1, 128, 0, B.TMAC_LUT_I8Q, lut)
     assert e.value.status == B.TMAC_EINVAL
+
+
+# ----------------------------------------------------- launch configuration of bench.py ----
+
+@pytest.mark.parametrize("i", [0, 2])
+def test_fused_call_in_graph_replay_over_a_weight_ring(T, torch, i):
+    """The benchmark replays a HIP graph of fused calls that walk a ring of packed-weight copies;
+    every replay must give the eager result (and the oracle's) for every copy."""
+    from paper_2407_00088_amd.runner import from_problem
+    p = wl.config2(i)
+    lin = from_problem(p, layout=L2)
+    A = torch.from_numpy(p.act).cuda()
+    ring = [lin.packed, lin.packed.clone(), lin.packed.clone()]
+    outs = [torch.zeros((1, p.M), dtype=torch.float32, device="cuda") for _ in ring]
+    eager = lin.forward_fused(A)
+    torch.cuda.synchronize()
+    assert orc.rel_frobenius(eager.cpu().numpy(), oracle_fp(p)) <= FP_TOL
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        lin.mpgemv_fused(A, 1, outs[0], packed=ring[0])
+    stream.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        for pk, o in zip(ring, outs):
+            lin.mpgemv_fused(A, 1, o, packed=pk)
+    for rep in range(3):
+        for o in outs:
+            o.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for o in outs:
+            assert torch.equal(o, eager), rep
