@@ -68,9 +68,10 @@ typedef enum { TMAC_OUT_F32 = 0, TMAC_OUT_F16 = 1, TMAC_OUT_I32 = 2 } tmac_out_t
 /* Weight matrix description (Algorithm 1: W has shape [M, K]).
  *   bits   1..4, weight bit-width b
  *   g      LUT group size; must be 4 (one 16-entry table per 4 activations)
- *   group  quantisation group G along K: a multiple of 128, or 32, or 64, or == K
- *          (one scale per row); 0 = one scale and zero for the whole tensor
- *   layout TMAC_LAYOUT_*
+ *   group  quantisation group G along K (which sizes a layout accepts is said with the layout);
+ *          == K: one scale per row; 0 = one scale and zero for the whole tensor
+ *   layout TMAC_LAYOUT_*: 1 and 3 serve any number of activation rows (3 is the fast one for
+ *          many rows), 2 is the decode layout (few rows)
  *   zero_point  per-tensor zero in code units (group == 0 only), e.g. 1 for ternary
  *          weights stored as q = t+1 (Section 5.1: ternary weights run as 2-bit) */
 typedef struct {
@@ -124,7 +125,20 @@ typedef struct {
  *   scales   u16 sz[n_tiles][n_qgroups][8][2] = {fp16 scale, fp16 zero}
  *   Group sizes: any multiple of 16, or K, or 0 (per tensor).
  */
-enum { TMAC_LAYOUT_T16K128 = 1, TMAC_LAYOUT_R8U16 = 2 };
+/* Packed layout 3 ("tile 64 rows x chunks of 32 k", for the batched lookup kernel that serves many
+ * activation rows; Section 3.2: a large tile over M lets many weight rows reuse one table):
+ *
+ *   header   as layout 1 (Mp = M rounded up to 64, n_tiles = Mp/64, n_chunks = Kp/32)
+ *   indices  u32 idx[n_tiles][n_chunks][64][bits]: dword [t][c][r][i] holds the eight 4-bit
+ *            indices of bit plane i of row 64t+r for LUT groups kg = 8c + j, index j in nibble j
+ *            (bits 4j..4j+3).  One lane of the kernel owns one row and reads its `bits` dwords of
+ *            a chunk with one load; (x << 3) & 0x78787878 and (x >> 1) & 0x78787878 are the
+ *            byte offsets of the even and odd tables' entries.
+ *   scales   u16 sz[n_tiles][n_qgroups][64][2] = {fp16 scale, fp16 zero}
+ *   Group sizes: any multiple of 32, or K, or 0 (per tensor).  Table types: TMAC_LUT_F16 and
+ *   TMAC_LUT_I16.
+ */
+enum { TMAC_LAYOUT_T16K128 = 1, TMAC_LAYOUT_R8U16 = 2, TMAC_LAYOUT_R64K32 = 3 };
 
 typedef struct {
   uint32_t magic;        /* 0x43414D54 "TMAC" */

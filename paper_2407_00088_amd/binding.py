@@ -23,6 +23,7 @@ TMAC_LUT_F16, TMAC_LUT_I16, TMAC_LUT_I8Q = 0, 1, 2
 TMAC_OUT_F32, TMAC_OUT_F16, TMAC_OUT_I32 = 0, 1, 2
 TMAC_LAYOUT_T16K128 = 1   # LDS-table kernels (any N)
 TMAC_LAYOUT_R8U16 = 2     # register-table decode kernel (small N)
+TMAC_LAYOUT_R64K32 = 3    # batched lookup kernel, lane = weight row (many activation rows)
 
 EXPORTS = [
     "tmac_packed_bytes", "tmac_pack_weights", "tmac_lut_bytes", "tmac_precompute_lut",

@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libtmac_hip.so")
-SOURCES = ["tmac_kernels.hip", "tmac_perm.hip", "tmac_util.hip", "tmac_pack.cpp"]
+SOURCES = ["tmac_kernels.hip", "tmac_perm.hip", "tmac_rows.hip", "tmac_util.hip", "tmac_pack.cpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

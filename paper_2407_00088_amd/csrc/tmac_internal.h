@@ -14,13 +14,14 @@ constexpr uint32_t TMAC_MAGIC = 0x43414D54u;  // "TMAC"
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 // Geometry of a packed weight blob (both layouts).
-//   layout 1: row tiles of 16, k chunks of 128;  layout 2: row tiles of 8, lane-units of 16 k.
+//   layout 1: row tiles of 16, k chunks of 128;  layout 2: row tiles of 8, lane-units of 16 k;
+//   layout 3: row tiles of 64, k chunks of 32.
 struct Geometry {
   int Mp, Kp;          // padded M and K
-  int n_tiles;         // row tiles (16 rows in layout 1, 8 rows in layout 2)
-  int n_chunks;        // layout 1: 128-k chunks; layout 2: 16-k lane-units
+  int n_tiles;         // row tiles (16 rows in layout 1, 8 in layout 2, 64 in layout 3)
+  int n_chunks;        // layout 1: 128-k chunks; layout 2: 16-k lane-units; layout 3: 32-k chunks
   int n_qgroups;       // scale groups per row stored in the blob (0 when per-tensor)
-  int tile_rows;       // 16 or 8
+  int tile_rows;       // 16, 8 or 64
   uint64_t idx_off, idx_bytes, sz_off, sz_bytes, total_bytes;
 };
 
@@ -105,6 +106,11 @@ TMAC_HD inline int block_slot(int u, int c0, int ng) { return (u & 7) * ng + ((u
 int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, const void* A_dev,
                      int64_t lda, int lut_t, int N, const float* act_scale_dev, float weight_scale,
                      void* out_dev, int out_t, int64_t ldo, void* stream, int rows_per_group);
+
+// Batched lookup kernel (layout 3); defined in tmac_rows.hip.  Returns a tmac_status value.
+int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, int lut_t, int N,
+                     const float* act_scale_dev, float weight_scale, void* out_dev, int out_t, int64_t ldo,
+                     void* stream);
 
 // Records the last HIP error of this thread (diagnostics for TMAC_EHIP).
 void note_hip_error(int hip_error);

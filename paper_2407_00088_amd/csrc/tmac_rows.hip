@@ -1,0 +1,312 @@
+// Batched lookup kernel (gfx950) for packed layout 3: many activation rows (prefill mpGEMM).
+//
+// Section 3.2 of the paper argues that the tables must sit in fast on-chip memory and that a large
+// tile over M lets many weight rows reuse one table.  Here the tables of a K-slice and of four
+// activation rows live in LDS, laid out [table][entry][n] (four fp16 values = 8 bytes per entry),
+// and every LANE owns one weight row: a wavefront looks one table up for 64 rows at a time.  All
+// lanes of a ds_read_b64 address the same 128-byte table, whose 16 entries cover the 32 LDS banks
+// exactly once, so lanes that want the same entry are served by broadcast and lanes that want
+// different entries hit different banks: the lookups are free of bank conflicts, and one lookup
+// feeds four activation rows.
+//
+//   * Weight permutation / interleaving (Section 3.2): a lane reads the `bits` index dwords of its
+//     row and of one 32-k chunk with one load (16 bytes at 4 bit); the eight nibbles of a dword are
+//     the indices of eight consecutive tables, and (x << 3) & 0x78787878, (x >> 1) & 0x78787878
+//     turn them into the byte offsets of the entries (even and odd tables) four at a time.
+//   * Bit-plane shift-accumulate (Eq. 1): v_fma_mix_f32 takes the fp16 entry straight from the
+//     looked-up register and multiplies by 2^i.
+//   * Scale, zero and bias once per quantisation group (Section 4, bit-serial linear transform).
+//   * Axis order (Section 3.2 "axis reordering"): K is walked slice by slice inside the
+//     workgroup, so only a [4, 1024]-slice of the tables is live in LDS and no split-K
+//     reduction is needed; the sums of a row stay in the lane's registers: fixed order.
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <type_traits>
+
+#include "tmac.h"
+#include "tmac_internal.h"
+
+namespace tmac {
+
+typedef uint32_t ru32x4v __attribute__((ext_vector_type(4)));
+typedef uint32_t ru32x2v __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) char rows_lds_char;
+typedef __attribute__((address_space(3))) const ru32x2v rows_lds_u32x2;
+
+constexpr int ROWS_NT = 4;          // activation rows per workgroup
+constexpr int ROWS_WAVES = 4;       // 64-row tiles per workgroup
+constexpr int ROWS_KSL = 1024;      // k per LDS slice: 256 tables x 128 bytes = 32 KB
+
+struct RowsParams {
+  const uint32_t* idx;     // [n_tiles][n_chunks][64][bits] dwords
+  const uint32_t* sz;      // [n_tiles][nq][64] {fp16 scale, fp16 zero}
+  const uint16_t* tables;  // [N][KG][16] fp16 or int16
+  const void* S;           // [N][nq] fp32 / int32 group sums
+  void* out;
+  const float* act_scale;
+  int64_t ldo;
+  int M, N, KG, n_tiles, n_chunks, nq;
+  int cpg;                 // 32-k chunks per quantisation group (grouped mode)
+  int grouped;             // 1: group scales, 0: one scale per row or per tensor
+  int per_tensor, int_exact, icoef;
+  float wscale, zero_point, mid;
+  float pw[4];             // plane weights 1, 2, 4, 8: kernel arguments, so that plane 0 also takes the
+                           // fused convert-multiply-add (a literal 1.0 would be folded into cvt + add)
+  int out_t;
+};
+
+template <bool IS_INT, int BITS>
+__global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const RowsParams p) {
+  constexpr int NT = ROWS_NT;
+  constexpr int TPS = ROWS_KSL / 4;  // tables per slice
+  __shared__ __attribute__((aligned(1024))) char tab[TPS * 128];  // byte-permuted addresses need the alignment
+  using AccT = typename std::conditional<IS_INT, int, float>::type;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n0 = blockIdx.x * NT;                       // activation rows of this workgroup
+  const int tile_raw = blockIdx.y * ROWS_WAVES + wave;  // 64-row tile of this wave
+  const bool tile_ok = tile_raw < p.n_tiles;
+  const int tile = tile_ok ? tile_raw : p.n_tiles - 1;  // clamped: loads stay in range, stores are masked
+  const uint32_t* my_idx = p.idx + ((size_t)tile * p.n_chunks * 64 + lane) * BITS;
+  const uint32_t* my_sz = p.sz + (size_t)tile * p.nq * 64 + lane;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)((rows_lds_char*)tab);  // a multiple of 1024
+
+  float acc[NT];   // finished group sums (grouped mode)
+  AccT L[NT];      // look-up sums of the current quantisation group (or of the whole row)
+#pragma unroll
+  for (int t = 0; t < NT; ++t) { acc[t] = 0.f; L[t] = 0; }
+
+  auto load_idx = [&](int c, uint32_t (&x)[BITS]) {
+    const uint32_t* src = my_idx + (size_t)c * 64 * BITS;
+    if constexpr (BITS == 4) {
+      const ru32x4v v = *reinterpret_cast<const ru32x4v*>(src);
+      x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+    } else if constexpr (BITS == 2) {
+      const ru32x2v v = *reinterpret_cast<const ru32x2v*>(src);
+      x[0] = v.x; x[1] = v.y;
+    } else {
+#pragma unroll
+      for (int b = 0; b < BITS; ++b) x[b] = src[b];
+    }
+  };
+
+  int gq = 0, cg = 0;        // current quantisation group and chunks done in it (wave-uniform)
+  uint32_t szv = 0;          // {scale, zero} of the lane's row for the current group
+  float Sg[NT] = {0.f, 0.f, 0.f, 0.f};
+  uint32_t xn[BITS];
+  load_idx(0, xn);
+
+  for (int c0 = 0; c0 < p.n_chunks; c0 += ROWS_KSL / 32) {
+    // stage the tables of this K-slice for the NT activation rows: item = (table, half) reads the
+    // 8 entries of the four rows and writes them entry-major
+    __syncthreads();
+    for (int it = threadIdx.x; it < TPS * 2; it += 64 * ROWS_WAVES) {
+      const int kl = it >> 1, h = it & 1;
+      const int kg = c0 * 8 + kl;
+      ru32x4v v[NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        v[t] = ru32x4v{0u, 0u, 0u, 0u};
+        if (n0 + t < p.N && kg < p.KG)
+          v[t] = *reinterpret_cast<const ru32x4v*>(p.tables + ((size_t)(n0 + t) * p.KG + kg) * 16 + 8 * h);
+      }
+      ru32x4v* dst = reinterpret_cast<ru32x4v*>(tab + kl * 128 + h * 64);
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {  // dword d of every row holds entries 2d, 2d+1 of this half
+        ru32x4v o;
+        o.x = __builtin_amdgcn_perm(v[1][d], v[0][d], 0x05040100u);  // entry 2d: rows 0,1
+        o.y = __builtin_amdgcn_perm(v[3][d], v[2][d], 0x05040100u);  //           rows 2,3
+        o.z = __builtin_amdgcn_perm(v[1][d], v[0][d], 0x07060302u);  // entry 2d+1
+        o.w = __builtin_amdgcn_perm(v[3][d], v[2][d], 0x07060302u);
+        dst[d] = o;
+      }
+    }
+    __syncthreads();
+
+    const int c_end = min(c0 + ROWS_KSL / 32, p.n_chunks);
+    // The LDS reads run one index dword (eight lookups) ahead of the accumulation: issue(plane b+1)
+    // comes before consume(plane b), also across chunk boundaries inside a slice.
+    ru32x2v e[2][8];
+    auto issue = [&](uint32_t xw, uint32_t cbase, ru32x2v (&dst)[8]) {
+      const uint32_t ev = (xw << 3) & 0x78787878u, od = (xw >> 1) & 0x78787878u;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        // address = {0, cbase byte 2, cbase byte 1, byte j/2 of the offsets}: one byte permute;
+        // the table's own 128 * j goes into the instruction's offset field
+        const uint32_t a = __builtin_amdgcn_perm((j & 1) ? od : ev, cbase, 0x0C020100u + 4u + (uint32_t)(j >> 1));
+        dst[j] = *reinterpret_cast<rows_lds_u32x2*>(a + j * 128);
+      }
+    };
+    auto consume = [&](const ru32x2v (&src)[8], int b) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if constexpr (IS_INT) {
+          L[0] += (int)(int16_t)(src[j].x & 0xffffu) << b;
+          L[1] += ((int)src[j].x >> 16) << b;
+          L[2] += (int)(int16_t)(src[j].y & 0xffffu) << b;
+          L[3] += ((int)src[j].y >> 16) << b;
+        } else {
+          const float w = p.pw[b];
+          L[0] = fmaf(__half2float(__ushort_as_half((uint16_t)(src[j].x & 0xffffu))), w, L[0]);
+          L[1] = fmaf(__half2float(__ushort_as_half((uint16_t)(src[j].x >> 16))), w, L[1]);
+          L[2] = fmaf(__half2float(__ushort_as_half((uint16_t)(src[j].y & 0xffffu))), w, L[2]);
+          L[3] = fmaf(__half2float(__ushort_as_half((uint16_t)(src[j].y >> 16))), w, L[3]);
+        }
+      }
+    };
+    issue(xn[0], lds0, e[0]);  // plane 0 of the slice's first chunk (its indices are in xn)
+    for (int c = c0; c < c_end; ++c) {
+      uint32_t x[BITS];
+#pragma unroll
+      for (int b = 0; b < BITS; ++b) x[b] = xn[b];
+      if (c + 1 < p.n_chunks) load_idx(c + 1, xn);  // next chunk's indices, one chunk ahead
+      if (p.grouped && cg == 0 && gq < p.nq) {  // (chunks in the K padding belong to no group)
+        // scale/zero of the group that starts here and the activation sums its bias term needs
+        szv = my_sz[(size_t)gq * 64];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const int n = min(n0 + t, p.N - 1);
+          if constexpr (IS_INT) Sg[t] = (float)static_cast<const int*>(p.S)[(size_t)n * p.nq + gq];
+          else Sg[t] = static_cast<const float*>(p.S)[(size_t)n * p.nq + gq];
+        }
+      }
+      const uint32_t cbase = lds0 + (uint32_t)(c - c0) * 1024u;
+#pragma unroll
+      for (int b = 0; b < BITS; ++b) {
+        // e[(BITS * chunk + b) & 1] holds plane b; BITS * chunk is even except for odd BITS, where
+        // the parity alternates with the chunk: use the flat position
+        const int cur = (BITS % 2 == 0) ? (b & 1) : (((c - c0) * BITS + b) & 1);
+        if (b + 1 < BITS) {
+          if (cur == 0) issue(x[b + 1], cbase, e[1]); else issue(x[b + 1], cbase, e[0]);
+        } else if (c + 1 < c_end) {
+          if (cur == 0) issue(xn[0], cbase + 1024u, e[1]); else issue(xn[0], cbase + 1024u, e[0]);
+        }
+        if (cur == 0) consume(e[0], b); else consume(e[1], b);
+      }
+      if (p.grouped && gq < p.nq && ++cg == p.cpg) {
+        const float s = __half2float(__ushort_as_half((uint16_t)(szv & 0xffffu)));
+        const float z = __half2float(__ushort_as_half((uint16_t)(szv >> 16)));
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          acc[t] = fmaf(s, fmaf(p.mid - z, Sg[t], 0.5f * (float)L[t]), acc[t]);
+          L[t] = 0;
+        }
+        cg = 0;
+        ++gq;
+      }
+    }
+  }
+
+  // finish and store: lanes of a wave write 64 consecutive outputs of one activation row
+  const int m = tile_raw * 64 + lane;
+  if (!tile_ok || m >= p.M) return;
+  float s = p.wscale, z = p.zero_point;
+  if (!p.grouped && !p.per_tensor) {
+    const uint32_t v = my_sz[0];
+    s = __half2float(__ushort_as_half((uint16_t)(v & 0xffffu)));
+    z = __half2float(__ushort_as_half((uint16_t)(v >> 16)));
+  }
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int n = n0 + t;
+    if (n >= p.N) break;
+    const float as = p.act_scale ? p.act_scale[n] : 1.0f;
+    float res;
+    int ires = 0;
+    if (p.grouped) {
+      res = acc[t] * as;
+    } else if constexpr (IS_INT) {
+      const int St = static_cast<const int*>(p.S)[n];
+      if (p.int_exact) {
+        ires = ((int)L[t] + p.icoef * St) >> 1;  // numerator is always even
+        res = ((float)ires * as) * s;            // two roundings, left to right
+      } else {
+        res = (fmaf(p.mid - z, (float)St, 0.5f * (float)L[t]) * as) * s;
+      }
+    } else {
+      const float St = static_cast<const float*>(p.S)[n];
+      res = (s * fmaf(p.mid - z, St, 0.5f * (float)L[t])) * as;
+    }
+    const size_t o = (size_t)n * p.ldo + m;
+    if (p.out_t == TMAC_OUT_F32) static_cast<float*>(p.out)[o] = res;
+    else if (p.out_t == TMAC_OUT_F16) static_cast<__half*>(p.out)[o] = __float2half_rn(res);
+    else static_cast<int*>(p.out)[o] = ires;
+  }
+}
+
+template <bool IS_INT, int BITS>
+static hipError_t launch_rows_one(const RowsParams& p, hipStream_t st) {
+  RowsParams local = p;
+  void* args[] = {&local};
+  const dim3 grid((p.N + ROWS_NT - 1) / ROWS_NT, (p.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES);
+  return hipLaunchKernel(reinterpret_cast<const void*>(mpgemm_rows_kernel<IS_INT, BITS>), grid,
+                         dim3(64 * ROWS_WAVES), args, 0, st);
+}
+
+template <bool IS_INT>
+static hipError_t launch_rows_bits(const RowsParams& p, int bits, hipStream_t st) {
+  switch (bits) {
+    case 1: return launch_rows_one<IS_INT, 1>(p, st);
+    case 2: return launch_rows_one<IS_INT, 2>(p, st);
+    case 3: return launch_rows_one<IS_INT, 3>(p, st);
+    case 4: return launch_rows_one<IS_INT, 4>(p, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, int lut_t, int N,
+                     const float* act_scale_dev, float weight_scale, void* out_dev, int out_t, int64_t ldo,
+                     void* stream) {
+  if (lut_t != TMAC_LUT_F16 && lut_t != TMAC_LUT_I16) return TMAC_EUNSUPPORTED;
+  const Geometry ge = geometry(desc);
+  LutGeom lg;
+  if (!lut_geom(N, desc->K, desc->g, desc->group, lut_t, &lg)) return TMAC_EINVAL;
+  const bool is_int = (lut_t == TMAC_LUT_I16);
+  const bool one_group = (desc->group == 0 || desc->group == desc->K);
+  if ((N + ROWS_NT - 1) / ROWS_NT > 0x7fffffff || (ge.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES > 65535)
+    return TMAC_EUNSUPPORTED;
+  // int32 accumulators: |L| <= 508 * (2^b - 1) * K/4 must stay below 2^31
+  if (is_int && (double)508.0 * ((1 << desc->bits) - 1) * (desc->K / 4) >= 2147483647.0) return TMAC_EUNSUPPORTED;
+
+  RowsParams p;
+  const char* blob = static_cast<const char*>(packed_dev);
+  p.idx = reinterpret_cast<const uint32_t*>(blob + ge.idx_off);
+  p.sz = reinterpret_cast<const uint32_t*>(blob + ge.sz_off);
+  p.tables = static_cast<const uint16_t*>(lut_dev);
+  p.S = static_cast<const char*>(lut_dev) + lg.s_off;
+  p.out = out_dev;
+  p.act_scale = act_scale_dev;
+  p.ldo = ldo;
+  p.M = desc->M; p.N = N; p.KG = lg.KG; p.n_tiles = ge.n_tiles; p.n_chunks = ge.n_chunks; p.nq = lg.nq;
+  p.grouped = one_group ? 0 : 1;
+  p.cpg = one_group ? 0 : desc->group / 32;
+  p.per_tensor = (desc->group == 0);
+  p.wscale = weight_scale;
+  p.mid = 0.5f * (float)((1 << desc->bits) - 1);
+  p.zero_point = p.per_tensor ? desc->zero_point : 0.f;
+  p.int_exact = 0;
+  p.icoef = 0;
+  p.out_t = out_t;
+  p.pw[0] = 1.f; p.pw[1] = 2.f; p.pw[2] = 4.f; p.pw[3] = 8.f;
+  if (p.per_tensor && is_int) {
+    const float z = desc->zero_point;
+    if (z == rintf(z) && fabsf(z) < 64.f) {
+      p.int_exact = 1;
+      p.icoef = ((1 << desc->bits) - 1) - 2 * (int)z;
+    }
+  }
+  if (out_t == TMAC_OUT_I32 && !p.int_exact) return TMAC_EINVAL;
+  const hipError_t e = is_int ? launch_rows_bits<true>(p, desc->bits, static_cast<hipStream_t>(stream))
+                              : launch_rows_bits<false>(p, desc->bits, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) {
+    note_hip_error((int)e);
+    return TMAC_EHIP;
+  }
+  return TMAC_OK;
+}
+
+}  // namespace tmac

@@ -11,7 +11,7 @@ DECODE_MAX_N = 8  # up to this many activation rows the register-table layout is
 
 
 def default_layout(max_N: int) -> int:
-    return B.TMAC_LAYOUT_R8U16 if max_N <= DECODE_MAX_N else B.TMAC_LAYOUT_T16K128
+    return B.TMAC_LAYOUT_R8U16 if max_N <= DECODE_MAX_N else B.TMAC_LAYOUT_R64K32
 
 
 class LinearLUT:
@@ -81,6 +81,8 @@ def layout_supports_group(layout: int, K: int, group: int) -> bool:
         return True
     if layout == B.TMAC_LAYOUT_R8U16:
         return group % 16 == 0
+    if layout == B.TMAC_LAYOUT_R64K32:
+        return group % 32 == 0
     return group in (32, 64) or group % 128 == 0
 
 

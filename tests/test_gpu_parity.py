@@ -5,7 +5,8 @@ Bars: integer path bit-exact; fp16-table path within 2e-3 relative Frobenius err
 fp64 product (the rounding of table entries to fp16 alone costs a few 1e-4).
 
 Every case runs in both packed layouts where both apply: layout 1 feeds the LDS-table kernels
-(K-sliced and full-K), layout 2 the register-table decode kernel, called either as
+(K-sliced and full-K), layout 3 the batched lookup kernel with one lane per weight row ("rows"),
+layout 2 the register-table decode kernel, called either as
 tmac_precompute_lut + tmac_mpgemm ("regs") or as the single fused launch tmac_mpgemv_fused
 ("fused")."""
 import numpy as np
@@ -17,8 +18,8 @@ from oracle import tmac_oracle as orc
 pytestmark = pytest.mark.gpu
 
 FP_TOL = 2e-3
-L1, L2 = 1, 2
-LF = 3   # layout 2 through the fused entry point
+L1, L2, L3 = 1, 2, 3
+LF = 13  # layout 2 through the fused entry point
 
 
 @pytest.fixture(scope="module")
@@ -34,7 +35,7 @@ def torch():
     return torch
 
 
-@pytest.fixture(params=[L1, L2, LF], ids=["lds", "regs", "fused"])
+@pytest.fixture(params=[L1, L2, LF, L3], ids=["lds", "regs", "fused", "rows"])
 def layout(request):
     return request.param
 
@@ -275,8 +276,9 @@ def test_config4_bitnet_ternary(T, torch, i, layout):
 
 @pytest.mark.parametrize("bits", [2, 4])
 @pytest.mark.parametrize("i", [0, 1, 2])
-def test_config5_llama13b_prefill(T, torch, i, bits):
-    check_fp(T, torch, wl.config5(i, bits), layout=L1)
+@pytest.mark.parametrize("lay", [L1, L3], ids=["lds", "rows"])
+def test_config5_llama13b_prefill(T, torch, i, bits, lay):
+    check_fp(T, torch, wl.config5(i, bits), layout=lay)
 
 
 # ------------------------------------------------ both LDS lookup kernels ----
@@ -486,3 +488,38 @@ def test_fused_call_in_graph_replay_over_a_weight_ring(T, torch, i):
         torch.cuda.synchronize()
         for o in outs:
             assert torch.equal(o, eager), rep
+
+
+# --------------------------------------------- batched lookup kernel (layout 3) ----
+
+@pytest.mark.parametrize("N", [1, 3, 4, 5, 17, 64])
+@pytest.mark.parametrize("bits,group,M,K", [(4, 128, 200, 1408), (2, 32, 72, 1024), (3, 96, 41, 2304), (1, 0, 300, 1040),
+                                            (4, -1, 64, 3200)])
+def test_batched_kernel_shapes(T, torch, N, bits, group, M, K):
+    """Ragged M (tiles of 64), N not a multiple of the four rows a workgroup serves, K that spans
+    several LDS slices and ends inside one, group sizes from one chunk up, per-row and per-tensor."""
+    if group == 0:
+        rng = np.random.default_rng(700 + bits + N)
+        p = wl.Problem("rows_pt", 0, N, M, K, bits, 0, wl.uniform_codes(rng, M, K, bits), None, None,
+                       weight_scale=0.05, zero_point=0.5, act=wl.gaussian_act(rng, N, K))
+    else:
+        p = wl.make_grouped(0, 710 + bits + N, N, M, K, bits, K if group < 0 else group, name=f"rows_w{bits}_n{N}")
+    check_fp(T, torch, p, layout=L3)
+
+
+@pytest.mark.parametrize("N", [1, 6, 33])
+def test_batched_kernel_int_path(T, torch, N):
+    check_int(T, torch, wl.make_ternary(0, 720 + N, N, 200, 2240), layout=L3)
+
+
+def test_batched_kernel_rejects_what_it_cannot_do(T, torch):
+    from paper_2407_00088_amd import binding as B
+    from paper_2407_00088_amd.runner import from_problem
+    p = wl.make_grouped(0, 730, 4, 16, 128, 2, 16)
+    with pytest.raises(T.TmacError) as e:
+        from_problem(p, layout=L3).forward(torch.from_numpy(p.act).cuda())
+    assert e.value.status == B.TMAC_EUNSUPPORTED
+    p = wl.make_grouped(0, 731, 4, 16, 128, 2, 128)
+    with pytest.raises(T.TmacError) as e:
+        from_problem(p, layout=L3, lut_t=B.TMAC_LUT_I8Q).forward(torch.from_numpy(p.act).cuda())
+    assert e.value.status == B.TMAC_EUNSUPPORTED

@@ -1,0 +1,76 @@
+"""CPU-side tests of packed layout 3 (64-row tiles, one lane per row, chunks of 32 k), checked
+with an unpacker written here from the layout documented in include/tmac.h."""
+import struct
+
+import numpy as np
+import pytest
+
+import paper_2407_00088_amd as T
+from paper_2407_00088_amd import binding as B
+
+
+def unpack_layout3(blob: np.ndarray):
+    raw = blob.tobytes()
+    (magic, layout, M, K, bits, g, group, Mp, Kp, n_tiles, n_chunks, n_qgroups, zero_point, _r0,
+     idx_off, idx_bytes, sz_off, sz_bytes, total) = struct.unpack_from("<II10ifI5Q", raw, 0)
+    assert magic == 0x43414D54 and layout == 3 and g == 4
+    assert Mp == (M + 63) // 64 * 64 and Kp == (K + 127) // 128 * 128 and n_chunks == Kp // 32
+    assert total == len(raw) and idx_bytes == n_tiles * n_chunks * 64 * bits * 4
+    idx = np.frombuffer(raw, dtype="<u4", count=idx_bytes // 4, offset=idx_off).reshape(n_tiles, n_chunks, 64, bits)
+    q = np.zeros((Mp, Kp), dtype=np.uint8)
+    rows = np.arange(Mp)
+    for i in range(bits):
+        for j in range(8):
+            nib = ((idx[:, :, :, i] >> (4 * j)) & 15).transpose(0, 2, 1).reshape(Mp, n_chunks)   # [row, chunk]
+            for e in range(4):
+                cols = np.arange(n_chunks) * 32 + 4 * j + e
+                q[np.ix_(rows, cols)] |= (((nib >> e) & 1) << i).astype(np.uint8)
+    s = z = None
+    if group > 0:
+        sz = np.frombuffer(raw, dtype="<u2", count=sz_bytes // 2, offset=sz_off).reshape(n_tiles, n_qgroups, 64, 2)
+        s = sz[..., 0].transpose(0, 2, 1).reshape(Mp, n_qgroups).view(np.float16)
+        z = sz[..., 1].transpose(0, 2, 1).reshape(Mp, n_qgroups).view(np.float16)
+    return dict(M=M, K=K, bits=bits, group=group, Mp=Mp, Kp=Kp, n_qgroups=n_qgroups), q, s, z
+
+
+def desc3(M, K, bits, group, zero_point=0.0):
+    return T.wdesc(M, K, bits, group, zero_point=zero_point, layout=B.TMAC_LAYOUT_R64K32)
+
+
+@pytest.mark.parametrize("M,K,bits,group", [(256, 256, 2, 32), (37, 192, 4, 64), (64, 128, 1, 128), (130, 384, 3, 96),
+                                            (5, 36, 4, 36), (70, 200, 2, 0)])
+def test_layout3_roundtrip_random(M, K, bits, group):
+    rng = np.random.default_rng(M * 7 + K + bits)
+    q = rng.integers(0, 1 << bits, size=(M, K), dtype=np.uint8)
+    ng = K // group if group else 0
+    s = rng.uniform(0.01, 0.1, size=(M, ng)).astype(np.float16) if group else None
+    z = rng.uniform(0, (1 << bits) - 1, size=(M, ng)).astype(np.float16) if group else None
+    blob = T.tmac_pack_weights(desc3(M, K, bits, group), q, s, z)
+    hdr, q2, s2, z2 = unpack_layout3(blob)
+    assert (hdr["M"], hdr["K"], hdr["bits"], hdr["group"]) == (M, K, bits, group)
+    assert np.array_equal(q2[:M, :K], q)
+    assert not q2[M:].any() and not q2[:, K:].any()          # padding is index 0
+    if group:
+        assert np.array_equal(s2[:M].view(np.uint16), s.view(np.uint16))
+        assert np.array_equal(z2[:M].view(np.uint16), z.view(np.uint16))
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+def test_layout3_special_matrices(bits):
+    M, K = 66, 160
+    top = (1 << bits) - 1
+    for q in (np.zeros((M, K), np.uint8), np.full((M, K), top, np.uint8)):
+        _, q2, _, _ = unpack_layout3(T.tmac_pack_weights(desc3(M, K, bits, 0), q))
+        assert np.array_equal(q2[:M, :K], q)
+    q = np.zeros((M, K), np.uint8)
+    q[65, 159] = top
+    q[0, 0] = 1
+    _, q2, _, _ = unpack_layout3(T.tmac_pack_weights(desc3(M, K, bits, 0), q))
+    assert np.array_equal(q2[:M, :K], q)
+
+
+def test_layout3_sizes_and_group_rules():
+    d = desc3(5120, 5120, 4, 128)
+    assert T.tmac_packed_bytes(d) == 256 + 5120 * 5120 // 2 + 5120 * 40 * 4
+    assert T.tmac_workspace_bytes(d, 256) == 256
+    assert T.tmac_packed_bytes(desc3(100, 48, 2, 16)) > 0     # packs; the kernel rejects the group size
