@@ -59,6 +59,9 @@ def main():
     ap.add_argument("--ks", type=int, default=0, help="layout 1: tmac_tuning.chunks_per_wave override")
     ap.add_argument("--sweep", action="store_true", help="also time the W1..W4 and BitNet shapes")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead of graph replay")
+    ap.add_argument("--prefill-layout", type=int, default=3, help="packed layout of the N=256 sweep rows (3 or 1)")
+    ap.add_argument("--prefill-only", action="store_true",
+                    help="time only the N=256 rows of the sweep and print them (for profiling that kernel)")
     ap.add_argument("--two-call", action="store_true",
                     help="step = tmac_precompute_lut + tmac_mpgemm (two launches per GEMV) instead of the fused call")
     args = ap.parse_args()
@@ -161,6 +164,33 @@ def main():
         launches = max(1, total // reps)
         return timed(Replay(body or c.mpgemm, reps), launches, max(1, launches // 10))
 
+    def prefill_rows():
+        """Prefill mpGEMM, N = 256 (batched lookup kernel, layout 3; --prefill-layout 1 times the older
+        K-sliced LDS kernel): precompute + mpgemm per call."""
+        rows = []
+        for bits in (2, 4):
+            for i in range(3):
+                p = wl.config5(i, bits)
+                c = Case(p, layout=args.prefill_layout, ring_mb=0)
+
+                def both(c=c):
+                    c.precompute()
+                    c.mpgemm()
+                us = timed(Replay(both, 2), 10, 2)
+                pu = timed(Replay(c.precompute, 2), 10, 2)
+                flops = 2.0 * p.N * p.M * p.K
+                rows.append({"name": p.name, "bits": bits, "N": p.N, "call_us": round(us, 2),
+                             "precompute_us": round(pu, 2),
+                             "TOPS_equiv": round(flops / us / 1e6, 2),
+                             "lookups_per_s": round(p.N * p.M * (p.K / 4) * bits / us * 1e6, -6)})
+                del c
+                torch.cuda.empty_cache()
+        return rows
+
+    if args.prefill_only:
+        print(json.dumps({"prefill_n256": prefill_rows()}))
+        return
+
     cases = [Case(wl.config2(i)) for i in range(3)]
     step_bytes = sum(c.bytes for c in cases)
 
@@ -244,26 +274,7 @@ def main():
                 del c
                 torch.cuda.empty_cache()
             detail["stacked_projections"] = stacked
-        # prefill mpGEMM, N = 256 (LDS-table kernel, layout 1): precompute + mpgemm per call
-        prefill = []
-        for bits in (2, 4):
-            for i in range(3):
-                p = wl.config5(i, bits)
-                c = Case(p, layout=1, ring_mb=0)
-
-                def both(c=c):
-                    c.precompute()
-                    c.mpgemm()
-                us = timed(Replay(both, 2), 10, 2)
-                pu = timed(Replay(c.precompute, 2), 10, 2)
-                flops = 2.0 * p.N * p.M * p.K
-                prefill.append({"name": p.name, "bits": bits, "N": p.N, "call_us": round(us, 2),
-                                "precompute_us": round(pu, 2),
-                                "TOPS_equiv": round(flops / us / 1e6, 2),
-                                "lookups_per_s": round(p.N * p.M * (p.K / 4) * bits / us * 1e6, -6)})
-                del c
-                torch.cuda.empty_cache()
-        detail["prefill_n256"] = prefill
+        detail["prefill_n256"] = prefill_rows()
         xs = np.array([s["bits"] for s in sweep[:4]], dtype=np.float64)
         ys = np.array([s["mpgemm_us"] for s in sweep[:4]], dtype=np.float64)
         cfit, t0fit = np.polyfit(xs, ys, 1)

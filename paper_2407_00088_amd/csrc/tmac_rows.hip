@@ -128,37 +128,9 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
     __syncthreads();
 
     const int c_end = min(c0 + ROWS_KSL / 32, p.n_chunks);
-    // The LDS reads run one index dword (eight lookups) ahead of the accumulation: issue(plane b+1)
-    // comes before consume(plane b), also across chunk boundaries inside a slice.
-    ru32x2v e[2][8];
-    auto issue = [&](uint32_t xw, uint32_t cbase, ru32x2v (&dst)[8]) {
-      const uint32_t ev = (xw << 3) & 0x78787878u, od = (xw >> 1) & 0x78787878u;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        // address = {0, cbase byte 2, cbase byte 1, byte j/2 of the offsets}: one byte permute;
-        // the table's own 128 * j goes into the instruction's offset field
-        const uint32_t a = __builtin_amdgcn_perm((j & 1) ? od : ev, cbase, 0x0C020100u + 4u + (uint32_t)(j >> 1));
-        dst[j] = *reinterpret_cast<rows_lds_u32x2*>(a + j * 128);
-      }
-    };
-    auto consume = [&](const ru32x2v (&src)[8], int b) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        if constexpr (IS_INT) {
-          L[0] += (int)(int16_t)(src[j].x & 0xffffu) << b;
-          L[1] += ((int)src[j].x >> 16) << b;
-          L[2] += (int)(int16_t)(src[j].y & 0xffffu) << b;
-          L[3] += ((int)src[j].y >> 16) << b;
-        } else {
-          const float w = p.pw[b];
-          L[0] = fmaf(__half2float(__ushort_as_half((uint16_t)(src[j].x & 0xffffu))), w, L[0]);
-          L[1] = fmaf(__half2float(__ushort_as_half((uint16_t)(src[j].x >> 16))), w, L[1]);
-          L[2] = fmaf(__half2float(__ushort_as_half((uint16_t)(src[j].y & 0xffffu))), w, L[2]);
-          L[3] = fmaf(__half2float(__ushort_as_half((uint16_t)(src[j].y >> 16))), w, L[3]);
-        }
-      }
-    };
-    issue(xn[0], lds0, e[0]);  // plane 0 of the slice's first chunk (its indices are in xn)
+    // Per chunk and pair of bit planes: 16 LDS reads are issued first, then accumulated in issue
+    // order, so that the reads overlap each other and the accumulation of the earlier ones; the
+    // other waves of the SIMD cover the start of every round.
     for (int c = c0; c < c_end; ++c) {
       uint32_t x[BITS];
 #pragma unroll
@@ -175,17 +147,47 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
         }
       }
       const uint32_t cbase = lds0 + (uint32_t)(c - c0) * 1024u;
+      // rounds of at most two planes = 16 LDS reads: the hardware counts at most 15 outstanding LDS
+      // operations exactly, so a round's reads can be consumed one by one as they return
 #pragma unroll
-      for (int b = 0; b < BITS; ++b) {
-        // e[(BITS * chunk + b) & 1] holds plane b; BITS * chunk is even except for odd BITS, where
-        // the parity alternates with the chunk: use the flat position
-        const int cur = (BITS % 2 == 0) ? (b & 1) : (((c - c0) * BITS + b) & 1);
-        if (b + 1 < BITS) {
-          if (cur == 0) issue(x[b + 1], cbase, e[1]); else issue(x[b + 1], cbase, e[0]);
-        } else if (c + 1 < c_end) {
-          if (cur == 0) issue(xn[0], cbase + 1024u, e[1]); else issue(xn[0], cbase + 1024u, e[0]);
+      for (int b0 = 0; b0 < BITS; b0 += 2) {
+        constexpr int PL = 2;
+        ru32x2v e[PL][8];
+#pragma unroll
+        for (int bb = 0; bb < PL; ++bb) {
+          const int b = b0 + bb;
+          if (b >= BITS) break;
+          const uint32_t ev = (x[b] << 3) & 0x78787878u, od = (x[b] >> 1) & 0x78787878u;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            // address = {0, cbase byte 2, cbase byte 1, byte j/2 of the offsets}: one byte permute;
+            // the table's own 128 * j goes into the instruction's offset field
+            const uint32_t a = __builtin_amdgcn_perm((j & 1) ? od : ev, cbase, 0x0C020100u + 4u + (uint32_t)(j >> 1));
+            e[bb][j] = *reinterpret_cast<rows_lds_u32x2*>(a + j * 128);
+          }
         }
-        if (cur == 0) consume(e[0], b); else consume(e[1], b);
+        __builtin_amdgcn_sched_barrier(0);  // keep the reads above the accumulation
+#pragma unroll
+        for (int bb = 0; bb < PL; ++bb) {
+          const int b = b0 + bb;
+          if (b >= BITS) break;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            if constexpr (IS_INT) {
+              L[0] += (int)(int16_t)(e[bb][j].x & 0xffffu) << b;
+              L[1] += ((int)e[bb][j].x >> 16) << b;
+              L[2] += (int)(int16_t)(e[bb][j].y & 0xffffu) << b;
+              L[3] += ((int)e[bb][j].y >> 16) << b;
+            } else {
+              const float w = p.pw[b];
+              L[0] = fmaf(__half2float(__ushort_as_half((uint16_t)(e[bb][j].x & 0xffffu))), w, L[0]);
+              L[1] = fmaf(__half2float(__ushort_as_half((uint16_t)(e[bb][j].x >> 16))), w, L[1]);
+              L[2] = fmaf(__half2float(__ushort_as_half((uint16_t)(e[bb][j].y & 0xffffu))), w, L[2]);
+              L[3] = fmaf(__half2float(__ushort_as_half((uint16_t)(e[bb][j].y >> 16))), w, L[3]);
+            }
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
       if (p.grouped && gq < p.nq && ++cg == p.cpg) {
         const float s = __half2float(__ushort_as_half((uint16_t)(szv & 0xffffu)));
