@@ -190,9 +190,10 @@ tmac_status tmac_precompute_lut(const void* A_dev, tmac_act_t act, int32_t N, in
                                 int64_t lda, int32_t g, int32_t group, tmac_lut_t lut,
                                 void* lut_dev, size_t lut_bytes, void* stream);
 
-/* Bytes of workspace tmac_mpgemm needs (split-K partial sums and arrival counters).
- * The workspace must be zero-filled once before its first use; every call leaves the
- * counters at zero again.  Calls that share a workspace must not overlap in time. */
+/* Bytes of workspace tmac_mpgemm needs for exactly N activation rows (split-K partial sums and
+ * arrival counters; how a call is split depends on N, so a buffer meant for several N must take
+ * the largest).  The workspace must be zero-filled once before its first use; every call leaves
+ * the counters at zero again.  Calls that share a workspace must not overlap in time. */
 size_t tmac_workspace_bytes(const tmac_wdesc* desc, int32_t N);
 
 /* Look-up, bit-plane shift-accumulate, scale/zero, reduce (Algorithm 1 main loop, Eq. 1,

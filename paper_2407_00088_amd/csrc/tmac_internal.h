@@ -107,10 +107,17 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
                      int64_t lda, int lut_t, int N, const float* act_scale_dev, float weight_scale,
                      void* out_dev, int out_t, int64_t ldo, void* stream, int rows_per_group);
 
-// Batched lookup kernel (layout 3); defined in tmac_rows.hip.  Returns a tmac_status value.
+// Batched lookup kernel (layout 3); defined in tmac_rows.hip.
+struct RowsPlan {
+  int n_tiles_n, row_blocks;  // workgroups along N (4 activation rows each) and M (256 weight rows each)
+  int cps, slices;            // 32-k chunks per K slice, number of K slices (gridDim.z)
+  size_t part_bytes, ctr_bytes;  // workspace: partial sums and arrival counters (0 when slices == 1)
+};
+RowsPlan rows_plan(const tmac_wdesc* desc, int N);
+// Returns a tmac_status value.
 int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, int lut_t, int N,
                      const float* act_scale_dev, float weight_scale, void* out_dev, int out_t, int64_t ldo,
-                     void* stream);
+                     void* workspace_dev, size_t workspace_bytes, void* stream);
 
 // Records the last HIP error of this thread (diagnostics for TMAC_EHIP).
 void note_hip_error(int hip_error);

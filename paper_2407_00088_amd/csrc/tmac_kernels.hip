@@ -901,7 +901,11 @@ extern "C" tmac_status tmac_precompute_lut(const void* A_dev, tmac_act_t act, in
 
 extern "C" size_t tmac_workspace_bytes(const tmac_wdesc* desc, int32_t N) {
   if (!desc_valid(desc) || N <= 0) return 0;
-  if (desc->layout != TMAC_LAYOUT_T16K128) return 256;  // only the K-sliced LDS kernel needs a workspace
+  if (desc->layout == TMAC_LAYOUT_R8U16) return 256;  // the register-table kernel uses none
+  if (desc->layout == TMAC_LAYOUT_R64K32) {
+    const RowsPlan pl = rows_plan(desc, N);
+    return pl.part_bytes + pl.ctr_bytes + 256;
+  }
   const Geometry ge = geometry(desc);
   const size_t max_slices = (ge.n_chunks + KS_MAX_SLICES_CHUNKS - 1) / KS_MAX_SLICES_CHUNKS;
   const size_t part = (max_slices * (size_t)N * ge.Mp * 4 + 255) / 256 * 256;
@@ -948,7 +952,8 @@ extern "C" tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed
                    tuning->rows_per_group != 0))
       return TMAC_EUNSUPPORTED;
     return static_cast<tmac_status>(launch_rows_gemm(desc, packed_dev, lut_dev, (int)lut, N, act_scale_dev,
-                                                      weight_scale, out_dev, (int)out, ldo, stream));
+                                                      weight_scale, out_dev, (int)out, ldo, workspace_dev,
+                                                      workspace_bytes, stream));
   }
   // int32 accumulators: |L| <= 508 * (2^b - 1) * K/4 must stay below 2^31
   if (is_int && (double)508.0 * ((1 << desc->bits) - 1) * (desc->K / 4) >= 2147483647.0) return TMAC_EUNSUPPORTED;

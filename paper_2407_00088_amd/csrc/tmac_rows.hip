@@ -17,8 +17,13 @@
 //     looked-up register and multiplies by 2^i.
 //   * Scale, zero and bias once per quantisation group (Section 4, bit-serial linear transform).
 //   * Axis order (Section 3.2 "axis reordering"): K is walked slice by slice inside the
-//     workgroup, so only a [4, 1024]-slice of the tables is live in LDS and no split-K
-//     reduction is needed; the sums of a row stay in the lane's registers: fixed order.
+//     workgroup, so only a [4, 1024]-slice of the tables is live in LDS; the sums of a row stay
+//     in the lane's registers: fixed order.
+//   * Few activation rows (batched decode) leave too few (row block, n tile) pairs to fill the
+//     chip: K is then also split over gridDim.z workgroups, whose partial sums meet in the
+//     workspace; the last workgroup to arrive adds them in slice order (fixed order again) and
+//     writes the result.  Nobody waits for anybody: a counter per output block tells which
+//     workgroup is last.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -50,6 +55,10 @@ struct RowsParams {
   int64_t ldo;
   int M, N, KG, n_tiles, n_chunks, nq;
   int cpg;                 // 32-k chunks per quantisation group (grouped mode)
+  int cps;                 // 32-k chunks per workgroup along K (a multiple of cpg); gridDim.z slices
+  int Mp;                  // M rounded up to 64
+  float* ws_part;          // split K: [slices][N][Mp] partial sums (fp32, or int32 bit patterns)
+  int* ws_ctr;             // split K: arrival counters, one per (row block, n tile), zero between calls
   int grouped;             // 1: group scales, 0: one scale per row or per tensor
   int per_tensor, int_exact, icoef;
   float wscale, zero_point, mid;
@@ -63,6 +72,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
   constexpr int NT = ROWS_NT;
   constexpr int TPS = ROWS_KSL / 4;  // tables per slice
   __shared__ __attribute__((aligned(1024))) char tab[TPS * 128];  // byte-permuted addresses need the alignment
+  __shared__ int s_last;
   using AccT = typename std::conditional<IS_INT, int, float>::type;
 
   const int lane = threadIdx.x & 63;
@@ -94,13 +104,15 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
     }
   };
 
-  int gq = 0, cg = 0;        // current quantisation group and chunks done in it (wave-uniform)
+  // this workgroup's share of K: chunks [cz0, cz1)
+  const int cz0 = blockIdx.z * p.cps, cz1 = min(cz0 + p.cps, p.n_chunks);
+  int gq = p.grouped ? cz0 / p.cpg : 0, cg = 0;  // current quantisation group, chunks done in it (wave-uniform)
   uint32_t szv = 0;          // {scale, zero} of the lane's row for the current group
   float Sg[NT] = {0.f, 0.f, 0.f, 0.f};
   uint32_t xn[BITS];
-  load_idx(0, xn);
+  load_idx(cz0, xn);
 
-  for (int c0 = 0; c0 < p.n_chunks; c0 += ROWS_KSL / 32) {
+  for (int c0 = cz0; c0 < cz1; c0 += ROWS_KSL / 32) {
     // stage the tables of this K-slice for the NT activation rows: item = (table, half) reads the
     // 8 entries of the four rows and writes them entry-major
     __syncthreads();
@@ -127,7 +139,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
     }
     __syncthreads();
 
-    const int c_end = min(c0 + ROWS_KSL / 32, p.n_chunks);
+    const int c_end = min(c0 + ROWS_KSL / 32, cz1);
     // Per chunk and pair of bit planes: 16 LDS reads are issued first, then accumulated in issue
     // order, so that the reads overlap each other and the accumulation of the earlier ones; the
     // other waves of the SIMD cover the start of every round.
@@ -135,7 +147,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
       uint32_t x[BITS];
 #pragma unroll
       for (int b = 0; b < BITS; ++b) x[b] = xn[b];
-      if (c + 1 < p.n_chunks) load_idx(c + 1, xn);  // next chunk's indices, one chunk ahead
+      if (c + 1 < cz1) load_idx(c + 1, xn);  // next chunk's indices, one chunk ahead
       if (p.grouped && cg == 0 && gq < p.nq) {  // (chunks in the K padding belong to no group)
         // scale/zero of the group that starts here and the activation sums its bias term needs
         szv = my_sz[(size_t)gq * 64];
@@ -205,38 +217,109 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
 
   // finish and store: lanes of a wave write 64 consecutive outputs of one activation row
   const int m = tile_raw * 64 + lane;
-  if (!tile_ok || m >= p.M) return;
+  const bool row_ok = tile_ok && m < p.M;
   float s = p.wscale, z = p.zero_point;
   if (!p.grouped && !p.per_tensor) {
     const uint32_t v = my_sz[0];
     s = __half2float(__ushort_as_half((uint16_t)(v & 0xffffu)));
     z = __half2float(__ushort_as_half((uint16_t)(v >> 16)));
   }
-#pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    const int n = n0 + t;
-    if (n >= p.N) break;
+  // vf: finished group sums (grouped) or raw look-up sum (fp); vi: raw integer look-up sum
+  auto finish = [&](int n, float vf, int vi) {
     const float as = p.act_scale ? p.act_scale[n] : 1.0f;
     float res;
     int ires = 0;
     if (p.grouped) {
-      res = acc[t] * as;
+      res = vf * as;
     } else if constexpr (IS_INT) {
       const int St = static_cast<const int*>(p.S)[n];
       if (p.int_exact) {
-        ires = ((int)L[t] + p.icoef * St) >> 1;  // numerator is always even
-        res = ((float)ires * as) * s;            // two roundings, left to right
+        ires = (vi + p.icoef * St) >> 1;  // numerator is always even
+        res = ((float)ires * as) * s;     // two roundings, left to right
       } else {
-        res = (fmaf(p.mid - z, (float)St, 0.5f * (float)L[t]) * as) * s;
+        res = (fmaf(p.mid - z, (float)St, 0.5f * (float)vi) * as) * s;
       }
     } else {
       const float St = static_cast<const float*>(p.S)[n];
-      res = (s * fmaf(p.mid - z, St, 0.5f * (float)L[t])) * as;
+      res = (s * fmaf(p.mid - z, St, 0.5f * vf)) * as;
     }
     const size_t o = (size_t)n * p.ldo + m;
     if (p.out_t == TMAC_OUT_F32) static_cast<float*>(p.out)[o] = res;
     else if (p.out_t == TMAC_OUT_F16) static_cast<__half*>(p.out)[o] = __float2half_rn(res);
     else static_cast<int*>(p.out)[o] = ires;
+  };
+  constexpr bool RAW_INT = IS_INT;  // ungrouped integer tables: partial sums are exact integers
+  const int nz = gridDim.z;
+  if (nz == 1) {
+    if (!row_ok) return;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      if (n0 + t >= p.N) break;
+      finish(n0 + t, p.grouped ? acc[t] : (float)L[t], IS_INT ? (int)L[t] : 0);
+    }
+    return;
+  }
+
+  // Split K: publish the partial sums; the last workgroup to arrive for this (row block, n tile)
+  // adds the slices in slice order and writes the result.  Visibility across the chip's XCDs (one
+  // L2 each): partials are written with agent-scope atomic stores, every wave waits for its
+  // stores (workgroup-scope release), the barrier orders all waves before thread 0's agent-scope
+  // counter increment, and the reader uses agent-scope atomic loads, which do not hit stale
+  // lines of its own L2.
+  const bool raw_int = RAW_INT && !p.grouped;
+  if (tile_ok) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int n = n0 + t;
+      if (n < p.N) {
+        const size_t o = ((size_t)blockIdx.z * p.N + n) * p.Mp + (size_t)tile_raw * 64 + lane;
+        const float v = p.grouped ? acc[t] : (raw_int ? __int_as_float((int)L[t]) : (float)L[t]);
+        __hip_atomic_store(p.ws_part + o, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int* ctr = p.ws_ctr + (size_t)blockIdx.y * gridDim.x + blockIdx.x;
+    const int ticket = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = (ticket == nz - 1);
+    if (last) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = last;
+  }
+  __syncthreads();
+  if (!s_last || !row_ok) return;
+  // four slices x NT rows of loads in flight per round trip; sums taken in slice order
+  float sf[NT] = {0.f, 0.f, 0.f, 0.f};
+  int si[NT] = {0, 0, 0, 0};
+  const size_t mrow = (size_t)tile_raw * 64 + lane;
+  for (int sl0 = 0; sl0 < nz; sl0 += 4) {
+    float v[4][NT];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int sl = min(sl0 + u, nz - 1);
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const int n = min(n0 + t, p.N - 1);
+        v[u][t] = __hip_atomic_load(p.ws_part + ((size_t)sl * p.N + n) * p.Mp + mrow, __ATOMIC_RELAXED,
+                                    __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (sl0 + u < nz) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          if (raw_int) si[t] += __float_as_int(v[u][t]);
+          else sf[t] += v[u][t];
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    if (n0 + t >= p.N) break;
+    finish(n0 + t, sf[t], si[t]);
   }
 }
 
@@ -244,7 +327,8 @@ template <bool IS_INT, int BITS>
 static hipError_t launch_rows_one(const RowsParams& p, hipStream_t st) {
   RowsParams local = p;
   void* args[] = {&local};
-  const dim3 grid((p.N + ROWS_NT - 1) / ROWS_NT, (p.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES);
+  const dim3 grid((p.N + ROWS_NT - 1) / ROWS_NT, (p.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES,
+                  (p.n_chunks + p.cps - 1) / p.cps);
   return hipLaunchKernel(reinterpret_cast<const void*>(mpgemm_rows_kernel<IS_INT, BITS>), grid,
                          dim3(64 * ROWS_WAVES), args, 0, st);
 }
@@ -260,17 +344,46 @@ static hipError_t launch_rows_bits(const RowsParams& p, int bits, hipStream_t st
   return hipErrorInvalidValue;
 }
 
+// How a call is split: workgroups along N and M, and the number of K slices (1 when the (row block,
+// n tile) pairs alone fill the chip; otherwise enough slices of at least 256 k, whole quantisation
+// groups each, to give about two workgroups per CU).
+RowsPlan rows_plan(const tmac_wdesc* desc, int N) {
+  const Geometry ge = geometry(desc);
+  RowsPlan pl;
+  pl.n_tiles_n = (N + ROWS_NT - 1) / ROWS_NT;
+  pl.row_blocks = (ge.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES;
+  const bool one_group = (desc->group == 0 || desc->group == desc->K);
+  const int cpg = (one_group || desc->group < 32) ? 1 : desc->group / 32;  // (sizes below 32 are rejected at launch)
+  const int min_cps = (8 + cpg - 1) / cpg * cpg;  // at least 256 k, whole groups
+  const int64_t pairs = (int64_t)pl.n_tiles_n * pl.row_blocks;
+  int64_t want = pairs >= 512 ? 1 : (512 + pairs - 1) / pairs;
+  const int max_slices = (ge.n_chunks + min_cps - 1) / min_cps;
+  if (want > max_slices) want = max_slices;
+  int cps = (int)((ge.n_chunks + want - 1) / want);
+  cps = (cps + cpg - 1) / cpg * cpg;
+  if (cps < min_cps) cps = min_cps;
+  pl.cps = cps;
+  pl.slices = (ge.n_chunks + cps - 1) / cps;
+  pl.part_bytes = pl.slices > 1 ? ((size_t)pl.slices * N * ge.Mp * 4 + 255) / 256 * 256 : 0;
+  pl.ctr_bytes = pl.slices > 1 ? ((size_t)pairs * 4 + 255) / 256 * 256 : 0;
+  return pl;
+}
+
 int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, int lut_t, int N,
                      const float* act_scale_dev, float weight_scale, void* out_dev, int out_t, int64_t ldo,
-                     void* stream) {
+                     void* workspace_dev, size_t workspace_bytes, void* stream) {
   if (lut_t != TMAC_LUT_F16 && lut_t != TMAC_LUT_I16) return TMAC_EUNSUPPORTED;
   const Geometry ge = geometry(desc);
   LutGeom lg;
   if (!lut_geom(N, desc->K, desc->g, desc->group, lut_t, &lg)) return TMAC_EINVAL;
   const bool is_int = (lut_t == TMAC_LUT_I16);
   const bool one_group = (desc->group == 0 || desc->group == desc->K);
-  if ((N + ROWS_NT - 1) / ROWS_NT > 0x7fffffff || (ge.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES > 65535)
-    return TMAC_EUNSUPPORTED;
+  const RowsPlan pl = rows_plan(desc, N);
+  if (pl.n_tiles_n > 0x7fffffff || pl.row_blocks > 65535 || pl.slices > 65535) return TMAC_EUNSUPPORTED;
+  if (pl.slices > 1) {
+    if (!workspace_dev) return TMAC_EINVAL;
+    if (workspace_bytes < pl.part_bytes + pl.ctr_bytes) return TMAC_ESIZE;
+  }
   // int32 accumulators: |L| <= 508 * (2^b - 1) * K/4 must stay below 2^31
   if (is_int && (double)508.0 * ((1 << desc->bits) - 1) * (desc->K / 4) >= 2147483647.0) return TMAC_EUNSUPPORTED;
 
@@ -285,7 +398,11 @@ int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void*
   p.ldo = ldo;
   p.M = desc->M; p.N = N; p.KG = lg.KG; p.n_tiles = ge.n_tiles; p.n_chunks = ge.n_chunks; p.nq = lg.nq;
   p.grouped = one_group ? 0 : 1;
-  p.cpg = one_group ? 0 : desc->group / 32;
+  p.cpg = one_group ? 1 : desc->group / 32;
+  p.cps = pl.cps;
+  p.Mp = ge.Mp;
+  p.ws_part = static_cast<float*>(workspace_dev);
+  p.ws_ctr = workspace_dev ? reinterpret_cast<int*>(static_cast<char*>(workspace_dev) + pl.part_bytes) : nullptr;
   p.per_tensor = (desc->group == 0);
   p.wscale = weight_scale;
   p.mid = 0.5f * (float)((1 << desc->bits) - 1);

@@ -37,8 +37,9 @@ class LinearLUT:
         self.packed_bytes = int(blob.size)
         self.packed = torch.from_numpy(blob).to(device)
         self.lut = torch.empty(B.tmac_lut_bytes(max_N, K, group, self.lut_t), dtype=torch.uint8, device=device)
-        self.workspace = torch.zeros(max(B.tmac_workspace_bytes(self.desc, max_N), 256), dtype=torch.uint8,
-                                     device=device)
+        # the split of a call (and with it the workspace) depends on N: size for every N up to max_N
+        ws = max(B.tmac_workspace_bytes(self.desc, n) for n in range(1, max_N + 1))
+        self.workspace = torch.zeros(max(ws, 256), dtype=torch.uint8, device=device)
 
     def precompute(self, A, N: Optional[int] = None, stream=None):
         N = A.shape[0] if N is None else N

@@ -72,5 +72,6 @@ def test_layout3_special_matrices(bits):
 def test_layout3_sizes_and_group_rules():
     d = desc3(5120, 5120, 4, 128)
     assert T.tmac_packed_bytes(d) == 256 + 5120 * 5120 // 2 + 5120 * 40 * 4
-    assert T.tmac_workspace_bytes(d, 256) == 256
+    assert T.tmac_workspace_bytes(d, 256) == 256             # enough (row block, n tile) pairs: K is not split
+    assert T.tmac_workspace_bytes(d, 4) > 4 * 5120 * 4        # few rows: partial sums of the K slices
     assert T.tmac_packed_bytes(desc3(100, 48, 2, 16)) > 0     # packs; the kernel rejects the group size
