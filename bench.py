@@ -53,13 +53,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--ring-mb", type=int, default=RING_MB)
-    ap.add_argument("--layout", type=int, default=2, help="packed layout: 2 = register-table kernel, 1 = LDS kernels")
-    ap.add_argument("--rows", type=int, default=0, help="layout 2: tmac_tuning.rows_per_group override (8 or 16)")
-    ap.add_argument("--kernel", type=int, default=0, help="layout 1: tmac_tuning.kernel override (0 = default)")
-    ap.add_argument("--ks", type=int, default=0, help="layout 1: tmac_tuning.chunks_per_wave override")
+    ap.add_argument("--rows", type=int, default=0, help="tmac_tuning.rows_per_group override (8 or 16)")
     ap.add_argument("--sweep", action="store_true", help="also time the W1..W4 and BitNet shapes")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead of graph replay")
-    ap.add_argument("--prefill-layout", type=int, default=3, help="packed layout of the N=256 sweep rows (3 or 1)")
     ap.add_argument("--prefill-only", action="store_true",
                     help="time only the N=256 rows of the sweep and print them (for profiling that kernel)")
     ap.add_argument("--two-call", action="store_true",
@@ -81,18 +77,14 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda"
-    tuning = None
-    if args.layout == 1 and (args.ks or args.kernel):
-        tuning = tmac_tuning(args.ks, 0, args.kernel)
-    elif args.layout == 2 and args.rows:
-        tuning = tmac_tuning(0, 0, 0, args.rows)
+    tuning = tmac_tuning(args.rows) if args.rows else None
     stream = torch.cuda.Stream()
     sink = torch.zeros(256, dtype=torch.uint8, device=dev)
 
     class Case:
-        def __init__(self, p, layout=None, ring_mb=None, lut_t=None):
+        def __init__(self, p, ring_mb=None, lut_t=None):
             self.p = p
-            self.lin = from_problem(p, layout=args.layout if layout is None else layout, lut_t=lut_t)
+            self.lin = from_problem(p, lut_t=lut_t)   # N <= 8: register-table layout; above: batched layout
             self.bytes = algorithmic_bytes(p.M, p.K, p.bits, p.group, p.N, act_bytes=1 if p.int_path else 2)
             n_copies = max(2, ((args.ring_mb if ring_mb is None else ring_mb) << 20) // self.lin.packed_bytes + 1)
             self.ring = [self.lin.packed] + [self.lin.packed.clone() for _ in range(n_copies - 1)]
@@ -165,13 +157,12 @@ def main():
         return timed(Replay(body or c.mpgemm, reps), launches, max(1, launches // 10))
 
     def prefill_rows():
-        """Prefill mpGEMM, N = 256 (batched lookup kernel, layout 3; --prefill-layout 1 times the older
-        K-sliced LDS kernel): precompute + mpgemm per call."""
+        """Prefill mpGEMM, N = 256 (batched lookup kernel): precompute + mpgemm per call."""
         rows = []
         for bits in (2, 4):
             for i in range(3):
                 p = wl.config5(i, bits)
-                c = Case(p, layout=args.prefill_layout, ring_mb=0)
+                c = Case(p, ring_mb=0)
 
                 def both(c=c):
                     c.precompute()
@@ -194,7 +185,7 @@ def main():
     cases = [Case(wl.config2(i)) for i in range(3)]
     step_bytes = sum(c.bytes for c in cases)
 
-    fused = (args.layout == 2 and not args.two_call)
+    fused = not args.two_call
 
     def step():
         for c in cases:
@@ -214,7 +205,7 @@ def main():
     # dominant kernel: the lookup kernel alone (the fused one when the step uses it), back-to-back
     # over the weight ring
     mp_us = [measure_kernel(c, args.steps) for c in cases]
-    fu_us = [measure_kernel(c, args.steps, c.fused) for c in cases] if args.layout == 2 else [None] * 3
+    fu_us = [measure_kernel(c, args.steps, c.fused) for c in cases]
     per_us = fu_us if fused else mp_us
     achieved = sum(c.bytes for c in cases) / (sum(per_us) * 1e-6) / 1e9
     pre_us = [timed(Replay(c.precompute, 50), max(1, args.steps // 50), 2) for c in cases]
@@ -237,7 +228,7 @@ def main():
         for p in extra:
             c = Case(p)
             us = measure_kernel(c, args.steps)
-            fu = measure_kernel(c, args.steps, c.fused) if args.layout == 2 else None
+            fu = measure_kernel(c, args.steps, c.fused)
             pu = timed(Replay(c.precompute, 50), max(1, args.steps // 50), 2)
             ru = measure_kernel(c, args.steps, c.stream_read)
             sweep.append({"name": p.name, "bits": p.bits, "mpgemm_us": round(us, 3),
@@ -248,32 +239,31 @@ def main():
             del c
             torch.cuda.empty_cache()
         detail["sweep"] = sweep
-        if args.layout == 2:
-            # int8 table quantisation (Section 3.3): lookup kernel with int8 tables, two-call path
-            tq = []
-            for i in range(3):
-                c = Case(wl.config2(i), lut_t=T.TMAC_LUT_I8Q)
-                us = measure_kernel(c, args.steps)
-                pu = timed(Replay(c.precompute, 50), max(1, args.steps // 50), 2)
-                tq.append({"name": c.p.name + "_int8_tables", "mpgemm_us": round(us, 3), "precompute_us": round(pu, 3),
-                           "bytes": c.bytes, "GBps": round(c.bytes / us / 1e3, 1),
-                           "frac_hbm_peak": round(c.bytes / us / 1e3 / HBM_PEAK_GBPS, 4)})
-                del c
-                torch.cuda.empty_cache()
-            detail["table_quantisation"] = tq
-            # stacked projections in one call (Q,K,V and gate,up of Llama-2-7B stacked along M): the
-            # fraction of the roofline the same kernel reaches once a call moves more bytes
-            stacked = []
-            for M, K in ((12288, 4096), (22016, 4096)):
-                c = Case(wl.make_grouped(3, 50 + M // 1000, 1, M, K, 4, 128, name=f"stacked_{M}x{K}_w4_n1"))
-                fu = measure_kernel(c, args.steps, c.fused)
-                ru = measure_kernel(c, args.steps, c.stream_read)
-                stacked.append({"name": c.p.name, "fused_us": round(fu, 3), "plain_read_of_same_bytes_us": round(ru, 3),
-                                "bytes": c.bytes, "GBps": round(c.bytes / fu / 1e3, 1),
-                                "frac_hbm_peak": round(c.bytes / fu / 1e3 / HBM_PEAK_GBPS, 4)})
-                del c
-                torch.cuda.empty_cache()
-            detail["stacked_projections"] = stacked
+        # int8 table quantisation (Section 3.3): lookup kernel with int8 tables, two-call path
+        tq = []
+        for i in range(3):
+            c = Case(wl.config2(i), lut_t=T.TMAC_LUT_I8Q)
+            us = measure_kernel(c, args.steps)
+            pu = timed(Replay(c.precompute, 50), max(1, args.steps // 50), 2)
+            tq.append({"name": c.p.name + "_int8_tables", "mpgemm_us": round(us, 3), "precompute_us": round(pu, 3),
+                       "bytes": c.bytes, "GBps": round(c.bytes / us / 1e3, 1),
+                       "frac_hbm_peak": round(c.bytes / us / 1e3 / HBM_PEAK_GBPS, 4)})
+            del c
+            torch.cuda.empty_cache()
+        detail["table_quantisation"] = tq
+        # stacked projections in one call (Q,K,V and gate,up of Llama-2-7B stacked along M): the
+        # fraction of the roofline the same kernel reaches once a call moves more bytes
+        stacked = []
+        for M, K in ((12288, 4096), (22016, 4096)):
+            c = Case(wl.make_grouped(3, 50 + M // 1000, 1, M, K, 4, 128, name=f"stacked_{M}x{K}_w4_n1"))
+            fu = measure_kernel(c, args.steps, c.fused)
+            ru = measure_kernel(c, args.steps, c.stream_read)
+            stacked.append({"name": c.p.name, "fused_us": round(fu, 3), "plain_read_of_same_bytes_us": round(ru, 3),
+                            "bytes": c.bytes, "GBps": round(c.bytes / fu / 1e3, 1),
+                            "frac_hbm_peak": round(c.bytes / fu / 1e3 / HBM_PEAK_GBPS, 4)})
+            del c
+            torch.cuda.empty_cache()
+        detail["stacked_projections"] = stacked
         detail["prefill_n256"] = prefill_rows()
         xs = np.array([s["bits"] for s in sweep[:4]], dtype=np.float64)
         ys = np.array([s["mpgemm_us"] for s in sweep[:4]], dtype=np.float64)
@@ -329,9 +319,8 @@ def main():
                                  if (fused and not args.rows) else None),
                      "traffic_unit": "bytes per step (three launches), rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated",
                      "algorithmic_bytes": step_bytes,
-                     "kernel": (("mpgemv_perm_kernel<f16 tables, 4 bit, chunk scales, 8 rows, "
-                                 + ("fused table build>" if fused else "tables from the LUT buffer>"))
-                                if args.layout == 2 else "mpgemv_fullk_kernel<f16 tables, 4 bit, group scales>"),
+                     "kernel": ("mpgemv_perm_kernel<f16 tables, 4 bit, chunk scales, 8 rows, "
+                                + ("fused table build>" if fused else "tables from the LUT buffer>")),
                      "launch_us": [round(u, 3) for u in per_us]},
         "cpu_baseline": cpu,
         "detail": detail,

@@ -70,8 +70,8 @@ typedef enum { TMAC_OUT_F32 = 0, TMAC_OUT_F16 = 1, TMAC_OUT_I32 = 2 } tmac_out_t
  *   g      LUT group size; must be 4 (one 16-entry table per 4 activations)
  *   group  quantisation group G along K (which sizes a layout accepts is said with the layout);
  *          == K: one scale per row; 0 = one scale and zero for the whole tensor
- *   layout TMAC_LAYOUT_*: 1 and 3 serve any number of activation rows (3 is the fast one for
- *          many rows), 2 is the decode layout (few rows)
+ *   layout TMAC_LAYOUT_*: 2 is the decode layout (few activation rows: up to about 8), 3 serves
+ *          any number of activation rows and is the fast one from about 16 on
  *   zero_point  per-tensor zero in code units (group == 0 only), e.g. 1 for ternary
  *          weights stored as q = t+1 (Section 5.1: ternary weights run as 2-bit) */
 typedef struct {
@@ -80,26 +80,16 @@ typedef struct {
   int32_t reserved;     /* must be 0 */
 } tmac_wdesc;
 
-/* Packed layout 1 ("tile 16 rows x 128 k"; Section 3.2 weight permutation + interleaving):
+/* A packed blob is a 256-byte header (struct tmac_blob_header below), the index region and the
+ * scale/zero region, each starting at a multiple of 256 bytes.  Rows >= M and k >= K are padded
+ * with index 0.  Bit (k % 4) of a 4-bit index belongs to element k (lowest k = least significant
+ * bit).  K is padded to a multiple of 128 (Kp).
  *
- *   header   256 bytes (struct tmac_blob_header below)
- *   indices  u32 idx[n_tiles][n_chunks][64][bits]
- *            tile t = rows 16t..16t+15, chunk c = k in [128c, 128c+128), lane = 16*phi + r
- *            (r = row in tile, phi = 0..3).  The dword [t][c][16*phi+r][i] holds the eight
- *            4-bit indices of bit plane i of row 16t+r for LUT groups kg = 32c + 4j + phi,
- *            j = 0..7; index j sits in nibble position 2j (j < 4) or 2(j-4)+1 (j >= 4), so
- *            that (x<<1)&0x1E1E1E1E and (x>>3)&0x1E1E1E1E yield byte-aligned table offsets
- *            in order.  Bit (k % 4) of an index belongs to element k (lowest k = LSB).
- *            Rows >= M and k >= K are padded with index 0.
- *   scales   u16 sz[n_tiles][n_qgroups][16][2]  = {fp16 scale, fp16 zero} per row and
- *            quantisation group (n_qgroups = K/G, 1 when group == K, absent when group == 0)
- *   One wavefront reads 64*4*bits contiguous bytes per (tile, chunk).
- */
-/* Packed layout 2 ("tile 8 rows x units of 16 k", for the register-table decode kernel;
+ * Packed layout 2 ("tile 8 rows x units of 16 k", for the register-table decode kernel;
  * Section 3.2 permutation + interleaving, Section 3.3 mirror consolidation folded into
  * the stored indices):
  *
- *   header   as layout 1 (Mp = M rounded up to 8, n_tiles = Mp/8, n_chunks = Kp/16 units)
+ *   header   Mp = M rounded up to 8, n_tiles = Mp/8, n_chunks = Kp/16 units
  *   indices  per tile t (rows 8t..8t+7) the records of its n_units units, 4*bits dwords each:
  *            record[tb][d], unit u = k in [16u, 16u+16), table tb = LUT group kg = 4u + tb.
  *            One lane of the kernel owns one unit (four tables held in registers).  Eight
@@ -128,7 +118,7 @@ typedef struct {
 /* Packed layout 3 ("tile 64 rows x chunks of 32 k", for the batched lookup kernel that serves many
  * activation rows; Section 3.2: a large tile over M lets many weight rows reuse one table):
  *
- *   header   as layout 1 (Mp = M rounded up to 64, n_tiles = Mp/64, n_chunks = Kp/32)
+ *   header   Mp = M rounded up to 64, n_tiles = Mp/64, n_chunks = Kp/32
  *   indices  u32 idx[n_tiles][n_chunks][64][bits]: dword [t][c][r][i] holds the eight 4-bit
  *            indices of bit plane i of row 64t+r for LUT groups kg = 8c + j, index j in nibble j
  *            (bits 4j..4j+3).  One lane of the kernel owns one row and reads its `bits` dwords of
@@ -138,13 +128,13 @@ typedef struct {
  *   Group sizes: any multiple of 32, or K, or 0 (per tensor).  Table types: TMAC_LUT_F16 and
  *   TMAC_LUT_I16.
  */
-enum { TMAC_LAYOUT_T16K128 = 1, TMAC_LAYOUT_R8U16 = 2, TMAC_LAYOUT_R64K32 = 3 };
+enum { TMAC_LAYOUT_R8U16 = 2, TMAC_LAYOUT_R64K32 = 3 };
 
 typedef struct {
   uint32_t magic;        /* 0x43414D54 "TMAC" */
   uint32_t layout;
   int32_t  M, K, bits, g, group;
-  int32_t  Mp, Kp;       /* M rounded up to 16, K rounded up to 128 */
+  int32_t  Mp, Kp;       /* M rounded up to the layout's row tile, K rounded up to 128 */
   int32_t  n_tiles, n_chunks, n_qgroups;
   float    zero_point;   /* per-tensor zero (group == 0) */
   uint32_t reserved0;
@@ -223,23 +213,17 @@ tmac_status tmac_mpgemm(const tmac_wdesc* desc, const void* packed_dev, const vo
  *   A_dev       [N,K] fp16 (TMAC_ACT_F16: fp16 tables) or int8 (TMAC_ACT_I8: exact integer
  *               tables), 16-byte aligned, leading dimension lda a multiple of 8 (fp16) or 16 (int8)
  *   other arguments as tmac_mpgemm; no LUT buffer and no workspace.
- * Errors: TMAC_EINVAL, TMAC_EUNSUPPORTED (layout 1, K % 16 != 0, unsupported group), TMAC_EHIP. */
+ * Errors: TMAC_EINVAL, TMAC_EUNSUPPORTED (layout 3, K % 16 != 0, unsupported group), TMAC_EHIP. */
 tmac_status tmac_mpgemv_fused(const tmac_wdesc* desc, const void* packed_dev, const void* A_dev,
                               tmac_act_t act, int32_t N, int64_t lda, const float* act_scale_dev,
                               float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
                               void* stream);
 
 /* Launch-shape knobs for benchmarking sweeps; 0 = library default.
- *   kernel           1 = K-sliced kernel (tables of a K-slice in LDS, split-K reduction through
- *                    the workspace), 2 = full-K decode kernel (all tables of one activation row
- *                    in LDS, one 16-row tile per workgroup; needs K <= 20416 and a group size
- *                    that is 0, K or a multiple of 128; TMAC_EUNSUPPORTED otherwise)
- *   chunks_per_wave  K-sliced kernel: 128-k chunks one wavefront covers: 2, 4 or 8
- *   n_tile           K-sliced kernel: activation rows handled per workgroup pass: 1 or 4
- *   rows_per_group   register-table kernel (layout 2, which takes none of the knobs above):
- *                    weight rows per workgroup, 8 or 16 */
+ *   rows_per_group   register-table kernel (layout 2): weight rows per workgroup, 8 or 16;
+ *                    must be 0 for layout 3 (TMAC_EUNSUPPORTED otherwise) */
 typedef struct {
-  int32_t chunks_per_wave, n_tile, kernel, rows_per_group, reserved[4];
+  int32_t rows_per_group, reserved[7];
 } tmac_tuning;
 
 /* Same as tmac_mpgemm with explicit launch-shape knobs (NULL = defaults). */

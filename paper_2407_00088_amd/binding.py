@@ -21,7 +21,6 @@ TMAC_OK, TMAC_EINVAL, TMAC_EUNSUPPORTED, TMAC_ESIZE, TMAC_EHIP = range(5)
 TMAC_ACT_F16, TMAC_ACT_I8 = 0, 1
 TMAC_LUT_F16, TMAC_LUT_I16, TMAC_LUT_I8Q = 0, 1, 2
 TMAC_OUT_F32, TMAC_OUT_F16, TMAC_OUT_I32 = 0, 1, 2
-TMAC_LAYOUT_T16K128 = 1   # LDS-table kernels (any N)
 TMAC_LAYOUT_R8U16 = 2     # register-table decode kernel (small N)
 TMAC_LAYOUT_R64K32 = 3    # batched lookup kernel, lane = weight row (many activation rows)
 
@@ -39,8 +38,7 @@ class tmac_wdesc(C.Structure):
 
 
 class tmac_tuning(C.Structure):
-    _fields_ = [("chunks_per_wave", C.c_int32), ("n_tile", C.c_int32), ("kernel", C.c_int32),
-                ("rows_per_group", C.c_int32), ("reserved", C.c_int32 * 4)]
+    _fields_ = [("rows_per_group", C.c_int32), ("reserved", C.c_int32 * 7)]
 
 
 class TmacError(RuntimeError):
@@ -99,7 +97,7 @@ def _check(status: int, where: str) -> None:
 
 
 def wdesc(M: int, K: int, bits: int, group: int, zero_point: float = 0.0, g: int = 4,
-          layout: int = TMAC_LAYOUT_T16K128) -> tmac_wdesc:
+          layout: int = TMAC_LAYOUT_R64K32) -> tmac_wdesc:
     return tmac_wdesc(M, K, bits, g, group, layout, float(zero_point), 0)
 
 

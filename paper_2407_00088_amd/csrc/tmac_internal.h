@@ -14,14 +14,13 @@ constexpr uint32_t TMAC_MAGIC = 0x43414D54u;  // "TMAC"
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 // Geometry of a packed weight blob (both layouts).
-//   layout 1: row tiles of 16, k chunks of 128;  layout 2: row tiles of 8, lane-units of 16 k;
-//   layout 3: row tiles of 64, k chunks of 32.
+//   layout 2: row tiles of 8, lane-units of 16 k;  layout 3: row tiles of 64, k chunks of 32.
 struct Geometry {
   int Mp, Kp;          // padded M and K
-  int n_tiles;         // row tiles (16 rows in layout 1, 8 in layout 2, 64 in layout 3)
-  int n_chunks;        // layout 1: 128-k chunks; layout 2: 16-k lane-units; layout 3: 32-k chunks
+  int n_tiles;         // row tiles (8 rows in layout 2, 64 in layout 3)
+  int n_chunks;        // layout 2: 16-k lane-units; layout 3: 32-k chunks
   int n_qgroups;       // scale groups per row stored in the blob (0 when per-tensor)
-  int tile_rows;       // 16, 8 or 64
+  int tile_rows;       // 8 or 64
   uint64_t idx_off, idx_bytes, sz_off, sz_bytes, total_bytes;
 };
 
@@ -43,8 +42,8 @@ struct LutGeom {
   size_t total;
 };
 
-// lut_t: a tmac_lut_t value.  The 16-entry tables [N][KG][16] at offset 0 (read by the LDS
-// kernels) exist for the 16-bit table types only.
+// lut_t: a tmac_lut_t value.  The 16-entry tables [N][KG][16] at offset 0 (read by the batched
+// kernel) exist for the 16-bit table types only.
 inline bool lut_geom(int N, int K, int g, int group, int lut_t, LutGeom* lg) {
   if (N <= 0 || K <= 0 || g != 4 || K % 4 != 0 || group < 0) return false;
   if (group > 0 && (K % group != 0 || group % 4 != 0)) return false;

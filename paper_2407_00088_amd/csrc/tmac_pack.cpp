@@ -4,9 +4,8 @@
 // g = 4 consecutive bits of a plane along K are packed into one 4-bit index, bit (k % g)
 // belonging to element k.  Section 3.2 "Weight permutation": the indices are stored tile by
 // tile in exactly the order the lookup kernel walks them, so that one wavefront reads one
-// contiguous run per step.  Section 3.2 "Weight interleaving": inside a dword the eight
-// indices are placed so that the kernel's mask-and-shift unpacking leaves them in processing
-// order.  Section 3.3 "Mirror consolidation" (layout 2 only): an index p >= 8 is stored as a
+// contiguous run per step.  Section 3.2 "Weight interleaving": inside a dword the indices
+// are placed so that the kernel's mask-and-shift unpacking leaves them in processing order.  Section 3.3 "Mirror consolidation" (layout 2 only): an index p >= 8 is stored as a
 // sign bit plus the 3-bit selector of its mirror entry 15 - p, because T[p] = -T[15 - p].
 #include <cstring>
 
@@ -20,8 +19,7 @@ bool desc_valid(const tmac_wdesc* d) {
   if (d->M <= 0 || d->K <= 0) return false;
   if (d->bits < 1 || d->bits > 4) return false;
   if (d->g != 4) return false;
-  if (d->layout != TMAC_LAYOUT_T16K128 && d->layout != TMAC_LAYOUT_R8U16 && d->layout != TMAC_LAYOUT_R64K32)
-    return false;
+  if (d->layout != TMAC_LAYOUT_R8U16 && d->layout != TMAC_LAYOUT_R64K32) return false;
   if (d->K % d->g != 0) return false;
   if (d->group < 0 || d->reserved != 0) return false;
   if (!(d->zero_point == d->zero_point)) return false;  // NaN
@@ -32,8 +30,6 @@ bool desc_valid(const tmac_wdesc* d) {
 }
 
 // Group sizes the lookup kernels can apply scales for.
-//   layout 1: whole chunks (multiples of 128), the sub-chunk sizes 32 and 64, one group per
-//             row, or one per tensor.
 //   layout 2: any multiple of 16 (a lane's four tables must share one group), one group per
 //             row, or one per tensor.
 //   layout 3: any multiple of 32 (a chunk of eight tables must share one group), one group per
@@ -42,8 +38,7 @@ bool group_supported(const tmac_wdesc* d) {
   const int G = d->group;
   if (G == 0 || G == d->K) return true;
   if (d->layout == TMAC_LAYOUT_R8U16) return G % 16 == 0;
-  if (d->layout == TMAC_LAYOUT_R64K32) return G % 32 == 0;
-  return G == 32 || G == 64 || (G % 128 == 0);
+  return G % 32 == 0;
 }
 
 Geometry geometry(const tmac_wdesc* d) {
@@ -57,17 +52,11 @@ Geometry geometry(const tmac_wdesc* d) {
     ge.n_tiles = ge.Mp / 8;
     ge.n_chunks = ge.Kp / 16;
     ge.idx_bytes = (uint64_t)ge.n_tiles * ge.n_chunks * 16 * d->bits;
-  } else if (d->layout == TMAC_LAYOUT_R64K32) {
+  } else {
     ge.tile_rows = 64;
     ge.Mp = round_up(d->M, 64);
     ge.n_tiles = ge.Mp / 64;
     ge.n_chunks = ge.Kp / 32;
-    ge.idx_bytes = (uint64_t)ge.n_tiles * ge.n_chunks * 64 * d->bits * 4;
-  } else {
-    ge.tile_rows = 16;
-    ge.Mp = round_up(d->M, 16);
-    ge.n_tiles = ge.Mp / 16;
-    ge.n_chunks = ge.Kp / 128;
     ge.idx_bytes = (uint64_t)ge.n_tiles * ge.n_chunks * 64 * d->bits * 4;
   }
   ge.sz_off = (ge.idx_off + ge.idx_bytes + 255) / 256 * 256;
@@ -87,27 +76,6 @@ static inline uint32_t index_of(const uint8_t* row, int K, int kg, int plane) {
 
 // Mirror-consolidated form of an index: sign bit 3, selector of the stored half in bits 0..2.
 static inline uint32_t mirror_fold(uint32_t p) { return p < 8 ? p : (8u | (15u - p)); }
-
-static void pack_indices_layout1(const tmac_wdesc* d, const Geometry& ge, const uint8_t* q, uint32_t* idx) {
-  const int M = d->M, K = d->K, b = d->bits;
-  for (int t = 0; t < ge.n_tiles; ++t)
-    for (int c = 0; c < ge.n_chunks; ++c)
-      for (int lane = 0; lane < 64; ++lane) {
-        const int r = lane & 15, phi = lane >> 4;
-        const int m = 16 * t + r;
-        if (m >= M) continue;
-        uint32_t* dst = idx + (((size_t)t * ge.n_chunks + c) * 64 + lane) * b;
-        const uint8_t* row = q + (size_t)m * K;
-        for (int i = 0; i < b; ++i) {
-          uint32_t word = 0;
-          for (int j = 0; j < 8; ++j) {
-            const int pos = (j < 4) ? 2 * j : 2 * (j - 4) + 1;
-            word |= index_of(row, K, 32 * c + 4 * j + phi, i) << (4 * pos);
-          }
-          dst[i] = word;
-        }
-      }
-}
 
 // Layout 3: lane = row of a 64-row tile; per (tile, 32-k chunk, row) `bits` dwords, dword i holding the
 // eight indices of plane i for the chunk's eight tables, table j in nibble j.
@@ -220,8 +188,7 @@ extern "C" tmac_status tmac_pack_weights(const tmac_wdesc* desc, const uint8_t* 
 
   uint32_t* idx = reinterpret_cast<uint32_t*>(out + ge.idx_off);
   if (desc->layout == TMAC_LAYOUT_R8U16) pack_indices_layout2(desc, ge, q, idx);
-  else if (desc->layout == TMAC_LAYOUT_R64K32) pack_indices_layout3(desc, ge, q, idx);
-  else pack_indices_layout1(desc, ge, q, idx);
+  else pack_indices_layout3(desc, ge, q, idx);
 
   // scales and zeros, {s, z} per (row tile, quantisation group, row in tile)
   if (G > 0) {
@@ -253,4 +220,4 @@ extern "C" const char* tmac_status_str(tmac_status s) {
   return "unknown status";
 }
 
-extern "C" int32_t tmac_version(void) { return 1000 * 0 + 4; }
+extern "C" int32_t tmac_version(void) { return 1000 * 0 + 5; }

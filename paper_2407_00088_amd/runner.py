@@ -82,9 +82,7 @@ def layout_supports_group(layout: int, K: int, group: int) -> bool:
         return True
     if layout == B.TMAC_LAYOUT_R8U16:
         return group % 16 == 0
-    if layout == B.TMAC_LAYOUT_R64K32:
-        return group % 32 == 0
-    return group in (32, 64) or group % 128 == 0
+    return group % 32 == 0
 
 
 def from_problem(p, max_N: Optional[int] = None, device: str = "cuda", layout: Optional[int] = None,

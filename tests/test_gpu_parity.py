@@ -4,9 +4,8 @@ element on the same seeded inputs.
 Bars: integer path bit-exact; fp16-table path within 2e-3 relative Frobenius error of the
 fp64 product (the rounding of table entries to fp16 alone costs a few 1e-4).
 
-Every case runs in both packed layouts where both apply: layout 1 feeds the LDS-table kernels
-(K-sliced and full-K), layout 3 the batched lookup kernel with one lane per weight row ("rows"),
-layout 2 the register-table decode kernel, called either as
+Every case runs in both packed layouts where both apply: layout 3 feeds the batched lookup kernel
+with one lane per weight row ("rows"), layout 2 the register-table decode kernel, called either as
 tmac_precompute_lut + tmac_mpgemm ("regs") or as the single fused launch tmac_mpgemv_fused
 ("fused")."""
 import numpy as np
@@ -18,7 +17,7 @@ from oracle import tmac_oracle as orc
 pytestmark = pytest.mark.gpu
 
 FP_TOL = 2e-3
-L1, L2, L3 = 1, 2, 3
+L2, L3 = 2, 3
 LF = 13  # layout 2 through the fused entry point
 
 
@@ -35,7 +34,7 @@ def torch():
     return torch
 
 
-@pytest.fixture(params=[L1, L2, LF, L3], ids=["lds", "regs", "fused", "rows"])
+@pytest.fixture(params=[L2, LF, L3], ids=["regs", "fused", "rows"])
 def layout(request):
     return request.param
 
@@ -51,7 +50,7 @@ def make_lin(p, layout):
     return from_problem(p, layout=layout)
 
 
-def run_fp(T, torch, p, out_t=None, tuning=None, layout=L1):
+def run_fp(T, torch, p, out_t=None, tuning=None, layout=L3):
     lin = make_lin(p, layout)
     A = torch.from_numpy(p.act).cuda()
     if layout == LF:
@@ -66,7 +65,7 @@ def oracle_fp(p):
     return orc.mpgemm_definition(p.act, p.q, p.scales, p.zeros, p.group, p.weight_scale, p.zero_point)
 
 
-def check_fp(T, torch, p, tuning=None, tol=FP_TOL, layout=L1):
+def check_fp(T, torch, p, tuning=None, tol=FP_TOL, layout=L3):
     got = run_fp(T, torch, p, tuning=tuning, layout=layout)
     ref = oracle_fp(p)
     assert got.shape == ref.shape and got.dtype == np.float32
@@ -77,7 +76,7 @@ def check_fp(T, torch, p, tuning=None, tol=FP_TOL, layout=L1):
     return err
 
 
-def run_int(T, torch, p, out_t, tuning=None, layout=L1):
+def run_int(T, torch, p, out_t, tuning=None, layout=L3):
     lin = make_lin(p, layout)
     A = torch.from_numpy(p.act_q).cuda()
     s_a = torch.from_numpy(p.act_scale).cuda()
@@ -89,7 +88,7 @@ def run_int(T, torch, p, out_t, tuning=None, layout=L1):
     return out.cpu().numpy()
 
 
-def check_int(T, torch, p, tuning=None, layout=L1):
+def check_int(T, torch, p, tuning=None, layout=L3):
     ref_i = orc.ternary_int_matmul(p.act_q, p.q, int(p.zero_point))
     got_i = run_int(T, torch, p, T.TMAC_OUT_I32, tuning, layout)
     assert got_i.dtype == np.int32
@@ -130,14 +129,6 @@ def test_ragged_k_padding(T, torch, K, layout):
         check_fp(T, torch, wl.make_grouped(0, 51, 1, 40, K, 2, 32, name=f"ragk32_{K}"), layout=layout)
 
 
-@pytest.mark.parametrize("ks", [2, 4, 8])
-@pytest.mark.parametrize("nt", [1, 4])
-def test_launch_shapes_agree(T, torch, ks, nt):
-    from paper_2407_00088_amd.binding import tmac_tuning
-    p = wl.make_grouped(0, 60, 6, 200, 1280, 4, 128, name=f"tune_ks{ks}_nt{nt}")
-    check_fp(T, torch, p, tuning=tmac_tuning(ks, nt))
-
-
 @pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 9])
 def test_small_batches(T, torch, N, layout):
     p = wl.make_grouped(0, 70 + N, N, 64, 512, 3, 128, name=f"batch_{N}")
@@ -151,11 +142,11 @@ def test_single_row_and_single_tile(T, torch, layout):
 
 def test_long_k_multi_pass(T, torch):
     """K beyond 16 waves x 64 units x 16: the register-table kernel walks several blocks per wave;
-    K beyond the LDS capacity of the full-K kernel falls back to the K-sliced kernel."""
+    the batched kernel walks 24 LDS slices (or K slices over workgroups)."""
     p = wl.make_grouped(0, 85, 1, 24, 20480, 4, 128, name="k20480")
     check_fp(T, torch, p, layout=L2)
     check_fp(T, torch, wl.make_grouped(0, 86, 2, 24, 24576, 2, 0 + 256, name="k24576"), layout=L2)
-    check_fp(T, torch, wl.make_grouped(0, 86, 1, 24, 24576, 2, 256, name="k24576_lds"), layout=L1)
+    check_fp(T, torch, wl.make_grouped(0, 86, 1, 24, 24576, 2, 256, name="k24576_rows"), layout=L3)
 
 
 def test_fp16_output_is_rounded_fp32(T, torch, layout):
@@ -231,15 +222,9 @@ def test_int_path_extreme_values_four_bit_long_k(T, torch):
     p = wl.Problem("extreme4", 0, 1, M, K, 4, 0, q, None, None, weight_scale=1.0, zero_point=0.0,
                    act_q=a_q, act_scale=np.array([1.0], np.float32))
     ref = orc.ternary_int_matmul(a_q, q, 0)
-    for layout in (L1, L2):
+    for layout in (L3, L2):
         got = run_int(T, torch, p, T.TMAC_OUT_I32, layout=layout)
         assert np.array_equal(got.astype(np.int64), ref), layout
-
-
-@pytest.mark.parametrize("ks", [2, 8])
-def test_int_path_launch_shapes(T, torch, ks):
-    from paper_2407_00088_amd.binding import tmac_tuning
-    check_int(T, torch, wl.make_ternary(0, 90 + ks, 2, 144, 1664), tuning=tmac_tuning(ks, 1))
 
 
 def test_int_tables_with_group_scales(T, torch, layout):
@@ -276,41 +261,8 @@ def test_config4_bitnet_ternary(T, torch, i, layout):
 
 @pytest.mark.parametrize("bits", [2, 4])
 @pytest.mark.parametrize("i", [0, 1, 2])
-@pytest.mark.parametrize("lay", [L1, L3], ids=["lds", "rows"])
-def test_config5_llama13b_prefill(T, torch, i, bits, lay):
-    check_fp(T, torch, wl.config5(i, bits), layout=lay)
-
-
-# ------------------------------------------------ both LDS lookup kernels ----
-
-@pytest.mark.parametrize("kernel", [1, 2])
-@pytest.mark.parametrize("bits,group,K", [(4, 128, 1408), (2, 256, 1024), (3, 0, 640), (1, 896, 896)])
-def test_both_lds_kernels_fp(T, torch, kernel, bits, group, K):
-    """kernel 1 = K-sliced with split-K reduction, kernel 2 = full-K decode kernel
-    (K = 1408 gives 11 chunks: a ragged last batch for the 8 waves)."""
-    from paper_2407_00088_amd.binding import tmac_tuning
-    M, N = 72, 2
-    if group == 0:
-        rng = np.random.default_rng(300 + bits)
-        p = wl.Problem("both_pt", 0, N, M, K, bits, 0, wl.uniform_codes(rng, M, K, bits), None, None,
-                       weight_scale=0.05, zero_point=2.0, act=wl.gaussian_act(rng, N, K))
-    else:
-        p = wl.make_grouped(0, 310 + bits, N, M, K, bits, group, name=f"both_k{kernel}_w{bits}")
-    check_fp(T, torch, p, tuning=tmac_tuning(0, 0, kernel))
-
-
-@pytest.mark.parametrize("kernel", [1, 2])
-def test_both_lds_kernels_int(T, torch, kernel):
-    from paper_2407_00088_amd.binding import tmac_tuning
-    check_int(T, torch, wl.make_ternary(0, 320 + kernel, 3, 200, 2240), tuning=tmac_tuning(0, 0, kernel))
-
-
-def test_full_k_kernel_rejects_what_it_cannot_do(T, torch):
-    from paper_2407_00088_amd.binding import tmac_tuning
-    p = wl.make_grouped(0, 330, 1, 32, 256, 2, 32, name="g32_fullk")
-    with pytest.raises(T.TmacError) as ei:
-        run_fp(T, torch, p, tuning=tmac_tuning(0, 0, 2))
-    assert ei.value.status == T.TMAC_EUNSUPPORTED
+def test_config5_llama13b_prefill(T, torch, i, bits):
+    check_fp(T, torch, wl.config5(i, bits), layout=L3)
 
 
 # ------------------------------------- register-table kernel launch shapes ----
@@ -334,11 +286,11 @@ def test_register_kernel_rows_per_group(T, torch, rows, bits, group, M, K, fused
                        weight_scale=0.05, zero_point=2.0, act=wl.gaussian_act(rng, N, K))
     else:
         p = wl.make_grouped(0, 410 + bits, N, M, K, bits, group, name=f"rpg{rows}_w{bits}")
-    got = run(p, tmac_tuning(0, 0, 0, rows))
+    got = run(p, tmac_tuning(rows))
     err = orc.rel_frobenius(got, oracle_fp(p))
     assert err <= FP_TOL, err
     # both launch shapes add the same terms in the same order
-    other = run(p, tmac_tuning(0, 0, 0, 24 - rows))
+    other = run(p, tmac_tuning(24 - rows))
     assert np.array_equal(got.view(np.uint32), other.view(np.uint32))
 
 
@@ -346,7 +298,7 @@ def test_register_kernel_rows_per_group(T, torch, rows, bits, group, M, K, fused
 @pytest.mark.parametrize("rows", [8, 16])
 def test_register_kernel_rows_per_group_int(T, torch, rows, fused):
     from paper_2407_00088_amd.binding import tmac_tuning
-    check_int(T, torch, wl.make_ternary(0, 420 + rows, 3, 200, 2240), tuning=tmac_tuning(0, 0, 0, rows),
+    check_int(T, torch, wl.make_ternary(0, 420 + rows, 3, 200, 2240), tuning=tmac_tuning(rows),
               layout=LF if fused else L2)
 
 
@@ -369,7 +321,7 @@ def test_fused_rejects_what_it_cannot_do(T, torch):
     p = wl.make_grouped(0, 510, 1, 16, 136, 2, 8)
     A = torch.from_numpy(p.act).cuda()
     out = torch.empty((1, 16), dtype=torch.float32, device="cuda")
-    for layout, K in ((L1, 128), (L2, 136)):
+    for layout, K in ((L3, 128), (L2, 136)):
         q = p.q[:, :K]
         d = B.wdesc(16, K, 2, 0, 1.0, layout=layout)
         packed = torch.from_numpy(B.tmac_pack_weights(d, q)).cuda()
@@ -448,7 +400,7 @@ def test_table_quantisation_rejects_what_it_cannot_do(T, torch):
     from paper_2407_00088_amd.runner import from_problem
     p = wl.make_grouped(0, 640, 1, 16, 128, 2, 128)
     with pytest.raises(T.TmacError) as e:
-        from_problem(p, layout=L1, lut_t=B.TMAC_LUT_I8Q).forward(torch.from_numpy(p.act).cuda())
+        from_problem(p, layout=L3, lut_t=B.TMAC_LUT_I8Q).forward(torch.from_numpy(p.act).cuda())
     assert e.value.status == B.TMAC_EUNSUPPORTED
     t = wl.make_ternary(0, 641, 1, 16, 128)
     lut = torch.empty(B.tmac_lut_bytes(1, 128, 0, B.TMAC_LUT_I8Q), dtype=torch.uint8, device="cuda")

@@ -1,5 +1,5 @@
 """CPU-side tests of the library's host logic: exported symbols, the offline packer
-(checked with an unpacker written here from the layout documented in include/tmac.h),
+(checked with the unpackers of blob_unpack.py, written from the layouts documented in include/tmac.h),
 buffer-size queries and every argument check that returns before a launch."""
 import ctypes as C
 import os
@@ -10,6 +10,7 @@ import numpy as np
 import pytest
 
 import paper_2407_00088_amd as T
+from blob_unpack import unpack_layout3
 from paper_2407_00088_amd import binding as B
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -26,36 +27,9 @@ def test_library_exports_every_declared_symbol():
     assert T.tmac_version() >= 1
 
 
-# ------------------------------------------------------------------ unpacker ----
-
-def unpack_blob(blob: np.ndarray):
-    """Inverse of the documented layout 1; independent of the packer's code."""
-    raw = blob.tobytes()
-    (magic, layout, M, K, bits, g, group, Mp, Kp, n_tiles, n_chunks, n_qgroups, zero_point, _r0,
-     idx_off, idx_bytes, sz_off, sz_bytes, total) = struct.unpack_from("<II10ifI5Q", raw, 0)
-    assert magic == 0x43414D54 and layout == 1 and g == 4
-    assert Mp == (M + 15) // 16 * 16 and Kp == (K + 127) // 128 * 128
-    assert total == len(raw) and idx_bytes == n_tiles * n_chunks * 64 * bits * 4
-    idx = np.frombuffer(raw, dtype="<u4", count=idx_bytes // 4, offset=idx_off).reshape(n_tiles, n_chunks, 64, bits)
-    q = np.zeros((Mp, Kp), dtype=np.uint8)
-    for lane in range(64):
-        r, phi = lane & 15, lane >> 4
-        for j in range(8):
-            pos = 2 * j if j < 4 else 2 * (j - 4) + 1
-            for i in range(bits):
-                nib = (idx[:, :, lane, i] >> (4 * pos)) & 15          # [tiles, chunks]
-                for e in range(4):
-                    bit = ((nib >> e) & 1).astype(np.uint8)
-                    rows = np.arange(n_tiles) * 16 + r
-                    cols = np.arange(n_chunks) * 128 + 4 * (4 * j + phi) + e
-                    q[np.ix_(rows, cols)] |= bit << i
-    s = z = None
-    if group > 0:
-        sz = np.frombuffer(raw, dtype="<u2", count=sz_bytes // 2, offset=sz_off).reshape(n_tiles, n_qgroups, 16, 2)
-        s = sz[..., 0].transpose(0, 2, 1).reshape(Mp, n_qgroups).view(np.float16)
-        z = sz[..., 1].transpose(0, 2, 1).reshape(Mp, n_qgroups).view(np.float16)
-    hdr = dict(M=M, K=K, bits=bits, group=group, Mp=Mp, Kp=Kp, zero_point=zero_point, n_qgroups=n_qgroups)
-    return hdr, q, s, z
+# the default packed layout (3) is the one these generic tests pack into
+def unpack_blob(blob):
+    return unpack_layout3(blob)
 
 
 @pytest.mark.parametrize("M,K,bits,group", [
@@ -90,7 +64,7 @@ def test_pack_special_matrices(bits):
     top = (1 << bits) - 1
     for q in (np.zeros((M, K), np.uint8), np.full((M, K), top, np.uint8)):
         _, q2, _, _ = unpack_blob(T.tmac_pack_weights(d, q))
-        assert np.array_equal(q2, q)
+        assert np.array_equal(q2[:M, :K], q) and not q2[M:].any()
     # every index nibble inside the matrix is covered exactly once: all-max codes set
     # exactly M*K*bits bits in the index region
     blob = T.tmac_pack_weights(d, np.full((M, K), top, np.uint8))
@@ -102,7 +76,7 @@ def test_pack_special_matrices(bits):
         q = np.zeros((M, K), np.uint8)
         q[m, k] = top
         _, q2, _, _ = unpack_blob(T.tmac_pack_weights(d, q))
-        assert np.array_equal(q2, q)
+        assert np.array_equal(q2[:M, :K], q) and not q2[M:].any()
 
 
 def test_null_zeros_means_mid_level():
@@ -110,7 +84,7 @@ def test_null_zeros_means_mid_level():
     q = np.zeros((M, K), np.uint8)
     s = np.full((M, 1), 0.5, np.float16)
     _, _, s2, z2 = unpack_blob(T.tmac_pack_weights(T.wdesc(M, K, bits, G), q, s, None))
-    assert np.all(z2 == np.float16(7.5)) and np.all(s2 == np.float16(0.5))
+    assert np.all(z2[:M] == np.float16(7.5)) and np.all(s2[:M] == np.float16(0.5))
 
 
 def test_sizes():
@@ -141,7 +115,7 @@ def _desc(**kw):
 
 
 @pytest.mark.parametrize("kw", [dict(bits=0), dict(bits=5), dict(g=8), dict(K=126), dict(M=0),
-                                dict(group=48), dict(group=6), dict(layout=7), dict(reserved=1)])
+                                dict(group=48), dict(group=6), dict(layout=7), dict(layout=1), dict(reserved=1)])
 def test_bad_desc_is_rejected(kw):
     d = _desc(**kw)
     assert T.tmac_packed_bytes(d) == 0
@@ -209,6 +183,6 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
     assert call(a8=B.TMAC_OUT_I32) == B.TMAC_EINVAL    # int output from fp16 tables
     bad = _desc(bits=7)
     assert call(a0=C.byref(bad)) == B.TMAC_EINVAL
-    g96 = _desc(M=16, K=192, bits=2, group=96)
-    assert call(a0=C.byref(g96), a9=16) == B.TMAC_EUNSUPPORTED
+    g48 = _desc(M=16, K=192, bits=2, group=48)          # layout 3 needs whole 32-k chunks per group
+    assert call(a0=C.byref(g48), a9=16) == B.TMAC_EUNSUPPORTED
     assert T.status_str(B.TMAC_ESIZE) == "buffer too small"

@@ -1,36 +1,12 @@
 """CPU-side tests of packed layout 3 (64-row tiles, one lane per row, chunks of 32 k), checked
-with an unpacker written here from the layout documented in include/tmac.h."""
-import struct
-
+with the unpacker of blob_unpack.py, written from the layout documented in include/tmac.h."""
 import numpy as np
 import pytest
 
+from blob_unpack import unpack_layout3
+
 import paper_2407_00088_amd as T
 from paper_2407_00088_amd import binding as B
-
-
-def unpack_layout3(blob: np.ndarray):
-    raw = blob.tobytes()
-    (magic, layout, M, K, bits, g, group, Mp, Kp, n_tiles, n_chunks, n_qgroups, zero_point, _r0,
-     idx_off, idx_bytes, sz_off, sz_bytes, total) = struct.unpack_from("<II10ifI5Q", raw, 0)
-    assert magic == 0x43414D54 and layout == 3 and g == 4
-    assert Mp == (M + 63) // 64 * 64 and Kp == (K + 127) // 128 * 128 and n_chunks == Kp // 32
-    assert total == len(raw) and idx_bytes == n_tiles * n_chunks * 64 * bits * 4
-    idx = np.frombuffer(raw, dtype="<u4", count=idx_bytes // 4, offset=idx_off).reshape(n_tiles, n_chunks, 64, bits)
-    q = np.zeros((Mp, Kp), dtype=np.uint8)
-    rows = np.arange(Mp)
-    for i in range(bits):
-        for j in range(8):
-            nib = ((idx[:, :, :, i] >> (4 * j)) & 15).transpose(0, 2, 1).reshape(Mp, n_chunks)   # [row, chunk]
-            for e in range(4):
-                cols = np.arange(n_chunks) * 32 + 4 * j + e
-                q[np.ix_(rows, cols)] |= (((nib >> e) & 1) << i).astype(np.uint8)
-    s = z = None
-    if group > 0:
-        sz = np.frombuffer(raw, dtype="<u2", count=sz_bytes // 2, offset=sz_off).reshape(n_tiles, n_qgroups, 64, 2)
-        s = sz[..., 0].transpose(0, 2, 1).reshape(Mp, n_qgroups).view(np.float16)
-        z = sz[..., 1].transpose(0, 2, 1).reshape(Mp, n_qgroups).view(np.float16)
-    return dict(M=M, K=K, bits=bits, group=group, Mp=Mp, Kp=Kp, n_qgroups=n_qgroups), q, s, z
 
 
 def desc3(M, K, bits, group, zero_point=0.0):
