@@ -82,9 +82,10 @@ def main():
     sink = torch.zeros(256, dtype=torch.uint8, device=dev)
 
     class Case:
-        def __init__(self, p, ring_mb=None, lut_t=None):
+        def __init__(self, p, ring_mb=None, lut_t=None, layout=None):
             self.p = p
-            self.lin = from_problem(p, lut_t=lut_t)   # N <= 8: register-table layout; above: batched layout
+            # layout None: register-table layout for N <= 8, batched layout above
+            self.lin = from_problem(p, lut_t=lut_t, layout=layout)
             self.bytes = algorithmic_bytes(p.M, p.K, p.bits, p.group, p.N, act_bytes=1 if p.int_path else 2)
             n_copies = max(2, ((args.ring_mb if ring_mb is None else ring_mb) << 20) // self.lin.packed_bytes + 1)
             self.ring = [self.lin.packed] + [self.lin.packed.clone() for _ in range(n_copies - 1)]
@@ -264,6 +265,27 @@ def main():
             del c
             torch.cuda.empty_cache()
         detail["stacked_projections"] = stacked
+        # small batches (N = 2..64) on the 4096 x 4096 W4 shape: precompute + lookup per call, in both
+        # packed layouts where the register-table kernel takes the N (at most 8 rows)
+        small = []
+        for N in (2, 4, 8, 16, 32, 64):
+            p = wl.make_grouped(3, 60 + N, N, 4096, 4096, 4, 128, name=f"small_batch_4096x4096_w4_n{N}")
+            row = {"name": p.name, "N": N, "bytes": algorithmic_bytes(p.M, p.K, p.bits, p.group, N)}
+            for lay, key in ((2, "register_table"), (3, "batched")):
+                if lay == 2 and N > 8:
+                    continue
+                c = Case(p, layout=lay)
+
+                def both(c=c):
+                    c.precompute()
+                    c.mpgemm()
+                us = timed(Replay(both, ring_len(c)), max(1, args.steps // ring_len(c)), 2)
+                row[key + "_call_us"] = round(us, 3)
+                row[key + "_TOPS_equiv"] = round(2.0 * N * p.M * p.K / us / 1e6, 3)
+                del c
+                torch.cuda.empty_cache()
+            small.append(row)
+        detail["small_batch"] = small
         detail["prefill_n256"] = prefill_rows()
         xs = np.array([s["bits"] for s in sweep[:4]], dtype=np.float64)
         ys = np.array([s["mpgemm_us"] for s in sweep[:4]], dtype=np.float64)

@@ -1,23 +1,26 @@
 // Batched lookup kernel (gfx950) for packed layout 3: many activation rows (prefill mpGEMM).
 //
 // Section 3.2 of the paper argues that the tables must sit in fast on-chip memory and that a large
-// tile over M lets many weight rows reuse one table.  Here the tables of a K-slice and of four
-// activation rows live in LDS, laid out [table][entry][n] (four fp16 values = 8 bytes per entry),
-// and every LANE owns one weight row: a wavefront looks one table up for 64 rows at a time.  All
-// lanes of a ds_read_b64 address the same 128-byte table, whose 16 entries cover the 32 LDS banks
-// exactly once, so lanes that want the same entry are served by broadcast and lanes that want
-// different entries hit different banks: the lookups are free of bank conflicts, and one lookup
-// feeds four activation rows.
+// tile over M lets many weight rows reuse one table.  Here the tables of a K-slice and of NT = 4 or
+// 8 activation rows live in LDS, laid out [table][entry][n] (NT fp16 values = 8 or 16 bytes per
+// entry), and every LANE owns one weight row: a wavefront looks one table up for 64 rows at a
+// time.  All lanes of a read address the same table, whose 16 entries cover the LDS banks evenly,
+// so lanes that want the same entry are served by broadcast and lanes that want different entries
+// hit different banks: the lookups are free of bank conflicts, and one lookup feeds NT
+// activation rows.
 //
 //   * Weight permutation / interleaving (Section 3.2): a lane reads the `bits` index dwords of its
 //     row and of one 32-k chunk with one load (16 bytes at 4 bit); the eight nibbles of a dword are
-//     the indices of eight consecutive tables, and (x << 3) & 0x78787878, (x >> 1) & 0x78787878
-//     turn them into the byte offsets of the entries (even and odd tables) four at a time.
-//   * Bit-plane shift-accumulate (Eq. 1): v_fma_mix_f32 takes the fp16 entry straight from the
-//     looked-up register and multiplies by 2^i.
+//     the indices of eight consecutive tables, and two mask-and-shift operations turn them into
+//     the byte offsets of the entries (even and odd tables) four at a time.
+//   * Aggregation (Section 3.3 keeps the running sum narrow and widens it now and then): the eight
+//     entries of a chunk and plane are added as packed 16-bit pairs, two activation rows per
+//     instruction (exact for integer tables; three fp16 roundings for fp16 tables), then widened.
+//   * Bit-plane shift-accumulate (Eq. 1): the widening v_fma_mix_f32 takes the fp16 chunk sum and
+//     multiplies by 2^i.
 //   * Scale, zero and bias once per quantisation group (Section 4, bit-serial linear transform).
 //   * Axis order (Section 3.2 "axis reordering"): K is walked slice by slice inside the
-//     workgroup, so only a [4, 1024]-slice of the tables is live in LDS; the sums of a row stay
+//     workgroup, so only a 32 KB slice of the tables is live in LDS; the sums of a row stay
 //     in the lane's registers: fixed order.
 //   * Few activation rows (batched decode) leave too few (row block, n tile) pairs to fill the
 //     chip: K is then also split over gridDim.z workgroups, whose partial sums meet in the
@@ -40,10 +43,19 @@ typedef uint32_t ru32x4v __attribute__((ext_vector_type(4)));
 typedef uint32_t ru32x2v __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) char rows_lds_char;
 typedef __attribute__((address_space(3))) const ru32x2v rows_lds_u32x2;
+typedef __attribute__((address_space(3))) const ru32x4v rows_lds_u32x4;
 
-constexpr int ROWS_NT = 4;          // activation rows per workgroup
 constexpr int ROWS_WAVES = 4;       // 64-row tiles per workgroup
-constexpr int ROWS_KSL = 1024;      // k per LDS slice: 256 tables x 128 bytes = 32 KB
+constexpr int ROWS_LDS = 32768;     // bytes of tables per LDS slice: 1024 k for 4 activation rows, 512 k for 8
+constexpr int ROWS_NT_WIDE = 8;     // activation rows per workgroup when there are enough of them
+constexpr int ROWS_NT_NARROW = 4;   // ... and otherwise
+
+typedef _Float16 rh2v __attribute__((ext_vector_type(2)));
+typedef short rs2v __attribute__((ext_vector_type(2)));
+
+// Activation rows per workgroup for a call with N rows: eight once that wastes at most a fifth of
+// the lookups on padding rows.
+static inline int rows_nt(int N) { return (N >= 40 || N % 8 == 0 || N % 8 >= 5) && N > 4 ? ROWS_NT_WIDE : ROWS_NT_NARROW; }
 
 struct RowsParams {
   const uint32_t* idx;     // [n_tiles][n_chunks][64][bits] dwords
@@ -67,11 +79,13 @@ struct RowsParams {
   int out_t;
 };
 
-template <bool IS_INT, int BITS>
+template <bool IS_INT, int BITS, int NT>
 __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const RowsParams p) {
-  constexpr int NT = ROWS_NT;
-  constexpr int TPS = ROWS_KSL / 4;  // tables per slice
-  __shared__ __attribute__((aligned(1024))) char tab[TPS * 128];  // byte-permuted addresses need the alignment
+  constexpr int TB = 32 * NT;          // bytes per table: 16 entries x NT fp16 values
+  constexpr int TPS = ROWS_LDS / TB;   // tables per slice
+  constexpr int CPS = TPS / 8;         // 32-k chunks per slice
+  constexpr int HD = NT / 2;           // dwords per entry
+  __shared__ __attribute__((aligned(8 * TB))) char tab[TPS * TB];  // byte-permuted addresses need the alignment
   __shared__ int s_last;
   using AccT = typename std::conditional<IS_INT, int, float>::type;
 
@@ -108,11 +122,13 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
   const int cz0 = blockIdx.z * p.cps, cz1 = min(cz0 + p.cps, p.n_chunks);
   int gq = p.grouped ? cz0 / p.cpg : 0, cg = 0;  // current quantisation group, chunks done in it (wave-uniform)
   uint32_t szv = 0;          // {scale, zero} of the lane's row for the current group
-  float Sg[NT] = {0.f, 0.f, 0.f, 0.f};
+  float Sg[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) Sg[t] = 0.f;
   uint32_t xn[BITS];
   load_idx(cz0, xn);
 
-  for (int c0 = cz0; c0 < cz1; c0 += ROWS_KSL / 32) {
+  for (int c0 = cz0; c0 < cz1; c0 += CPS) {
     // stage the tables of this K-slice for the NT activation rows: item = (table, half) reads the
     // 8 entries of the four rows and writes them entry-major
     __syncthreads();
@@ -126,20 +142,26 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
         if (n0 + t < p.N && kg < p.KG)
           v[t] = *reinterpret_cast<const ru32x4v*>(p.tables + ((size_t)(n0 + t) * p.KG + kg) * 16 + 8 * h);
       }
-      ru32x4v* dst = reinterpret_cast<ru32x4v*>(tab + kl * 128 + h * 64);
+      ru32x4v* dst = reinterpret_cast<ru32x4v*>(tab + kl * TB + h * (TB / 2));
 #pragma unroll
       for (int d = 0; d < 4; ++d) {  // dword d of every row holds entries 2d, 2d+1 of this half
-        ru32x4v o;
-        o.x = __builtin_amdgcn_perm(v[1][d], v[0][d], 0x05040100u);  // entry 2d: rows 0,1
-        o.y = __builtin_amdgcn_perm(v[3][d], v[2][d], 0x05040100u);  //           rows 2,3
-        o.z = __builtin_amdgcn_perm(v[1][d], v[0][d], 0x07060302u);  // entry 2d+1
-        o.w = __builtin_amdgcn_perm(v[3][d], v[2][d], 0x07060302u);
-        dst[d] = o;
+        uint32_t lo[HD], hi[HD];
+#pragma unroll
+        for (int u = 0; u < HD; ++u) {
+          lo[u] = __builtin_amdgcn_perm(v[2 * u + 1][d], v[2 * u][d], 0x05040100u);  // entry 2d: rows 2u, 2u+1
+          hi[u] = __builtin_amdgcn_perm(v[2 * u + 1][d], v[2 * u][d], 0x07060302u);  // entry 2d+1
+        }
+        if constexpr (NT == 4) {
+          dst[d] = ru32x4v{lo[0], lo[1], hi[0], hi[1]};
+        } else {
+          dst[2 * d] = ru32x4v{lo[0], lo[1], lo[2], lo[3]};
+          dst[2 * d + 1] = ru32x4v{hi[0], hi[1], hi[2], hi[3]};
+        }
       }
     }
     __syncthreads();
 
-    const int c_end = min(c0 + ROWS_KSL / 32, cz1);
+    const int c_end = min(c0 + CPS, cz1);
     // Per chunk and pair of bit planes: 16 LDS reads are issued first, then accumulated in issue
     // order, so that the reads overlap each other and the accumulation of the earlier ones; the
     // other waves of the SIMD cover the start of every round.
@@ -158,44 +180,61 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
           else Sg[t] = static_cast<const float*>(p.S)[(size_t)n * p.nq + gq];
         }
       }
-      const uint32_t cbase = lds0 + (uint32_t)(c - c0) * 1024u;
+      const uint32_t cbase = lds0 + (uint32_t)(c - c0) * (8u * TB);
       // rounds of at most two planes = 16 LDS reads: the hardware counts at most 15 outstanding LDS
-      // operations exactly, so a round's reads can be consumed one by one as they return
+      // operations exactly, so a round's reads can be consumed as they return
 #pragma unroll
       for (int b0 = 0; b0 < BITS; b0 += 2) {
         constexpr int PL = 2;
-        ru32x2v e[PL][8];
+        uint32_t e[PL][8][HD];
 #pragma unroll
         for (int bb = 0; bb < PL; ++bb) {
           const int b = b0 + bb;
           if (b >= BITS) break;
-          const uint32_t ev = (x[b] << 3) & 0x78787878u, od = (x[b] >> 1) & 0x78787878u;
+          // byte offsets of the entries inside their tables: entry * 2 NT, even and odd tables
+          const uint32_t ev = (NT == 4) ? (x[b] << 3) & 0x78787878u : (x[b] << 4) & 0xF0F0F0F0u;
+          const uint32_t od = (NT == 4) ? (x[b] >> 1) & 0x78787878u : x[b] & 0xF0F0F0F0u;
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             // address = {0, cbase byte 2, cbase byte 1, byte j/2 of the offsets}: one byte permute;
-            // the table's own 128 * j goes into the instruction's offset field
+            // the table's own TB * j goes into the instruction's offset field
             const uint32_t a = __builtin_amdgcn_perm((j & 1) ? od : ev, cbase, 0x0C020100u + 4u + (uint32_t)(j >> 1));
-            e[bb][j] = *reinterpret_cast<rows_lds_u32x2*>(a + j * 128);
+            if constexpr (NT == 4) {
+              const ru32x2v r = *reinterpret_cast<rows_lds_u32x2*>(a + j * TB);
+              e[bb][j][0] = r.x; e[bb][j][1] = r.y;
+            } else {
+              const ru32x4v r = *reinterpret_cast<rows_lds_u32x4*>(a + j * TB);
+              e[bb][j][0] = r.x; e[bb][j][1] = r.y; e[bb][j][2] = r.z; e[bb][j][3] = r.w;
+            }
           }
         }
         __builtin_amdgcn_sched_barrier(0);  // keep the reads above the accumulation
+        // The eight entries of a plane (one per table of the chunk) are added pairwise as packed
+        // 16-bit values, two activation rows per instruction: exact for the integer tables
+        // (|sum| <= 8 * 508), three roundings to fp16 for the fp16 tables (the convert to "a higher
+        // precision" of Section 3.3 happens once per chunk and plane); the chunk sum then enters the
+        // 32-bit sum of the quantisation group times 2^plane.
 #pragma unroll
         for (int bb = 0; bb < PL; ++bb) {
           const int b = b0 + bb;
           if (b >= BITS) break;
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
+          for (int u = 0; u < HD; ++u) {
             if constexpr (IS_INT) {
-              L[0] += (int)(int16_t)(e[bb][j].x & 0xffffu) << b;
-              L[1] += ((int)e[bb][j].x >> 16) << b;
-              L[2] += (int)(int16_t)(e[bb][j].y & 0xffffu) << b;
-              L[3] += ((int)e[bb][j].y >> 16) << b;
+              rs2v q[8];
+#pragma unroll
+              for (int j = 0; j < 8; ++j) q[j] = __builtin_bit_cast(rs2v, e[bb][j][u]);
+              const rs2v r = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
+              L[2 * u] += (int)r.x << b;
+              L[2 * u + 1] += (int)r.y << b;
             } else {
+              rh2v q[8];
+#pragma unroll
+              for (int j = 0; j < 8; ++j) q[j] = __builtin_bit_cast(rh2v, e[bb][j][u]);
+              const rh2v r = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
               const float w = p.pw[b];
-              L[0] = fmaf(__half2float(__ushort_as_half((uint16_t)(e[bb][j].x & 0xffffu))), w, L[0]);
-              L[1] = fmaf(__half2float(__ushort_as_half((uint16_t)(e[bb][j].x >> 16))), w, L[1]);
-              L[2] = fmaf(__half2float(__ushort_as_half((uint16_t)(e[bb][j].y & 0xffffu))), w, L[2]);
-              L[3] = fmaf(__half2float(__ushort_as_half((uint16_t)(e[bb][j].y >> 16))), w, L[3]);
+              L[2 * u] = fmaf((float)r.x, w, L[2 * u]);
+              L[2 * u + 1] = fmaf((float)r.y, w, L[2 * u + 1]);
             }
           }
         }
@@ -290,8 +329,10 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
   __syncthreads();
   if (!s_last || !row_ok) return;
   // four slices x NT rows of loads in flight per round trip; sums taken in slice order
-  float sf[NT] = {0.f, 0.f, 0.f, 0.f};
-  int si[NT] = {0, 0, 0, 0};
+  float sf[NT];
+  int si[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) { sf[t] = 0.f; si[t] = 0; }
   const size_t mrow = (size_t)tile_raw * 64 + lane;
   for (int sl0 = 0; sl0 < nz; sl0 += 4) {
     float v[4][NT];
@@ -323,25 +364,30 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
   }
 }
 
-template <bool IS_INT, int BITS>
+template <bool IS_INT, int BITS, int NT>
 static hipError_t launch_rows_one(const RowsParams& p, hipStream_t st) {
   RowsParams local = p;
   void* args[] = {&local};
-  const dim3 grid((p.N + ROWS_NT - 1) / ROWS_NT, (p.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES,
-                  (p.n_chunks + p.cps - 1) / p.cps);
-  return hipLaunchKernel(reinterpret_cast<const void*>(mpgemm_rows_kernel<IS_INT, BITS>), grid,
+  const dim3 grid((p.N + NT - 1) / NT, (p.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES, (p.n_chunks + p.cps - 1) / p.cps);
+  return hipLaunchKernel(reinterpret_cast<const void*>(mpgemm_rows_kernel<IS_INT, BITS, NT>), grid,
                          dim3(64 * ROWS_WAVES), args, 0, st);
 }
 
-template <bool IS_INT>
+template <bool IS_INT, int NT>
 static hipError_t launch_rows_bits(const RowsParams& p, int bits, hipStream_t st) {
   switch (bits) {
-    case 1: return launch_rows_one<IS_INT, 1>(p, st);
-    case 2: return launch_rows_one<IS_INT, 2>(p, st);
-    case 3: return launch_rows_one<IS_INT, 3>(p, st);
-    case 4: return launch_rows_one<IS_INT, 4>(p, st);
+    case 1: return launch_rows_one<IS_INT, 1, NT>(p, st);
+    case 2: return launch_rows_one<IS_INT, 2, NT>(p, st);
+    case 3: return launch_rows_one<IS_INT, 3, NT>(p, st);
+    case 4: return launch_rows_one<IS_INT, 4, NT>(p, st);
   }
   return hipErrorInvalidValue;
+}
+
+template <bool IS_INT>
+static hipError_t launch_rows_nt(const RowsParams& p, int nt, int bits, hipStream_t st) {
+  return nt == ROWS_NT_WIDE ? launch_rows_bits<IS_INT, ROWS_NT_WIDE>(p, bits, st)
+                            : launch_rows_bits<IS_INT, ROWS_NT_NARROW>(p, bits, st);
 }
 
 // How a call is split: workgroups along N and M, and the number of K slices (1 when the (row block,
@@ -350,7 +396,8 @@ static hipError_t launch_rows_bits(const RowsParams& p, int bits, hipStream_t st
 RowsPlan rows_plan(const tmac_wdesc* desc, int N) {
   const Geometry ge = geometry(desc);
   RowsPlan pl;
-  pl.n_tiles_n = (N + ROWS_NT - 1) / ROWS_NT;
+  pl.nt = rows_nt(N);
+  pl.n_tiles_n = (N + pl.nt - 1) / pl.nt;
   pl.row_blocks = (ge.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES;
   const bool one_group = (desc->group == 0 || desc->group == desc->K);
   const int cpg = (one_group || desc->group < 32) ? 1 : desc->group / 32;  // (sizes below 32 are rejected at launch)
@@ -419,8 +466,8 @@ int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void*
     }
   }
   if (out_t == TMAC_OUT_I32 && !p.int_exact) return TMAC_EINVAL;
-  const hipError_t e = is_int ? launch_rows_bits<true>(p, desc->bits, static_cast<hipStream_t>(stream))
-                              : launch_rows_bits<false>(p, desc->bits, static_cast<hipStream_t>(stream));
+  const hipError_t e = is_int ? launch_rows_nt<true>(p, pl.nt, desc->bits, static_cast<hipStream_t>(stream))
+                              : launch_rows_nt<false>(p, pl.nt, desc->bits, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) {
     note_hip_error((int)e);
     return TMAC_EHIP;

@@ -174,9 +174,10 @@ def test_closed_forms_on_device(T, torch, layout):
     p = wl.Problem("zeros", 0, 1, M, K, b, G, np.zeros((M, K), np.uint8), s, z, act=a)
     S = a.astype(np.float64).reshape(1, K // G, G).sum(-1)
     expect = -np.einsum("ng,mg->nm", S, s.astype(np.float64) * z.astype(np.float64))
-    # the look-up term and the bias term cancel to first order here, which amplifies the fp16
-    # rounding of the table entries: a few 1e-4 is expected
-    assert orc.rel_frobenius(run_fp(T, torch, p, layout=layout), expect) < 1e-3
+    # the look-up term and the bias term cancel to first order here, and every plane looks up the
+    # same entry, so the fp16 roundings (table entries; chunk sums in the batched kernel) add up
+    # coherently over the planes: up to 1.2e-3 instead of the usual few 1e-4, still inside the bar
+    assert orc.rel_frobenius(run_fp(T, torch, p, layout=layout), expect) < FP_TOL
     q = wl.uniform_codes(rng, M, K, 1)
     half = np.full((M, K // G), 0.5, np.float16)
     p1 = wl.Problem("sign", 0, 1, M, K, 1, G, q, s, half, act=a)
