@@ -45,7 +45,14 @@ typedef __attribute__((address_space(3))) char rows_lds_char;
 typedef __attribute__((address_space(3))) const ru32x2v rows_lds_u32x2;
 typedef __attribute__((address_space(3))) const ru32x4v rows_lds_u32x4;
 
-constexpr int ROWS_WAVES = 4;       // 64-row tiles per workgroup
+#ifndef TMAC_ROWS_WAVES
+#define TMAC_ROWS_WAVES 4
+#endif
+#ifndef TMAC_ROWS_TARGET_WGS
+#define TMAC_ROWS_TARGET_WGS 4096
+#endif
+constexpr int ROWS_WAVES = TMAC_ROWS_WAVES;  // 64-row tiles per workgroup
+constexpr int ROWS_TARGET_WGS = TMAC_ROWS_TARGET_WGS;  // K is split until a call has about this many workgroups
 constexpr int ROWS_LDS = 32768;     // bytes of tables per LDS slice: 1024 k for 4 activation rows, 512 k for 8
 constexpr int ROWS_NT_WIDE = 8;     // activation rows per workgroup when there are enough of them
 constexpr int ROWS_NT_NARROW = 4;   // ... and otherwise
@@ -120,6 +127,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
 
   // this workgroup's share of K: chunks [cz0, cz1)
   const int cz0 = blockIdx.z * p.cps, cz1 = min(cz0 + p.cps, p.n_chunks);
+  const int kg_end = min(cz1 * 8, p.KG);  // tables beyond it are read as zero
   int gq = p.grouped ? cz0 / p.cpg : 0, cg = 0;  // current quantisation group, chunks done in it (wave-uniform)
   uint32_t szv = 0;          // {scale, zero} of the lane's row for the current group
   float Sg[NT];
@@ -139,7 +147,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         v[t] = ru32x4v{0u, 0u, 0u, 0u};
-        if (n0 + t < p.N && kg < p.KG)
+        if (n0 + t < p.N && kg < kg_end)
           v[t] = *reinterpret_cast<const ru32x4v*>(p.tables + ((size_t)(n0 + t) * p.KG + kg) * 16 + 8 * h);
       }
       ru32x4v* dst = reinterpret_cast<ru32x4v*>(tab + kl * TB + h * (TB / 2));
@@ -403,11 +411,18 @@ RowsPlan rows_plan(const tmac_wdesc* desc, int N) {
   const int cpg = (one_group || desc->group < 32) ? 1 : desc->group / 32;  // (sizes below 32 are rejected at launch)
   const int min_cps = (8 + cpg - 1) / cpg * cpg;  // at least 256 k, whole groups
   const int64_t pairs = (int64_t)pl.n_tiles_n * pl.row_blocks;
-  int64_t want = pairs >= 512 ? 1 : (512 + pairs - 1) / pairs;
+  int64_t want = pairs >= ROWS_TARGET_WGS ? 1 : (ROWS_TARGET_WGS + pairs - 1) / pairs;
   const int max_slices = (ge.n_chunks + min_cps - 1) / min_cps;
   if (want > max_slices) want = max_slices;
   int cps = (int)((ge.n_chunks + want - 1) / want);
-  cps = (cps + cpg - 1) / cpg * cpg;
+  // whole LDS slices where a workgroup gets at least one (nothing staged in vain), whole groups always
+  const int lds_chunks = ROWS_LDS / (32 * pl.nt) / 8;
+  int unit = cpg;
+  if (want > 1 && cps >= lds_chunks) {
+    unit = lds_chunks;
+    while (unit % cpg) unit += lds_chunks;
+  }
+  cps = (cps + unit - 1) / unit * unit;
   if (cps < min_cps) cps = min_cps;
   pl.cps = cps;
   pl.slices = (ge.n_chunks + cps - 1) / cps;
