@@ -82,10 +82,10 @@ def main():
     sink = torch.zeros(256, dtype=torch.uint8, device=dev)
 
     class Case:
-        def __init__(self, p, ring_mb=None, lut_t=None, layout=None):
+        def __init__(self, p, ring_mb=None, lut_t=None, layout=None, g=4):
             self.p = p
-            # layout None: register-table layout for N <= 8, batched layout above
-            self.lin = from_problem(p, lut_t=lut_t, layout=layout)
+            # layout None: register-table layout for N <= 8 (g = 4), batched layout otherwise
+            self.lin = from_problem(p, lut_t=lut_t, layout=layout, g=g)
             self.bytes = algorithmic_bytes(p.M, p.K, p.bits, p.group, p.N, act_bytes=1 if p.int_path else 2)
             n_copies = max(2, ((args.ring_mb if ring_mb is None else ring_mb) << 20) // self.lin.packed_bytes + 1)
             self.ring = [self.lin.packed] + [self.lin.packed.clone() for _ in range(n_copies - 1)]
@@ -286,6 +286,26 @@ def main():
                 torch.cuda.empty_cache()
             small.append(row)
         detail["small_batch"] = small
+        # LUT group size g = 2, 4, 8 in the batched kernel (Section 4 on the choice of g): fewer,
+        # larger tables against more look-ups; precompute + lookup per call
+        gs = []
+        for p in (wl.make_grouped(3, 76, 16, 4096, 4096, 4, 128, name="g_sweep_4096x4096_w4_n16"),
+                  wl.config5(0, 4)):
+            for g in (2, 4, 8):
+                c = Case(p, layout=3, g=g, ring_mb=0 if p.N > 16 else None)
+
+                def both(c=c):
+                    c.precompute()
+                    c.mpgemm()
+                reps = ring_len(c) if p.N <= 16 else 2
+                us = timed(Replay(both, reps), max(2, args.steps // (4 * reps)) if p.N <= 16 else 10, 2)
+                pu = timed(Replay(c.precompute, 20), 5, 1)
+                gs.append({"name": p.name, "N": p.N, "g": g, "call_us": round(us, 2), "precompute_us": round(pu, 2),
+                           "lut_bytes": int(c.lin.lut.numel()),
+                           "TOPS_equiv": round(2.0 * p.N * p.M * p.K / us / 1e6, 2)})
+                del c
+                torch.cuda.empty_cache()
+        detail["g_sweep"] = gs
         detail["prefill_n256"] = prefill_rows()
         xs = np.array([s["bits"] for s in sweep[:4]], dtype=np.float64)
         ys = np.array([s["mpgemm_us"] for s in sweep[:4]], dtype=np.float64)

@@ -67,7 +67,9 @@ typedef enum { TMAC_OUT_F32 = 0, TMAC_OUT_F16 = 1, TMAC_OUT_I32 = 2 } tmac_out_t
 
 /* Weight matrix description (Algorithm 1: W has shape [M, K]).
  *   bits   1..4, weight bit-width b
- *   g      LUT group size; must be 4 (one 16-entry table per 4 activations)
+ *   g      LUT group size: 4 (one 16-entry table per 4 activations, the paper's choice) in both
+ *          layouts; layout 3 also takes 2 and 8 (4- and 256-entry tables: Section 4 discusses
+ *          how g trades table size against the number of look-ups); K % g == 0
  *   group  quantisation group G along K (which sizes a layout accepts is said with the layout);
  *          == K: one scale per row; 0 = one scale and zero for the whole tensor
  *   layout TMAC_LAYOUT_*: 2 is the decode layout (few activation rows: up to about 8), 3 serves
@@ -123,7 +125,9 @@ typedef struct {
  *            indices of bit plane i of row 64t+r for LUT groups kg = 8c + j, index j in nibble j
  *            (bits 4j..4j+3).  One lane of the kernel owns one row and reads its `bits` dwords of
  *            a chunk with one load; (x << 3) & 0x78787878 and (x >> 1) & 0x78787878 are the
- *            byte offsets of the even and odd tables' entries.
+ *            byte offsets of the even and odd tables' entries.  Bit t of the dword is bit plane
+ *            i of q[64t+r][32c+t], so the same dword read as sixteen 2-bit or four 8-bit fields
+ *            holds the indices for g = 2 or g = 8: the index region does not depend on g.
  *   scales   u16 sz[n_tiles][n_qgroups][64][2] = {fp16 scale, fp16 zero}
  *   Group sizes: any multiple of 32, or K, or 0 (per tensor).  Table types: TMAC_LUT_F16 and
  *   TMAC_LUT_I16.
@@ -161,7 +165,9 @@ tmac_status tmac_pack_weights(const tmac_wdesc* desc, const uint8_t* q_host,
                               const uint16_t* scales_host, const uint16_t* zeros_host,
                               void* packed_host, size_t packed_bytes);
 
-/* Bytes of the LUT buffer for N activation rows: tables [N][Kp/4][16] (2 bytes each, k
+/* Bytes of the LUT buffer for N activation rows.  g = 2 or 8 (16-bit table types only): tables
+ * [N][Kp/g][2^g] (2 bytes each, all-zero tables in the k padding), then the group sums
+ * S[N][n_qgroups], 256-byte aligned.  g = 4: tables [N][Kp/4][16] (2 bytes each, k
  * padded to 128 with all-zero tables; absent for TMAC_LUT_I8Q, which has unit scales [N][Kp/16]
  * and one-byte half tables instead), then the group sums S[N][n_qgroups], then the sums
  * of every 16 consecutive activations S16[N][Kp/16] (both fp32 for TMAC_LUT_F16, int32 for
@@ -172,7 +178,7 @@ size_t tmac_lut_bytes(int32_t N, int32_t K, int32_t g, int32_t group, tmac_lut_t
 
 /* Online table precompute (Algorithm 1 Precompute; Section 3.1; mirror consolidation of
  * Section 3.3 is used to compute half of the entries and negate them for the rest):
- *   T[n,kg,p] = sum_{j<4} (bit j of p ? +a : -a)[n, 4kg+j],  S[n,G] = sum_{k in G} a[n,k].
+ *   T[n,kg,p] = sum_{j<g} (bit j of p ? +a : -a)[n, g*kg+j],  S[n,G] = sum_{k in G} a[n,k].
  *   A_dev  [N,K] row-major with leading dimension lda (elements): fp16 or int8
  *   TMAC_ACT_F16 goes with TMAC_LUT_F16 or TMAC_LUT_I8Q, TMAC_ACT_I8 with TMAC_LUT_I16.
  * Errors: TMAC_EINVAL, TMAC_ESIZE, TMAC_EHIP. */

@@ -42,21 +42,28 @@ struct LutGeom {
   size_t total;
 };
 
-// lut_t: a tmac_lut_t value.  The 16-entry tables [N][KG][16] at offset 0 (read by the batched
-// kernel) exist for the 16-bit table types only.
+// lut_t: a tmac_lut_t value.  The 2^g-entry tables [N][KG][2^g] at offset 0 (read by the batched
+// kernel) exist for the 16-bit table types only; the per-16 and per-128 sums and the half tables
+// of the register-table kernel exist for g = 4 only.
 inline bool lut_geom(int N, int K, int g, int group, int lut_t, LutGeom* lg) {
-  if (N <= 0 || K <= 0 || g != 4 || K % 4 != 0 || group < 0) return false;
-  if (group > 0 && (K % group != 0 || group % 4 != 0)) return false;
+  if (N <= 0 || K <= 0 || (g != 2 && g != 4 && g != 8) || K % 4 != 0 || K % g != 0 || group < 0) return false;
+  if (group > 0 && (K % group != 0 || group % 4 != 0 || group % g != 0)) return false;
   const bool q8 = (lut_t == TMAC_LUT_I8Q);
+  if (q8 && g != 4) return false;
   lg->Kp = round_up(K, 128);
-  lg->KG = lg->Kp / 4;
+  lg->KG = lg->Kp / g;
   lg->U = lg->Kp / 16;
   lg->Geff = (group == 0) ? K : group;
   lg->nq = K / lg->Geff;
   lg->ht_slots = q8 ? 2 : 4;
-  const size_t tab = q8 ? 0 : (size_t)N * lg->KG * 16 * 2;
+  const size_t tab = q8 ? 0 : (size_t)N * lg->KG * (2u << g);
   lg->s_off = (tab + 255) / 256 * 256;
   lg->s16_off = (lg->s_off + (size_t)N * lg->nq * 4 + 255) / 256 * 256;
+  if (g != 4) {
+    lg->s128_off = lg->usc_off = lg->ht_off = lg->s16_off;
+    lg->total = lg->s16_off + 256;
+    return true;
+  }
   lg->s128_off = (lg->s16_off + (size_t)N * lg->U * 4 + 255) / 256 * 256;
   lg->usc_off = (lg->s128_off + (size_t)N * (lg->U / 8) * 4 + 255) / 256 * 256;
   lg->ht_off = q8 ? (lg->usc_off + (size_t)N * lg->U * 4 + 255) / 256 * 256 : lg->usc_off;

@@ -177,6 +177,82 @@ __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict_
   }
 }
 
+// Tables for LUT group sizes other than 4 (Section 4 discusses the choice of g): [N][KG][2^G]
+// 16-bit entries, T[p] = sum_j (bit j of p ? +a_j : -a_j) over the G activations of the group,
+// added pairwise in fp32 and rounded once to fp16 (exact int16 for int8 activations).  One thread
+// writes eight consecutive entries (16 bytes): two whole tables at G = 2, an eighth of one at
+// G = 8 (its eight entries differ in the signs of a_0..a_2 only).
+template <bool IS_INT, int G>
+__global__ __launch_bounds__(256) void precompute_g_kernel(const void* __restrict__ A_, int N, int K, int64_t lda,
+                                                           int KG, uint4* __restrict__ tables,
+                                                           void* __restrict__ S_, int Geff, int nq,
+                                                           int n_tab_blocks) {
+  static_assert(G == 2 || G == 8, "g = 4 has its own kernel");
+  if ((int)blockIdx.x >= n_tab_blocks) {
+    group_sums_wave<IS_INT>(A_, N, lda, S_, Geff, nq, ((int)blockIdx.x - n_tab_blocks) * 4 + (threadIdx.x >> 6));
+    return;
+  }
+  constexpr int ENT = 1 << G;
+  const int64_t per_row = (int64_t)KG * ENT / 8;  // 16-byte items per activation row
+  const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (tid >= (int64_t)N * per_row) return;
+  const int n = (int)(tid / per_row);
+  const int64_t flat = (tid % per_row) * 8;       // first entry of the item in [KG][ENT]
+  const int kg0 = (int)(flat >> G);
+  const int k0 = kg0 * G;                         // first activation the item depends on
+  constexpr int NA = G == 2 ? 4 : 8;              // activations the item depends on
+  float af[NA];
+  int ai[NA];
+#pragma unroll
+  for (int j = 0; j < NA; ++j) { af[j] = 0.f; ai[j] = 0; }
+  const bool live = k0 < K;                       // K is a multiple of 4 and of G: all or nothing
+  if (live) {
+    if constexpr (IS_INT) {
+      const int8_t* a = static_cast<const int8_t*>(A_) + n * lda + k0;
+#pragma unroll
+      for (int j = 0; j < NA; ++j) ai[j] = a[j];
+    } else {
+      const __half* a = static_cast<const __half*>(A_) + n * lda + k0;
+#pragma unroll
+      for (int j = 0; j < NA; ++j) af[j] = __half2float(a[j]);
+    }
+  }
+  uint16_t e[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    if constexpr (G == 2) {
+      const int t = u >> 2, pp = u & 3;           // table kg0 + t, entry pp
+      if constexpr (IS_INT) {
+        e[u] = (uint16_t)(int16_t)(((pp & 1) ? ai[2 * t] : -ai[2 * t]) + ((pp & 2) ? ai[2 * t + 1] : -ai[2 * t + 1]));
+      } else {
+        const float v = ((pp & 1) ? af[2 * t] : -af[2 * t]) + ((pp & 2) ? af[2 * t + 1] : -af[2 * t + 1]);
+        e[u] = __half_as_ushort(__float2half_rn(v));
+      }
+    } else {
+      const int pp = (int)(flat & (ENT - 1)) + u;
+      if constexpr (IS_INT) {
+        int v = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v += ((pp >> j) & 1) ? ai[j] : -ai[j];
+        e[u] = (uint16_t)(int16_t)v;
+      } else {
+        float x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = ((pp >> j) & 1) ? af[j] : -af[j];
+        const float v = ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
+        e[u] = __half_as_ushort(__float2half_rn(v));
+      }
+    }
+  }
+  uint4 o;
+  o.x = (uint32_t)e[0] | ((uint32_t)e[1] << 16);
+  o.y = (uint32_t)e[2] | ((uint32_t)e[3] << 16);
+  o.z = (uint32_t)e[4] | ((uint32_t)e[5] << 16);
+  o.w = (uint32_t)e[6] | ((uint32_t)e[7] << 16);
+  if (!live) o = make_uint4(0, 0, 0, 0);          // k padding: all-zero tables
+  tables[tid] = o;
+}
+
 // Table quantisation (Section 3.3): one thread per unit of 16 activations builds the mirror halves
 // of its four tables in fp32 (same sums as above), takes the unit's largest magnitude
 // amax = max_t sum_j |a_j| (attained by the entry whose signs match), and stores
@@ -304,6 +380,28 @@ extern "C" tmac_status tmac_precompute_lut(const void* A_dev, tmac_act_t act, in
   if (lut_bytes < lg.total) return TMAC_ESIZE;
 
   const int n_sum_blocks = (N * lg.nq + 3) / 4;
+  if (g != 4) {
+    const int64_t n_items = (int64_t)N * lg.KG * (1 << g) / 8;
+    const int n_tab_blocks = (int)((n_items + 255) / 256);
+    uint4* tables = static_cast<uint4*>(lut_dev);
+    void* S = static_cast<char*>(lut_dev) + lg.s_off;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const dim3 grid(n_tab_blocks + n_sum_blocks), block(256);
+    const bool is_int = (act == TMAC_ACT_I8);
+    hipError_t e;
+    if (g == 2) {
+      e = is_int ? launch(precompute_g_kernel<true, 2>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S, lg.Geff,
+                          lg.nq, n_tab_blocks)
+                 : launch(precompute_g_kernel<false, 2>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S,
+                          lg.Geff, lg.nq, n_tab_blocks);
+    } else {
+      e = is_int ? launch(precompute_g_kernel<true, 8>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S, lg.Geff,
+                          lg.nq, n_tab_blocks)
+                 : launch(precompute_g_kernel<false, 8>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S,
+                          lg.Geff, lg.nq, n_tab_blocks);
+    }
+    return e == hipSuccess ? TMAC_OK : TMAC_EHIP;
+  }
   if (lut == TMAC_LUT_I8Q) {
     char* base = static_cast<char*>(lut_dev);
     const int n_unit_blocks = (int)(((int64_t)N * lg.U + 255) / 256);

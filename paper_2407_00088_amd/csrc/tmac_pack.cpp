@@ -18,9 +18,9 @@ bool desc_valid(const tmac_wdesc* d) {
   if (!d) return false;
   if (d->M <= 0 || d->K <= 0) return false;
   if (d->bits < 1 || d->bits > 4) return false;
-  if (d->g != 4) return false;
   if (d->layout != TMAC_LAYOUT_R8U16 && d->layout != TMAC_LAYOUT_R64K32) return false;
-  if (d->K % d->g != 0) return false;
+  if (d->g != 4 && !(d->layout == TMAC_LAYOUT_R64K32 && (d->g == 2 || d->g == 8))) return false;
+  if (d->K % 4 != 0 || d->K % d->g != 0) return false;
   if (d->group < 0 || d->reserved != 0) return false;
   if (!(d->zero_point == d->zero_point)) return false;  // NaN
   if (d->group > 0) {

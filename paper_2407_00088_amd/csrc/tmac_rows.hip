@@ -62,7 +62,12 @@ typedef short rs2v __attribute__((ext_vector_type(2)));
 
 // Activation rows per workgroup for a call with N rows: eight once that wastes at most a fifth of
 // the lookups on padding rows.
-static inline int rows_nt(int N) { return (N >= 40 || N % 8 == 0 || N % 8 >= 5) && N > 4 ? ROWS_NT_WIDE : ROWS_NT_NARROW; }
+// 256-entry tables (g = 8) take the narrow form always: eight rows of them would leave an LDS slice
+// two chunks long.
+static inline int rows_nt(int N, int g) {
+  if (g == 8) return ROWS_NT_NARROW;
+  return (N >= 40 || N % 8 == 0 || N % 8 >= 5) && N > 4 ? ROWS_NT_WIDE : ROWS_NT_NARROW;
+}
 
 struct RowsParams {
   const uint32_t* idx;     // [n_tiles][n_chunks][64][bits] dwords
@@ -86,13 +91,30 @@ struct RowsParams {
   int out_t;
 };
 
-template <bool IS_INT, int BITS, int NT>
+// 32-k chunks of tables one LDS slice holds, for LUT group size g and nt activation rows
+constexpr int rows_lds_chunks(int g, int nt) { return ROWS_LDS / ((32 / g) * (1 << g) * 2 * nt); }
+
+// a[0] = sum of a[0..N), added pairwise: ((a0 + a1) + (a2 + a3)) + ...
+template <typename T, int N>
+__device__ __forceinline__ void tree_sum(T (&a)[N]) {
+#pragma unroll
+  for (int s = 1; s < N; s *= 2) {
+#pragma unroll
+    for (int i = 0; i + s < N; i += 2 * s) a[i] += a[i + s];
+  }
+}
+
+template <bool IS_INT, int BITS, int NT, int G>
 __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const RowsParams p) {
-  constexpr int TB = 32 * NT;          // bytes per table: 16 entries x NT fp16 values
-  constexpr int TPS = ROWS_LDS / TB;   // tables per slice
-  constexpr int CPS = TPS / 8;         // 32-k chunks per slice
+  constexpr int ENT = 1 << G;          // entries per table
+  constexpr int ES = 2 * NT;           // bytes per entry: NT 16-bit values
+  constexpr int TB = ENT * ES;         // bytes per table
+  constexpr int TPC = 32 / G;          // tables, i.e. lookups per plane, of a 32-k chunk
+  constexpr int CB = TPC * TB;         // bytes per chunk
+  constexpr int CPS = rows_lds_chunks(G, NT);  // 32-k chunks per slice
   constexpr int HD = NT / 2;           // dwords per entry
-  __shared__ __attribute__((aligned(8 * TB))) char tab[TPS * TB];  // byte-permuted addresses need the alignment
+  static_assert(CPS >= 1 && CB % 256 == 0, "chunk bases must keep a zero low byte");
+  __shared__ __attribute__((aligned(2048))) char tab[ROWS_LDS];  // byte-permuted addresses need the alignment
   __shared__ int s_last;
   using AccT = typename std::conditional<IS_INT, int, float>::type;
 
@@ -127,7 +149,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
 
   // this workgroup's share of K: chunks [cz0, cz1)
   const int cz0 = blockIdx.z * p.cps, cz1 = min(cz0 + p.cps, p.n_chunks);
-  const int kg_end = min(cz1 * 8, p.KG);  // tables beyond it are read as zero
+  const int kg_end = min(cz1 * TPC, p.KG);  // tables beyond it are read as zero
   int gq = p.grouped ? cz0 / p.cpg : 0, cg = 0;  // current quantisation group, chunks done in it (wave-uniform)
   uint32_t szv = 0;          // {scale, zero} of the lane's row for the current group
   float Sg[NT];
@@ -140,17 +162,18 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
     // stage the tables of this K-slice for the NT activation rows: item = (table, half) reads the
     // 8 entries of the four rows and writes them entry-major
     __syncthreads();
-    for (int it = threadIdx.x; it < TPS * 2; it += 64 * ROWS_WAVES) {
-      const int kl = it >> 1, h = it & 1;
-      const int kg = c0 * 8 + kl;
+    // (an item is eight consecutive entries of the slice: half a table at g = 4, two tables at g = 2)
+    for (int it = threadIdx.x; it < ROWS_LDS / (8 * ES); it += 64 * ROWS_WAVES) {
+      const int flat = it * 8;                        // first entry, counted from the slice's first table
+      const int kg = c0 * TPC + (flat >> G);
       ru32x4v v[NT];
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         v[t] = ru32x4v{0u, 0u, 0u, 0u};
         if (n0 + t < p.N && kg < kg_end)
-          v[t] = *reinterpret_cast<const ru32x4v*>(p.tables + ((size_t)(n0 + t) * p.KG + kg) * 16 + 8 * h);
+          v[t] = *reinterpret_cast<const ru32x4v*>(p.tables + ((size_t)(n0 + t) * p.KG + (size_t)c0 * TPC) * ENT + flat);
       }
-      ru32x4v* dst = reinterpret_cast<ru32x4v*>(tab + kl * TB + h * (TB / 2));
+      ru32x4v* dst = reinterpret_cast<ru32x4v*>(tab + flat * ES);
 #pragma unroll
       for (int d = 0; d < 4; ++d) {  // dword d of every row holds entries 2d, 2d+1 of this half
         uint32_t lo[HD], hi[HD];
@@ -188,25 +211,43 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
           else Sg[t] = static_cast<const float*>(p.S)[(size_t)n * p.nq + gq];
         }
       }
-      const uint32_t cbase = lds0 + (uint32_t)(c - c0) * (8u * TB);
-      // rounds of at most two planes = 16 LDS reads: the hardware counts at most 15 outstanding LDS
-      // operations exactly, so a round's reads can be consumed as they return
+      const uint32_t cbase = lds0 + (uint32_t)(c - c0) * (uint32_t)CB;
+      // rounds of 16 LDS reads (one, two or four planes at g = 2, 4, 8): the hardware counts at
+      // most 15 outstanding LDS operations exactly, so a round's reads can be consumed as they return
+      constexpr int PL = 16 / TPC;
 #pragma unroll
-      for (int b0 = 0; b0 < BITS; b0 += 2) {
-        constexpr int PL = 2;
-        uint32_t e[PL][8][HD];
+      for (int b0 = 0; b0 < BITS; b0 += PL) {
+        uint32_t e[PL][TPC][HD];
 #pragma unroll
         for (int bb = 0; bb < PL; ++bb) {
           const int b = b0 + bb;
           if (b >= BITS) break;
-          // byte offsets of the entries inside their tables: entry * 2 NT, even and odd tables
-          const uint32_t ev = (NT == 4) ? (x[b] << 3) & 0x78787878u : (x[b] << 4) & 0xF0F0F0F0u;
-          const uint32_t od = (NT == 4) ? (x[b] >> 1) & 0x78787878u : x[b] & 0xF0F0F0F0u;
+          // byte offsets of the entries inside their tables (entry * ES), four tables per dword
+          uint32_t off[4];
+          if constexpr (G == 4) {
+            off[0] = (NT == 4) ? (x[b] << 3) & 0x78787878u : (x[b] << 4) & 0xF0F0F0F0u;  // even tables
+            off[1] = (NT == 4) ? (x[b] >> 1) & 0x78787878u : x[b] & 0xF0F0F0F0u;         // odd tables
+          } else if constexpr (G == 2) {
+            // field r of byte i is table 4 i + r
+            if constexpr (NT == 4) {
+              off[0] = (x[b] << 3) & 0x18181818u; off[1] = (x[b] << 1) & 0x18181818u;
+              off[2] = (x[b] >> 1) & 0x18181818u; off[3] = (x[b] >> 3) & 0x18181818u;
+            } else {
+              off[0] = (x[b] << 4) & 0x30303030u; off[1] = (x[b] << 2) & 0x30303030u;
+              off[2] = x[b] & 0x30303030u;        off[3] = (x[b] >> 2) & 0x30303030u;
+            }
+          }
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            // address = {0, cbase byte 2, cbase byte 1, byte j/2 of the offsets}: one byte permute;
-            // the table's own TB * j goes into the instruction's offset field
-            const uint32_t a = __builtin_amdgcn_perm((j & 1) ? od : ev, cbase, 0x0C020100u + 4u + (uint32_t)(j >> 1));
+          for (int j = 0; j < TPC; ++j) {
+            uint32_t a;
+            if constexpr (G == 8) {
+              a = cbase + ((x[b] >> (8 * j)) & 0xffu) * (uint32_t)ES;
+            } else {
+              // address = {0, cbase byte 2, cbase byte 1, one byte of the offsets}: one byte permute;
+              // the table's own TB * j goes into the instruction's offset field
+              constexpr int FPB = 8 / G;  // index fields per byte
+              a = __builtin_amdgcn_perm(off[j % FPB], cbase, 0x0C020100u + 4u + (uint32_t)(j / FPB));
+            }
             if constexpr (NT == 4) {
               const ru32x2v r = *reinterpret_cast<rows_lds_u32x2*>(a + j * TB);
               e[bb][j][0] = r.x; e[bb][j][1] = r.y;
@@ -217,11 +258,11 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
           }
         }
         __builtin_amdgcn_sched_barrier(0);  // keep the reads above the accumulation
-        // The eight entries of a plane (one per table of the chunk) are added pairwise as packed
-        // 16-bit values, two activation rows per instruction: exact for the integer tables
-        // (|sum| <= 8 * 508), three roundings to fp16 for the fp16 tables (the convert to "a higher
-        // precision" of Section 3.3 happens once per chunk and plane); the chunk sum then enters the
-        // 32-bit sum of the quantisation group times 2^plane.
+        // The entries of a plane (one per table of the chunk) are added pairwise as packed 16-bit
+        // values, two activation rows per instruction: exact for the integer tables (|sum| <= 4096),
+        // log2(32/g) roundings to fp16 for the fp16 tables (the convert to "a higher precision" of
+        // Section 3.3 happens once per chunk and plane); the chunk sum then enters the 32-bit sum of
+        // the quantisation group times 2^plane.
 #pragma unroll
         for (int bb = 0; bb < PL; ++bb) {
           const int b = b0 + bb;
@@ -229,20 +270,20 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
 #pragma unroll
           for (int u = 0; u < HD; ++u) {
             if constexpr (IS_INT) {
-              rs2v q[8];
+              rs2v q[TPC];
 #pragma unroll
-              for (int j = 0; j < 8; ++j) q[j] = __builtin_bit_cast(rs2v, e[bb][j][u]);
-              const rs2v r = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
-              L[2 * u] += (int)r.x << b;
-              L[2 * u + 1] += (int)r.y << b;
+              for (int j = 0; j < TPC; ++j) q[j] = __builtin_bit_cast(rs2v, e[bb][j][u]);
+              tree_sum(q);
+              L[2 * u] += (int)q[0].x << b;
+              L[2 * u + 1] += (int)q[0].y << b;
             } else {
-              rh2v q[8];
+              rh2v q[TPC];
 #pragma unroll
-              for (int j = 0; j < 8; ++j) q[j] = __builtin_bit_cast(rh2v, e[bb][j][u]);
-              const rh2v r = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
+              for (int j = 0; j < TPC; ++j) q[j] = __builtin_bit_cast(rh2v, e[bb][j][u]);
+              tree_sum(q);
               const float w = p.pw[b];
-              L[2 * u] = fmaf((float)r.x, w, L[2 * u]);
-              L[2 * u + 1] = fmaf((float)r.y, w, L[2 * u + 1]);
+              L[2 * u] = fmaf((float)q[0].x, w, L[2 * u]);
+              L[2 * u + 1] = fmaf((float)q[0].y, w, L[2 * u + 1]);
             }
           }
         }
@@ -372,30 +413,34 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
   }
 }
 
-template <bool IS_INT, int BITS, int NT>
+template <bool IS_INT, int BITS, int NT, int G>
 static hipError_t launch_rows_one(const RowsParams& p, hipStream_t st) {
   RowsParams local = p;
   void* args[] = {&local};
   const dim3 grid((p.N + NT - 1) / NT, (p.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES, (p.n_chunks + p.cps - 1) / p.cps);
-  return hipLaunchKernel(reinterpret_cast<const void*>(mpgemm_rows_kernel<IS_INT, BITS, NT>), grid,
+  return hipLaunchKernel(reinterpret_cast<const void*>(mpgemm_rows_kernel<IS_INT, BITS, NT, G>), grid,
                          dim3(64 * ROWS_WAVES), args, 0, st);
 }
 
-template <bool IS_INT, int NT>
+template <bool IS_INT, int NT, int G>
 static hipError_t launch_rows_bits(const RowsParams& p, int bits, hipStream_t st) {
   switch (bits) {
-    case 1: return launch_rows_one<IS_INT, 1, NT>(p, st);
-    case 2: return launch_rows_one<IS_INT, 2, NT>(p, st);
-    case 3: return launch_rows_one<IS_INT, 3, NT>(p, st);
-    case 4: return launch_rows_one<IS_INT, 4, NT>(p, st);
+    case 1: return launch_rows_one<IS_INT, 1, NT, G>(p, st);
+    case 2: return launch_rows_one<IS_INT, 2, NT, G>(p, st);
+    case 3: return launch_rows_one<IS_INT, 3, NT, G>(p, st);
+    case 4: return launch_rows_one<IS_INT, 4, NT, G>(p, st);
   }
   return hipErrorInvalidValue;
 }
 
 template <bool IS_INT>
-static hipError_t launch_rows_nt(const RowsParams& p, int nt, int bits, hipStream_t st) {
-  return nt == ROWS_NT_WIDE ? launch_rows_bits<IS_INT, ROWS_NT_WIDE>(p, bits, st)
-                            : launch_rows_bits<IS_INT, ROWS_NT_NARROW>(p, bits, st);
+static hipError_t launch_rows_nt(const RowsParams& p, int g, int nt, int bits, hipStream_t st) {
+  if (g == 8) return launch_rows_bits<IS_INT, ROWS_NT_NARROW, 8>(p, bits, st);  // (rows_nt: always narrow)
+  if (g == 2)
+    return nt == ROWS_NT_WIDE ? launch_rows_bits<IS_INT, ROWS_NT_WIDE, 2>(p, bits, st)
+                              : launch_rows_bits<IS_INT, ROWS_NT_NARROW, 2>(p, bits, st);
+  return nt == ROWS_NT_WIDE ? launch_rows_bits<IS_INT, ROWS_NT_WIDE, 4>(p, bits, st)
+                            : launch_rows_bits<IS_INT, ROWS_NT_NARROW, 4>(p, bits, st);
 }
 
 // How a call is split: workgroups along N and M, and the number of K slices (1 when the (row block,
@@ -404,7 +449,7 @@ static hipError_t launch_rows_nt(const RowsParams& p, int nt, int bits, hipStrea
 RowsPlan rows_plan(const tmac_wdesc* desc, int N) {
   const Geometry ge = geometry(desc);
   RowsPlan pl;
-  pl.nt = rows_nt(N);
+  pl.nt = rows_nt(N, desc->g);
   pl.n_tiles_n = (N + pl.nt - 1) / pl.nt;
   pl.row_blocks = (ge.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES;
   const bool one_group = (desc->group == 0 || desc->group == desc->K);
@@ -416,7 +461,7 @@ RowsPlan rows_plan(const tmac_wdesc* desc, int N) {
   if (want > max_slices) want = max_slices;
   int cps = (int)((ge.n_chunks + want - 1) / want);
   // whole LDS slices where a workgroup gets at least one (nothing staged in vain), whole groups always
-  const int lds_chunks = ROWS_LDS / (32 * pl.nt) / 8;
+  const int lds_chunks = rows_lds_chunks(desc->g, pl.nt);
   int unit = cpg;
   if (want > 1 && cps >= lds_chunks) {
     unit = lds_chunks;
@@ -446,8 +491,8 @@ int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void*
     if (!workspace_dev) return TMAC_EINVAL;
     if (workspace_bytes < pl.part_bytes + pl.ctr_bytes) return TMAC_ESIZE;
   }
-  // int32 accumulators: |L| <= 508 * (2^b - 1) * K/4 must stay below 2^31
-  if (is_int && (double)508.0 * ((1 << desc->bits) - 1) * (desc->K / 4) >= 2147483647.0) return TMAC_EUNSUPPORTED;
+  // int32 accumulators: |L| <= 128 * (2^b - 1) * K must stay below 2^31
+  if (is_int && (double)128.0 * ((1 << desc->bits) - 1) * desc->K >= 2147483647.0) return TMAC_EUNSUPPORTED;
 
   RowsParams p;
   const char* blob = static_cast<const char*>(packed_dev);
@@ -481,8 +526,8 @@ int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void*
     }
   }
   if (out_t == TMAC_OUT_I32 && !p.int_exact) return TMAC_EINVAL;
-  const hipError_t e = is_int ? launch_rows_nt<true>(p, pl.nt, desc->bits, static_cast<hipStream_t>(stream))
-                              : launch_rows_nt<false>(p, pl.nt, desc->bits, static_cast<hipStream_t>(stream));
+  const hipError_t e = is_int ? launch_rows_nt<true>(p, desc->g, pl.nt, desc->bits, static_cast<hipStream_t>(stream))
+                              : launch_rows_nt<false>(p, desc->g, pl.nt, desc->bits, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) {
     note_hip_error((int)e);
     return TMAC_EHIP;

@@ -23,12 +23,14 @@ class LinearLUT:
                  scales: Optional[np.ndarray] = None, zeros: Optional[np.ndarray] = None,
                  zero_point: float = 0.0, weight_scale: float = 1.0, int_path: bool = False,
                  max_N: int = 1, device: str = "cuda", packed_host: Optional[np.ndarray] = None,
-                 layout: Optional[int] = None, lut_t: Optional[int] = None):
+                 layout: Optional[int] = None, lut_t: Optional[int] = None, g: int = 4):
         import torch
         self.torch = torch
         self.device = device
-        self.layout = default_layout(max_N) if layout is None else layout
-        self.desc = B.wdesc(M, K, bits, group, zero_point, layout=self.layout)
+        # LUT group sizes other than 4 exist in the batched layout only
+        self.layout = (default_layout(max_N) if g == 4 else B.TMAC_LAYOUT_R64K32) if layout is None else layout
+        self.g = g
+        self.desc = B.wdesc(M, K, bits, group, zero_point, g=g, layout=self.layout)
         self.M, self.K, self.bits, self.group = M, K, bits, group
         self.weight_scale = float(weight_scale)
         self.lut_t = (B.TMAC_LUT_I16 if int_path else B.TMAC_LUT_F16) if lut_t is None else lut_t
@@ -36,14 +38,14 @@ class LinearLUT:
         blob = packed_host if packed_host is not None else B.tmac_pack_weights(self.desc, q, scales, zeros)
         self.packed_bytes = int(blob.size)
         self.packed = torch.from_numpy(blob).to(device)
-        self.lut = torch.empty(B.tmac_lut_bytes(max_N, K, group, self.lut_t), dtype=torch.uint8, device=device)
+        self.lut = torch.empty(B.tmac_lut_bytes(max_N, K, group, self.lut_t, g=g), dtype=torch.uint8, device=device)
         # the split of a call (and with it the workspace) depends on N: size for every N up to max_N
         ws = max(B.tmac_workspace_bytes(self.desc, n) for n in range(1, max_N + 1))
         self.workspace = torch.zeros(max(ws, 256), dtype=torch.uint8, device=device)
 
     def precompute(self, A, N: Optional[int] = None, stream=None):
         N = A.shape[0] if N is None else N
-        B.tmac_precompute_lut(A, N, self.K, self.group, self.lut_t, self.lut, stream=stream)
+        B.tmac_precompute_lut(A, N, self.K, self.group, self.lut_t, self.lut, g=self.g, stream=stream)
 
     def mpgemm(self, N: int, out, out_t: int = B.TMAC_OUT_F32, act_scale=None, stream=None, tuning=None,
                packed=None):
@@ -86,9 +88,9 @@ def layout_supports_group(layout: int, K: int, group: int) -> bool:
 
 
 def from_problem(p, max_N: Optional[int] = None, device: str = "cuda", layout: Optional[int] = None,
-                 lut_t: Optional[int] = None) -> LinearLUT:
+                 lut_t: Optional[int] = None, g: int = 4) -> LinearLUT:
     """Build a LinearLUT from a workload description object with fields M, K, bits, group, q,
     scales, zeros, zero_point, weight_scale and int_path."""
     return LinearLUT(p.M, p.K, p.bits, p.group, p.q, p.scales, p.zeros, zero_point=p.zero_point,
                      weight_scale=p.weight_scale, int_path=p.int_path, max_N=max_N or p.N, device=device,
-                     layout=layout, lut_t=lut_t)
+                     layout=layout, lut_t=lut_t, g=g)

@@ -73,7 +73,7 @@ def unpack_layout3(blob: np.ndarray):
     raw = blob.tobytes()
     (magic, layout, M, K, bits, g, group, Mp, Kp, n_tiles, n_chunks, n_qgroups, zero_point, _r0,
      idx_off, idx_bytes, sz_off, sz_bytes, total) = struct.unpack_from("<II10ifI5Q", raw, 0)
-    assert magic == 0x43414D54 and layout == 3 and g == 4
+    assert magic == 0x43414D54 and layout == 3 and g in (2, 4, 8)
     assert Mp == (M + 63) // 64 * 64 and Kp == (K + 127) // 128 * 128 and n_chunks == Kp // 32
     assert total == len(raw) and idx_bytes == n_tiles * n_chunks * 64 * bits * 4
     idx = np.frombuffer(raw, dtype="<u4", count=idx_bytes // 4, offset=idx_off).reshape(n_tiles, n_chunks, 64, bits)
@@ -90,4 +90,5 @@ def unpack_layout3(blob: np.ndarray):
         sz = np.frombuffer(raw, dtype="<u2", count=sz_bytes // 2, offset=sz_off).reshape(n_tiles, n_qgroups, 64, 2)
         s = sz[..., 0].transpose(0, 2, 1).reshape(Mp, n_qgroups).view(np.float16)
         z = sz[..., 1].transpose(0, 2, 1).reshape(Mp, n_qgroups).view(np.float16)
-    return dict(M=M, K=K, bits=bits, group=group, Mp=Mp, Kp=Kp, zero_point=zero_point, n_qgroups=n_qgroups), q, s, z
+    return dict(M=M, K=K, bits=bits, g=g, group=group, Mp=Mp, Kp=Kp, zero_point=zero_point,
+                n_qgroups=n_qgroups), q, s, z

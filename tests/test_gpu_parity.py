@@ -476,3 +476,57 @@ def test_batched_kernel_rejects_what_it_cannot_do(T, torch):
     with pytest.raises(T.TmacError) as e:
         from_problem(p, layout=L3, lut_t=B.TMAC_LUT_I8Q).forward(torch.from_numpy(p.act).cuda())
     assert e.value.status == B.TMAC_EUNSUPPORTED
+
+
+# ------------------------------------------- LUT group sizes 2 and 8 (layout 3) ----
+
+def run_g(T, torch, p, g, int_out=None):
+    from paper_2407_00088_amd.runner import from_problem
+    lin = from_problem(p, layout=L3, g=g)
+    if p.int_path:
+        out = lin.forward(torch.from_numpy(p.act_q).cuda(), out_t=int_out, act_scale=torch.from_numpy(p.act_scale).cuda())
+    else:
+        out = lin.forward(torch.from_numpy(p.act).cuda())
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+@pytest.mark.parametrize("g", [2, 8])
+@pytest.mark.parametrize("N", [1, 5, 13, 72])
+@pytest.mark.parametrize("bits,group,M,K", [(4, 128, 200, 1408), (2, 32, 72, 1024), (3, 96, 41, 2304), (1, -1, 130, 3208)])
+def test_other_lut_group_sizes_fp(T, torch, g, N, bits, group, M, K):
+    """g = 2 (4-entry tables, sixteen look-ups per chunk and plane) and g = 8 (256-entry tables,
+    four look-ups): ragged M and N, K that ends inside a chunk (g = 8: K % 8 == 0) and spans several
+    LDS slices and K slices, group sizes from one chunk up and one group per row."""
+    p = wl.make_grouped(0, 800 + 10 * g + bits + N, N, M, K, bits, K if group < 0 else group, name=f"g{g}_w{bits}_n{N}")
+    got = run_g(T, torch, p, g)
+    err = orc.rel_frobenius(got, oracle_fp(p))
+    print(f"{p.name}: rel_frobenius={err:.3e}", flush=True)
+    assert err <= FP_TOL
+
+
+@pytest.mark.parametrize("g", [2, 8])
+@pytest.mark.parametrize("N,M,K", [(1, 3200, 3200), (9, 100, 8640), (40, 257, 1032)])
+def test_other_lut_group_sizes_int_exact(T, torch, g, N, M, K):
+    """Ternary weights, int8 activations: bit-exact int32 and fp32 outputs at g = 2 and g = 8."""
+    p = wl.make_ternary(0, 820 + g + N, N, M, K, name=f"g{g}_ternary_n{N}")
+    ref_i = orc.ternary_int_matmul(p.act_q, p.q, 1)
+    assert np.array_equal(run_g(T, torch, p, g, T.TMAC_OUT_I32).astype(np.int64), ref_i)
+    ref_f = orc.int_path_output_f32(ref_i, p.act_scale, p.weight_scale)
+    assert np.array_equal(run_g(T, torch, p, g, T.TMAC_OUT_F32).view(np.uint32), ref_f.view(np.uint32))
+
+
+@pytest.mark.parametrize("g", [2, 8])
+def test_other_lut_group_sizes_full_shape(T, torch, g):
+    """Config-2 shape 4096 x 4096, 16 activation rows."""
+    p = wl.make_grouped(2, 830 + g, 16, 4096, 4096, 4, 128, name=f"g{g}_4096x4096_n16")
+    err = orc.rel_frobenius(run_g(T, torch, p, g), oracle_fp(p))
+    print(f"{p.name}: rel_frobenius={err:.3e}", flush=True)
+    assert err <= 1e-3
+
+
+def test_other_lut_group_sizes_are_layout3_only(T, torch):
+    from paper_2407_00088_amd.runner import from_problem
+    p = wl.make_grouped(0, 840, 1, 64, 256, 2, 64, name="g8_l2")
+    with pytest.raises(Exception):
+        from_problem(p, layout=L2, g=8)

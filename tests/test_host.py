@@ -114,8 +114,9 @@ def _desc(**kw):
     return d
 
 
-@pytest.mark.parametrize("kw", [dict(bits=0), dict(bits=5), dict(g=8), dict(K=126), dict(M=0),
-                                dict(group=48), dict(group=6), dict(layout=7), dict(layout=1), dict(reserved=1)])
+@pytest.mark.parametrize("kw", [dict(bits=0), dict(bits=5), dict(g=3), dict(g=16), dict(g=8, layout=2), dict(K=126),
+                                dict(K=132, g=8), dict(M=0), dict(group=48), dict(group=6), dict(group=4, g=8),
+                                dict(layout=7), dict(layout=1), dict(reserved=1)])
 def test_bad_desc_is_rejected(kw):
     d = _desc(**kw)
     assert T.tmac_packed_bytes(d) == 0
@@ -151,7 +152,7 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
     fake = C.c_void_p(0x1000)          # never dereferenced: every call fails its checks first
     odd = C.c_void_p(0x1004)
     assert lib.tmac_lut_bytes(1, 126, 4, 0, 0) == 0
-    assert lib.tmac_lut_bytes(1, 128, 8, 0, 0) == 0
+    assert lib.tmac_lut_bytes(1, 128, 3, 0, 0) == 0
     assert lib.tmac_lut_bytes(0, 128, 4, 0, 0) == 0
     assert lib.tmac_lut_bytes(1, 128, 4, 0, 7) == 0
     P = lib.tmac_precompute_lut

@@ -54,3 +54,30 @@ def test_layout3_sizes_and_group_rules():
     assert T.tmac_workspace_bytes(d, 256) == 5 * 256 * 5120 * 4 + 640 * 4 + 256
     assert T.tmac_workspace_bytes(d, 4) > 4 * 5120 * 4        # few rows: partial sums of the K slices
     assert T.tmac_packed_bytes(desc3(100, 48, 2, 16)) > 0     # packs; the kernel rejects the group size
+
+
+@pytest.mark.parametrize("g", [2, 8])
+def test_index_region_does_not_depend_on_g(g):
+    """Bit t of an index dword is bit plane i of q[m][32c+t]: the same bytes serve g = 2, 4, 8;
+    only the header's g field differs."""
+    rng = np.random.default_rng(40 + g)
+    M, K, bits = 70, 160, 3
+    q = rng.integers(0, 1 << bits, size=(M, K), dtype=np.uint8)
+    s = rng.uniform(0.01, 0.1, size=(M, K // 32)).astype(np.float16)
+    z = rng.uniform(0, 7, size=(M, K // 32)).astype(np.float16)
+    b4 = T.tmac_pack_weights(desc3(M, K, bits, 32), q, s, z)
+    bg = T.tmac_pack_weights(T.wdesc(M, K, bits, 32, g=g, layout=B.TMAC_LAYOUT_R64K32), q, s, z)
+    assert b4.size == bg.size
+    diff = np.flatnonzero(b4 != bg)
+    assert diff.size > 0 and diff.max() < 256          # header only
+    hdr, q2, _, _ = unpack_layout3(bg)
+    assert hdr["g"] == g and np.array_equal(q2[:M, :K], q)
+
+
+def test_lut_bytes_for_other_group_sizes():
+    # tables [N][Kp/g][2^g] of 2 bytes, group sums [N][nq] fp32, 256 spare bytes
+    assert T.tmac_lut_bytes(3, 4096, 128, B.TMAC_LUT_F16, g=2) == 3 * 2048 * 4 * 2 + 512 + 256
+    assert T.tmac_lut_bytes(3, 4096, 128, B.TMAC_LUT_I16, g=8) == 3 * 512 * 256 * 2 + 512 + 256
+    assert T.tmac_lut_bytes(1, 4096, 128, B.TMAC_LUT_I8Q, g=8) == 0      # int8 tables: g = 4 only
+    assert T.tmac_lut_bytes(1, 4100, 0, B.TMAC_LUT_F16, g=8) == 0        # K % g
+    assert T.tmac_lut_bytes(1, 4096, 4, B.TMAC_LUT_F16, g=8) == 0        # group % g

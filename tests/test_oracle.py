@@ -208,6 +208,39 @@ def test_lut_route_random_matches_definition(bits, K, G):
     assert np.array_equal(Ri, (ai.astype(np.int64) @ q.astype(np.int64).T).astype(np.float64))
 
 
+@pytest.mark.parametrize("g", [2, 8])
+def test_lut_route_other_group_sizes(g):
+    """LUT group sizes 2 and 8 (Section 4 on the choice of g): table shape and closed forms, every
+    entry against the signed sum it stands for, exhaustive codes of one group at 1 bit (g = 8:
+    all 256 patterns) and 2 bit (g = 2: all 16 pairs) against numpy's integer matmul, and random
+    grouped data against the definition."""
+    rng = np.random.default_rng(300 + g)
+    A = rng.integers(-50, 50, size=(2, 16)).astype(np.float64)
+    lut = orc.precompute_lut(A, g)
+    assert lut.shape == (2, 16 // g, 1 << g)
+    assert np.array_equal(lut + lut[..., ::-1], np.zeros_like(lut))
+    assert np.array_equal(lut[..., -1], A.reshape(2, 16 // g, g).sum(-1))
+    for p in range(1 << g):
+        expect = sum((A[1, g + j] if (p >> j) & 1 else -A[1, g + j]) for j in range(g))
+        assert lut[1, 1, p] == expect
+    bits = 1 if g == 8 else 2
+    q = np.array(list(itertools.product(range(1 << bits), repeat=g)), dtype=np.uint8)   # [(2^b)^g, g]
+    a = A[:, :g]
+    ref = (a.astype(np.int64) @ q.astype(np.int64).T).astype(np.float64)
+    assert np.array_equal(orc.lut_mpgemm(a, q, bits, group=0, g=g), ref)
+    assert np.array_equal(orc.algorithm1_unscaled(a, q, bits, g=g), ref)
+    N, M, K, G, b = 2, 8, 64, 32, 3
+    q = rng.integers(0, 1 << b, size=(M, K), dtype=np.uint8)
+    sc = rng.uniform(0.01, 0.1, size=(M, K // G)).astype(np.float16)
+    z = rng.uniform(0, 7, size=(M, K // G)).astype(np.float16)
+    act = rng.standard_normal((N, K)).astype(np.float16)
+    assert np.allclose(orc.lut_mpgemm(act, q, b, sc, z, group=G, g=g), orc.mpgemm_definition(act, q, sc, z, group=G),
+                       rtol=1e-11, atol=1e-12)
+    aq = rng.integers(-127, 128, size=(N, K)).astype(np.int8)
+    t = rng.integers(0, 3, size=(M, K), dtype=np.uint8)
+    assert np.array_equal(orc.lut_int_matmul(aq, t, 2, 1, g=g)[0], orc.ternary_int_matmul(aq, t, 1))
+
+
 def test_bias_vanishes_at_mid_zero_point():
     """z = (2^b-1)/2 leaves only the look-up term: R = sum_G s * 1/2 * sum_i 2^i L_i."""
     rng = np.random.default_rng(6)
