@@ -79,6 +79,7 @@ struct RowsParams {
   int64_t ldo;
   int M, N, KG, n_tiles, n_chunks, nq;
   int cpg;                 // 32-k chunks per quantisation group (grouped mode)
+  int cpg_log2;            // its logarithm when it is a power of two (the eight-chunk kernel needs one)
   int cps;                 // 32-k chunks per workgroup along K (a multiple of cpg); gridDim.z slices
   int Mp;                  // M rounded up to 64
   float* ws_part;          // split K: [slices][N][Mp] partial sums (fp32, or int32 bit patterns)
@@ -104,15 +105,169 @@ __device__ __forceinline__ void tree_sum(T (&a)[N]) {
   }
 }
 
+
+template <int NT, int G>
+struct RowsShape {
+  static constexpr int ENT = 1 << G;          // entries per table
+  static constexpr int ES = 2 * NT;           // bytes per entry: NT 16-bit values
+  static constexpr int TB = ENT * ES;         // bytes per table
+  static constexpr int TPC = 32 / G;          // tables, i.e. lookups per plane, of a 32-k chunk
+  static constexpr int CB = TPC * TB;         // bytes per chunk
+  static constexpr int HD = NT / 2;           // dwords per entry
+};
+
+// Stage tables into LDS as [table][entry][n]: item `it` is eight consecutive entries (half a table
+// at g = 4, two tables at g = 2) counted from table kg0; it reads them for the NT activation rows
+// n0.. and writes them entry-major.  Tables from kg_end on are written as zeros.
+template <int NT, int G>
+__device__ __forceinline__ void rows_stage_item(const RowsParams& p, char* tab, int it, int n0, int kg0, int kg_end) {
+  using Sh = RowsShape<NT, G>;
+  const int flat = it * 8;
+  const int kg = kg0 + (flat >> G);
+  ru32x4v v[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    v[t] = ru32x4v{0u, 0u, 0u, 0u};
+    if (n0 + t < p.N && kg < kg_end)
+      v[t] = *reinterpret_cast<const ru32x4v*>(p.tables + ((size_t)(n0 + t) * p.KG + (size_t)kg0) * Sh::ENT + flat);
+  }
+  ru32x4v* dst = reinterpret_cast<ru32x4v*>(tab + flat * Sh::ES);
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {  // dword d of every row holds entries 2d, 2d+1 of the item
+    uint32_t lo[Sh::HD], hi[Sh::HD];
+#pragma unroll
+    for (int u = 0; u < Sh::HD; ++u) {
+      lo[u] = __builtin_amdgcn_perm(v[2 * u + 1][d], v[2 * u][d], 0x05040100u);  // entry 2d: rows 2u, 2u+1
+      hi[u] = __builtin_amdgcn_perm(v[2 * u + 1][d], v[2 * u][d], 0x07060302u);  // entry 2d+1
+    }
+    if constexpr (NT == 4) {
+      dst[d] = ru32x4v{lo[0], lo[1], hi[0], hi[1]};
+    } else {
+      dst[2 * d] = ru32x4v{lo[0], lo[1], lo[2], lo[3]};
+      dst[2 * d + 1] = ru32x4v{hi[0], hi[1], hi[2], hi[3]};
+    }
+  }
+}
+
+// The lookups of one 32-k chunk: x = the lane's `BITS` index dwords, cbase = LDS byte address of
+// the chunk's first table (low byte zero); L += sum over planes of 2^plane * (sum of the looked-up
+// entries), per activation row.
+template <bool IS_INT, int BITS, int NT, int G, typename AccT>
+__device__ __forceinline__ void rows_chunk(const uint32_t (&x)[BITS], uint32_t cbase, AccT (&L)[NT], const float (&pw)[4]) {
+  using Sh = RowsShape<NT, G>;
+  constexpr int TPC = Sh::TPC, HD = Sh::HD, TB = Sh::TB;
+  // rounds of 16 LDS reads (one, two or four planes at g = 2, 4, 8): the hardware counts at
+  // most 15 outstanding LDS operations exactly, so a round's reads can be consumed as they return
+  constexpr int PL = 16 / TPC;
+#pragma unroll
+  for (int b0 = 0; b0 < BITS; b0 += PL) {
+    uint32_t e[PL][TPC][HD];
+#pragma unroll
+    for (int bb = 0; bb < PL; ++bb) {
+      const int b = b0 + bb;
+      if (b >= BITS) break;
+      // byte offsets of the entries inside their tables (entry * ES), four tables per dword
+      uint32_t off[4];
+      if constexpr (G == 4) {
+        off[0] = (NT == 4) ? (x[b] << 3) & 0x78787878u : (x[b] << 4) & 0xF0F0F0F0u;  // even tables
+        off[1] = (NT == 4) ? (x[b] >> 1) & 0x78787878u : x[b] & 0xF0F0F0F0u;         // odd tables
+      } else if constexpr (G == 2) {
+        // field r of byte i is table 4 i + r
+        if constexpr (NT == 4) {
+          off[0] = (x[b] << 3) & 0x18181818u; off[1] = (x[b] << 1) & 0x18181818u;
+          off[2] = (x[b] >> 1) & 0x18181818u; off[3] = (x[b] >> 3) & 0x18181818u;
+        } else {
+          off[0] = (x[b] << 4) & 0x30303030u; off[1] = (x[b] << 2) & 0x30303030u;
+          off[2] = x[b] & 0x30303030u;        off[3] = (x[b] >> 2) & 0x30303030u;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < TPC; ++j) {
+        uint32_t a;
+        if constexpr (G == 8) {
+          a = cbase + ((x[b] >> (8 * j)) & 0xffu) * (uint32_t)Sh::ES;
+        } else {
+          // address = {0, cbase byte 2, cbase byte 1, one byte of the offsets}: one byte permute;
+          // the table's own TB * j goes into the instruction's offset field
+          constexpr int FPB = 8 / G;  // index fields per byte
+          a = __builtin_amdgcn_perm(off[j % FPB], cbase, 0x0C020100u + 4u + (uint32_t)(j / FPB));
+        }
+        if constexpr (NT == 4) {
+          const ru32x2v r = *reinterpret_cast<rows_lds_u32x2*>(a + j * TB);
+          e[bb][j][0] = r.x; e[bb][j][1] = r.y;
+        } else {
+          const ru32x4v r = *reinterpret_cast<rows_lds_u32x4*>(a + j * TB);
+          e[bb][j][0] = r.x; e[bb][j][1] = r.y; e[bb][j][2] = r.z; e[bb][j][3] = r.w;
+        }
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);  // keep the reads above the accumulation
+    // The entries of a plane (one per table of the chunk) are added pairwise as packed 16-bit
+    // values, two activation rows per instruction: exact for the integer tables (|sum| <= 4096),
+    // log2(32/g) roundings to fp16 for the fp16 tables (the convert to "a higher precision" of
+    // Section 3.3 happens once per chunk and plane); the chunk sum then enters the 32-bit sum of
+    // the quantisation group times 2^plane.
+#pragma unroll
+    for (int bb = 0; bb < PL; ++bb) {
+      const int b = b0 + bb;
+      if (b >= BITS) break;
+#pragma unroll
+      for (int u = 0; u < HD; ++u) {
+        if constexpr (IS_INT) {
+          rs2v q[TPC];
+#pragma unroll
+          for (int j = 0; j < TPC; ++j) q[j] = __builtin_bit_cast(rs2v, e[bb][j][u]);
+          tree_sum(q);
+          L[2 * u] += (int)q[0].x << b;
+          L[2 * u + 1] += (int)q[0].y << b;
+        } else {
+          rh2v q[TPC];
+#pragma unroll
+          for (int j = 0; j < TPC; ++j) q[j] = __builtin_bit_cast(rh2v, e[bb][j][u]);
+          tree_sum(q);
+          const float w = pw[b];
+          L[2 * u] = fmaf((float)q[0].x, w, L[2 * u]);
+          L[2 * u + 1] = fmaf((float)q[0].y, w, L[2 * u + 1]);
+        }
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// Last step for output (n, m): vf = finished group sums (group scales) or the raw look-up sum (fp
+// tables), vi = the raw integer look-up sum; s, z = scale and zero of row m when there is one
+// scale per row or per tensor.
+template <bool IS_INT>
+__device__ __forceinline__ void rows_finish(const RowsParams& p, int n, int m, float vf, int vi, float s, float z) {
+  const float as = p.act_scale ? p.act_scale[n] : 1.0f;
+  float res;
+  int ires = 0;
+  if (p.grouped) {
+    res = vf * as;
+  } else if constexpr (IS_INT) {
+    const int St = static_cast<const int*>(p.S)[n];
+    if (p.int_exact) {
+      ires = (vi + p.icoef * St) >> 1;  // numerator is always even
+      res = ((float)ires * as) * s;     // two roundings, left to right
+    } else {
+      res = (fmaf(p.mid - z, (float)St, 0.5f * (float)vi) * as) * s;
+    }
+  } else {
+    const float St = static_cast<const float*>(p.S)[n];
+    res = (s * fmaf(p.mid - z, St, 0.5f * vf)) * as;
+  }
+  const size_t o = (size_t)n * p.ldo + m;
+  if (p.out_t == TMAC_OUT_F32) static_cast<float*>(p.out)[o] = res;
+  else if (p.out_t == TMAC_OUT_F16) static_cast<__half*>(p.out)[o] = __float2half_rn(res);
+  else static_cast<int*>(p.out)[o] = ires;
+}
+
 template <bool IS_INT, int BITS, int NT, int G>
 __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const RowsParams p) {
-  constexpr int ENT = 1 << G;          // entries per table
-  constexpr int ES = 2 * NT;           // bytes per entry: NT 16-bit values
-  constexpr int TB = ENT * ES;         // bytes per table
-  constexpr int TPC = 32 / G;          // tables, i.e. lookups per plane, of a 32-k chunk
-  constexpr int CB = TPC * TB;         // bytes per chunk
+  using Sh = RowsShape<NT, G>;
+  constexpr int ES = Sh::ES, TPC = Sh::TPC, CB = Sh::CB;
   constexpr int CPS = rows_lds_chunks(G, NT);  // 32-k chunks per slice
-  constexpr int HD = NT / 2;           // dwords per entry
   static_assert(CPS >= 1 && CB % 256 == 0, "chunk bases must keep a zero low byte");
   __shared__ __attribute__((aligned(2048))) char tab[ROWS_LDS];  // byte-permuted addresses need the alignment
   __shared__ int s_last;
@@ -162,34 +317,8 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
     // stage the tables of this K-slice for the NT activation rows: item = (table, half) reads the
     // 8 entries of the four rows and writes them entry-major
     __syncthreads();
-    // (an item is eight consecutive entries of the slice: half a table at g = 4, two tables at g = 2)
-    for (int it = threadIdx.x; it < ROWS_LDS / (8 * ES); it += 64 * ROWS_WAVES) {
-      const int flat = it * 8;                        // first entry, counted from the slice's first table
-      const int kg = c0 * TPC + (flat >> G);
-      ru32x4v v[NT];
-#pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        v[t] = ru32x4v{0u, 0u, 0u, 0u};
-        if (n0 + t < p.N && kg < kg_end)
-          v[t] = *reinterpret_cast<const ru32x4v*>(p.tables + ((size_t)(n0 + t) * p.KG + (size_t)c0 * TPC) * ENT + flat);
-      }
-      ru32x4v* dst = reinterpret_cast<ru32x4v*>(tab + flat * ES);
-#pragma unroll
-      for (int d = 0; d < 4; ++d) {  // dword d of every row holds entries 2d, 2d+1 of this half
-        uint32_t lo[HD], hi[HD];
-#pragma unroll
-        for (int u = 0; u < HD; ++u) {
-          lo[u] = __builtin_amdgcn_perm(v[2 * u + 1][d], v[2 * u][d], 0x05040100u);  // entry 2d: rows 2u, 2u+1
-          hi[u] = __builtin_amdgcn_perm(v[2 * u + 1][d], v[2 * u][d], 0x07060302u);  // entry 2d+1
-        }
-        if constexpr (NT == 4) {
-          dst[d] = ru32x4v{lo[0], lo[1], hi[0], hi[1]};
-        } else {
-          dst[2 * d] = ru32x4v{lo[0], lo[1], lo[2], lo[3]};
-          dst[2 * d + 1] = ru32x4v{hi[0], hi[1], hi[2], hi[3]};
-        }
-      }
-    }
+    for (int it = threadIdx.x; it < ROWS_LDS / (8 * ES); it += 64 * ROWS_WAVES)
+      rows_stage_item<NT, G>(p, tab, it, n0, c0 * TPC, kg_end);
     __syncthreads();
 
     const int c_end = min(c0 + CPS, cz1);
@@ -211,84 +340,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
           else Sg[t] = static_cast<const float*>(p.S)[(size_t)n * p.nq + gq];
         }
       }
-      const uint32_t cbase = lds0 + (uint32_t)(c - c0) * (uint32_t)CB;
-      // rounds of 16 LDS reads (one, two or four planes at g = 2, 4, 8): the hardware counts at
-      // most 15 outstanding LDS operations exactly, so a round's reads can be consumed as they return
-      constexpr int PL = 16 / TPC;
-#pragma unroll
-      for (int b0 = 0; b0 < BITS; b0 += PL) {
-        uint32_t e[PL][TPC][HD];
-#pragma unroll
-        for (int bb = 0; bb < PL; ++bb) {
-          const int b = b0 + bb;
-          if (b >= BITS) break;
-          // byte offsets of the entries inside their tables (entry * ES), four tables per dword
-          uint32_t off[4];
-          if constexpr (G == 4) {
-            off[0] = (NT == 4) ? (x[b] << 3) & 0x78787878u : (x[b] << 4) & 0xF0F0F0F0u;  // even tables
-            off[1] = (NT == 4) ? (x[b] >> 1) & 0x78787878u : x[b] & 0xF0F0F0F0u;         // odd tables
-          } else if constexpr (G == 2) {
-            // field r of byte i is table 4 i + r
-            if constexpr (NT == 4) {
-              off[0] = (x[b] << 3) & 0x18181818u; off[1] = (x[b] << 1) & 0x18181818u;
-              off[2] = (x[b] >> 1) & 0x18181818u; off[3] = (x[b] >> 3) & 0x18181818u;
-            } else {
-              off[0] = (x[b] << 4) & 0x30303030u; off[1] = (x[b] << 2) & 0x30303030u;
-              off[2] = x[b] & 0x30303030u;        off[3] = (x[b] >> 2) & 0x30303030u;
-            }
-          }
-#pragma unroll
-          for (int j = 0; j < TPC; ++j) {
-            uint32_t a;
-            if constexpr (G == 8) {
-              a = cbase + ((x[b] >> (8 * j)) & 0xffu) * (uint32_t)ES;
-            } else {
-              // address = {0, cbase byte 2, cbase byte 1, one byte of the offsets}: one byte permute;
-              // the table's own TB * j goes into the instruction's offset field
-              constexpr int FPB = 8 / G;  // index fields per byte
-              a = __builtin_amdgcn_perm(off[j % FPB], cbase, 0x0C020100u + 4u + (uint32_t)(j / FPB));
-            }
-            if constexpr (NT == 4) {
-              const ru32x2v r = *reinterpret_cast<rows_lds_u32x2*>(a + j * TB);
-              e[bb][j][0] = r.x; e[bb][j][1] = r.y;
-            } else {
-              const ru32x4v r = *reinterpret_cast<rows_lds_u32x4*>(a + j * TB);
-              e[bb][j][0] = r.x; e[bb][j][1] = r.y; e[bb][j][2] = r.z; e[bb][j][3] = r.w;
-            }
-          }
-        }
-        __builtin_amdgcn_sched_barrier(0);  // keep the reads above the accumulation
-        // The entries of a plane (one per table of the chunk) are added pairwise as packed 16-bit
-        // values, two activation rows per instruction: exact for the integer tables (|sum| <= 4096),
-        // log2(32/g) roundings to fp16 for the fp16 tables (the convert to "a higher precision" of
-        // Section 3.3 happens once per chunk and plane); the chunk sum then enters the 32-bit sum of
-        // the quantisation group times 2^plane.
-#pragma unroll
-        for (int bb = 0; bb < PL; ++bb) {
-          const int b = b0 + bb;
-          if (b >= BITS) break;
-#pragma unroll
-          for (int u = 0; u < HD; ++u) {
-            if constexpr (IS_INT) {
-              rs2v q[TPC];
-#pragma unroll
-              for (int j = 0; j < TPC; ++j) q[j] = __builtin_bit_cast(rs2v, e[bb][j][u]);
-              tree_sum(q);
-              L[2 * u] += (int)q[0].x << b;
-              L[2 * u + 1] += (int)q[0].y << b;
-            } else {
-              rh2v q[TPC];
-#pragma unroll
-              for (int j = 0; j < TPC; ++j) q[j] = __builtin_bit_cast(rh2v, e[bb][j][u]);
-              tree_sum(q);
-              const float w = p.pw[b];
-              L[2 * u] = fmaf((float)q[0].x, w, L[2 * u]);
-              L[2 * u + 1] = fmaf((float)q[0].y, w, L[2 * u + 1]);
-            }
-          }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      rows_chunk<IS_INT, BITS, NT, G>(x, lds0 + (uint32_t)(c - c0) * (uint32_t)CB, L, p.pw);
       if (p.grouped && gq < p.nq && ++cg == p.cpg) {
         const float s = __half2float(__ushort_as_half((uint16_t)(szv & 0xffffu)));
         const float z = __half2float(__ushort_as_half((uint16_t)(szv >> 16)));
@@ -312,30 +364,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
     s = __half2float(__ushort_as_half((uint16_t)(v & 0xffffu)));
     z = __half2float(__ushort_as_half((uint16_t)(v >> 16)));
   }
-  // vf: finished group sums (grouped) or raw look-up sum (fp); vi: raw integer look-up sum
-  auto finish = [&](int n, float vf, int vi) {
-    const float as = p.act_scale ? p.act_scale[n] : 1.0f;
-    float res;
-    int ires = 0;
-    if (p.grouped) {
-      res = vf * as;
-    } else if constexpr (IS_INT) {
-      const int St = static_cast<const int*>(p.S)[n];
-      if (p.int_exact) {
-        ires = (vi + p.icoef * St) >> 1;  // numerator is always even
-        res = ((float)ires * as) * s;     // two roundings, left to right
-      } else {
-        res = (fmaf(p.mid - z, (float)St, 0.5f * (float)vi) * as) * s;
-      }
-    } else {
-      const float St = static_cast<const float*>(p.S)[n];
-      res = (s * fmaf(p.mid - z, St, 0.5f * vf)) * as;
-    }
-    const size_t o = (size_t)n * p.ldo + m;
-    if (p.out_t == TMAC_OUT_F32) static_cast<float*>(p.out)[o] = res;
-    else if (p.out_t == TMAC_OUT_F16) static_cast<__half*>(p.out)[o] = __float2half_rn(res);
-    else static_cast<int*>(p.out)[o] = ires;
-  };
+  auto finish = [&](int n, float vf, int vi) { rows_finish<IS_INT>(p, n, m, vf, vi, s, z); };
   constexpr bool RAW_INT = IS_INT;  // ungrouped integer tables: partial sums are exact integers
   const int nz = gridDim.z;
   if (nz == 1) {
@@ -443,15 +472,198 @@ static hipError_t launch_rows_nt(const RowsParams& p, int g, int nt, int bits, h
                             : launch_rows_bits<IS_INT, ROWS_NT_NARROW, 4>(p, bits, st);
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Few activation rows: one slice of eight chunks per workgroup, sums finished by a second kernel
+// ------------------------------------------------------------------------------------------
+// With few activation rows a call is a chain of latencies, not a stream: the general kernel above
+// asks for a chunk's indices one chunk ahead and meets the other slices of K through counters in
+// memory (store, wait, count, wait, load).  Here the share of a workgroup is fixed at eight
+// chunks (256 k, g = 4), so that every global load it will ever need (indices of all eight chunks,
+// scales and zeros, tables, group sums) is requested in one go at the start, the chunk loop is
+// straight-line code, and the partial sums are written with plain stores; rows_sum_kernel, the
+// next kernel on the stream, adds the slices in slice order and finishes.
+constexpr int R8_CH = 8;
+
+template <bool IS_INT, int BITS, int NT>
+__global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows8_kernel(const RowsParams p) {
+  constexpr int G = 4;
+  using Sh = RowsShape<NT, G>;
+  __shared__ __attribute__((aligned(2048))) char tab[R8_CH * Sh::CB];
+  __shared__ float sS[R8_CH][NT];  // per chunk: the sum of activations of its quantisation group
+  using AccT = typename std::conditional<IS_INT, int, float>::type;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n0 = blockIdx.x * NT;
+  const int tile_raw = blockIdx.y * ROWS_WAVES + wave;
+  const bool tile_ok = tile_raw < p.n_tiles;
+  const int tile = tile_ok ? tile_raw : p.n_tiles - 1;  // clamped: loads stay in range, stores are masked
+  const uint32_t* my_idx = p.idx + ((size_t)tile * p.n_chunks * 64 + lane) * BITS;
+  const uint32_t* my_sz = p.sz + (size_t)tile * p.nq * 64 + lane;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)((rows_lds_char*)tab);
+  const int cz0 = blockIdx.z * R8_CH;
+  const int nc = min(R8_CH, p.n_chunks - cz0);  // chunks of this workgroup (at least one)
+
+  // 1. all global loads, unconditional (clamped addresses): indices, {scale, zero} of every chunk's group
+  uint32_t x[R8_CH][BITS];
+#pragma unroll
+  for (int c = 0; c < R8_CH; ++c) {
+    const uint32_t* src = my_idx + (size_t)min(cz0 + c, p.n_chunks - 1) * 64 * BITS;
+    if constexpr (BITS == 4) {
+      const ru32x4v v = *reinterpret_cast<const ru32x4v*>(src);
+      x[c][0] = v.x; x[c][1] = v.y; x[c][2] = v.z; x[c][3] = v.w;
+    } else if constexpr (BITS == 2) {
+      const ru32x2v v = *reinterpret_cast<const ru32x2v*>(src);
+      x[c][0] = v.x; x[c][1] = v.y;
+    } else {
+#pragma unroll
+      for (int b = 0; b < BITS; ++b) x[c][b] = src[b];
+    }
+  }
+  uint32_t szv[R8_CH];
+#pragma unroll
+  for (int c = 0; c < R8_CH; ++c) {
+    const int gq = p.grouped ? min((cz0 + c) >> p.cpg_log2, p.nq - 1) : 0;
+    szv[c] = (p.grouped || !p.per_tensor) ? my_sz[(size_t)gq * 64] : 0u;
+  }
+
+  // 2. tables of the eight chunks, and the group sums, into LDS
+  const int kg_end = min((cz0 + nc) * Sh::TPC, p.KG);
+  for (int it = threadIdx.x; it < R8_CH * Sh::CB / (8 * Sh::ES); it += 64 * ROWS_WAVES)
+    rows_stage_item<NT, G>(p, tab, it, n0, cz0 * Sh::TPC, kg_end);
+  if (p.grouped && threadIdx.x < R8_CH * NT) {
+    const int c = threadIdx.x / NT, t = threadIdx.x % NT;
+    const int gq = min((cz0 + c) >> p.cpg_log2, p.nq - 1);
+    const int n = min(n0 + t, p.N - 1);
+    if constexpr (IS_INT) sS[c][t] = (float)static_cast<const int*>(p.S)[(size_t)n * p.nq + gq];
+    else sS[c][t] = static_cast<const float*>(p.S)[(size_t)n * p.nq + gq];
+  }
+  __syncthreads();
+
+  // 3. the chunks, straight-line
+  float acc[NT];
+  AccT L[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) { acc[t] = 0.f; L[t] = 0; }
+  const int cmask = (1 << p.cpg_log2) - 1;
+#pragma unroll
+  for (int c = 0; c < R8_CH; ++c) {
+    if (c < nc) {
+      rows_chunk<IS_INT, BITS, NT, G>(x[c], lds0 + (uint32_t)c * (uint32_t)Sh::CB, L, p.pw);
+      // a quantisation group ends with this chunk (chunks in the K padding belong to no group)
+      if (p.grouped && ((cz0 + c + 1) & cmask) == 0 && ((cz0 + c) >> p.cpg_log2) < p.nq) {
+        const float s = __half2float(__ushort_as_half((uint16_t)(szv[c] & 0xffffu)));
+        const float z = __half2float(__ushort_as_half((uint16_t)(szv[c] >> 16)));
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          acc[t] = fmaf(s, fmaf(p.mid - z, sS[c][t], 0.5f * (float)L[t]), acc[t]);
+          L[t] = 0;
+        }
+      }
+    }
+  }
+
+  // 4. one slice: finish here; several: publish the partial sums for rows_sum_kernel
+  const int m = tile_raw * 64 + lane;
+  if (gridDim.z == 1) {
+    if (!tile_ok || m >= p.M) return;
+    float s = p.wscale, z = p.zero_point;
+    if (!p.grouped && !p.per_tensor) {
+      s = __half2float(__ushort_as_half((uint16_t)(szv[0] & 0xffffu)));
+      z = __half2float(__ushort_as_half((uint16_t)(szv[0] >> 16)));
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      if (n0 + t >= p.N) break;
+      rows_finish<IS_INT>(p, n0 + t, m, p.grouped ? acc[t] : (float)L[t], IS_INT ? (int)L[t] : 0, s, z);
+    }
+    return;
+  }
+  if (!tile_ok) return;
+  const bool raw_int = IS_INT && !p.grouped;  // ungrouped integer tables: partial sums are exact integers
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int n = n0 + t;
+    if (n < p.N) {
+      const size_t o = ((size_t)blockIdx.z * p.N + n) * p.Mp + (size_t)m;
+      p.ws_part[o] = p.grouped ? acc[t] : (raw_int ? __int_as_float((int)L[t]) : (float)L[t]);
+    }
+  }
+}
+
+// Adds the partial sums [nz][N][Mp] of the K slices in slice order and finishes: one thread per
+// output, sixteen loads in flight.
+template <bool IS_INT>
+__global__ __launch_bounds__(64) void rows_sum_kernel(const RowsParams p, int nz) {
+  const int m = blockIdx.x * 64 + threadIdx.x, n = blockIdx.y;
+  if (m >= p.M) return;
+  const bool raw_int = IS_INT && !p.grouped;
+  const float* src = p.ws_part + (size_t)n * p.Mp + m;
+  const size_t stride = (size_t)p.N * p.Mp;
+  float sf = 0.f;
+  int si = 0;
+  for (int sl0 = 0; sl0 < nz; sl0 += 16) {
+    float v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = src[(size_t)min(sl0 + u, nz - 1) * stride];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      if (sl0 + u < nz) {
+        if (raw_int) si += __float_as_int(v[u]);
+        else sf += v[u];
+      }
+    }
+  }
+  float s = p.wscale, z = p.zero_point;
+  if (!p.grouped && !p.per_tensor) {
+    const uint32_t v = p.sz[(size_t)(m >> 6) * p.nq * 64 + (m & 63)];
+    s = __half2float(__ushort_as_half((uint16_t)(v & 0xffffu)));
+    z = __half2float(__ushort_as_half((uint16_t)(v >> 16)));
+  }
+  rows_finish<IS_INT>(p, n, m, sf, si, s, z);
+}
+
+template <bool IS_INT, int BITS, int NT>
+static hipError_t launch_rows8_one(const RowsParams& p, hipStream_t st) {
+  RowsParams local = p;
+  int nz = (p.n_chunks + R8_CH - 1) / R8_CH;
+  void* args[] = {&local};
+  const dim3 grid((p.N + NT - 1) / NT, (p.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES, nz);
+  hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(mpgemm_rows8_kernel<IS_INT, BITS, NT>), grid,
+                                 dim3(64 * ROWS_WAVES), args, 0, st);
+  if (e != hipSuccess || nz == 1) return e;
+  void* args2[] = {&local, &nz};
+  return hipLaunchKernel(reinterpret_cast<const void*>(rows_sum_kernel<IS_INT>), dim3((p.M + 63) / 64, p.N),
+                         dim3(64), args2, 0, st);
+}
+
+template <bool IS_INT, int NT>
+static hipError_t launch_rows8_bits(const RowsParams& p, int bits, hipStream_t st) {
+  switch (bits) {
+    case 1: return launch_rows8_one<IS_INT, 1, NT>(p, st);
+    case 2: return launch_rows8_one<IS_INT, 2, NT>(p, st);
+    case 3: return launch_rows8_one<IS_INT, 3, NT>(p, st);
+    case 4: return launch_rows8_one<IS_INT, 4, NT>(p, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <bool IS_INT>
+static hipError_t launch_rows8_nt(const RowsParams& p, int nt, int bits, hipStream_t st) {
+  return nt == ROWS_NT_WIDE ? launch_rows8_bits<IS_INT, ROWS_NT_WIDE>(p, bits, st)
+                            : launch_rows8_bits<IS_INT, ROWS_NT_NARROW>(p, bits, st);
+}
+
 // How a call is split: workgroups along N and M, and the number of K slices (1 when the (row block,
 // n tile) pairs alone fill the chip; otherwise enough slices of at least 256 k, whole quantisation
 // groups each, to give about two workgroups per CU).
 RowsPlan rows_plan(const tmac_wdesc* desc, int N) {
   const Geometry ge = geometry(desc);
   RowsPlan pl;
+  pl.row_blocks = (ge.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES;
   pl.nt = rows_nt(N, desc->g);
   pl.n_tiles_n = (N + pl.nt - 1) / pl.nt;
-  pl.row_blocks = (ge.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES;
   const bool one_group = (desc->group == 0 || desc->group == desc->K);
   const int cpg = (one_group || desc->group < 32) ? 1 : desc->group / 32;  // (sizes below 32 are rejected at launch)
   const int min_cps = (8 + cpg - 1) / cpg * cpg;  // at least 256 k, whole groups
@@ -470,6 +682,9 @@ RowsPlan rows_plan(const tmac_wdesc* desc, int N) {
   cps = (cps + unit - 1) / unit * unit;
   if (cps < min_cps) cps = min_cps;
   pl.cps = cps;
+  // eight-chunk slices, several of them, g = 4, a group size that divides 256 (or no groups):
+  // the kernel pair for few activation rows
+  pl.eight = desc->g == 4 && cps == R8_CH && ge.n_chunks > R8_CH && (one_group || R8_CH % cpg == 0);
   pl.slices = (ge.n_chunks + cps - 1) / cps;
   pl.part_bytes = pl.slices > 1 ? ((size_t)pl.slices * N * ge.Mp * 4 + 255) / 256 * 256 : 0;
   pl.ctr_bytes = pl.slices > 1 ? ((size_t)pairs * 4 + 255) / 256 * 256 : 0;
@@ -506,6 +721,8 @@ int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void*
   p.M = desc->M; p.N = N; p.KG = lg.KG; p.n_tiles = ge.n_tiles; p.n_chunks = ge.n_chunks; p.nq = lg.nq;
   p.grouped = one_group ? 0 : 1;
   p.cpg = one_group ? 1 : desc->group / 32;
+  p.cpg_log2 = 0;
+  while ((2 << p.cpg_log2) <= p.cpg) ++p.cpg_log2;
   p.cps = pl.cps;
   p.Mp = ge.Mp;
   p.ws_part = static_cast<float*>(workspace_dev);
@@ -526,8 +743,10 @@ int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void*
     }
   }
   if (out_t == TMAC_OUT_I32 && !p.int_exact) return TMAC_EINVAL;
-  const hipError_t e = is_int ? launch_rows_nt<true>(p, desc->g, pl.nt, desc->bits, static_cast<hipStream_t>(stream))
-                              : launch_rows_nt<false>(p, desc->g, pl.nt, desc->bits, static_cast<hipStream_t>(stream));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  if (pl.eight) e = is_int ? launch_rows8_nt<true>(p, pl.nt, desc->bits, st) : launch_rows8_nt<false>(p, pl.nt, desc->bits, st);
+  else e = is_int ? launch_rows_nt<true>(p, desc->g, pl.nt, desc->bits, st) : launch_rows_nt<false>(p, desc->g, pl.nt, desc->bits, st);
   if (e != hipSuccess) {
     note_hip_error((int)e);
     return TMAC_EHIP;

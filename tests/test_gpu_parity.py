@@ -530,3 +530,36 @@ def test_other_lut_group_sizes_are_layout3_only(T, torch):
     p = wl.make_grouped(0, 840, 1, 64, 256, 2, 64, name="g8_l2")
     with pytest.raises(Exception):
         from_problem(p, layout=L2, g=8)
+
+
+@pytest.mark.parametrize("N,M,K,group", [(16, 1024, 2048, 128), (16, 1024, 2304, 96), (256, 512, 1024, 128)])
+def test_batched_calls_in_graph_replay(T, torch, N, M, K, group):
+    """precompute + lookup of the batched layout captured in a HIP graph and replayed, as bench.py
+    times them: K slices summed by the second kernel (group 128), by the last workgroup to arrive
+    through the counters in the workspace (group 96: the counters must be back at zero after every
+    call), and no split at all.  Every replay must give the eager result bit for bit."""
+    from paper_2407_00088_amd.runner import from_problem
+    p = wl.make_grouped(0, 860 + N + group, N, M, K, 4, group, name="graph_rows")
+    lin = from_problem(p, layout=L3)
+    A = torch.from_numpy(p.act).cuda()
+    eager = lin.forward(A)
+    torch.cuda.synchronize()
+    assert orc.rel_frobenius(eager.cpu().numpy(), oracle_fp(p)) <= FP_TOL
+    out = torch.zeros((N, M), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        lin.precompute(A)
+        lin.mpgemm(N, out)
+    stream.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        for _ in range(2):
+            lin.precompute(A)
+            lin.mpgemm(N, out)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), rep
+        assert torch.equal(lin.forward(A), eager)   # eager calls between replays share the workspace
