@@ -563,3 +563,70 @@ def test_batched_calls_in_graph_replay(T, torch, N, M, K, group):
         torch.cuda.synchronize()
         assert torch.equal(out, eager), rep
         assert torch.equal(lin.forward(A), eager)   # eager calls between replays share the workspace
+
+
+# ----------------------------------------------------- seeded random shapes ----
+
+@pytest.mark.parametrize("seed", range(80))
+def test_random_shapes_all_paths(T, torch, seed):
+    """Seeded random problems (ragged M, K a multiple of 32 up to 6 k, 1-4 bits, N up to 80, group
+    sizes 32..K, per-row and per-tensor scales) through whichever of the paths accepts them:
+    register-table kernel from the LUT buffer and fused, batched kernels at g = 4, 2 and 8."""
+    from paper_2407_00088_amd.runner import from_problem, layout_supports_group
+    rng = np.random.default_rng(9000 + seed)
+    bits = int(rng.integers(1, 5))
+    K = 32 * int(rng.integers(1, 190))
+    M = int(rng.integers(1, 400))
+    N = int(rng.choice([1, 1, 2, 3, 5, 8, 9, 16, 23, 40, 80]))
+    divisors = [d for d in (32, 64, 96, 128, 256, 512) if K % d == 0]
+    mode = rng.choice(["group", "row", "tensor"])
+    if mode == "group":
+        p = wl.make_grouped(0, 9000 + seed, N, M, K, bits, int(rng.choice(divisors)), name=f"rand{seed}")
+    elif mode == "row":
+        p = wl.make_grouped(0, 9000 + seed, N, M, K, bits, K, name=f"rand{seed}")
+    else:
+        p = wl.Problem(f"rand{seed}", 0, N, M, K, bits, 0, wl.uniform_codes(rng, M, K, bits), None, None,
+                       weight_scale=0.03, zero_point=float(rng.integers(0, 1 << bits)), act=wl.gaussian_act(rng, N, K))
+    ref = oracle_fp(p)
+    A = torch.from_numpy(p.act).cuda()
+    ran = []
+    for layout, g, fused in ((L2, 4, False), (L2, 4, True), (L3, 4, False), (L3, 2, False), (L3, 8, False)):
+        if layout == L2 and N > 8:
+            continue
+        if not layout_supports_group(layout, K, p.group) or K % g:
+            continue
+        lin = from_problem(p, layout=layout, g=g)
+        out = lin.forward_fused(A) if fused else lin.forward(A)
+        torch.cuda.synchronize()
+        err = orc.rel_frobenius(out.cpu().numpy(), ref)
+        assert err <= FP_TOL, (seed, layout, g, fused, M, K, N, bits, p.group, err)
+        ran.append(err)
+    assert ran
+    print(f"rand{seed}: M={M} K={K} N={N} b={bits} G={p.group} paths={len(ran)} max_err={max(ran):.2e}", flush=True)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_shapes_int_path_exact(T, torch, seed):
+    """Seeded random ternary problems with int8 activations: every path must give the oracle's int32
+    result and its two-rounding fp32 output bit for bit."""
+    from paper_2407_00088_amd.runner import from_problem
+    rng = np.random.default_rng(9500 + seed)
+    K = 32 * int(rng.integers(1, 280))
+    M = int(rng.integers(1, 500))
+    N = int(rng.choice([1, 1, 2, 4, 7, 8, 12, 33, 70]))
+    p = wl.make_ternary(0, 9500 + seed, N, M, K, weight_scale=float(rng.uniform(0.005, 0.05)), name=f"randint{seed}")
+    ref_i = orc.ternary_int_matmul(p.act_q, p.q, 1)
+    ref_f = orc.int_path_output_f32(ref_i, p.act_scale, p.weight_scale)
+    A = torch.from_numpy(p.act_q).cuda()
+    s_a = torch.from_numpy(p.act_scale).cuda()
+    for layout, g, fused in ((L2, 4, False), (L2, 4, True), (L3, 4, False), (L3, 2, False), (L3, 8, False)):
+        if layout == L2 and N > 8:
+            continue
+        if K % g:
+            continue
+        lin = from_problem(p, layout=layout, g=g)
+        run = lin.forward_fused if fused else lin.forward
+        got_i = run(A, out_t=T.TMAC_OUT_I32, act_scale=s_a).cpu().numpy()
+        got_f = run(A, out_t=T.TMAC_OUT_F32, act_scale=s_a).cpu().numpy()
+        assert np.array_equal(got_i.astype(np.int64), ref_i), (seed, layout, g, fused, M, K, N)
+        assert np.array_equal(got_f.view(np.uint32), ref_f.view(np.uint32)), (seed, layout, g, fused, M, K, N)
