@@ -58,6 +58,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead of graph replay")
     ap.add_argument("--prefill-only", action="store_true",
                     help="time only the N=256 rows of the sweep and print them (for profiling that kernel)")
+    ap.add_argument("--small-batch-only", action="store_true",
+                    help="time only the N = 2..64 rows of the sweep and print them (for profiling those kernels)")
     ap.add_argument("--two-call", action="store_true",
                     help="step = tmac_precompute_lut + tmac_mpgemm (two launches per GEMV) instead of the fused call")
     args = ap.parse_args()
@@ -157,6 +159,29 @@ def main():
         launches = max(1, total // reps)
         return timed(Replay(body or c.mpgemm, reps), launches, max(1, launches // 10))
 
+    def small_batch_rows():
+        """Small batches (N = 2..64) on the 4096 x 4096 W4 shape: precompute + lookup per call, in both
+        packed layouts where the register-table kernel takes the N (at most 8 rows)."""
+        small = []
+        for N in (2, 4, 8, 16, 32, 64):
+            p = wl.make_grouped(3, 60 + N, N, 4096, 4096, 4, 128, name=f"small_batch_4096x4096_w4_n{N}")
+            row = {"name": p.name, "N": N, "bytes": algorithmic_bytes(p.M, p.K, p.bits, p.group, N)}
+            for lay, key in ((2, "register_table"), (3, "batched")):
+                if lay == 2 and N > 8:
+                    continue
+                c = Case(p, layout=lay)
+
+                def both(c=c):
+                    c.precompute()
+                    c.mpgemm()
+                us = timed(Replay(both, ring_len(c)), max(1, args.steps // ring_len(c)), 2)
+                row[key + "_call_us"] = round(us, 3)
+                row[key + "_TOPS_equiv"] = round(2.0 * N * p.M * p.K / us / 1e6, 3)
+                del c
+                torch.cuda.empty_cache()
+            small.append(row)
+        return small
+
     def prefill_rows():
         """Prefill mpGEMM, N = 256 (batched lookup kernel): precompute + mpgemm per call."""
         rows = []
@@ -178,6 +203,10 @@ def main():
                 del c
                 torch.cuda.empty_cache()
         return rows
+
+    if args.small_batch_only:
+        print(json.dumps({"small_batch": small_batch_rows()}))
+        return
 
     if args.prefill_only:
         print(json.dumps({"prefill_n256": prefill_rows()}))
@@ -265,27 +294,7 @@ def main():
             del c
             torch.cuda.empty_cache()
         detail["stacked_projections"] = stacked
-        # small batches (N = 2..64) on the 4096 x 4096 W4 shape: precompute + lookup per call, in both
-        # packed layouts where the register-table kernel takes the N (at most 8 rows)
-        small = []
-        for N in (2, 4, 8, 16, 32, 64):
-            p = wl.make_grouped(3, 60 + N, N, 4096, 4096, 4, 128, name=f"small_batch_4096x4096_w4_n{N}")
-            row = {"name": p.name, "N": N, "bytes": algorithmic_bytes(p.M, p.K, p.bits, p.group, N)}
-            for lay, key in ((2, "register_table"), (3, "batched")):
-                if lay == 2 and N > 8:
-                    continue
-                c = Case(p, layout=lay)
-
-                def both(c=c):
-                    c.precompute()
-                    c.mpgemm()
-                us = timed(Replay(both, ring_len(c)), max(1, args.steps // ring_len(c)), 2)
-                row[key + "_call_us"] = round(us, 3)
-                row[key + "_TOPS_equiv"] = round(2.0 * N * p.M * p.K / us / 1e6, 3)
-                del c
-                torch.cuda.empty_cache()
-            small.append(row)
-        detail["small_batch"] = small
+        detail["small_batch"] = small_batch_rows()
         # LUT group size g = 2, 4, 8 in the batched kernel (Section 4 on the choice of g): fewer,
         # larger tables against more look-ups; precompute + lookup per call
         gs = []
