@@ -1,4 +1,5 @@
-// Batched lookup kernel (gfx950) for packed layout 3: many activation rows (prefill mpGEMM).
+// Batched lookup kernels (gfx950) for packed layout 3: several to many activation rows (batched
+// decode, prefill mpGEMM).
 //
 // Section 3.2 of the paper argues that the tables must sit in fast on-chip memory and that a large
 // tile over M lets many weight rows reuse one table.  Here the tables of a K-slice and of NT = 4 or
@@ -26,7 +27,8 @@
 //     chip: K is then also split over gridDim.z workgroups, whose partial sums meet in the
 //     workspace; the last workgroup to arrive adds them in slice order (fixed order again) and
 //     writes the result.  Nobody waits for anybody: a counter per output block tells which
-//     workgroup is last.
+//     workgroup is last.  When the slices are as short as eight chunks (a handful of activation
+//     rows), mpgemm_rows8_kernel and rows_sum_kernel further down take the call instead.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
