@@ -172,6 +172,52 @@ def lookup_sum(lut, idx, lut_groups_per_qgroup):
     return out
 
 
+def lookup_sum_narrow(lut16, idx, lut_groups_per_qgroup, tables_per_sum=8):
+    """Look-up + aggregation for one bit plane with a narrow running sum
+    (Section 3.3 / Section 4, "fast aggregation": look-up results are added in
+    the tables' own precision and converted to a higher precision now and
+    then).  Reading for 16-bit float tables: the entries of ``tables_per_sum``
+    consecutive LUT groups are added pairwise in fp16,
+    ((e0+e1)+(e2+e3))+((e4+e5)+(e6+e7)), every add rounded to fp16; these short
+    sums are then added in fp64.  ``lut16`` must be a float16 table."""
+    assert lut16.dtype == np.float16
+    N, KG, _ = lut16.shape
+    M, KG2 = idx.shape
+    T = tables_per_sum
+    assert KG == KG2 and KG % lut_groups_per_qgroup == 0 and lut_groups_per_qgroup % T == 0
+    assert T & (T - 1) == 0
+    nq = KG // lut_groups_per_qgroup
+    out = np.zeros((N, M, nq), dtype=np.float64)
+    kg_range = np.arange(KG)
+    for n in range(N):
+        v = lut16[n][kg_range[None, :], idx].reshape(M, KG // T, T)      # fp16
+        while v.shape[-1] > 1:
+            v = (v[..., 0::2] + v[..., 1::2]).astype(np.float16)          # one rounding per add
+        short = v[..., 0].astype(np.float64)                              # [M, KG/T]
+        out[n] = short.reshape(M, nq, lut_groups_per_qgroup // T).sum(axis=2)
+    return out
+
+
+def lut_mpgemm_narrow(act, q, bits, scales, zeros, group, g=4, tables_per_sum=8):
+    """The LUT route with fp16 tables and the narrow running sum of
+    ``lookup_sum_narrow`` (group scales only); everything else as ``lut_mpgemm``."""
+    q = np.asarray(q)
+    M, K = q.shape
+    nq = K // group
+    s = np.asarray(scales).astype(np.float64)
+    z = np.asarray(zeros).astype(np.float64)
+    lut = precompute_lut(act, g, dtype=np.float16)
+    S = group_sums(act, group).astype(np.float64)
+    mid = (2.0 ** bits - 1.0) / 2.0
+    Lsum = np.zeros((lut.shape[0], M, nq), dtype=np.float64)
+    for i, plane in enumerate(bit_planes(q, bits)):
+        Lsum += (2.0 ** i) * lookup_sum_narrow(lut, group_indices(plane, g), group // g, tables_per_sum)
+    R = np.zeros((lut.shape[0], M), dtype=np.float64)
+    for gq in range(nq):
+        R += s[None, :, gq] * (0.5 * Lsum[:, :, gq] + (mid - z[None, :, gq]) * S[:, gq][:, None])
+    return R
+
+
 def group_sums(act, group):
     """S[n, G] = sum of the activations of quantisation group G (the product of
     A with the all-ones matrix J of Section 4, per group)."""

@@ -630,3 +630,37 @@ def test_random_shapes_int_path_exact(T, torch, seed):
         got_f = run(A, out_t=T.TMAC_OUT_F32, act_scale=s_a).cpu().numpy()
         assert np.array_equal(got_i.astype(np.int64), ref_i), (seed, layout, g, fused, M, K, N)
         assert np.array_equal(got_f.view(np.uint32), ref_f.view(np.uint32)), (seed, layout, g, fused, M, K, N)
+
+
+@pytest.mark.parametrize("N,bits", [(16, 4), (48, 2), (3, 3)])
+def test_batched_kernel_matches_the_narrow_sum_route(T, torch, N, bits):
+    """The batched kernel adds the eight entries of a 32-k chunk and plane pairwise in fp16 before
+    widening: against the oracle route that takes exactly these roundings (fp64 elsewhere) only the
+    fp32 accumulation is left, orders of magnitude below the distance to the exact product."""
+    p = wl.make_grouped(0, 880 + N, N, 256, 2048, bits, 128, name=f"narrow_n{N}")
+    got = run_fp(T, torch, p, layout=L3)
+    model = orc.lut_mpgemm_narrow(p.act, p.q, bits, p.scales, p.zeros, p.group)
+    exact = oracle_fp(p)
+    e_model, e_exact = orc.rel_frobenius(got, model), orc.rel_frobenius(got, exact)
+    print(f"{p.name}: vs narrow-sum route {e_model:.2e}, vs exact {e_exact:.2e}", flush=True)
+    assert e_model <= 2e-6 and e_exact <= FP_TOL
+
+
+@pytest.mark.parametrize("lay", [L2, LF], ids=["regs", "fused"])
+@pytest.mark.parametrize("bits,group", [(4, 128), (2, 32), (3, 0), (1, -1)])
+def test_decode_kernel_matches_the_fp16_table_route(T, torch, lay, bits, group):
+    """The register-table kernel rounds every table entry to fp16 once and accumulates in fp32:
+    against the oracle route with fp16 tables (fp64 elsewhere) only the fp32 accumulation is left."""
+    M, K = 200, 4096
+    if group == 0:
+        rng = np.random.default_rng(890 + bits)
+        p = wl.Problem("tabroute", 0, 1, M, K, bits, 0, wl.uniform_codes(rng, M, K, bits), None, None,
+                       weight_scale=0.04, zero_point=2.0, act=wl.gaussian_act(rng, 1, K))
+    else:
+        p = wl.make_grouped(0, 890 + bits, 1, M, K, bits, K if group < 0 else group, name="tabroute")
+    got = run_fp(T, torch, p, layout=lay)
+    model = orc.lut_mpgemm(p.act, p.q, bits, p.scales, p.zeros, p.group, p.weight_scale, p.zero_point,
+                           table_dtype=np.float16)
+    e_model, e_exact = orc.rel_frobenius(got, model), orc.rel_frobenius(got, oracle_fp(p))
+    print(f"tabroute b{bits} G{p.group} layout{lay}: vs fp16-table route {e_model:.2e}, vs exact {e_exact:.2e}", flush=True)
+    assert e_model <= 2e-6 and e_exact <= FP_TOL

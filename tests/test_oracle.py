@@ -416,3 +416,28 @@ def test_table_quantisation_route_error_matches_the_papers_magnitude():
     err2 = orc.rel_frobenius(orc.lut_mpgemm_tq(p2.act, p2.q, 2, p2.scales, p2.zeros, 8),
                              orc.mpgemm_definition(p2.act, p2.q, p2.scales, p2.zeros, 8))
     assert err2 < 2e-2
+
+
+# ---------------------------------------------- narrow running sums (fp16) ----
+
+def test_narrow_sum_is_exact_on_small_integers_and_bounded_on_gaussian_data():
+    """fp16 pairwise sums of eight table entries (the batched kernel's aggregation, Section 3.3 /
+    Section 4 "fast aggregation" read for fp16 tables): exact whenever every partial sum is an
+    integer below 2048 (then the route must equal the definition bit for bit), and on Gaussian
+    activations an error of a few 1e-4, between the error of fp16 tables alone and the 2e-3 bar."""
+    rng = np.random.default_rng(77)
+    N, M, K, G, b = 2, 24, 512, 128, 4
+    q = rng.integers(0, 16, size=(M, K), dtype=np.uint8)
+    ones = np.ones((M, K // G), np.float16)
+    zer = np.zeros((M, K // G), np.float16)
+    ai = rng.integers(-30, 31, size=(N, K)).astype(np.float16)      # |entry| <= 120, |sum of 8| <= 960
+    exact = (ai.astype(np.int64) @ q.astype(np.int64).T).astype(np.float64)
+    assert np.array_equal(orc.lut_mpgemm_narrow(ai, q, b, ones, zer, G), exact)
+    p = wl.make_grouped(5, 40, 4, 96, 5120, 4, 128)
+    ref = orc.mpgemm_definition(p.act, p.q, p.scales, p.zeros, p.group)
+    e_tab = orc.rel_frobenius(orc.lut_mpgemm(p.act, p.q, 4, p.scales, p.zeros, p.group, table_dtype=np.float16), ref)
+    e_nar = orc.rel_frobenius(orc.lut_mpgemm_narrow(p.act, p.q, 4, p.scales, p.zeros, p.group), ref)
+    assert 5e-5 < e_tab < e_nar < 8e-4
+    # sums of two entries only: closer to the tables' own error
+    e_2 = orc.rel_frobenius(orc.lut_mpgemm_narrow(p.act, p.q, 4, p.scales, p.zeros, p.group, tables_per_sum=2), ref)
+    assert e_tab < e_2 < e_nar
