@@ -179,6 +179,9 @@ def main():
                 us = timed(Replay(both, ring_len(c)), max(1, args.steps // ring_len(c)), 2)
                 row[key + "_call_us"] = round(us, 3)
                 row[key + "_TOPS_equiv"] = round(2.0 * N * p.M * p.K / us / 1e6, 3)
+                if lay == 2:  # the same rows through the fused call (tables built in the lookup kernel)
+                    fu = measure_kernel(c, args.steps, c.fused)
+                    row[key + "_fused_call_us"] = round(fu, 3)
                 del c
                 torch.cuda.empty_cache()
             small.append(row)
