@@ -664,3 +664,21 @@ def test_decode_kernel_matches_the_fp16_table_route(T, torch, lay, bits, group):
     e_model, e_exact = orc.rel_frobenius(got, model), orc.rel_frobenius(got, oracle_fp(p))
     print(f"tabroute b{bits} G{p.group} layout{lay}: vs fp16-table route {e_model:.2e}, vs exact {e_exact:.2e}", flush=True)
     assert e_model <= 2e-6 and e_exact <= FP_TOL
+
+
+@pytest.mark.parametrize("g", [2, 4, 8])
+@pytest.mark.parametrize("K", [8, 16, 24, 40, 136])
+def test_tiny_k_all_lut_group_sizes(T, torch, g, K):
+    """K shorter than one 32-k chunk or ending inside one (padding chunks and tables are zero), one
+    scale per row and per tensor, a single weight row and a handful of activation rows."""
+    from paper_2407_00088_amd.runner import from_problem
+    for M, N, per_tensor in ((1, 1, False), (5, 3, True), (70, 9, False)):
+        rng = np.random.default_rng(950 + K + g + M)
+        if per_tensor:
+            p = wl.Problem("tinyk", 0, N, M, K, 3, 0, wl.uniform_codes(rng, M, K, 3), None, None,
+                           weight_scale=0.07, zero_point=3.0, act=wl.gaussian_act(rng, N, K))
+        else:
+            p = wl.make_grouped(0, 950 + K + g + M, N, M, K, 3, K, name="tinyk")
+        out = from_problem(p, layout=L3, g=g).forward(torch.from_numpy(p.act).cuda())
+        torch.cuda.synchronize()
+        assert orc.rel_frobenius(out.cpu().numpy(), oracle_fp(p)) <= FP_TOL, (g, K, M, N)
