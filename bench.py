@@ -308,6 +308,26 @@ def main():
             del c
             torch.cuda.empty_cache()
         detail["stacked_projections"] = stacked
+        # one Llama-2-7B decoder block, N = 1: its seven projections as seven fused launches, and with
+        # Q,K,V and gate,up stacked along M (four launches); weights of every launch from its own ring
+        blk = {}
+        shapes = {"qkv": (12288, 4096), "o": (4096, 4096), "gate_up": (22016, 4096), "down": (4096, 11008),
+                  "gate": (11008, 4096)}
+        cs = {k: Case(wl.make_grouped(3, 90 + i, 1, M, K, 4, 128, name=f"block_{k}"), ring_mb=args.ring_mb // 2)
+              for i, (k, (M, K)) in enumerate(shapes.items())}
+        for key, seq in (("stacked_4_launches", ["qkv", "o", "gate_up", "down"]),
+                         ("separate_7_launches", ["o", "o", "o", "o", "gate", "gate", "down"])):
+            def block_step(seq=seq):
+                for k in seq:
+                    cs[k].fused()
+            reps = max(ring_len(cs[k]) for k in seq)
+            us = timed(Replay(block_step, reps), max(1, args.steps // reps), 2)
+            nbytes = sum(cs[k].bytes for k in seq)
+            blk[key] = {"us": round(us, 3), "bytes": nbytes, "GBps": round(nbytes / us / 1e3, 1),
+                        "frac_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)}
+        del cs
+        torch.cuda.empty_cache()
+        detail["decoder_block_llama2_7b"] = blk
         detail["small_batch"] = small_batch_rows()
         # LUT group size g = 2, 4, 8 in the batched kernel (Section 4 on the choice of g): fewer,
         # larger tables against more look-ups; precompute + lookup per call
