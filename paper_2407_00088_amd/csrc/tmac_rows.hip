@@ -265,6 +265,7 @@ __device__ __forceinline__ void rows_finish(const RowsParams& p, int n, int m, f
   else static_cast<int*>(p.out)[o] = ires;
 }
 
+
 template <bool IS_INT, int BITS, int NT, int G>
 __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const RowsParams p) {
   using Sh = RowsShape<NT, G>;
@@ -487,6 +488,35 @@ static hipError_t launch_rows_nt(const RowsParams& p, int g, int nt, int bits, h
 // next kernel on the stream, adds the slices in slice order and finishes.
 constexpr int R8_CH = 8;
 
+// Which (n tile, row block, K slice) a workgroup serves.  The hardware hands workgroups to the
+// chip's eight XCDs (one L2 each) round-robin by linear id; with the plain blockIdx mapping the
+// n tiles that share a block of packed indices would sit on eight different L2s and each would
+// fetch the block from memory.  Here the (row block, K slice) groups go round-robin over the XCDs
+// and the n tiles of a group follow each other on one XCD, so a block of indices is fetched once
+// (measured: 74 -> 26 MB fetched at 64 activation rows of a 4096 x 4096 4-bit matrix, same time;
+// the general kernel keeps the plain order, where the same remapping trades index re-reads for
+// table re-reads and changes neither bytes nor time).
+struct RowsUnit {
+  int nt, rb, kz;
+};
+__device__ __forceinline__ RowsUnit rows_unit() {
+  const uint32_t gx = gridDim.x, gy = gridDim.y, groups = gy * gridDim.z;
+  const uint32_t lin = (blockIdx.z * gy + blockIdx.y) * gx + blockIdx.x;
+  const uint32_t whole = (groups & ~7u) * gx;  // ids of the groups that fill all eight XCDs evenly
+  uint32_t grp = lin / gx, nt = lin % gx;      // the few groups left over keep the plain order
+  if (lin < whole) {
+    const uint32_t xcd = lin & 7u, slot = lin >> 3;
+    grp = xcd + 8u * (slot / gx);
+    nt = slot % gx;
+  }
+  RowsUnit r;
+  r.nt = (int)nt;
+  r.rb = (int)(grp % gy);
+  r.kz = (int)(grp / gy);
+  return r;
+}
+
+
 template <bool IS_INT, int BITS, int NT>
 __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows8_kernel(const RowsParams p) {
   constexpr int G = 4;
@@ -497,14 +527,15 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows8_kernel(const Row
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int n0 = blockIdx.x * NT;
-  const int tile_raw = blockIdx.y * ROWS_WAVES + wave;
+  const RowsUnit un = rows_unit();
+  const int n0 = un.nt * NT;
+  const int tile_raw = un.rb * ROWS_WAVES + wave;
   const bool tile_ok = tile_raw < p.n_tiles;
   const int tile = tile_ok ? tile_raw : p.n_tiles - 1;  // clamped: loads stay in range, stores are masked
   const uint32_t* my_idx = p.idx + ((size_t)tile * p.n_chunks * 64 + lane) * BITS;
   const uint32_t* my_sz = p.sz + (size_t)tile * p.nq * 64 + lane;
   const uint32_t lds0 = (uint32_t)(uintptr_t)((rows_lds_char*)tab);
-  const int cz0 = blockIdx.z * R8_CH;
+  const int cz0 = un.kz * R8_CH;
   const int nc = min(R8_CH, p.n_chunks - cz0);  // chunks of this workgroup (at least one)
 
   // 1. all global loads, unconditional (clamped addresses): indices, {scale, zero} of every chunk's group
@@ -588,7 +619,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows8_kernel(const Row
   for (int t = 0; t < NT; ++t) {
     const int n = n0 + t;
     if (n < p.N) {
-      const size_t o = ((size_t)blockIdx.z * p.N + n) * p.Mp + (size_t)m;
+      const size_t o = ((size_t)un.kz * p.N + n) * p.Mp + (size_t)m;
       p.ws_part[o] = p.grouped ? acc[t] : (raw_int ? __int_as_float((int)L[t]) : (float)L[t]);
     }
   }
