@@ -225,6 +225,26 @@ tmac_status tmac_mpgemv_fused(const tmac_wdesc* desc, const void* packed_dev, co
                               float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
                               void* stream);
 
+/* One call for either layout and any N: the result of tmac_precompute_lut followed by
+ * tmac_mpgemm (fp16 tables for TMAC_ACT_F16, exact integer tables for TMAC_ACT_I8), computed
+ * from the activations.  The tables are built inside the lookup kernel where a kernel does that
+ * (Algorithm 1 Precompute next to the look-ups that use it: no second launch and no table
+ * traffic): layout 2 with K % 16 == 0 (this is then tmac_mpgemv_fused), and layout 3 with g = 4,
+ * group scales whose group size divides 256, and at most 32 activation rows in a call that is cut
+ * into K slices of 256 (the case a separate precompute launch costs most).  Every other call
+ * runs tmac_precompute_lut into the second region of the workspace and tmac_mpgemm after it.
+ *   A_dev          [N,K] fp16 or int8, 16-byte aligned, leading dimension lda a multiple of 8
+ *                  (16 for int8 with layout 2)
+ *   workspace_dev  tmac_fused_workspace_bytes(desc, N, act) bytes, 16-byte aligned, zero-filled
+ *                  once before its first use (its first region is tmac_mpgemm's workspace);
+ *                  calls that share it must not overlap in time
+ * Errors: TMAC_EINVAL, TMAC_EUNSUPPORTED, TMAC_ESIZE, TMAC_EHIP. */
+size_t tmac_fused_workspace_bytes(const tmac_wdesc* desc, int32_t N, tmac_act_t act);
+tmac_status tmac_mpgemm_fused(const tmac_wdesc* desc, const void* packed_dev, const void* A_dev,
+                              tmac_act_t act, int32_t N, int64_t lda, const float* act_scale_dev,
+                              float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
+                              void* workspace_dev, size_t workspace_bytes, void* stream);
+
 /* Launch-shape knobs for benchmarking sweeps; 0 = library default.
  *   rows_per_group   register-table kernel (layout 2): weight rows per workgroup, 8 or 16;
  *                    must be 0 for layout 3 (TMAC_EUNSUPPORTED otherwise) */

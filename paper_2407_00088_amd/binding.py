@@ -28,6 +28,7 @@ EXPORTS = [
     "tmac_packed_bytes", "tmac_pack_weights", "tmac_lut_bytes", "tmac_precompute_lut",
     "tmac_workspace_bytes", "tmac_mpgemm", "tmac_mpgemm_ex", "tmac_status_str", "tmac_version",
     "tmac_last_error_detail", "tmac_stream_read", "tmac_mpgemv_fused", "tmac_mpgemv_fused_ex",
+    "tmac_fused_workspace_bytes", "tmac_mpgemm_fused",
 ]
 
 
@@ -76,6 +77,9 @@ def _load() -> C.CDLL:
     lib.tmac_mpgemv_fused.argtypes = [D, P, P, C.c_int, I32, I64, P, F, P, C.c_int, I64, P]
     lib.tmac_mpgemv_fused_ex.restype = C.c_int
     lib.tmac_mpgemv_fused_ex.argtypes = [D, P, P, C.c_int, I32, I64, P, F, P, C.c_int, I64, P, C.POINTER(tmac_tuning)]
+    lib.tmac_fused_workspace_bytes.restype, lib.tmac_fused_workspace_bytes.argtypes = SZ, [D, I32, C.c_int]
+    lib.tmac_mpgemm_fused.restype = C.c_int
+    lib.tmac_mpgemm_fused.argtypes = [D, P, P, C.c_int, I32, I64, P, F, P, C.c_int, I64, P, SZ, P]
     lib.tmac_status_str.restype, lib.tmac_status_str.argtypes = C.c_char_p, [C.c_int]
     lib.tmac_version.restype, lib.tmac_version.argtypes = I32, []
     lib.tmac_last_error_detail.restype, lib.tmac_last_error_detail.argtypes = C.c_char_p, []
@@ -207,6 +211,28 @@ def tmac_mpgemv_fused(desc: tmac_wdesc, packed, A, N: int, out, out_t: int, act:
         _check(lib.tmac_mpgemv_fused(*args), "tmac_mpgemv_fused")
     else:
         _check(lib.tmac_mpgemv_fused_ex(*args, C.byref(tuning)), "tmac_mpgemv_fused_ex")
+
+
+def tmac_fused_workspace_bytes(desc: tmac_wdesc, N: int, act: int) -> int:
+    return int(lib.tmac_fused_workspace_bytes(C.byref(desc), N, act))
+
+
+def tmac_mpgemm_fused(desc: tmac_wdesc, packed, A, N: int, out, out_t: int, workspace, act: Optional[int] = None,
+                      lda: Optional[int] = None, act_scale=None, weight_scale: float = 1.0,
+                      ldo: Optional[int] = None, stream=None) -> None:
+    """packed / A / out / act_scale / workspace: device tensors; A fp16 or int8 [N, K]."""
+    import torch
+    if act is None:
+        act = TMAC_ACT_I8 if A.dtype == torch.int8 else TMAC_ACT_F16
+    if lda is None:
+        lda = A.stride(0) if A.dim() == 2 else desc.K
+    if ldo is None:
+        ldo = out.stride(0) if out.dim() == 2 else desc.M
+    as_ptr = C.c_void_p(act_scale.data_ptr()) if act_scale is not None else None
+    _check(lib.tmac_mpgemm_fused(C.byref(desc), C.c_void_p(packed.data_ptr()), C.c_void_p(A.data_ptr()), act, N, lda,
+                                 as_ptr, C.c_float(weight_scale), C.c_void_p(out.data_ptr()), out_t, ldo,
+                                 C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                                 _stream_ptr(stream)), "tmac_mpgemm_fused")
 
 
 # ---------------------------------------------------------------------------------------

@@ -122,10 +122,12 @@ struct RowsPlan {
   size_t part_bytes, ctr_bytes;  // workspace: partial sums and arrival counters (0 when slices == 1)
 };
 RowsPlan rows_plan(const tmac_wdesc* desc, int N);
-// Returns a tmac_status value.
-int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, int lut_t, int N,
-                     const float* act_scale_dev, float weight_scale, void* out_dev, int out_t, int64_t ldo,
-                     void* workspace_dev, size_t workspace_bytes, void* stream);
+bool rows_builds_tables(const tmac_wdesc* desc, int N);
+// Returns a tmac_status value.  lut_dev NULL: tables built in the kernel from A_dev (where
+// rows_builds_tables(desc, N) holds).
+int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, const void* A_dev,
+                     int64_t lda, int lut_t, int N, const float* act_scale_dev, float weight_scale, void* out_dev,
+                     int out_t, int64_t ldo, void* workspace_dev, size_t workspace_bytes, void* stream);
 
 // Records the last HIP error of this thread (diagnostics for TMAC_EHIP).
 void note_hip_error(int hip_error);

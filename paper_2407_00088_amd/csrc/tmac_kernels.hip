@@ -458,7 +458,7 @@ extern "C" tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed
   }
   // batched lookup kernel (lane = weight row); no launch-shape knobs
   if (rpg != 0) return TMAC_EUNSUPPORTED;
-  return static_cast<tmac_status>(launch_rows_gemm(desc, packed_dev, lut_dev, (int)lut, N, act_scale_dev,
+  return static_cast<tmac_status>(launch_rows_gemm(desc, packed_dev, lut_dev, nullptr, 0, (int)lut, N, act_scale_dev,
                                                     weight_scale, out_dev, (int)out, ldo, workspace_dev,
                                                     workspace_bytes, stream));
 }
@@ -491,6 +491,51 @@ extern "C" tmac_status tmac_mpgemv_fused(const tmac_wdesc* desc, const void* pac
                                          void* stream) {
   return tmac_mpgemv_fused_ex(desc, packed_dev, A_dev, act, N, lda, act_scale_dev, weight_scale, out_dev, out, ldo,
                               stream, nullptr);
+}
+
+// Bytes of the two regions of the workspace of tmac_mpgemm_fused: the split-K workspace of
+// tmac_mpgemm, then (only where the tables are not built inside the lookup kernel) a LUT buffer.
+static bool fused_regions(const tmac_wdesc* desc, int N, tmac_act_t act, size_t* ws, size_t* lut) {
+  if (!desc_valid(desc) || N <= 0 || (act != TMAC_ACT_F16 && act != TMAC_ACT_I8)) return false;
+  const tmac_lut_t lt = (act == TMAC_ACT_I8) ? TMAC_LUT_I16 : TMAC_LUT_F16;
+  *ws = (tmac_workspace_bytes(desc, N) + 255) / 256 * 256;
+  const bool in_kernel = (desc->layout == TMAC_LAYOUT_R8U16) ? (desc->K % 16 == 0 && group_supported(desc))
+                                                             : (group_supported(desc) && rows_builds_tables(desc, N));
+  *lut = in_kernel ? 0 : tmac_lut_bytes(N, desc->K, desc->g, desc->group, lt);
+  return true;
+}
+
+extern "C" size_t tmac_fused_workspace_bytes(const tmac_wdesc* desc, int32_t N, tmac_act_t act) {
+  size_t ws, lut;
+  if (!fused_regions(desc, N, act, &ws, &lut)) return 0;
+  return ws + lut;
+}
+
+extern "C" tmac_status tmac_mpgemm_fused(const tmac_wdesc* desc, const void* packed_dev, const void* A_dev,
+                                         tmac_act_t act, int32_t N, int64_t lda, const float* act_scale_dev,
+                                         float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
+                                         void* workspace_dev, size_t workspace_bytes, void* stream) {
+  size_t ws, lutb;
+  if (!fused_regions(desc, N, act, &ws, &lutb)) return TMAC_EINVAL;
+  if (!packed_dev || !A_dev || !out_dev || !workspace_dev) return TMAC_EINVAL;
+  if (out != TMAC_OUT_F32 && out != TMAC_OUT_F16 && out != TMAC_OUT_I32) return TMAC_EINVAL;
+  if (!aligned16(packed_dev) || !aligned16(A_dev) || !aligned16(workspace_dev)) return TMAC_EINVAL;
+  if (ldo < desc->M || lda < desc->K || lda % 8 != 0) return TMAC_EINVAL;
+  if (!group_supported(desc)) return TMAC_EUNSUPPORTED;
+  if (workspace_bytes < ws + lutb) return TMAC_ESIZE;
+  const tmac_lut_t lt = (act == TMAC_ACT_I8) ? TMAC_LUT_I16 : TMAC_LUT_F16;
+  if (lutb == 0) {
+    if (desc->layout == TMAC_LAYOUT_R8U16)
+      return tmac_mpgemv_fused(desc, packed_dev, A_dev, act, N, lda, act_scale_dev, weight_scale, out_dev, out, ldo,
+                               stream);
+    return static_cast<tmac_status>(launch_rows_gemm(desc, packed_dev, nullptr, A_dev, lda, (int)lt, N, act_scale_dev,
+                                                      weight_scale, out_dev, (int)out, ldo, workspace_dev, ws, stream));
+  }
+  void* lut_dev = static_cast<char*>(workspace_dev) + ws;
+  const tmac_status st = tmac_precompute_lut(A_dev, act, N, desc->K, lda, desc->g, desc->group, lt, lut_dev, lutb, stream);
+  if (st != TMAC_OK) return st;
+  return tmac_mpgemm(desc, packed_dev, lut_dev, lt, N, act_scale_dev, weight_scale, out_dev, out, ldo, workspace_dev,
+                     ws, stream);
 }
 
 extern "C" tmac_status tmac_mpgemm(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev,

@@ -89,6 +89,9 @@ struct RowsParams {
   int grouped;             // 1: group scales, 0: one scale per row or per tensor
   int per_tensor, int_exact, icoef;
   float wscale, zero_point, mid;
+  const void* A;           // fused table build: activations [N][lda], fp16 or int8 (else unused)
+  int64_t lda;
+  int K;
   float pw[4];             // plane weights 1, 2, 4, 8: kernel arguments, so that plane 0 also takes the
                            // fused convert-multiply-add (a literal 1.0 would be folded into cvt + add)
   int out_t;
@@ -118,20 +121,81 @@ struct RowsShape {
   static constexpr int HD = NT / 2;           // dwords per entry
 };
 
+
+// Algorithm 1 Precompute for one (activation row, LUT group of four) inside a lookup kernel: the
+// eight entries 8h..8h+7 of the table, as four dwords of two 16-bit entries, with the arithmetic
+// of the stand-alone precompute kernel ((+-a0 +- a1) + (+-a2 - a3) in fp32, one rounding to
+// fp16; entries 8..15 are the negated entries 7..0: mirror consolidation, Section 3.3).
+template <bool IS_INT>
+__device__ __forceinline__ ru32x4v rows_build_half_table(const void* A, int64_t lda, int n, int kg, int h, bool live) {
+  uint32_t low[4];  // entries 0..7
+  if constexpr (IS_INT) {
+    int a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+    if (live) {
+      const uint32_t v = *reinterpret_cast<const uint32_t*>(static_cast<const int8_t*>(A) + n * lda + 4 * kg);
+      a0 = (int8_t)(v & 0xff); a1 = (int8_t)((v >> 8) & 0xff); a2 = (int8_t)((v >> 16) & 0xff); a3 = (int8_t)(v >> 24);
+    }
+    int e[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) e[q] = ((q & 1) ? a0 : -a0) + ((q & 2) ? a1 : -a1) + ((q & 4) ? a2 : -a2) - a3;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const int x = h ? -e[7 - 2 * d] : e[2 * d], y = h ? -e[6 - 2 * d] : e[2 * d + 1];
+      low[d] = ((uint32_t)x & 0xffffu) | ((uint32_t)y << 16);
+    }
+    return ru32x4v{low[0], low[1], low[2], low[3]};
+  } else {
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    if (live) {
+      const ru32x2v v = *reinterpret_cast<const ru32x2v*>(static_cast<const __half*>(A) + n * lda + 4 * kg);
+      a0 = __half2float(__ushort_as_half((uint16_t)(v.x & 0xffffu)));
+      a1 = __half2float(__ushort_as_half((uint16_t)(v.x >> 16)));
+      a2 = __half2float(__ushort_as_half((uint16_t)(v.y & 0xffffu)));
+      a3 = __half2float(__ushort_as_half((uint16_t)(v.y >> 16)));
+    }
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      float f[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int q = 2 * d + i;
+        f[i] = (((q & 1) ? a0 : -a0) + ((q & 2) ? a1 : -a1)) + (((q & 4) ? a2 : -a2) - a3);
+      }
+      rh2v pk;
+      pk.x = (_Float16)f[0];
+      pk.y = (_Float16)f[1];
+      low[d] = __builtin_bit_cast(uint32_t, pk);
+    }
+    if (!h) return ru32x4v{low[0], low[1], low[2], low[3]};
+    // entries 8 + q = -(entry 7 - q): halves swapped, order reversed, sign bits flipped
+    ru32x4v r;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) r[d] = __builtin_amdgcn_alignbit(low[3 - d], low[3 - d], 16) ^ 0x80008000u;
+    return r;
+  }
+}
+
 // Stage tables into LDS as [table][entry][n]: item `it` is eight consecutive entries (half a table
 // at g = 4, two tables at g = 2) counted from table kg0; it reads them for the NT activation rows
 // n0.. and writes them entry-major.  Tables from kg_end on are written as zeros.
-template <int NT, int G>
+// FUSED (g = 4): the entries are built here from the activations instead of read from the LUT buffer.
+template <int NT, int G, bool FUSED = false, bool IS_INT = false>
 __device__ __forceinline__ void rows_stage_item(const RowsParams& p, char* tab, int it, int n0, int kg0, int kg_end) {
   using Sh = RowsShape<NT, G>;
+  static_assert(!FUSED || G == 4, "tables are built in the kernel for g = 4 only");
   const int flat = it * 8;
   const int kg = kg0 + (flat >> G);
   ru32x4v v[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
-    v[t] = ru32x4v{0u, 0u, 0u, 0u};
-    if (n0 + t < p.N && kg < kg_end)
-      v[t] = *reinterpret_cast<const ru32x4v*>(p.tables + ((size_t)(n0 + t) * p.KG + (size_t)kg0) * Sh::ENT + flat);
+    if constexpr (FUSED) {
+      const bool live = n0 + t < p.N && kg < kg_end && 4 * kg < p.K;
+      v[t] = rows_build_half_table<IS_INT>(p.A, p.lda, min(n0 + t, p.N - 1), kg, it & 1, live);
+    } else {
+      v[t] = ru32x4v{0u, 0u, 0u, 0u};
+      if (n0 + t < p.N && kg < kg_end)
+        v[t] = *reinterpret_cast<const ru32x4v*>(p.tables + ((size_t)(n0 + t) * p.KG + (size_t)kg0) * Sh::ENT + flat);
+    }
   }
   ru32x4v* dst = reinterpret_cast<ru32x4v*>(tab + flat * Sh::ES);
 #pragma unroll
@@ -517,8 +581,9 @@ __device__ __forceinline__ RowsUnit rows_unit() {
 }
 
 
-template <bool IS_INT, int BITS, int NT>
+template <bool IS_INT, int BITS, int NT, bool FUSED>
 __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows8_kernel(const RowsParams p) {
+  static_assert(ROWS_WAVES * 64 >= 32 * NT, "one thread per eight activations of the slice");
   constexpr int G = 4;
   using Sh = RowsShape<NT, G>;
   __shared__ __attribute__((aligned(2048))) char tab[R8_CH * Sh::CB];
@@ -563,6 +628,32 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows8_kernel(const Row
 
   // 2. tables of the eight chunks, and the group sums, into LDS
   const int kg_end = min((cz0 + nc) * Sh::TPC, p.KG);
+  if constexpr (FUSED) {
+    // (group scales only) sums of the quantisation groups of the slice, from the activations: thread
+    // i takes eight activations of row i / 32, the 4 cpg threads of a group add up by butterfly
+    // (they sit in one half of a wavefront), and one thread per chunk publishes the group's sum
+    const int t = threadIdx.x >> 5, seg = threadIdx.x & 31;
+    float ssum = 0.f;
+    const int n = n0 + t, k0 = (cz0 << 5) + 8 * seg;
+    if (t < NT && n < p.N && k0 < p.K) {
+      if constexpr (IS_INT) {
+        const ru32x2v v = *reinterpret_cast<const ru32x2v*>(static_cast<const int8_t*>(p.A) + n * p.lda + k0);
+        int si = __builtin_amdgcn_sdot4((int)v.x, 0x01010101, 0, false);
+        si = __builtin_amdgcn_sdot4((int)v.y, 0x01010101, si, false);
+        ssum = (float)si;  // sums of a group stay below 2^24: exact
+      } else {
+        const ru32x4v v = *reinterpret_cast<const ru32x4v*>(static_cast<const __half*>(p.A) + n * p.lda + k0);
+        float f[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = __half2float(__ushort_as_half((uint16_t)(v[i >> 1] >> (16 * (i & 1)))));
+        ssum = ((f[0] + f[1]) + (f[2] + f[3])) + ((f[4] + f[5]) + (f[6] + f[7]));
+      }
+    }
+    for (int o = 1; o < (4 << p.cpg_log2); o <<= 1) ssum += __shfl_xor(ssum, o);
+    if (t < NT && (seg & 3) == 0) sS[seg >> 2][t] = ssum;
+    for (int it = threadIdx.x; it < R8_CH * Sh::CB / (8 * Sh::ES); it += 64 * ROWS_WAVES)
+      rows_stage_item<NT, G, true, IS_INT>(p, tab, it, n0, cz0 * Sh::TPC, kg_end);
+  } else {
   for (int it = threadIdx.x; it < R8_CH * Sh::CB / (8 * Sh::ES); it += 64 * ROWS_WAVES)
     rows_stage_item<NT, G>(p, tab, it, n0, cz0 * Sh::TPC, kg_end);
   if (p.grouped && threadIdx.x < R8_CH * NT) {
@@ -571,6 +662,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows8_kernel(const Row
     const int n = min(n0 + t, p.N - 1);
     if constexpr (IS_INT) sS[c][t] = (float)static_cast<const int*>(p.S)[(size_t)n * p.nq + gq];
     else sS[c][t] = static_cast<const float*>(p.S)[(size_t)n * p.nq + gq];
+  }
   }
   __syncthreads();
 
@@ -657,13 +749,13 @@ __global__ __launch_bounds__(64) void rows_sum_kernel(const RowsParams p, int nz
   rows_finish<IS_INT>(p, n, m, sf, si, s, z);
 }
 
-template <bool IS_INT, int BITS, int NT>
+template <bool IS_INT, int BITS, int NT, bool FUSED>
 static hipError_t launch_rows8_one(const RowsParams& p, hipStream_t st) {
   RowsParams local = p;
   int nz = (p.n_chunks + R8_CH - 1) / R8_CH;
   void* args[] = {&local};
   const dim3 grid((p.N + NT - 1) / NT, (p.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES, nz);
-  hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(mpgemm_rows8_kernel<IS_INT, BITS, NT>), grid,
+  hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(mpgemm_rows8_kernel<IS_INT, BITS, NT, FUSED>), grid,
                                  dim3(64 * ROWS_WAVES), args, 0, st);
   if (e != hipSuccess || nz == 1) return e;
   void* args2[] = {&local, &nz};
@@ -671,21 +763,21 @@ static hipError_t launch_rows8_one(const RowsParams& p, hipStream_t st) {
                          dim3(64), args2, 0, st);
 }
 
-template <bool IS_INT, int NT>
+template <bool IS_INT, int NT, bool FUSED>
 static hipError_t launch_rows8_bits(const RowsParams& p, int bits, hipStream_t st) {
   switch (bits) {
-    case 1: return launch_rows8_one<IS_INT, 1, NT>(p, st);
-    case 2: return launch_rows8_one<IS_INT, 2, NT>(p, st);
-    case 3: return launch_rows8_one<IS_INT, 3, NT>(p, st);
-    case 4: return launch_rows8_one<IS_INT, 4, NT>(p, st);
+    case 1: return launch_rows8_one<IS_INT, 1, NT, FUSED>(p, st);
+    case 2: return launch_rows8_one<IS_INT, 2, NT, FUSED>(p, st);
+    case 3: return launch_rows8_one<IS_INT, 3, NT, FUSED>(p, st);
+    case 4: return launch_rows8_one<IS_INT, 4, NT, FUSED>(p, st);
   }
   return hipErrorInvalidValue;
 }
 
-template <bool IS_INT>
+template <bool IS_INT, bool FUSED = false>
 static hipError_t launch_rows8_nt(const RowsParams& p, int nt, int bits, hipStream_t st) {
-  return nt == ROWS_NT_WIDE ? launch_rows8_bits<IS_INT, ROWS_NT_WIDE>(p, bits, st)
-                            : launch_rows8_bits<IS_INT, ROWS_NT_NARROW>(p, bits, st);
+  return nt == ROWS_NT_WIDE ? launch_rows8_bits<IS_INT, ROWS_NT_WIDE, FUSED>(p, bits, st)
+                            : launch_rows8_bits<IS_INT, ROWS_NT_NARROW, FUSED>(p, bits, st);
 }
 
 // How a call is split: workgroups along N and M, and the number of K slices (1 when the (row block,
@@ -724,10 +816,23 @@ RowsPlan rows_plan(const tmac_wdesc* desc, int N) {
   return pl;
 }
 
-int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, int lut_t, int N,
-                     const float* act_scale_dev, float weight_scale, void* out_dev, int out_t, int64_t ldo,
-                     void* workspace_dev, size_t workspace_bytes, void* stream) {
+// Whether a call builds its tables inside the lookup kernel when it is given activations instead
+// of a LUT buffer: the eight-chunk kernel with group scales, up to 32 activation rows (every
+// block of 256 weight rows builds the tables again: from 64 rows on that costs more than the
+// launch of the precompute kernel it saves).
+bool rows_builds_tables(const tmac_wdesc* desc, int N) {
+  const bool one_group = (desc->group == 0 || desc->group == desc->K);
+  return !one_group && N <= 32 && rows_plan(desc, N).eight;
+}
+
+// lut_dev: buffer of tmac_precompute_lut, or NULL with A_dev / lda given (only where
+// rows_builds_tables says so).
+int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, const void* A_dev,
+                     int64_t lda, int lut_t, int N, const float* act_scale_dev, float weight_scale, void* out_dev,
+                     int out_t, int64_t ldo, void* workspace_dev, size_t workspace_bytes, void* stream) {
   if (lut_t != TMAC_LUT_F16 && lut_t != TMAC_LUT_I16) return TMAC_EUNSUPPORTED;
+  const bool fused = (lut_dev == nullptr);
+  if (fused && (!A_dev || !rows_builds_tables(desc, N))) return TMAC_EUNSUPPORTED;
   const Geometry ge = geometry(desc);
   LutGeom lg;
   if (!lut_geom(N, desc->K, desc->g, desc->group, lut_t, &lg)) return TMAC_EINVAL;
@@ -747,7 +852,10 @@ int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void*
   p.idx = reinterpret_cast<const uint32_t*>(blob + ge.idx_off);
   p.sz = reinterpret_cast<const uint32_t*>(blob + ge.sz_off);
   p.tables = static_cast<const uint16_t*>(lut_dev);
-  p.S = static_cast<const char*>(lut_dev) + lg.s_off;
+  p.S = fused ? nullptr : static_cast<const char*>(lut_dev) + lg.s_off;
+  p.A = A_dev;
+  p.lda = lda;
+  p.K = desc->K;
   p.out = out_dev;
   p.act_scale = act_scale_dev;
   p.ldo = ldo;
@@ -778,7 +886,8 @@ int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void*
   if (out_t == TMAC_OUT_I32 && !p.int_exact) return TMAC_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (pl.eight) e = is_int ? launch_rows8_nt<true>(p, pl.nt, desc->bits, st) : launch_rows8_nt<false>(p, pl.nt, desc->bits, st);
+  if (fused) e = is_int ? launch_rows8_nt<true, true>(p, pl.nt, desc->bits, st) : launch_rows8_nt<false, true>(p, pl.nt, desc->bits, st);
+  else if (pl.eight) e = is_int ? launch_rows8_nt<true>(p, pl.nt, desc->bits, st) : launch_rows8_nt<false>(p, pl.nt, desc->bits, st);
   else e = is_int ? launch_rows_nt<true>(p, desc->g, pl.nt, desc->bits, st) : launch_rows_nt<false>(p, desc->g, pl.nt, desc->bits, st);
   if (e != hipSuccess) {
     note_hip_error((int)e);

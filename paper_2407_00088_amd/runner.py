@@ -59,6 +59,24 @@ class LinearLUT:
         B.tmac_mpgemv_fused(self.desc, self.packed if packed is None else packed, A, N, out, out_t,
                             act_scale=act_scale, weight_scale=self.weight_scale, stream=stream, tuning=tuning)
 
+    def mpgemm_fused(self, A, N: int, out, out_t: int = B.TMAC_OUT_F32, act_scale=None, stream=None, packed=None):
+        """One call for either layout (tmac_mpgemm_fused); its workspace is allocated on first use."""
+        act = B.TMAC_ACT_I8 if A.dtype == self.torch.int8 else B.TMAC_ACT_F16
+        need = max(B.tmac_fused_workspace_bytes(self.desc, n, act) for n in range(1, self.max_N + 1))
+        if getattr(self, "fused_ws", None) is None or self.fused_ws.numel() < need:
+            self.fused_ws = self.torch.zeros(max(need, 256), dtype=self.torch.uint8, device=self.device)
+        B.tmac_mpgemm_fused(self.desc, self.packed if packed is None else packed, A, N, out, out_t, self.fused_ws,
+                            act_scale=act_scale, weight_scale=self.weight_scale, stream=stream)
+
+    def forward_one_call(self, A, out_t: int = B.TMAC_OUT_F32, act_scale=None):
+        torch = self.torch
+        N = A.shape[0]
+        assert N <= self.max_N
+        dt = {B.TMAC_OUT_F32: torch.float32, B.TMAC_OUT_F16: torch.float16, B.TMAC_OUT_I32: torch.int32}[out_t]
+        out = torch.empty((N, self.M), dtype=dt, device=self.device)
+        self.mpgemm_fused(A, N, out, out_t, act_scale=act_scale)
+        return out
+
     def forward_fused(self, A, out_t: int = B.TMAC_OUT_F32, act_scale=None, tuning=None):
         torch = self.torch
         N = A.shape[0]

@@ -682,3 +682,80 @@ def test_tiny_k_all_lut_group_sizes(T, torch, g, K):
         out = from_problem(p, layout=L3, g=g).forward(torch.from_numpy(p.act).cuda())
         torch.cuda.synchronize()
         assert orc.rel_frobenius(out.cpu().numpy(), oracle_fp(p)) <= FP_TOL, (g, K, M, N)
+
+
+# ------------------------------------------------- one-call entry point ----
+
+@pytest.mark.parametrize("layout,g,N,M,K,bits,group", [
+    (L3, 4, 16, 300, 2048, 4, 128),    # tables built in the eight-chunk kernel
+    (L3, 4, 9, 64, 4096, 2, 32),
+    (L3, 4, 32, 130, 1280, 3, 256),
+    (L3, 4, 40, 130, 1280, 3, 256),    # more than 32 rows: precompute launch inside the call
+    (L3, 4, 3, 70, 1024, 1, 64),       # four activation rows per workgroup
+    (L3, 4, 16, 200, 2304, 4, 96),     # group size does not divide 256: precompute launch inside the call
+    (L3, 4, 16, 200, 2048, 4, -1),     # one scale per row: the same
+    (L3, 4, 256, 512, 1024, 4, 128),   # many rows, no short slices: the same
+    (L3, 8, 16, 128, 2048, 4, 128),    # other LUT group size: the same
+    (L2, 4, 1, 100, 4096, 4, 128),     # register-table kernel, tables built in the kernel
+    (L2, 4, 4, 100, 4072, 2, -1),      # K % 16 != 0: precompute launch inside the call
+])
+def test_one_call_entry_point_fp(T, torch, layout, g, N, M, K, bits, group):
+    """tmac_mpgemm_fused against the oracle and against tmac_precompute_lut + tmac_mpgemm (same table
+    entries; only the order of the activation sums may differ)."""
+    from paper_2407_00088_amd.runner import from_problem
+    p = wl.make_grouped(0, 960 + N + bits, N, M, K, bits, K if group < 0 else group, name="onecall")
+    lin = from_problem(p, layout=layout, g=g)
+    A = torch.from_numpy(p.act).cuda()
+    two = lin.forward(A).cpu().numpy()
+    for _ in range(2):   # twice: the workspace is reused
+        one = lin.forward_one_call(A).cpu().numpy()
+        assert orc.rel_frobenius(one, oracle_fp(p)) <= FP_TOL
+        assert orc.rel_frobenius(one, two) <= 2e-6
+
+
+@pytest.mark.parametrize("layout,N,M,K", [(L3, 12, 257, 3200), (L3, 70, 100, 8640), (L2, 2, 64, 3200)])
+def test_one_call_entry_point_int_exact(T, torch, layout, N, M, K):
+    from paper_2407_00088_amd.runner import from_problem
+    p = wl.make_ternary(0, 970 + N, N, M, K, name="onecall_int")
+    lin = from_problem(p, layout=layout)
+    A, s_a = torch.from_numpy(p.act_q).cuda(), torch.from_numpy(p.act_scale).cuda()
+    ref_i = orc.ternary_int_matmul(p.act_q, p.q, 1)
+    got = lin.forward_one_call(A, out_t=T.TMAC_OUT_I32, act_scale=s_a).cpu().numpy()
+    assert np.array_equal(got.astype(np.int64), ref_i)
+    got_f = lin.forward_one_call(A, out_t=T.TMAC_OUT_F32, act_scale=s_a).cpu().numpy()
+    assert np.array_equal(got_f.view(np.uint32), orc.int_path_output_f32(ref_i, p.act_scale, p.weight_scale).view(np.uint32))
+
+
+def test_one_call_entry_point_int_group_scales_in_kernel(T, torch):
+    """int8 activations with group scales, tables and group sums built in the kernel: integer tables
+    and sums are exact, so the result must equal the two-call path bit for bit."""
+    from paper_2407_00088_amd.runner import from_problem
+    rng = np.random.default_rng(975)
+    N, M, K, G = 16, 200, 2048, 128
+    q = wl.uniform_codes(rng, M, K, 4)
+    a_q, s_a = wl.absmax_int8(wl.gaussian_act(rng, N, K))
+    p = wl.Problem("onecall_intg", 0, N, M, K, 4, G, q, wl.group_scales(rng, M, K // G), wl.group_zeros(rng, M, K // G, 4),
+                   act_q=a_q, act_scale=s_a)
+    lin = from_problem(p, layout=L3)
+    A, sa = torch.from_numpy(a_q).cuda(), torch.from_numpy(s_a).cuda()
+    two = lin.forward(A, act_scale=sa)
+    one = lin.forward_one_call(A, act_scale=sa)
+    assert torch.equal(one, two)
+    ref = orc.mpgemm_definition(a_q.astype(np.float64) * s_a[:, None].astype(np.float64), q, p.scales, p.zeros, G)
+    assert orc.rel_frobenius(one.cpu().numpy(), ref) <= 1e-5
+
+
+def test_one_call_entry_point_rejects(T, torch):
+    from paper_2407_00088_amd import binding as B
+    from paper_2407_00088_amd.runner import from_problem
+    p = wl.make_grouped(0, 980, 16, 64, 1024, 4, 128, name="onecall_bad")
+    lin = from_problem(p, layout=L3)
+    A = torch.from_numpy(p.act).cuda()
+    out = torch.empty((16, 64), dtype=torch.float32, device="cuda")
+    need = B.tmac_fused_workspace_bytes(lin.desc, 16, B.TMAC_ACT_F16)
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+    B.tmac_mpgemm_fused(lin.desc, lin.packed, A, 16, out, B.TMAC_OUT_F32, ws)
+    with pytest.raises(Exception):
+        B.tmac_mpgemm_fused(lin.desc, lin.packed, A, 16, out, B.TMAC_OUT_F32, ws[: need - 256])
+    with pytest.raises(Exception):
+        B.tmac_mpgemm_fused(lin.desc, lin.packed, A, 16, out, B.TMAC_OUT_F32, ws, lda=1028)

@@ -81,3 +81,26 @@ def test_lut_bytes_for_other_group_sizes():
     assert T.tmac_lut_bytes(1, 4096, 128, B.TMAC_LUT_I8Q, g=8) == 0      # int8 tables: g = 4 only
     assert T.tmac_lut_bytes(1, 4100, 0, B.TMAC_LUT_F16, g=8) == 0        # K % g
     assert T.tmac_lut_bytes(1, 4096, 4, B.TMAC_LUT_F16, g=8) == 0        # group % g
+
+
+def test_fused_workspace_regions():
+    """tmac_fused_workspace_bytes = tmac_mpgemm's workspace (rounded to 256) plus a LUT buffer only
+    where the tables are not built inside the lookup kernel."""
+    F16, I8 = B.TMAC_ACT_F16, B.TMAC_ACT_I8
+    d = desc3(4096, 4096, 4, 128)
+    ws16 = T.tmac_workspace_bytes(d, 16)
+    assert B.tmac_fused_workspace_bytes(d, 16, F16) == ws16                      # short slices: in the kernel
+    assert B.tmac_fused_workspace_bytes(d, 16, I8) == ws16
+    big = desc3(13824, 5120, 4, 128)
+    assert B.tmac_fused_workspace_bytes(big, 256, F16) == \
+        T.tmac_workspace_bytes(big, 256) + T.tmac_lut_bytes(256, 5120, 128, B.TMAC_LUT_F16)
+    row = desc3(4096, 4096, 4, 4096)                                              # one scale per row
+    assert B.tmac_fused_workspace_bytes(row, 16, F16) == \
+        T.tmac_workspace_bytes(row, 16) + T.tmac_lut_bytes(16, 4096, 4096, B.TMAC_LUT_F16)
+    g96 = desc3(4096, 4608, 4, 96)                                                # 3 chunks per group
+    assert B.tmac_fused_workspace_bytes(g96, 16, F16) > T.tmac_workspace_bytes(g96, 16) + 4608 * 16 * 8
+    d2 = T.wdesc(4096, 4096, 4, 128, layout=B.TMAC_LAYOUT_R8U16)
+    assert B.tmac_fused_workspace_bytes(d2, 1, F16) == 256                        # register-table kernel builds them
+    d2b = T.wdesc(64, 4072, 2, 4072, layout=B.TMAC_LAYOUT_R8U16)
+    assert B.tmac_fused_workspace_bytes(d2b, 1, F16) == 256 + T.tmac_lut_bytes(1, 4072, 4072, B.TMAC_LUT_F16)
+    assert B.tmac_fused_workspace_bytes(d, 0, F16) == 0 and B.tmac_fused_workspace_bytes(d, 1, 7) == 0
