@@ -220,4 +220,4 @@ extern "C" const char* tmac_status_str(tmac_status s) {
   return "unknown status";
 }
 
-extern "C" int32_t tmac_version(void) { return 1000 * 0 + 5; }
+extern "C" int32_t tmac_version(void) { return 1000 * 0 + 6; }
