@@ -230,11 +230,13 @@ tmac_status tmac_mpgemv_fused(const tmac_wdesc* desc, const void* packed_dev, co
  * from the activations.  The tables are built inside the lookup kernel where a kernel does that
  * (Algorithm 1 Precompute next to the look-ups that use it: no second launch and no table
  * traffic): layout 2 with K % 16 == 0 (this is then tmac_mpgemv_fused), and layout 3 with g = 4,
- * group scales whose group size divides 256, and at most 32 activation rows in a call that is cut
- * into K slices of 256 (the case a separate precompute launch costs most).  Every other call
+ * K % 8 == 0, a group size that divides 256 (or one scale per row or tensor), and at most 32
+ * activation rows in a call that is cut into K slices of 256 (the case a separate precompute
+ * launch costs most).  Every other call
  * runs tmac_precompute_lut into the second region of the workspace and tmac_mpgemm after it.
- *   A_dev          [N,K] fp16 or int8, 16-byte aligned, leading dimension lda a multiple of 8
- *                  (16 for int8 with layout 2)
+ *   A_dev          [N,K] fp16 or int8, 16-byte aligned; leading dimension lda a multiple of 8
+ *                  where the tables are built in the kernel (16 for int8 with layout 2), else as
+ *                  for tmac_precompute_lut
  *   workspace_dev  tmac_fused_workspace_bytes(desc, N, act) bytes, 16-byte aligned, zero-filled
  *                  once before its first use (its first region is tmac_mpgemm's workspace);
  *                  calls that share it must not overlap in time

@@ -434,7 +434,7 @@ extern "C" size_t tmac_workspace_bytes(const tmac_wdesc* desc, int32_t N) {
   if (!desc_valid(desc) || N <= 0) return 0;
   if (desc->layout == TMAC_LAYOUT_R8U16) return 256;  // the register-table kernel uses none
   const RowsPlan pl = rows_plan(desc, N);
-  return pl.part_bytes + pl.ctr_bytes + 256;
+  return pl.part_bytes + pl.ctr_bytes + pl.srow_bytes + 256;
 }
 
 extern "C" tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev,
@@ -520,7 +520,8 @@ extern "C" tmac_status tmac_mpgemm_fused(const tmac_wdesc* desc, const void* pac
   if (!packed_dev || !A_dev || !out_dev || !workspace_dev) return TMAC_EINVAL;
   if (out != TMAC_OUT_F32 && out != TMAC_OUT_F16 && out != TMAC_OUT_I32) return TMAC_EINVAL;
   if (!aligned16(packed_dev) || !aligned16(A_dev) || !aligned16(workspace_dev)) return TMAC_EINVAL;
-  if (ldo < desc->M || lda < desc->K || lda % 8 != 0) return TMAC_EINVAL;
+  if (ldo < desc->M || lda < desc->K) return TMAC_EINVAL;
+  if (lutb == 0 && lda % 8 != 0) return TMAC_EINVAL;  // the kernels read eight activations per load
   if (!group_supported(desc)) return TMAC_EUNSUPPORTED;
   if (workspace_bytes < ws + lutb) return TMAC_ESIZE;
   const tmac_lut_t lt = (act == TMAC_ACT_I8) ? TMAC_LUT_I16 : TMAC_LUT_F16;

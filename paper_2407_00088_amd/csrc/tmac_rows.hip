@@ -86,6 +86,8 @@ struct RowsParams {
   int Mp;                  // M rounded up to 64
   float* ws_part;          // split K: [slices][N][Mp] partial sums (fp32, or int32 bit patterns)
   int* ws_ctr;             // split K: arrival counters, one per (row block, n tile), zero between calls
+  float* ws_srow;          // fused table build, one scale per row or tensor: [slices][N] sums of the
+                           // activations of a K slice (fp32, or int32 bit patterns)
   int grouped;             // 1: group scales, 0: one scale per row or per tensor
   int per_tensor, int_exact, icoef;
   float wscale, zero_point, mid;
@@ -301,18 +303,29 @@ __device__ __forceinline__ void rows_chunk(const uint32_t (&x)[BITS], uint32_t c
   }
 }
 
+// Sum of activation row n from the LUT buffer (one scale per row or per tensor: nq = 1).
+template <bool IS_INT>
+__device__ __forceinline__ void rows_row_sum(const RowsParams& p, int n, float& Sf, int& Si) {
+  Sf = 0.f;
+  Si = 0;
+  if (p.grouped) return;
+  if constexpr (IS_INT) Si = static_cast<const int*>(p.S)[n];
+  else Sf = static_cast<const float*>(p.S)[n];
+}
+
 // Last step for output (n, m): vf = finished group sums (group scales) or the raw look-up sum (fp
 // tables), vi = the raw integer look-up sum; s, z = scale and zero of row m when there is one
-// scale per row or per tensor.
+// scale per row or per tensor; Sf / Si = the sum of activation row n in that case.
 template <bool IS_INT>
-__device__ __forceinline__ void rows_finish(const RowsParams& p, int n, int m, float vf, int vi, float s, float z) {
+__device__ __forceinline__ void rows_finish(const RowsParams& p, int n, int m, float vf, int vi, float s, float z,
+                                            float Sf, int Si) {
   const float as = p.act_scale ? p.act_scale[n] : 1.0f;
   float res;
   int ires = 0;
   if (p.grouped) {
     res = vf * as;
   } else if constexpr (IS_INT) {
-    const int St = static_cast<const int*>(p.S)[n];
+    const int St = Si;
     if (p.int_exact) {
       ires = (vi + p.icoef * St) >> 1;  // numerator is always even
       res = ((float)ires * as) * s;     // two roundings, left to right
@@ -320,7 +333,7 @@ __device__ __forceinline__ void rows_finish(const RowsParams& p, int n, int m, f
       res = (fmaf(p.mid - z, (float)St, 0.5f * (float)vi) * as) * s;
     }
   } else {
-    const float St = static_cast<const float*>(p.S)[n];
+    const float St = Sf;
     res = (s * fmaf(p.mid - z, St, 0.5f * vf)) * as;
   }
   const size_t o = (size_t)n * p.ldo + m;
@@ -431,7 +444,12 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
     s = __half2float(__ushort_as_half((uint16_t)(v & 0xffffu)));
     z = __half2float(__ushort_as_half((uint16_t)(v >> 16)));
   }
-  auto finish = [&](int n, float vf, int vi) { rows_finish<IS_INT>(p, n, m, vf, vi, s, z); };
+  auto finish = [&](int n, float vf, int vi) {
+    float Sf;
+    int Si;
+    rows_row_sum<IS_INT>(p, n, Sf, Si);
+    rows_finish<IS_INT>(p, n, m, vf, vi, s, z, Sf, Si);
+  };
   constexpr bool RAW_INT = IS_INT;  // ungrouped integer tables: partial sums are exact integers
   const int nz = gridDim.z;
   if (nz == 1) {
@@ -629,7 +647,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows8_kernel(const Row
   // 2. tables of the eight chunks, and the group sums, into LDS
   const int kg_end = min((cz0 + nc) * Sh::TPC, p.KG);
   if constexpr (FUSED) {
-    // (group scales only) sums of the quantisation groups of the slice, from the activations: thread
+    // sums of the quantisation groups of the slice, from the activations: thread
     // i takes eight activations of row i / 32, the 4 cpg threads of a group add up by butterfly
     // (they sit in one half of a wavefront), and one thread per chunk publishes the group's sum
     const int t = threadIdx.x >> 5, seg = threadIdx.x & 31;
@@ -649,8 +667,14 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows8_kernel(const Row
         ssum = ((f[0] + f[1]) + (f[2] + f[3])) + ((f[4] + f[5]) + (f[6] + f[7]));
       }
     }
-    for (int o = 1; o < (4 << p.cpg_log2); o <<= 1) ssum += __shfl_xor(ssum, o);
-    if (t < NT && (seg & 3) == 0) sS[seg >> 2][t] = ssum;
+    // (one scale per row or per tensor: the whole slice's sum per row, for rows_sum_kernel)
+    const int span = p.grouped ? (4 << p.cpg_log2) : 32;
+    for (int o = 1; o < span; o <<= 1) ssum += __shfl_xor(ssum, o);
+    if (p.grouped) {
+      if (t < NT && (seg & 3) == 0) sS[seg >> 2][t] = ssum;
+    } else if (un.rb == 0 && t < NT && n < p.N && seg == 0) {
+      p.ws_srow[(size_t)un.kz * p.N + n] = IS_INT ? __int_as_float((int)ssum) : ssum;
+    }
     for (int it = threadIdx.x; it < R8_CH * Sh::CB / (8 * Sh::ES); it += 64 * ROWS_WAVES)
       rows_stage_item<NT, G, true, IS_INT>(p, tab, it, n0, cz0 * Sh::TPC, kg_end);
   } else {
@@ -701,7 +725,10 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows8_kernel(const Row
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       if (n0 + t >= p.N) break;
-      rows_finish<IS_INT>(p, n0 + t, m, p.grouped ? acc[t] : (float)L[t], IS_INT ? (int)L[t] : 0, s, z);
+      float Sf;
+      int Si;
+      rows_row_sum<IS_INT>(p, n0 + t, Sf, Si);
+      rows_finish<IS_INT>(p, n0 + t, m, p.grouped ? acc[t] : (float)L[t], IS_INT ? (int)L[t] : 0, s, z, Sf, Si);
     }
     return;
   }
@@ -746,7 +773,20 @@ __global__ __launch_bounds__(64) void rows_sum_kernel(const RowsParams p, int nz
     s = __half2float(__ushort_as_half((uint16_t)(v & 0xffffu)));
     z = __half2float(__ushort_as_half((uint16_t)(v >> 16)));
   }
-  rows_finish<IS_INT>(p, n, m, sf, si, s, z);
+  float Sf = 0.f;
+  int Si = 0;
+  if (!p.grouped) {
+    if (p.ws_srow) {  // fused table build: the row sum is the sum of the slices' sums, in slice order
+      for (int sl = 0; sl < nz; ++sl) {
+        const float v = p.ws_srow[(size_t)sl * p.N + n];
+        if constexpr (IS_INT) Si += __float_as_int(v);
+        else Sf += v;
+      }
+    } else {
+      rows_row_sum<IS_INT>(p, n, Sf, Si);
+    }
+  }
+  rows_finish<IS_INT>(p, n, m, sf, si, s, z, Sf, Si);
 }
 
 template <bool IS_INT, int BITS, int NT, bool FUSED>
@@ -813,16 +853,16 @@ RowsPlan rows_plan(const tmac_wdesc* desc, int N) {
   pl.slices = (ge.n_chunks + cps - 1) / cps;
   pl.part_bytes = pl.slices > 1 ? ((size_t)pl.slices * N * ge.Mp * 4 + 255) / 256 * 256 : 0;
   pl.ctr_bytes = pl.slices > 1 ? ((size_t)pairs * 4 + 255) / 256 * 256 : 0;
+  pl.srow_bytes = pl.eight ? ((size_t)pl.slices * N * 4 + 255) / 256 * 256 : 0;
   return pl;
 }
 
 // Whether a call builds its tables inside the lookup kernel when it is given activations instead
-// of a LUT buffer: the eight-chunk kernel with group scales, up to 32 activation rows (every
+// of a LUT buffer: the eight-chunk kernel, up to 32 activation rows (every
 // block of 256 weight rows builds the tables again: from 64 rows on that costs more than the
 // launch of the precompute kernel it saves).
 bool rows_builds_tables(const tmac_wdesc* desc, int N) {
-  const bool one_group = (desc->group == 0 || desc->group == desc->K);
-  return !one_group && N <= 32 && rows_plan(desc, N).eight;
+  return N <= 32 && desc->K % 8 == 0 && rows_plan(desc, N).eight;  // (activations are summed eight at a time)
 }
 
 // lut_dev: buffer of tmac_precompute_lut, or NULL with A_dev / lda given (only where
@@ -842,7 +882,7 @@ int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void*
   if (pl.n_tiles_n > 0x7fffffff || pl.row_blocks > 65535 || pl.slices > 65535) return TMAC_EUNSUPPORTED;
   if (pl.slices > 1) {
     if (!workspace_dev) return TMAC_EINVAL;
-    if (workspace_bytes < pl.part_bytes + pl.ctr_bytes) return TMAC_ESIZE;
+    if (workspace_bytes < pl.part_bytes + pl.ctr_bytes + pl.srow_bytes) return TMAC_ESIZE;
   }
   // int32 accumulators: |L| <= 128 * (2^b - 1) * K must stay below 2^31
   if (is_int && (double)128.0 * ((1 << desc->bits) - 1) * desc->K >= 2147483647.0) return TMAC_EUNSUPPORTED;
@@ -868,6 +908,8 @@ int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void*
   p.Mp = ge.Mp;
   p.ws_part = static_cast<float*>(workspace_dev);
   p.ws_ctr = workspace_dev ? reinterpret_cast<int*>(static_cast<char*>(workspace_dev) + pl.part_bytes) : nullptr;
+  p.ws_srow = (fused && one_group) ? reinterpret_cast<float*>(static_cast<char*>(workspace_dev) + pl.part_bytes + pl.ctr_bytes)
+                                   : nullptr;
   p.per_tensor = (desc->group == 0);
   p.wscale = weight_scale;
   p.mid = 0.5f * (float)((1 << desc->bits) - 1);

@@ -693,7 +693,9 @@ def test_tiny_k_all_lut_group_sizes(T, torch, g, K):
     (L3, 4, 40, 130, 1280, 3, 256),    # more than 32 rows: precompute launch inside the call
     (L3, 4, 3, 70, 1024, 1, 64),       # four activation rows per workgroup
     (L3, 4, 16, 200, 2304, 4, 96),     # group size does not divide 256: precompute launch inside the call
-    (L3, 4, 16, 200, 2048, 4, -1),     # one scale per row: the same
+    (L3, 4, 16, 200, 2048, 4, -1),     # one scale per row: tables and row sums built in the kernel
+    (L3, 4, 5, 70, 3208, 2, -1),       # K ends inside a chunk
+    (L3, 4, 5, 70, 3204, 2, -1),       # K % 8 != 0: precompute launch inside the call
     (L3, 4, 256, 512, 1024, 4, 128),   # many rows, no short slices: the same
     (L3, 8, 16, 128, 2048, 4, 128),    # other LUT group size: the same
     (L2, 4, 1, 100, 4096, 4, 128),     # register-table kernel, tables built in the kernel

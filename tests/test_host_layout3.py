@@ -94,9 +94,10 @@ def test_fused_workspace_regions():
     big = desc3(13824, 5120, 4, 128)
     assert B.tmac_fused_workspace_bytes(big, 256, F16) == \
         T.tmac_workspace_bytes(big, 256) + T.tmac_lut_bytes(256, 5120, 128, B.TMAC_LUT_F16)
-    row = desc3(4096, 4096, 4, 4096)                                              # one scale per row
-    assert B.tmac_fused_workspace_bytes(row, 16, F16) == \
-        T.tmac_workspace_bytes(row, 16) + T.tmac_lut_bytes(16, 4096, 4096, B.TMAC_LUT_F16)
+    row = desc3(4096, 4096, 4, 4096)                                              # one scale per row: in the kernel too
+    assert B.tmac_fused_workspace_bytes(row, 16, F16) == T.tmac_workspace_bytes(row, 16)
+    assert B.tmac_fused_workspace_bytes(row, 64, F16) == \
+        T.tmac_workspace_bytes(row, 64) + T.tmac_lut_bytes(64, 4096, 4096, B.TMAC_LUT_F16)   # more than 32 rows
     g96 = desc3(4096, 4608, 4, 96)                                                # 3 chunks per group
     assert B.tmac_fused_workspace_bytes(g96, 16, F16) > T.tmac_workspace_bytes(g96, 16) + 4608 * 16 * 8
     d2 = T.wdesc(4096, 4096, 4, 128, layout=B.TMAC_LAYOUT_R8U16)
