@@ -601,6 +601,9 @@ def test_random_shapes_all_paths(T, torch, seed):
         err = orc.rel_frobenius(out.cpu().numpy(), ref)
         assert err <= FP_TOL, (seed, layout, g, fused, M, K, N, bits, p.group, err)
         ran.append(err)
+        if not fused:   # the one-call entry point on the same matrix
+            err1 = orc.rel_frobenius(lin.forward_one_call(A).cpu().numpy(), ref)
+            assert err1 <= FP_TOL, (seed, layout, g, "one call", M, K, N, bits, p.group, err1)
     assert ran
     print(f"rand{seed}: M={M} K={K} N={N} b={bits} G={p.group} paths={len(ran)} max_err={max(ran):.2e}", flush=True)
 
@@ -630,6 +633,9 @@ def test_random_shapes_int_path_exact(T, torch, seed):
         got_f = run(A, out_t=T.TMAC_OUT_F32, act_scale=s_a).cpu().numpy()
         assert np.array_equal(got_i.astype(np.int64), ref_i), (seed, layout, g, fused, M, K, N)
         assert np.array_equal(got_f.view(np.uint32), ref_f.view(np.uint32)), (seed, layout, g, fused, M, K, N)
+        if not fused:   # the one-call entry point on the same matrix
+            one_i = lin.forward_one_call(A, out_t=T.TMAC_OUT_I32, act_scale=s_a).cpu().numpy()
+            assert np.array_equal(one_i.astype(np.int64), ref_i), (seed, layout, g, "one call", M, K, N)
 
 
 @pytest.mark.parametrize("N,bits", [(16, 4), (48, 2), (3, 3)])
