@@ -767,3 +767,47 @@ def test_one_call_entry_point_rejects(T, torch):
         B.tmac_mpgemm_fused(lin.desc, lin.packed, A, 16, out, B.TMAC_OUT_F32, ws[: need - 256])
     with pytest.raises(Exception):
         B.tmac_mpgemm_fused(lin.desc, lin.packed, A, 16, out, B.TMAC_OUT_F32, ws, lda=1028)
+
+
+# ------------------------------------------------- the precompute step alone ----
+
+@pytest.mark.parametrize("g", [2, 4, 8])
+@pytest.mark.parametrize("int_act", [False, True], ids=["f16", "i8"])
+def test_precompute_tables_against_the_oracle(T, torch, g, int_act):
+    """Step a2 on its own: the tables [N][Kp/g][2^g] and the group sums S[N][K/G] that
+    tmac_precompute_lut leaves at the start of the LUT buffer, entry by entry against the oracle's
+    tables (Algorithm 1 Precompute).  Integer tables are exact; fp16 entries are the fp32 sum rounded
+    once, which can differ from the rounded fp64 sum by one ulp in rare cases."""
+    from paper_2407_00088_amd import binding as B
+    rng = np.random.default_rng(990 + g)
+    N, K, G = 5, 1160 if g != 8 else 1168, 0
+    lut_t = B.TMAC_LUT_I16 if int_act else B.TMAC_LUT_F16
+    if int_act:
+        a = rng.integers(-127, 128, size=(N, K)).astype(np.int8)
+    else:
+        a = wl.gaussian_act(rng, N, K)
+    buf = torch.zeros(B.tmac_lut_bytes(N, K, G, lut_t, g=g), dtype=torch.uint8, device="cuda")
+    B.tmac_precompute_lut(torch.from_numpy(a).cuda(), N, K, G, lut_t, buf, g=g)
+    torch.cuda.synchronize()
+    raw = buf.cpu().numpy()
+    Kp = (K + 127) // 128 * 128
+    KG, ENT = Kp // g, 1 << g
+    ref = orc.precompute_lut(a, g)                                   # [N, K/g, 2^g]
+    if int_act:
+        tab = raw[: N * KG * ENT * 2].view(np.int16).reshape(N, KG, ENT)
+        assert np.array_equal(tab[:, : K // g].astype(np.int64), ref)
+    else:
+        tab = raw[: N * KG * ENT * 2].view(np.float16).reshape(N, KG, ENT)
+        want = ref.astype(np.float16)
+        got = tab[:, : K // g]
+        diff = np.abs(got.view(np.int16).astype(np.int32) - want.view(np.int16).astype(np.int32))
+        assert diff.max() <= 1 and (diff != 0).mean() < 1e-3
+        assert np.allclose(got.astype(np.float64), ref, rtol=2.0 ** -10, atol=1e-7)
+    assert not tab[:, K // g:].any()                                  # tables of the k padding are zero
+    s_off = (N * KG * ENT * 2 + 255) // 256 * 256
+    if int_act:
+        S = raw[s_off: s_off + N * 4].view(np.int32)
+        assert np.array_equal(S.astype(np.int64), a.astype(np.int64).sum(axis=1))
+    else:
+        S = raw[s_off: s_off + N * 4].view(np.float32)
+        assert np.allclose(S, a.astype(np.float64).sum(axis=1), rtol=1e-5, atol=1e-4)
