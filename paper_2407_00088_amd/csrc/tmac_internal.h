@@ -40,11 +40,22 @@ struct LutGeom {
   size_t usc_off;       // int8 tables only: byte offset of the unit scales [N][U] (fp32)
   size_t ht_off;        // byte offset of the half tables, piece-major per block
   size_t total;
+  int NT;  // activation rows per n tile of the table region
 };
 
-// lut_t: a tmac_lut_t value.  The 2^g-entry tables [N][KG][2^g] at offset 0 (read by the batched
-// kernel) exist for the 16-bit table types only; the per-16 and per-128 sums and the half tables
-// of the register-table kernel exist for g = 4 only.
+// Activation rows the batched kernels serve per workgroup ("n tile") for a call with N rows: eight
+// once that wastes at most a fifth of the lookups on padding rows; 256-entry tables (g = 8) take
+// four always (eight rows of them would leave an LDS slice two chunks long).  The precompute
+// kernel lays the tables out per n tile, so both sides derive the tile from N and g alone.
+inline int rows_nt(int N, int g) {
+  if (g == 8) return 4;
+  return (N >= 40 || N % 8 == 0 || N % 8 >= 5) && N > 4 ? 8 : 4;
+}
+
+// lut_t: a tmac_lut_t value.  The 2^g-entry tables at offset 0 (read by the batched kernels; laid
+// out [n tile][KG][2^g][NT], i.e. as the kernels keep them in LDS) exist for the 16-bit table
+// types only; the per-16 and per-128 sums and the half tables of the register-table kernel exist
+// for g = 4 only.
 inline bool lut_geom(int N, int K, int g, int group, int lut_t, LutGeom* lg) {
   if (N <= 0 || K <= 0 || (g != 2 && g != 4 && g != 8) || K % 4 != 0 || K % g != 0 || group < 0) return false;
   if (group > 0 && (K % group != 0 || group % 4 != 0 || group % g != 0)) return false;
@@ -56,7 +67,9 @@ inline bool lut_geom(int N, int K, int g, int group, int lut_t, LutGeom* lg) {
   lg->Geff = (group == 0) ? K : group;
   lg->nq = K / lg->Geff;
   lg->ht_slots = q8 ? 2 : 4;
-  const size_t tab = q8 ? 0 : (size_t)N * lg->KG * (2u << g);
+  lg->NT = rows_nt(N, g);
+  const size_t n_pad = (size_t)(N + lg->NT - 1) / lg->NT * lg->NT;  // whole n tiles
+  const size_t tab = q8 ? 0 : n_pad * lg->KG * (2u << g);
   lg->s_off = (tab + 255) / 256 * 256;
   lg->s16_off = (lg->s_off + (size_t)N * lg->nq * 4 + 255) / 256 * 256;
   if (g != 4) {

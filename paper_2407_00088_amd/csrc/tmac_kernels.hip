@@ -71,6 +71,94 @@ __device__ __forceinline__ void group_sums_wave(const void* __restrict__ A_, int
   }
 }
 
+// The tables as the batched kernels keep them in LDS: [n tile][KG][2^G][NT] 16-bit entries, NT
+// activation rows side by side per entry, so that staging a K slice is a plain copy.  Thread `id`
+// builds the two consecutive entries 2 id, 2 id + 1 (counted over [n tile][KG][2^G]) for the NT
+// rows of its tile: T[p] = sum_j (bit j of p ? +a_j : -a_j), added pairwise in fp32 and rounded
+// once to fp16 (exact int16 for int8 activations); rows past N and tables past K are zero.
+template <bool IS_INT, int G, int NT>
+__device__ __forceinline__ void staged_tables(const void* __restrict__ A_, int N, int K, int64_t lda, int KG,
+                                              uint4* __restrict__ tables, int64_t id) {
+  constexpr int ENT = 1 << G;
+  const int64_t per_tile = (int64_t)KG * ENT / 2;
+  const int tile = (int)(id / per_tile);
+  const int64_t f = (id % per_tile) * 2;            // first of the two entries in [KG][ENT]
+  const int kg = (int)(f >> G), e0 = (int)(f & (ENT - 1));
+  const int k0 = kg * G;
+  uint32_t w[2][NT / 2];                            // [entry][pair of rows]
+#pragma unroll
+  for (int r = 0; r < NT; ++r) {
+    const int n = tile * NT + r;
+    uint16_t e[2] = {0, 0};
+    if (n < N && k0 < K) {                          // K is a multiple of 4 and of G: all or nothing
+      if constexpr (IS_INT) {
+        // (row bases and lda are multiples of 4 bytes: G elements come with 2- or 4-byte loads)
+        const int8_t* ap = static_cast<const int8_t*>(A_) + n * lda + k0;
+        int a[G];
+        if constexpr (G == 2) {
+          const uint16_t v = *reinterpret_cast<const uint16_t*>(ap);
+          a[0] = (int8_t)(v & 0xff); a[1] = (int8_t)(v >> 8);
+        } else {
+#pragma unroll
+          for (int q = 0; q < G / 4; ++q) {
+            const uint32_t v = reinterpret_cast<const uint32_t*>(ap)[q];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a[4 * q + j] = (int8_t)((v >> (8 * j)) & 0xff);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          int v = 0;
+#pragma unroll
+          for (int j = 0; j < G; ++j) v += (((e0 + u) >> j) & 1) ? a[j] : -a[j];
+          e[u] = (uint16_t)(int16_t)v;
+        }
+      } else {
+        // (row bases and lda are multiples of 8 bytes: G elements come with 4- or 8-byte loads)
+        const __half* ap = static_cast<const __half*>(A_) + n * lda + k0;
+        float x[G];
+        if constexpr (G == 2) {
+          const uint32_t v = *reinterpret_cast<const uint32_t*>(ap);
+          x[0] = __half2float(__ushort_as_half((uint16_t)(v & 0xffffu)));
+          x[1] = __half2float(__ushort_as_half((uint16_t)(v >> 16)));
+        } else {
+#pragma unroll
+          for (int q = 0; q < G / 4; ++q) {
+            const uint2 v = reinterpret_cast<const uint2*>(ap)[q];
+            x[4 * q + 0] = __half2float(__ushort_as_half((uint16_t)(v.x & 0xffffu)));
+            x[4 * q + 1] = __half2float(__ushort_as_half((uint16_t)(v.x >> 16)));
+            x[4 * q + 2] = __half2float(__ushort_as_half((uint16_t)(v.y & 0xffffu)));
+            x[4 * q + 3] = __half2float(__ushort_as_half((uint16_t)(v.y >> 16)));
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          float y[G];
+#pragma unroll
+          for (int j = 0; j < G; ++j) y[j] = (((e0 + u) >> j) & 1) ? x[j] : -x[j];
+#pragma unroll
+          for (int st = 1; st < G; st *= 2) {       // pairwise: ((y0+y1)+(y2+y3))+...
+#pragma unroll
+            for (int j = 0; j + st < G; j += 2 * st) y[j] += y[j + st];
+          }
+          e[u] = __half_as_ushort(__float2half_rn(y[0]));
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      if (r & 1) w[u][r >> 1] |= (uint32_t)e[u] << 16;
+      else w[u][r >> 1] = e[u];
+    }
+  }
+  if constexpr (NT == 8) {
+    tables[id * 2] = make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]);
+    tables[id * 2 + 1] = make_uint4(w[1][0], w[1][1], w[1][2], w[1][3]);
+  } else {
+    tables[id] = make_uint4(w[0][0], w[0][1], w[1][0], w[1][1]);
+  }
+}
+
 template <bool IS_INT>
 __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict__ A_, int N, int K,
                                                          int64_t lda, int KG,
@@ -78,7 +166,16 @@ __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict_
                                                          void* __restrict__ S_, void* __restrict__ S16_,
                                                          void* __restrict__ S128_,
                                                          uint4* __restrict__ HT, int U, int Geff, int nq,
-                                                         int n_tab_blocks) {
+                                                         int n_tab_blocks, int n_stage_blocks, int NT) {
+  if ((int)blockIdx.x >= n_tab_blocks && (int)blockIdx.x < n_tab_blocks + n_stage_blocks) {
+    // the tables of the batched kernels, one thread per two entries of an n tile
+    const int64_t id = (int64_t)((int)blockIdx.x - n_tab_blocks) * 256 + threadIdx.x;
+    const int64_t n_ids = (int64_t)((N + NT - 1) / NT) * KG * 8;
+    if (id >= n_ids) return;
+    if (NT == 8) staged_tables<IS_INT, 4, 8>(A_, N, K, lda, KG, tables, id);
+    else staged_tables<IS_INT, 4, 4>(A_, N, K, lda, KG, tables, id);
+    return;
+  }
   if ((int)blockIdx.x < n_tab_blocks) {
     const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (tid >= (int64_t)N * KG) return;
@@ -119,9 +216,6 @@ __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict_
 #pragma unroll
       for (int i = 0; i < 8; ++i) packed[i] = (uint32_t)e[2 * i] | ((uint32_t)e[2 * i + 1] << 16);
     }
-    uint4* dst = tables + tid * 2;
-    dst[0] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
-    dst[1] = make_uint4(packed[4], packed[5], packed[6], packed[7]);
     // Mirror-consolidated copy for the register-table kernel: entries 0..7 as fp16 (int16 entries
     // are at most 508 in magnitude, exact in fp16).  Units are grouped in nB blocks; inside a block
     // of nu units, table tb of the unit in slot s sits at 16-byte slot tb*nu + s, so that the
@@ -173,16 +267,14 @@ __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict_
       if ((kg & 31) == 0) static_cast<float*>(S128_)[tid >> 5] = sum4f;
     }
   } else {
-    group_sums_wave<IS_INT>(A_, N, lda, S_, Geff, nq, ((int)blockIdx.x - n_tab_blocks) * 4 + (threadIdx.x >> 6));
+    group_sums_wave<IS_INT>(A_, N, lda, S_, Geff, nq,
+                            ((int)blockIdx.x - n_tab_blocks - n_stage_blocks) * 4 + (threadIdx.x >> 6));
   }
 }
 
-// Tables for LUT group sizes other than 4 (Section 4 discusses the choice of g): [N][KG][2^G]
-// 16-bit entries, T[p] = sum_j (bit j of p ? +a_j : -a_j) over the G activations of the group,
-// added pairwise in fp32 and rounded once to fp16 (exact int16 for int8 activations).  One thread
-// writes eight consecutive entries (16 bytes): two whole tables at G = 2, an eighth of one at
-// G = 8 (its eight entries differ in the signs of a_0..a_2 only).
-template <bool IS_INT, int G>
+// Tables for LUT group sizes other than 4 (Section 4 discusses the choice of g), in the layout
+// of the batched kernels, and the group sums.
+template <bool IS_INT, int G, int NT>
 __global__ __launch_bounds__(256) void precompute_g_kernel(const void* __restrict__ A_, int N, int K, int64_t lda,
                                                            int KG, uint4* __restrict__ tables,
                                                            void* __restrict__ S_, int Geff, int nq,
@@ -192,65 +284,9 @@ __global__ __launch_bounds__(256) void precompute_g_kernel(const void* __restric
     group_sums_wave<IS_INT>(A_, N, lda, S_, Geff, nq, ((int)blockIdx.x - n_tab_blocks) * 4 + (threadIdx.x >> 6));
     return;
   }
-  constexpr int ENT = 1 << G;
-  const int64_t per_row = (int64_t)KG * ENT / 8;  // 16-byte items per activation row
-  const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (tid >= (int64_t)N * per_row) return;
-  const int n = (int)(tid / per_row);
-  const int64_t flat = (tid % per_row) * 8;       // first entry of the item in [KG][ENT]
-  const int kg0 = (int)(flat >> G);
-  const int k0 = kg0 * G;                         // first activation the item depends on
-  constexpr int NA = G == 2 ? 4 : 8;              // activations the item depends on
-  float af[NA];
-  int ai[NA];
-#pragma unroll
-  for (int j = 0; j < NA; ++j) { af[j] = 0.f; ai[j] = 0; }
-  const bool live = k0 < K;                       // K is a multiple of 4 and of G: all or nothing
-  if (live) {
-    if constexpr (IS_INT) {
-      const int8_t* a = static_cast<const int8_t*>(A_) + n * lda + k0;
-#pragma unroll
-      for (int j = 0; j < NA; ++j) ai[j] = a[j];
-    } else {
-      const __half* a = static_cast<const __half*>(A_) + n * lda + k0;
-#pragma unroll
-      for (int j = 0; j < NA; ++j) af[j] = __half2float(a[j]);
-    }
-  }
-  uint16_t e[8];
-#pragma unroll
-  for (int u = 0; u < 8; ++u) {
-    if constexpr (G == 2) {
-      const int t = u >> 2, pp = u & 3;           // table kg0 + t, entry pp
-      if constexpr (IS_INT) {
-        e[u] = (uint16_t)(int16_t)(((pp & 1) ? ai[2 * t] : -ai[2 * t]) + ((pp & 2) ? ai[2 * t + 1] : -ai[2 * t + 1]));
-      } else {
-        const float v = ((pp & 1) ? af[2 * t] : -af[2 * t]) + ((pp & 2) ? af[2 * t + 1] : -af[2 * t + 1]);
-        e[u] = __half_as_ushort(__float2half_rn(v));
-      }
-    } else {
-      const int pp = (int)(flat & (ENT - 1)) + u;
-      if constexpr (IS_INT) {
-        int v = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v += ((pp >> j) & 1) ? ai[j] : -ai[j];
-        e[u] = (uint16_t)(int16_t)v;
-      } else {
-        float x[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) x[j] = ((pp >> j) & 1) ? af[j] : -af[j];
-        const float v = ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
-        e[u] = __half_as_ushort(__float2half_rn(v));
-      }
-    }
-  }
-  uint4 o;
-  o.x = (uint32_t)e[0] | ((uint32_t)e[1] << 16);
-  o.y = (uint32_t)e[2] | ((uint32_t)e[3] << 16);
-  o.z = (uint32_t)e[4] | ((uint32_t)e[5] << 16);
-  o.w = (uint32_t)e[6] | ((uint32_t)e[7] << 16);
-  if (!live) o = make_uint4(0, 0, 0, 0);          // k padding: all-zero tables
-  tables[tid] = o;
+  const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (id >= (int64_t)((N + NT - 1) / NT) * KG * ((1 << G) / 2)) return;
+  staged_tables<IS_INT, G, NT>(A_, N, K, lda, KG, tables, id);
 }
 
 // Table quantisation (Section 3.3): one thread per unit of 16 activations builds the mirror halves
@@ -380,25 +416,30 @@ extern "C" tmac_status tmac_precompute_lut(const void* A_dev, tmac_act_t act, in
   if (lut_bytes < lg.total) return TMAC_ESIZE;
 
   const int n_sum_blocks = (N * lg.nq + 3) / 4;
+  const int64_t n_stage_ids = (int64_t)((N + lg.NT - 1) / lg.NT) * lg.KG * ((1 << g) / 2);
+  const int n_stage_blocks = (int)((n_stage_ids + 255) / 256);
   if (g != 4) {
-    const int64_t n_items = (int64_t)N * lg.KG * (1 << g) / 8;
-    const int n_tab_blocks = (int)((n_items + 255) / 256);
     uint4* tables = static_cast<uint4*>(lut_dev);
     void* S = static_cast<char*>(lut_dev) + lg.s_off;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const dim3 grid(n_tab_blocks + n_sum_blocks), block(256);
+    const dim3 grid(n_stage_blocks + n_sum_blocks), block(256);
     const bool is_int = (act == TMAC_ACT_I8);
     hipError_t e;
-    if (g == 2) {
-      e = is_int ? launch(precompute_g_kernel<true, 2>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S, lg.Geff,
-                          lg.nq, n_tab_blocks)
-                 : launch(precompute_g_kernel<false, 2>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S,
-                          lg.Geff, lg.nq, n_tab_blocks);
+    if (g == 2 && lg.NT == 8) {
+      e = is_int ? launch(precompute_g_kernel<true, 2, 8>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S,
+                          lg.Geff, lg.nq, n_stage_blocks)
+                 : launch(precompute_g_kernel<false, 2, 8>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S,
+                          lg.Geff, lg.nq, n_stage_blocks);
+    } else if (g == 2) {
+      e = is_int ? launch(precompute_g_kernel<true, 2, 4>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S,
+                          lg.Geff, lg.nq, n_stage_blocks)
+                 : launch(precompute_g_kernel<false, 2, 4>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S,
+                          lg.Geff, lg.nq, n_stage_blocks);
     } else {
-      e = is_int ? launch(precompute_g_kernel<true, 8>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S, lg.Geff,
-                          lg.nq, n_tab_blocks)
-                 : launch(precompute_g_kernel<false, 8>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S,
-                          lg.Geff, lg.nq, n_tab_blocks);
+      e = is_int ? launch(precompute_g_kernel<true, 8, 4>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S,
+                          lg.Geff, lg.nq, n_stage_blocks)
+                 : launch(precompute_g_kernel<false, 8, 4>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S,
+                          lg.Geff, lg.nq, n_stage_blocks);
     }
     return e == hipSuccess ? TMAC_OK : TMAC_EHIP;
   }
@@ -420,13 +461,13 @@ extern "C" tmac_status tmac_precompute_lut(const void* A_dev, tmac_act_t act, in
   void* S128 = static_cast<char*>(lut_dev) + lg.s128_off;
   uint4* HT = reinterpret_cast<uint4*>(static_cast<char*>(lut_dev) + lg.ht_off);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const dim3 grid(n_tab_blocks + n_sum_blocks), block(256);
+  const dim3 grid(n_tab_blocks + n_stage_blocks + n_sum_blocks), block(256);
   const hipError_t e =
       (act == TMAC_ACT_F16)
           ? launch(precompute_kernel<false>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S, S16, S128, HT,
-                   lg.U, lg.Geff, lg.nq, n_tab_blocks)
+                   lg.U, lg.Geff, lg.nq, n_tab_blocks, n_stage_blocks, lg.NT)
           : launch(precompute_kernel<true>, grid, block, 0, st, A_dev, N, K, lda, lg.KG, tables, S, S16, S128, HT,
-                   lg.U, lg.Geff, lg.nq, n_tab_blocks);
+                   lg.U, lg.Geff, lg.nq, n_tab_blocks, n_stage_blocks, lg.NT);
   return e == hipSuccess ? TMAC_OK : TMAC_EHIP;
 }
 

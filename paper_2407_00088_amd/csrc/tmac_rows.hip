@@ -62,19 +62,10 @@ constexpr int ROWS_NT_NARROW = 4;   // ... and otherwise
 typedef _Float16 rh2v __attribute__((ext_vector_type(2)));
 typedef short rs2v __attribute__((ext_vector_type(2)));
 
-// Activation rows per workgroup for a call with N rows: eight once that wastes at most a fifth of
-// the lookups on padding rows.
-// 256-entry tables (g = 8) take the narrow form always: eight rows of them would leave an LDS slice
-// two chunks long.
-static inline int rows_nt(int N, int g) {
-  if (g == 8) return ROWS_NT_NARROW;
-  return (N >= 40 || N % 8 == 0 || N % 8 >= 5) && N > 4 ? ROWS_NT_WIDE : ROWS_NT_NARROW;
-}
-
 struct RowsParams {
   const uint32_t* idx;     // [n_tiles][n_chunks][64][bits] dwords
   const uint32_t* sz;      // [n_tiles][nq][64] {fp16 scale, fp16 zero}
-  const uint16_t* tables;  // [N][KG][16] fp16 or int16
+  const uint16_t* tables;  // [n tile][KG][2^g][NT] fp16 or int16: the LDS layout, n tile by n tile
   const void* S;           // [N][nq] fp32 / int32 group sums
   void* out;
   const float* act_scale;
@@ -177,27 +168,46 @@ __device__ __forceinline__ ru32x4v rows_build_half_table(const void* A, int64_t 
   }
 }
 
-// Stage tables into LDS as [table][entry][n]: item `it` is eight consecutive entries (half a table
-// at g = 4, two tables at g = 2) counted from table kg0; it reads them for the NT activation rows
-// n0.. and writes them entry-major.  Tables from kg_end on are written as zeros.
-// FUSED (g = 4): the entries are built here from the activations instead of read from the LUT buffer.
-template <int NT, int G, bool FUSED = false, bool IS_INT = false>
+// Stage a K slice of tables into LDS: the LUT buffer holds them in the LDS layout, so this is a copy,
+// `per` 16-byte pieces per thread, all loads requested before the first store; consecutive lanes
+// write consecutive 16 bytes (no bank conflicts).  Tables from kg_end on are written as zeros.
+template <int NT, int G, int BYTES>
+__device__ __forceinline__ void rows_stage_copy(const RowsParams& p, char* tab, int ntile, int kg0, int kg_end) {
+  using Sh = RowsShape<NT, G>;
+  constexpr int THREADS = 64 * ROWS_WAVES, PER = BYTES / 16 / THREADS;
+  static_assert(PER >= 1 && BYTES % (16 * THREADS) == 0, "whole pieces per thread");
+  const char* src = reinterpret_cast<const char*>(p.tables) + ((size_t)ntile * p.KG + (size_t)kg0) * Sh::TB;
+  // (pieces of tables from kg_end on read the slice's first piece instead and are zeroed afterwards:
+  // no branches between the loads)
+  const int live_bytes = max(kg_end - kg0, 0) * Sh::TB;
+  ru32x4v v[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int off = (i * THREADS + (int)threadIdx.x) * 16;
+    v[i] = *reinterpret_cast<const ru32x4v*>(src + (off < live_bytes ? off : 0));
+  }
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int off = (i * THREADS + (int)threadIdx.x) * 16;
+    const ru32x4v z = {0u, 0u, 0u, 0u};
+    *reinterpret_cast<ru32x4v*>(tab + off) = off < live_bytes ? v[i] : z;
+  }
+}
+
+// Build and stage tables in one go (tables from the activations, g = 4): item `it` is eight
+// consecutive entries (half a table) counted from table kg0, built for the NT activation rows n0..
+// and written entry-major [table][entry][n].  Tables from kg_end on are written as zeros.
+template <int NT, int G, bool IS_INT>
 __device__ __forceinline__ void rows_stage_item(const RowsParams& p, char* tab, int it, int n0, int kg0, int kg_end) {
   using Sh = RowsShape<NT, G>;
-  static_assert(!FUSED || G == 4, "tables are built in the kernel for g = 4 only");
+  static_assert(G == 4, "tables are built in the kernel for g = 4 only");
   const int flat = it * 8;
   const int kg = kg0 + (flat >> G);
   ru32x4v v[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
-    if constexpr (FUSED) {
-      const bool live = n0 + t < p.N && kg < kg_end && 4 * kg < p.K;
-      v[t] = rows_build_half_table<IS_INT>(p.A, p.lda, min(n0 + t, p.N - 1), kg, it & 1, live);
-    } else {
-      v[t] = ru32x4v{0u, 0u, 0u, 0u};
-      if (n0 + t < p.N && kg < kg_end)
-        v[t] = *reinterpret_cast<const ru32x4v*>(p.tables + ((size_t)(n0 + t) * p.KG + (size_t)kg0) * Sh::ENT + flat);
-    }
+    const bool live = n0 + t < p.N && kg < kg_end && 4 * kg < p.K;
+    v[t] = rows_build_half_table<IS_INT>(p.A, p.lda, min(n0 + t, p.N - 1), kg, it & 1, live);
   }
   ru32x4v* dst = reinterpret_cast<ru32x4v*>(tab + flat * Sh::ES);
 #pragma unroll
@@ -346,7 +356,7 @@ __device__ __forceinline__ void rows_finish(const RowsParams& p, int n, int m, f
 template <bool IS_INT, int BITS, int NT, int G>
 __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const RowsParams p) {
   using Sh = RowsShape<NT, G>;
-  constexpr int ES = Sh::ES, TPC = Sh::TPC, CB = Sh::CB;
+  constexpr int TPC = Sh::TPC, CB = Sh::CB;
   constexpr int CPS = rows_lds_chunks(G, NT);  // 32-k chunks per slice
   static_assert(CPS >= 1 && CB % 256 == 0, "chunk bases must keep a zero low byte");
   __shared__ __attribute__((aligned(2048))) char tab[ROWS_LDS];  // byte-permuted addresses need the alignment
@@ -397,8 +407,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
     // stage the tables of this K-slice for the NT activation rows: item = (table, half) reads the
     // 8 entries of the four rows and writes them entry-major
     __syncthreads();
-    for (int it = threadIdx.x; it < ROWS_LDS / (8 * ES); it += 64 * ROWS_WAVES)
-      rows_stage_item<NT, G>(p, tab, it, n0, c0 * TPC, kg_end);
+    rows_stage_copy<NT, G, ROWS_LDS>(p, tab, blockIdx.x, c0 * TPC, kg_end);
     __syncthreads();
 
     const int c_end = min(c0 + CPS, cz1);
@@ -676,10 +685,9 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows8_kernel(const Row
       p.ws_srow[(size_t)un.kz * p.N + n] = IS_INT ? __int_as_float((int)ssum) : ssum;
     }
     for (int it = threadIdx.x; it < R8_CH * Sh::CB / (8 * Sh::ES); it += 64 * ROWS_WAVES)
-      rows_stage_item<NT, G, true, IS_INT>(p, tab, it, n0, cz0 * Sh::TPC, kg_end);
+      rows_stage_item<NT, G, IS_INT>(p, tab, it, n0, cz0 * Sh::TPC, kg_end);
   } else {
-  for (int it = threadIdx.x; it < R8_CH * Sh::CB / (8 * Sh::ES); it += 64 * ROWS_WAVES)
-    rows_stage_item<NT, G>(p, tab, it, n0, cz0 * Sh::TPC, kg_end);
+  rows_stage_copy<NT, G, R8_CH * Sh::CB>(p, tab, un.nt, cz0 * Sh::TPC, kg_end);
   if (p.grouped && threadIdx.x < R8_CH * NT) {
     const int c = threadIdx.x / NT, t = threadIdx.x % NT;
     const int gq = min((cz0 + c) >> p.cpg_log2, p.nq - 1);

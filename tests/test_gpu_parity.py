@@ -774,7 +774,7 @@ def test_one_call_entry_point_rejects(T, torch):
 @pytest.mark.parametrize("g", [2, 4, 8])
 @pytest.mark.parametrize("int_act", [False, True], ids=["f16", "i8"])
 def test_precompute_tables_against_the_oracle(T, torch, g, int_act):
-    """Step a2 on its own: the tables [N][Kp/g][2^g] and the group sums S[N][K/G] that
+    """Step a2 on its own: the tables [n tile][Kp/g][2^g][NT] and the group sums S[N][K/G] that
     tmac_precompute_lut leaves at the start of the LUT buffer, entry by entry against the oracle's
     tables (Algorithm 1 Precompute).  Integer tables are exact; fp16 entries are the fp32 sum rounded
     once, which can differ from the rounded fp64 sum by one ulp in rare cases."""
@@ -792,19 +792,24 @@ def test_precompute_tables_against_the_oracle(T, torch, g, int_act):
     raw = buf.cpu().numpy()
     Kp = (K + 127) // 128 * 128
     KG, ENT = Kp // g, 1 << g
+    NT = 4 if g == 8 else 8                                          # rows per n tile at N = 5 (tmac.h)
+    n_pad = (N + NT - 1) // NT * NT
     ref = orc.precompute_lut(a, g)                                   # [N, K/g, 2^g]
+    # the buffer holds [n tile][KG][2^g][NT]: back to [n][KG][2^g]
+    dt = np.int16 if int_act else np.float16
+    tab = raw[: n_pad * KG * ENT * 2].view(dt).reshape(n_pad // NT, KG, ENT, NT).transpose(0, 3, 1, 2).reshape(n_pad, KG, ENT)
+    assert not tab[N:].any()                                          # rows that pad the last n tile
+    tab = tab[:N]
     if int_act:
-        tab = raw[: N * KG * ENT * 2].view(np.int16).reshape(N, KG, ENT)
         assert np.array_equal(tab[:, : K // g].astype(np.int64), ref)
     else:
-        tab = raw[: N * KG * ENT * 2].view(np.float16).reshape(N, KG, ENT)
         want = ref.astype(np.float16)
         got = tab[:, : K // g]
         diff = np.abs(got.view(np.int16).astype(np.int32) - want.view(np.int16).astype(np.int32))
         assert diff.max() <= 1 and (diff != 0).mean() < 1e-3
         assert np.allclose(got.astype(np.float64), ref, rtol=2.0 ** -10, atol=1e-7)
     assert not tab[:, K // g:].any()                                  # tables of the k padding are zero
-    s_off = (N * KG * ENT * 2 + 255) // 256 * 256
+    s_off = (n_pad * KG * ENT * 2 + 255) // 256 * 256
     if int_act:
         S = raw[s_off: s_off + N * 4].view(np.int32)
         assert np.array_equal(S.astype(np.int64), a.astype(np.int64).sum(axis=1))

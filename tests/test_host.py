@@ -92,13 +92,17 @@ def test_sizes():
     idx = 4096 * 4096 // 2
     sz = 4096 * 32 * 4
     assert T.tmac_packed_bytes(d) == 256 + idx + sz
-    # tables + group sums (one 256-byte block) + per-16 sums (4 bytes per 16 k, 256-aligned)
-    # + per-128 sums (4 bytes per 128 k, 256-aligned) + fp16 half tables (4 bytes per k)
-    # (+ one 256-byte tail holding an all-zero table)
-    assert T.tmac_lut_bytes(1, 4096, 128, B.TMAC_LUT_F16) == 4096 * 8 + 256 + 1024 + 256 + 4096 * 4 + 256
-    assert T.tmac_lut_bytes(1, 3200, 0, B.TMAC_LUT_I16) == 3200 * 8 + 256 + 1024 + 256 + 3200 * 4 + 256
+    # tables (8 bytes per k, for whole n tiles of 4 or 8 activation rows) + group sums (one 256-byte
+    # block) + per-16 sums (4 bytes per 16 k, 256-aligned) + per-128 sums (4 bytes per 128 k,
+    # 256-aligned) + fp16 half tables (4 bytes per k) (+ one 256-byte tail holding an all-zero table)
+    assert T.tmac_lut_bytes(1, 4096, 128, B.TMAC_LUT_F16) == 4 * 4096 * 8 + 256 + 1024 + 256 + 4096 * 4 + 256
+    assert T.tmac_lut_bytes(1, 3200, 0, B.TMAC_LUT_I16) == 4 * 3200 * 8 + 256 + 1024 + 256 + 3200 * 4 + 256
     # K padded to 128 inside the LUT
-    assert T.tmac_lut_bytes(2, 8640, 0, B.TMAC_LUT_I16) == 2 * 8704 * 8 + 256 + 4352 + 768 + 2 * 8704 * 4 + 256
+    assert T.tmac_lut_bytes(2, 8640, 0, B.TMAC_LUT_I16) == 4 * 8704 * 8 + 256 + 4352 + 768 + 2 * 8704 * 4 + 256
+    # n tiles: four rows up to N = 4, eight from five on where that wastes at most a fifth
+    assert T.tmac_lut_bytes(6, 4096, 128, B.TMAC_LUT_F16) - T.tmac_lut_bytes(5, 4096, 128, B.TMAC_LUT_F16) == \
+        1024 + 4096 * 4                                        # same 8 table rows; one more row of per-16 sums and half tables
+    assert T.tmac_lut_bytes(9, 4096, 128, B.TMAC_LUT_F16) > 12 * 4096 * 8
     assert T.tmac_workspace_bytes(d, 1) > 0
 
 

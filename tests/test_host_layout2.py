@@ -87,8 +87,8 @@ def test_layout2_sizes_and_group_rules():
     d = desc2(4096, 4096, 4, 128)
     assert T.tmac_packed_bytes(d) == 256 + 4096 * 4096 // 2 + 4096 * 32 * 4
     assert T.tmac_workspace_bytes(d, 1) == 256
-    # LUT buffer: tables, group sums, per-16 sums, per-128 sums, half tables, zero slot
-    assert T.tmac_lut_bytes(1, 4096, 128, B.TMAC_LUT_F16) == 4096 * 8 + 256 + 1024 + 256 + 4096 * 4 + 256
+    # LUT buffer: tables (one n tile of four rows), group sums, per-16 sums, per-128 sums, half tables, zero slot
+    assert T.tmac_lut_bytes(1, 4096, 128, B.TMAC_LUT_F16) == 4 * 4096 * 8 + 256 + 1024 + 256 + 4096 * 4 + 256
     import ctypes as C
     fake = C.c_void_p(0x1000)
     g24 = desc2(16, 192, 2, 24)      # valid (24 % 4 == 0) but not a multiple of 16

@@ -75,9 +75,10 @@ def test_index_region_does_not_depend_on_g(g):
 
 
 def test_lut_bytes_for_other_group_sizes():
-    # tables [N][Kp/g][2^g] of 2 bytes, group sums [N][nq] fp32, 256 spare bytes
-    assert T.tmac_lut_bytes(3, 4096, 128, B.TMAC_LUT_F16, g=2) == 3 * 2048 * 4 * 2 + 512 + 256
-    assert T.tmac_lut_bytes(3, 4096, 128, B.TMAC_LUT_I16, g=8) == 3 * 512 * 256 * 2 + 512 + 256
+    # tables [n tile][Kp/g][2^g][NT] of 2 bytes (one tile of four rows here), group sums [N][nq] fp32,
+    # 256 spare bytes
+    assert T.tmac_lut_bytes(3, 4096, 128, B.TMAC_LUT_F16, g=2) == 4 * 2048 * 4 * 2 + 512 + 256
+    assert T.tmac_lut_bytes(3, 4096, 128, B.TMAC_LUT_I16, g=8) == 4 * 512 * 256 * 2 + 512 + 256
     assert T.tmac_lut_bytes(1, 4096, 128, B.TMAC_LUT_I8Q, g=8) == 0      # int8 tables: g = 4 only
     assert T.tmac_lut_bytes(1, 4100, 0, B.TMAC_LUT_F16, g=8) == 0        # K % g
     assert T.tmac_lut_bytes(1, 4096, 4, B.TMAC_LUT_F16, g=8) == 0        # group % g
