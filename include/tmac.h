@@ -165,9 +165,12 @@ tmac_status tmac_pack_weights(const tmac_wdesc* desc, const uint8_t* q_host,
                               const uint16_t* scales_host, const uint16_t* zeros_host,
                               void* packed_host, size_t packed_bytes);
 
-/* Bytes of the LUT buffer for N activation rows.  g = 2 or 8 (16-bit table types only): tables
- * [N][Kp/g][2^g] (2 bytes each, all-zero tables in the k padding), then the group sums
- * S[N][n_qgroups], 256-byte aligned.  g = 4: tables [N][Kp/4][16] (2 bytes each, k
+/* Bytes of the LUT buffer for N activation rows.  The tables of the batched kernels come first,
+ * laid out as those kernels keep them in LDS: [n tile][Kp/g][2^g][NT] 16-bit entries, where an
+ * n tile is NT consecutive activation rows (NT = 4 for N <= 4, for g = 8, and when N % 8 is 1..4
+ * below N = 40; else 8; rows that pad the last tile hold zeros) and the NT values of an entry sit
+ * side by side; all-zero tables in the k padding.  g = 2 or 8 (16-bit table types only): then
+ * the group sums S[N][n_qgroups], 256-byte aligned.  g = 4: these tables (k
  * padded to 128 with all-zero tables; absent for TMAC_LUT_I8Q, which has unit scales [N][Kp/16]
  * and one-byte half tables instead), then the group sums S[N][n_qgroups], then the sums
  * of every 16 consecutive activations S16[N][Kp/16] (both fp32 for TMAC_LUT_F16, int32 for
