@@ -176,7 +176,9 @@ tmac_status tmac_pack_weights(const tmac_wdesc* desc, const uint8_t* q_host,
  * of every 16 consecutive activations S16[N][Kp/16] (both fp32 for TMAC_LUT_F16, int32 for
  * TMAC_LUT_I16), the sums of every 128 consecutive activations S128[N][Kp/128] (same type) and
  * the mirror-consolidated byte-split half tables of the register-table kernel, each region
- * 256-byte aligned.  0 on bad arguments. */
+ * 256-byte aligned.  The three regions of the register-table kernel exist up to N = 64 (beyond
+ * that tmac_mpgemm returns TMAC_EUNSUPPORTED for layout 2; its fused call takes any N).
+ * 0 on bad arguments. */
 size_t tmac_lut_bytes(int32_t N, int32_t K, int32_t g, int32_t group, tmac_lut_t lut);
 
 /* Online table precompute (Algorithm 1 Precompute; Section 3.1; mirror consolidation of

@@ -29,6 +29,8 @@ bool group_supported(const tmac_wdesc* d);
 Geometry geometry(const tmac_wdesc* d);
 
 // Geometry of the LUT buffer written by tmac_precompute_lut.
+constexpr int TMAC_DECODE_MAX_ROWS = 64;  // activation rows the register-table kernel takes from a LUT buffer
+
 struct LutGeom {
   int Kp, KG, nq;       // K padded to 128, tables per row, quantisation groups per row (>= 1)
   int Geff;             // elements per quantisation group (K when one group per row/tensor)
@@ -41,6 +43,7 @@ struct LutGeom {
   size_t ht_off;        // byte offset of the half tables, piece-major per block
   size_t total;
   int NT;  // activation rows per n tile of the table region
+  bool decode_parts;  // per-16 and per-128 sums and half tables present
 };
 
 // Activation rows the batched kernels serve per workgroup ("n tile") for a call with N rows: eight
@@ -72,7 +75,11 @@ inline bool lut_geom(int N, int K, int g, int group, int lut_t, LutGeom* lg) {
   const size_t tab = q8 ? 0 : n_pad * lg->KG * (2u << g);
   lg->s_off = (tab + 255) / 256 * 256;
   lg->s16_off = (lg->s_off + (size_t)N * lg->nq * 4 + 255) / 256 * 256;
-  if (g != 4) {
+  // the regions of the register-table kernel exist for g = 4 and at most TMAC_DECODE_MAX_ROWS
+  // activation rows (that kernel serves a handful of rows; a prefill-sized buffer goes without them)
+  lg->decode_parts = (g == 4 && N <= TMAC_DECODE_MAX_ROWS);
+  if (!lg->decode_parts) {
+    if (q8) return false;
     lg->s128_off = lg->usc_off = lg->ht_off = lg->s16_off;
     lg->total = lg->s16_off + 256;
     return true;

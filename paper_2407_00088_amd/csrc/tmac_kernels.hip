@@ -454,7 +454,7 @@ extern "C" tmac_status tmac_precompute_lut(const void* A_dev, tmac_act_t act, in
     return eq == hipSuccess ? TMAC_OK : TMAC_EHIP;
   }
   const int64_t n_items = (int64_t)N * lg.KG;
-  const int n_tab_blocks = (int)((n_items + 255) / 256);
+  const int n_tab_blocks = lg.decode_parts ? (int)((n_items + 255) / 256) : 0;
   uint4* tables = static_cast<uint4*>(lut_dev);
   void* S = static_cast<char*>(lut_dev) + lg.s_off;
   void* S16 = static_cast<char*>(lut_dev) + lg.s16_off;

@@ -648,6 +648,7 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
   LutGeom lg;
   if (!lut_geom(N, desc->K, desc->g, desc->group, lut_t, &lg)) return TMAC_EINVAL;
   if (N > 65535) return TMAC_EUNSUPPORTED;
+  if (!fused && !lg.decode_parts) return TMAC_EUNSUPPORTED;  // a LUT buffer for this many rows has no half tables
   // 32-bit slot arithmetic inside the kernel
   if ((double)ge.n_tiles * lg.U * desc->bits >= 4294967296.0 || (double)N * lg.U * 4 >= 4294967296.0)
     return TMAC_EUNSUPPORTED;

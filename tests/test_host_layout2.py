@@ -107,3 +107,7 @@ def test_layout2_sizes_and_group_rules():
     st = B.lib.tmac_mpgemm(C.byref(ok), fake, fake, 0, 1, None, C.c_float(1.0), fake, B.TMAC_OUT_I32, 16, fake,
                            1 << 20, None)
     assert st == B.TMAC_EINVAL         # integer output needs integer tables
+    # more than 64 activation rows: the LUT buffer has no half tables, the two-call route says so
+    d = desc2(4096, 4096, 4, 128)
+    st = B.lib.tmac_mpgemm(C.byref(d), fake, fake, 0, 65, None, C.c_float(1.0), fake, 0, 4096, fake, 1 << 20, None)
+    assert st == B.TMAC_EUNSUPPORTED

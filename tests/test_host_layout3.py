@@ -84,6 +84,17 @@ def test_lut_bytes_for_other_group_sizes():
     assert T.tmac_lut_bytes(1, 4096, 4, B.TMAC_LUT_F16, g=8) == 0        # group % g
 
 
+def test_lut_bytes_beyond_the_register_table_kernel():
+    """More than 64 activation rows go to the batched kernels only: the buffer then holds the tables
+    (n tiles of 8 rows) and the group sums, and int8 tables, which only the register-table kernel
+    reads, are refused."""
+    assert T.tmac_lut_bytes(64, 4096, 128, B.TMAC_LUT_F16) > 64 * 4096 * 8 + 64 * 32 * 4 + 256
+    assert T.tmac_lut_bytes(65, 4096, 128, B.TMAC_LUT_F16) == 72 * 4096 * 8 + (65 * 32 * 4 + 255) // 256 * 256 + 256
+    assert T.tmac_lut_bytes(256, 5120, 128, B.TMAC_LUT_I16) == 256 * 5120 * 8 + 256 * 40 * 4 + 256
+    assert T.tmac_lut_bytes(64, 4096, 128, B.TMAC_LUT_I8Q) > 0
+    assert T.tmac_lut_bytes(65, 4096, 128, B.TMAC_LUT_I8Q) == 0
+
+
 def test_fused_workspace_regions():
     """tmac_fused_workspace_bytes = tmac_mpgemm's workspace (rounded to 256) plus a LUT buffer only
     where the tables are not built inside the lookup kernel."""
