@@ -415,8 +415,12 @@ extern "C" tmac_status tmac_precompute_lut(const void* A_dev, tmac_act_t act, in
   if ((reinterpret_cast<uintptr_t>(A_dev) & a_align) != 0 || (lda % 4) != 0) return TMAC_EINVAL;
   if (lut_bytes < lg.total) return TMAC_ESIZE;
 
-  const int n_sum_blocks = (N * lg.nq + 3) / 4;
+  const int64_t n_sum_blocks64 = ((int64_t)N * lg.nq + 3) / 4;
   const int64_t n_stage_ids = (int64_t)((N + lg.NT - 1) / lg.NT) * lg.KG * ((1 << g) / 2);
+  const int64_t n_items = (int64_t)N * lg.KG;  // tables (g = 4: one lane each in the half-table part)
+  // every part of the grid, and their sum, must fit the 32-bit block index
+  if (n_sum_blocks64 + (n_stage_ids + 255) / 256 + (n_items + 255) / 256 > 0x7fffffff) return TMAC_EUNSUPPORTED;
+  const int n_sum_blocks = (int)n_sum_blocks64;
   const int n_stage_blocks = (int)((n_stage_ids + 255) / 256);
   if (g != 4) {
     uint4* tables = static_cast<uint4*>(lut_dev);
@@ -453,7 +457,6 @@ extern "C" tmac_status tmac_precompute_lut(const void* A_dev, tmac_act_t act, in
                                  reinterpret_cast<uint4*>(base + lg.ht_off), lg.Geff, lg.nq, n_unit_blocks);
     return eq == hipSuccess ? TMAC_OK : TMAC_EHIP;
   }
-  const int64_t n_items = (int64_t)N * lg.KG;
   const int n_tab_blocks = lg.decode_parts ? (int)((n_items + 255) / 256) : 0;
   uint4* tables = static_cast<uint4*>(lut_dev);
   void* S = static_cast<char*>(lut_dev) + lg.s_off;
