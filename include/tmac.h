@@ -50,8 +50,9 @@ typedef enum {
 typedef enum { TMAC_ACT_F16 = 0, TMAC_ACT_I8 = 1 } tmac_act_t;
 
 /* Table entry type.
- *   TMAC_LUT_F16: entries are the fp32 signed sums of fp16 activations rounded once to fp16
- *                 (results within 2e-3 relative Frobenius error of the fp64 product).
+ *   TMAC_LUT_F16: entries are signed sums of fp16 activations formed with fp16 additions (see
+ *                 tmac_precompute_lut; results within 2e-3 relative Frobenius error of the fp64
+ *                 product).
  *   TMAC_LUT_I16: entries are exact int16 sums of int8 activations (|T| <= 4*127); all
  *                 aggregation is int32 and the result is bit-exact.
  *   TMAC_LUT_I8Q: table quantisation (Section 3.3): entries of fp16 activations' tables rounded
@@ -184,6 +185,11 @@ size_t tmac_lut_bytes(int32_t N, int32_t K, int32_t g, int32_t group, tmac_lut_t
 /* Online table precompute (Algorithm 1 Precompute; Section 3.1; mirror consolidation of
  * Section 3.3 is used to compute half of the entries and negate them for the rest):
  *   T[n,kg,p] = sum_{j<g} (bit j of p ? +a : -a)[n, g*kg+j],  S[n,G] = sum_{k in G} a[n,k].
+ * fp16 tables are built in fp16 arithmetic: the g signed terms are added pairwise,
+ * ((+-a0 +- a1) + (+-a2 +- a3)) + ..., every addition rounded to nearest even (one addition at
+ * g = 2, three levels at g = 8); the kernels that build their tables themselves take the same
+ * additions, so both routes give the same bits.  Integer tables are exact.  S is summed in fp32
+ * (int32).  int8 tables (TMAC_LUT_I8Q) are quantised from fp32 sums.
  *   A_dev  [N,K] row-major with leading dimension lda (elements): fp16 or int8
  *   TMAC_ACT_F16 goes with TMAC_LUT_F16 or TMAC_LUT_I8Q, TMAC_ACT_I8 with TMAC_LUT_I16.
  * Errors: TMAC_EINVAL, TMAC_ESIZE, TMAC_EHIP. */

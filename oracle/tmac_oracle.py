@@ -145,6 +145,31 @@ def precompute_lut(act, g=4, dtype=np.float64):
     return lut.astype(dtype)
 
 
+def precompute_lut_fp16_tree(act, g=4):
+    """Precompute in the activations' own precision (reading of Section 3.1 for
+    fp16 activations: the table is built with adds and subtracts of the same
+    type as its entries).  The g signed terms +-a_j are added pairwise,
+    ((+-a0 +- a1) + (+-a2 +- a3)) + ..., and every addition is rounded to fp16
+    (round to nearest even).  Returns a float16 array of shape (N, K/g, 2^g).
+    With g = 2 there is one addition and the result equals the once-rounded
+    exact sum; from g = 4 on entries can differ from it by the roundings of the
+    partial sums."""
+    A = np.asarray(act)
+    assert A.dtype == np.float16 and g & (g - 1) == 0
+    N, K = A.shape
+    assert K % g == 0
+    Ag = A.reshape(N, K // g, g).astype(np.float64)
+    lut = np.zeros((N, K // g, 1 << g), dtype=np.float16)
+    for p in range(1 << g):
+        terms = [Ag[:, :, j] if (p >> j) & 1 else -Ag[:, :, j] for j in range(g)]
+        while len(terms) > 1:
+            # the fp64 sum of two fp16 numbers is exact, so this is one rounding per addition
+            terms = [(terms[i] + terms[i + 1]).astype(np.float16).astype(np.float64)
+                     for i in range(0, len(terms), 2)]
+        lut[:, :, p] = terms[0].astype(np.float16)
+    return lut
+
+
 def mirror_half(lut):
     """Mirror consolidation (Section 3.3): keep entries 0..2^(g-1)-1 only."""
     return lut[..., : lut.shape[-1] // 2]
@@ -199,14 +224,15 @@ def lookup_sum_narrow(lut16, idx, lut_groups_per_qgroup, tables_per_sum=8):
 
 
 def lut_mpgemm_narrow(act, q, bits, scales, zeros, group, g=4, tables_per_sum=8):
-    """The LUT route with fp16 tables and the narrow running sum of
+    """The LUT route with fp16 tables built by fp16 additions
+    (``precompute_lut_fp16_tree``) and the narrow running sum of
     ``lookup_sum_narrow`` (group scales only); everything else as ``lut_mpgemm``."""
     q = np.asarray(q)
     M, K = q.shape
     nq = K // group
     s = np.asarray(scales).astype(np.float64)
     z = np.asarray(zeros).astype(np.float64)
-    lut = precompute_lut(act, g, dtype=np.float16)
+    lut = precompute_lut_fp16_tree(act, g)
     S = group_sums(act, group).astype(np.float64)
     mid = (2.0 ** bits - 1.0) / 2.0
     Lsum = np.zeros((lut.shape[0], M, nq), dtype=np.float64)
@@ -239,8 +265,9 @@ def lut_mpgemm(act, q, bits, scales=None, zeros=None, group=0, weight_scale=1.0,
 
     The first term is Algorithm 1's sum_i alpha_i R_i, the second is its R_beta
     with the zero point folded into the constant matrix B.
-    ``table_dtype=np.float16`` rounds every table entry to fp16 once (the fp16
-    table path); sums stay in fp64.
+    ``table_dtype=np.float16`` rounds every table entry to fp16 once;
+    ``table_dtype="fp16_tree"`` builds the tables with fp16 additions
+    (``precompute_lut_fp16_tree``); the sums over looked-up entries stay in fp64.
     """
     q = np.asarray(q)
     M, K = q.shape
@@ -253,7 +280,7 @@ def lut_mpgemm(act, q, bits, scales=None, zeros=None, group=0, weight_scale=1.0,
     else:
         s = np.asarray(scales).astype(np.float64)
         z = np.asarray(zeros).astype(np.float64)
-    lut = precompute_lut(act, g, dtype=table_dtype)
+    lut = precompute_lut_fp16_tree(act, g) if table_dtype == "fp16_tree" else precompute_lut(act, g, dtype=table_dtype)
     S = group_sums(act, G).astype(np.float64)                     # [N, nq]
     mid = (2.0 ** bits - 1.0) / 2.0
     N = lut.shape[0]

@@ -125,6 +125,32 @@ TMAC_HD inline int block_of(const BlockSplit& b, int c) {
 // slot of unit u inside its block (c0 = first chunk, ng = chunks of the block)
 TMAC_HD inline int block_slot(int u, int c0, int ng) { return (u & 7) * ng + ((u >> 3) - c0); }
 
+#if defined(__HIPCC__)
+// Algorithm 1 Precompute for one LUT group of four fp16 activations, in the activations' own
+// precision: x01 = {a0, a1}, x23 = {a2, a3} as packed pairs; T[p] = (+-a0 +- a1) + (+-a2 +- a3),
+// the pair sums first, then their sum, every addition in fp16 (round to nearest even).  out[d] =
+// {T[2d], T[2d+1]} for the mirror half p = 0..7 (a3 subtracted); entries 8..15 are the negated
+// entries 7..0 (Section 3.3), exactly, because negation commutes with rounding.  Six packed
+// additions; every table builder of the library goes through here so that they agree bit for bit.
+typedef _Float16 tmac_h2 __attribute__((ext_vector_type(2)));
+__device__ inline __attribute__((always_inline)) void half_table_f16(uint32_t x01, uint32_t x23, uint32_t (&out)[4]) {
+  const tmac_h2 a = __builtin_bit_cast(tmac_h2, x01), b = __builtin_bit_cast(tmac_h2, x23);
+  const tmac_h2 sd = tmac_h2{a.x, a.x} + tmac_h2{a.y, -a.y};  // {a0 + a1, a0 - a1}
+  const tmac_h2 tw = tmac_h2{b.x, b.x} + tmac_h2{b.y, -b.y};  // {a2 + a3, a2 - a3}
+  const tmac_h2 m0 = tmac_h2{-sd.x, sd.y}, m1 = tmac_h2{-sd.y, sd.x};  // signs of a0, a1: --, +-  and  -+, ++
+  out[0] = __builtin_bit_cast(uint32_t, m0 - tmac_h2{tw.x, tw.x});
+  out[1] = __builtin_bit_cast(uint32_t, m1 - tmac_h2{tw.x, tw.x});
+  out[2] = __builtin_bit_cast(uint32_t, m0 + tmac_h2{tw.y, tw.y});
+  out[3] = __builtin_bit_cast(uint32_t, m1 + tmac_h2{tw.y, tw.y});
+}
+// Sum of four fp16 activations given as two packed pairs, in fp32 (two dot products with ones).
+__device__ inline __attribute__((always_inline)) float sum4_f16(uint32_t x01, uint32_t x23) {
+  const tmac_h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+  const float s = __builtin_amdgcn_fdot2(__builtin_bit_cast(tmac_h2, x01), ones, 0.f, false);
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(tmac_h2, x23), ones, s, false);
+}
+#endif
+
 // Register-table decode kernel (layout 2); defined in tmac_perm.hip.  Arguments are those of
 // tmac_mpgemm after validation; with lut_dev == nullptr the kernel builds its tables itself from
 // the activations A_dev (leading dimension lda).  lut_t is a tmac_lut_t value.  Returns a

@@ -74,8 +74,9 @@ __device__ __forceinline__ void group_sums_wave(const void* __restrict__ A_, int
 // The tables as the batched kernels keep them in LDS: [n tile][KG][2^G][NT] 16-bit entries, NT
 // activation rows side by side per entry, so that staging a K slice is a plain copy.  Thread `id`
 // builds the two consecutive entries 2 id, 2 id + 1 (counted over [n tile][KG][2^G]) for the NT
-// rows of its tile: T[p] = sum_j (bit j of p ? +a_j : -a_j), added pairwise in fp32 and rounded
-// once to fp16 (exact int16 for int8 activations); rows past N and tables past K are zero.
+// rows of its tile: T[p] = sum_j (bit j of p ? +a_j : -a_j), added pairwise in fp16 (the tree of
+// half_table_f16, one level less at g = 2, one more at g = 8; exact int16 for int8 activations);
+// rows past N and tables past K are zero.
 template <bool IS_INT, int G, int NT>
 __device__ __forceinline__ void staged_tables(const void* __restrict__ A_, int N, int K, int64_t lda, int KG,
                                               uint4* __restrict__ tables, int64_t id) {
@@ -116,32 +117,29 @@ __device__ __forceinline__ void staged_tables(const void* __restrict__ A_, int N
       } else {
         // (row bases and lda are multiples of 8 bytes: G elements come with 4- or 8-byte loads)
         const __half* ap = static_cast<const __half*>(A_) + n * lda + k0;
-        float x[G];
+        _Float16 x[G];
         if constexpr (G == 2) {
-          const uint32_t v = *reinterpret_cast<const uint32_t*>(ap);
-          x[0] = __half2float(__ushort_as_half((uint16_t)(v & 0xffffu)));
-          x[1] = __half2float(__ushort_as_half((uint16_t)(v >> 16)));
+          const tmac_h2 v = *reinterpret_cast<const tmac_h2*>(ap);
+          x[0] = v.x; x[1] = v.y;
         } else {
 #pragma unroll
           for (int q = 0; q < G / 4; ++q) {
             const uint2 v = reinterpret_cast<const uint2*>(ap)[q];
-            x[4 * q + 0] = __half2float(__ushort_as_half((uint16_t)(v.x & 0xffffu)));
-            x[4 * q + 1] = __half2float(__ushort_as_half((uint16_t)(v.x >> 16)));
-            x[4 * q + 2] = __half2float(__ushort_as_half((uint16_t)(v.y & 0xffffu)));
-            x[4 * q + 3] = __half2float(__ushort_as_half((uint16_t)(v.y >> 16)));
+            const tmac_h2 v0 = __builtin_bit_cast(tmac_h2, v.x), v1 = __builtin_bit_cast(tmac_h2, v.y);
+            x[4 * q + 0] = v0.x; x[4 * q + 1] = v0.y; x[4 * q + 2] = v1.x; x[4 * q + 3] = v1.y;
           }
         }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-          float y[G];
+          _Float16 y[G];
 #pragma unroll
           for (int j = 0; j < G; ++j) y[j] = (((e0 + u) >> j) & 1) ? x[j] : -x[j];
 #pragma unroll
-          for (int st = 1; st < G; st *= 2) {       // pairwise: ((y0+y1)+(y2+y3))+...
+          for (int st = 1; st < G; st *= 2) {       // pairwise, every add in fp16: ((y0+y1)+(y2+y3))+...
 #pragma unroll
-            for (int j = 0; j + st < G; j += 2 * st) y[j] += y[j + st];
+            for (int j = 0; j + st < G; j += 2 * st) y[j] = y[j] + y[j + st];
           }
-          e[u] = __half_as_ushort(__float2half_rn(y[0]));
+          e[u] = __builtin_bit_cast(uint16_t, y[0]);
         }
       }
     }
@@ -180,41 +178,29 @@ __global__ __launch_bounds__(256) void precompute_kernel(const void* __restrict_
     const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (tid >= (int64_t)N * KG) return;
     const int n = (int)(tid / KG), kg = (int)(tid % KG);
-    uint32_t packed[8];
+    uint32_t packed[4];  // entries 0..7 (the mirror half), two per dword
     float sum4f = 0.f;  // sum of this table's four activations (for the per-16 unit sums)
     int sum4i = 0;
     if (4 * kg >= K) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) packed[i] = 0;  // k padding: all-zero table
+      for (int i = 0; i < 4; ++i) packed[i] = 0;  // k padding: all-zero table
     } else if constexpr (IS_INT) {
       const int8_t* a = static_cast<const int8_t*>(A_) + n * lda + 4 * kg;
       const int a0 = a[0], a1 = a[1], a2 = a[2], a3 = a[3];
       sum4i = a0 + a1 + a2 + a3;
-      int e[16];
+      int e[8];
 #pragma unroll
       for (int p = 0; p < 8; ++p) {
         e[p] = ((p & 1) ? a0 : -a0) + ((p & 2) ? a1 : -a1) + ((p & 4) ? a2 : -a2) - a3;
       }
 #pragma unroll
-      for (int p = 0; p < 8; ++p) e[15 - p] = -e[p];  // mirror half
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
+      for (int i = 0; i < 4; ++i)
         packed[i] = ((uint32_t)e[2 * i] & 0xffffu) | ((uint32_t)e[2 * i + 1] << 16);
     } else {
-      const __half* a = static_cast<const __half*>(A_) + n * lda + 4 * kg;
-      const float a0 = __half2float(a[0]), a1 = __half2float(a[1]);
-      const float a2 = __half2float(a[2]), a3 = __half2float(a[3]);
-      sum4f = ((a0 + a1) + a2) + a3;
-      uint16_t e[16];
-#pragma unroll
-      for (int p = 0; p < 8; ++p) {
-        const float v = (((p & 1) ? a0 : -a0) + ((p & 2) ? a1 : -a1)) + (((p & 4) ? a2 : -a2) - a3);
-        const __half h = __float2half_rn(v);
-        e[p] = __half_as_ushort(h);
-        e[15 - p] = e[p] ^ 0x8000u;  // mirror half: exact negation
-      }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) packed[i] = (uint32_t)e[2 * i] | ((uint32_t)e[2 * i + 1] << 16);
+      // (row bases and lda are multiples of 8 bytes)
+      const uint2 v = *reinterpret_cast<const uint2*>(static_cast<const __half*>(A_) + n * lda + 4 * kg);
+      sum4f = sum4_f16(v.x, v.y);
+      half_table_f16(v.x, v.y, packed);
     }
     // Mirror-consolidated copy for the register-table kernel: entries 0..7 as fp16 (int16 entries
     // are at most 508 in magnitude, exact in fp16).  Units are grouped in nB blocks; inside a block
@@ -290,7 +276,7 @@ __global__ __launch_bounds__(256) void precompute_g_kernel(const void* __restric
 }
 
 // Table quantisation (Section 3.3): one thread per unit of 16 activations builds the mirror halves
-// of its four tables in fp32 (same sums as above), takes the unit's largest magnitude
+// of its four tables in fp32 (they are rounded once, to int8), takes the unit's largest magnitude
 // amax = max_t sum_j |a_j| (attained by the entry whose signs match), and stores
 // rint(T * 127 / amax) as int8 together with the scale amax / 127.  Per unit: two 16-byte pieces
 // (tables 0,1 and 2,3; eight entries of one byte each), laid out like the fp16 half tables.

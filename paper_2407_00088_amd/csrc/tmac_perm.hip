@@ -273,12 +273,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
     // loads below the first lookups (or, in fused mode, the first use of the activations)
     __builtin_amdgcn_sched_barrier(0);
 
-    // 4. fused mode: unpack the activations; the activation sum the bias term needs
-    float af[16];
-    if constexpr (FUSED && !IS_INT) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) af[i] = __half2float(__ushort_as_half((uint16_t)(araw[i >> 1] >> (16 * (i & 1)))));
-    }
+    // 4. fused mode: the activation sum the bias term needs
     if constexpr (FUSED) {
       // sum of the lane's 16 activations, in the order of the precompute kernel's tree
       if constexpr (IS_INT) {
@@ -289,7 +284,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
       } else {
         float t4[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) t4[t] = ((af[4 * t] + af[4 * t + 1]) + af[4 * t + 2]) + af[4 * t + 3];
+        for (int t = 0; t < 4; ++t) t4[t] = sum4_f16(araw[2 * t], araw[2 * t + 1]);
         Sl = (t4[0] + t4[1]) + (t4[2] + t4[3]);
       }
       if constexpr (GM == 0) Stot += Sl;
@@ -305,30 +300,18 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
     if constexpr (FUSED) {
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
-        float e[8];
-        if constexpr (IS_INT) {
-          // entry q = sum_j (bit j of q ? +a_j : -a_j), a_3 subtracted: a signed dot product with +-1 bytes
-#pragma unroll
-          for (int q = 0; q < 8; ++q) {
-            const int sg = (int)(((q & 1) ? 0x01u : 0xFFu) | ((q & 2) ? 0x0100u : 0xFF00u) |
-                                 ((q & 4) ? 0x010000u : 0xFF0000u) | 0xFF000000u);
-            e[q] = (float)__builtin_amdgcn_sdot4((int)araw[t], sg, 0, false);  // exact
-          }
-        } else {
-          // (+-x0 +- x1) + (+-x2 - x3): negating a sum negates its rounded value, so four adds give the
-          // pair sums and one add each the entries, with the bits of the stand-alone precompute kernel
-          const float x0 = af[4 * t], x1 = af[4 * t + 1], x2 = af[4 * t + 2], x3 = af[4 * t + 3];
-          const float sp = x0 + x1, dp = x0 - x1, tq = x2 + x3, wq = x2 - x3;
-          e[0] = -sp - tq; e[1] = dp - tq; e[2] = -dp - tq; e[3] = sp - tq;
-          e[4] = wq - sp;  e[5] = dp + wq; e[6] = wq - dp;  e[7] = sp + wq;
-        }
         uint32_t pk[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          h2 v;
-          v.x = (_Float16)e[2 * i];
-          v.y = (_Float16)e[2 * i + 1];
-          pk[i] = __builtin_bit_cast(uint32_t, v);
+        if constexpr (IS_INT) {
+          // int8 activations are exact in fp16 and so is every sum of four of them (|T| <= 508): the
+          // fp16 additions of the fp16 path give the integer table
+          // (conversion: byte b + 128 under the high byte 0x64 is the fp16 number 1024 + 128 + b)
+          const uint32_t biased = araw[t] ^ 0x80808080u;
+          const h2 off = {(_Float16)1152.0f, (_Float16)1152.0f};
+          const h2 x01 = __builtin_bit_cast(h2, bperm(0x64646464u, biased, 0x04010400u)) - off;
+          const h2 x23 = __builtin_bit_cast(h2, bperm(0x64646464u, biased, 0x04030402u)) - off;
+          half_table_f16(__builtin_bit_cast(uint32_t, x01), __builtin_bit_cast(uint32_t, x23), pk);
+        } else {
+          half_table_f16(araw[2 * t], araw[2 * t + 1], pk);  // fp16 additions, as every table builder
         }
         lo0[t] = bperm(pk[1], pk[0], 0x06040200u);
         lo1[t] = bperm(pk[3], pk[2], 0x06040200u);

@@ -117,8 +117,8 @@ struct RowsShape {
 
 // Algorithm 1 Precompute for one (activation row, LUT group of four) inside a lookup kernel: the
 // eight entries 8h..8h+7 of the table, as four dwords of two 16-bit entries, with the arithmetic
-// of the stand-alone precompute kernel ((+-a0 +- a1) + (+-a2 - a3) in fp32, one rounding to
-// fp16; entries 8..15 are the negated entries 7..0: mirror consolidation, Section 3.3).
+// of the stand-alone precompute kernel ((+-a0 +- a1) + (+-a2 - a3), every addition in fp16;
+// entries 8..15 are the negated entries 7..0: mirror consolidation, Section 3.3).
 template <bool IS_INT>
 __device__ __forceinline__ ru32x4v rows_build_half_table(const void* A, int64_t lda, int n, int kg, int h, bool live) {
   uint32_t low[4];  // entries 0..7
@@ -138,27 +138,9 @@ __device__ __forceinline__ ru32x4v rows_build_half_table(const void* A, int64_t 
     }
     return ru32x4v{low[0], low[1], low[2], low[3]};
   } else {
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-    if (live) {
-      const ru32x2v v = *reinterpret_cast<const ru32x2v*>(static_cast<const __half*>(A) + n * lda + 4 * kg);
-      a0 = __half2float(__ushort_as_half((uint16_t)(v.x & 0xffffu)));
-      a1 = __half2float(__ushort_as_half((uint16_t)(v.x >> 16)));
-      a2 = __half2float(__ushort_as_half((uint16_t)(v.y & 0xffffu)));
-      a3 = __half2float(__ushort_as_half((uint16_t)(v.y >> 16)));
-    }
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      float f[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int q = 2 * d + i;
-        f[i] = (((q & 1) ? a0 : -a0) + ((q & 2) ? a1 : -a1)) + (((q & 4) ? a2 : -a2) - a3);
-      }
-      rh2v pk;
-      pk.x = (_Float16)f[0];
-      pk.y = (_Float16)f[1];
-      low[d] = __builtin_bit_cast(uint32_t, pk);
-    }
+    ru32x2v v = {0u, 0u};
+    if (live) v = *reinterpret_cast<const ru32x2v*>(static_cast<const __half*>(A) + n * lda + 4 * kg);
+    half_table_f16(v.x, v.y, low);
     if (!h) return ru32x4v{low[0], low[1], low[2], low[3]};
     // entries 8 + q = -(entry 7 - q): halves swapped, order reversed, sign bits flipped
     ru32x4v r;
