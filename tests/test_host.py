@@ -191,3 +191,15 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
     g48 = _desc(M=16, K=192, bits=2, group=48)          # layout 3 needs whole 32-k chunks per group
     assert call(a0=C.byref(g48), a9=16) == B.TMAC_EUNSUPPORTED
     assert T.status_str(B.TMAC_ESIZE) == "buffer too small"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU's throughput; --gpus N with N > 1 ends with a message and a
+    non-zero status before anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=300)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
