@@ -244,7 +244,9 @@ tmac_status tmac_mpgemv_fused(const tmac_wdesc* desc, const void* packed_dev, co
  * K % 8 == 0, a group size that divides 256 (or one scale per row or tensor), and at most 32
  * activation rows in a call that is cut into K slices of 256 (the case a separate precompute
  * launch costs most).  Every other call
- * runs tmac_precompute_lut into the second region of the workspace and tmac_mpgemm after it.
+ * runs tmac_precompute_lut into the second region of the workspace and tmac_mpgemm after it
+ * (layout 2 with K % 16 != 0 or an unsupported group size: at most 64 activation rows, beyond
+ * that TMAC_EUNSUPPORTED and a size of 0).
  *   A_dev          [N,K] fp16 or int8, 16-byte aligned; leading dimension lda a multiple of 8
  *                  where the tables are built in the kernel (16 for int8 with layout 2), else as
  *                  for tmac_precompute_lut

@@ -531,6 +531,8 @@ static bool fused_regions(const tmac_wdesc* desc, int N, tmac_act_t act, size_t*
   *ws = (tmac_workspace_bytes(desc, N) + 255) / 256 * 256;
   const bool in_kernel = (desc->layout == TMAC_LAYOUT_R8U16) ? (desc->K % 16 == 0 && group_supported(desc))
                                                              : (group_supported(desc) && rows_builds_tables(desc, N));
+  // (the register-table kernel reads its tables from a LUT buffer for at most TMAC_DECODE_MAX_ROWS rows)
+  if (!in_kernel && desc->layout == TMAC_LAYOUT_R8U16 && N > TMAC_DECODE_MAX_ROWS) return false;
   *lut = in_kernel ? 0 : tmac_lut_bytes(N, desc->K, desc->g, desc->group, lt);
   return true;
 }
@@ -546,7 +548,8 @@ extern "C" tmac_status tmac_mpgemm_fused(const tmac_wdesc* desc, const void* pac
                                          float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
                                          void* workspace_dev, size_t workspace_bytes, void* stream) {
   size_t ws, lutb;
-  if (!fused_regions(desc, N, act, &ws, &lutb)) return TMAC_EINVAL;
+  if (!desc_valid(desc) || N <= 0 || (act != TMAC_ACT_F16 && act != TMAC_ACT_I8)) return TMAC_EINVAL;
+  if (!fused_regions(desc, N, act, &ws, &lutb)) return TMAC_EUNSUPPORTED;
   if (!packed_dev || !A_dev || !out_dev || !workspace_dev) return TMAC_EINVAL;
   if (out != TMAC_OUT_F32 && out != TMAC_OUT_F16 && out != TMAC_OUT_I32) return TMAC_EINVAL;
   if (!aligned16(packed_dev) || !aligned16(A_dev) || !aligned16(workspace_dev)) return TMAC_EINVAL;

@@ -116,4 +116,7 @@ def test_fused_workspace_regions():
     assert B.tmac_fused_workspace_bytes(d2, 1, F16) == 256                        # register-table kernel builds them
     d2b = T.wdesc(64, 4072, 2, 4072, layout=B.TMAC_LAYOUT_R8U16)
     assert B.tmac_fused_workspace_bytes(d2b, 1, F16) == 256 + T.tmac_lut_bytes(1, 4072, 4072, B.TMAC_LUT_F16)
+    assert B.tmac_fused_workspace_bytes(d2b, 64, F16) > 0
+    assert B.tmac_fused_workspace_bytes(d2b, 65, F16) == 0     # LUT-buffer route of the register-table kernel: 64 rows at most
+    assert B.tmac_fused_workspace_bytes(d2, 65, F16) == 256     # tables built in the kernel: any number of rows
     assert B.tmac_fused_workspace_bytes(d, 0, F16) == 0 and B.tmac_fused_workspace_bytes(d, 1, 7) == 0
