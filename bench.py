@@ -250,12 +250,51 @@ def main():
                 torch.cuda.empty_cache()
         return rows
 
+    def lds_lookup_ceiling():
+        """Lookup rate of LDS alone (tmac_lds_lookup_probe): the ceiling of the batched kernels' lookups.
+        One 16-byte read of a wavefront serves 64 lanes x 8 activation rows = 512 lookups."""
+        wgs, rounds = 256 * 5 * 4, 2000
+
+        def probe():
+            T.tmac_lds_lookup_probe(wgs, rounds, sink)
+        us = timed(Replay(probe, 1), 5, 2)
+        wave_reads = wgs * 4 * rounds * 16
+        return {"workgroups": wgs, "rounds": rounds, "us": round(us, 1),
+                "wave_reads_per_s": round(wave_reads / us * 1e6, -6),
+                "bytes_per_clk_per_cu_at_2.4GHz": round(wave_reads * 1024 / us * 1e6 / 256 / 2.4e9, 1),
+                "lookups_per_s": round(wave_reads * 512 / us * 1e6, -9)}
+
+    def isolated_rows(cases_):
+        """The paper's own protocol (Section 5.1: warm-up, then the mean of 100 runs) on ONE copy of the
+        weights, an event pair around every call, launched eagerly: cache-hot and launch-dominated;
+        printed next to the steady-state figures, never instead of them."""
+        rows = []
+        for c in cases_:
+            row = {"name": c.p.name}
+            for key, body in (("fused_us", c.fused), ("mpgemm_us", c.mpgemm), ("precompute_us", c.precompute)):
+                ring, c.ring = c.ring, c.ring[:1]
+                ts = []
+                with torch.cuda.stream(stream):
+                    for it in range(110):
+                        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        t0.record(stream)
+                        body()
+                        t1.record(stream)
+                        stream.synchronize()
+                        if it >= 10:
+                            ts.append(t0.elapsed_time(t1) * 1e3)
+                c.ring = ring
+                ts.sort()
+                row[key] = {"mean": round(sum(ts) / len(ts), 2), "median": round(ts[len(ts) // 2], 2)}
+            rows.append(row)
+        return rows
+
     if args.small_batch_only:
         print(json.dumps({"small_batch": small_batch_rows()}))
         return
 
     if args.prefill_only:
-        print(json.dumps({"prefill_n256": prefill_rows()}))
+        print(json.dumps({"prefill_n256": prefill_rows(), "lds_lookup_ceiling": lds_lookup_ceiling()}))
         return
 
     cases = [Case(wl.config2(i)) for i in range(3)]
@@ -302,6 +341,7 @@ def main():
                                  "plain_read_of_same_bytes_us": round(ru, 3)})
 
     if args.sweep:
+        detail["isolated_one_copy_eager"] = isolated_rows(cases)
         sweep = []
         del cases[1:]
         torch.cuda.empty_cache()
@@ -387,6 +427,7 @@ def main():
                 torch.cuda.empty_cache()
         detail["g_sweep"] = gs
         detail["prefill_n256"] = prefill_rows()
+        detail["lds_lookup_ceiling"] = lds_lookup_ceiling()
         xs = np.array([s["bits"] for s in sweep[:4]], dtype=np.float64)
         ys = np.array([s["mpgemm_us"] for s in sweep[:4]], dtype=np.float64)
         cfit, t0fit = np.polyfit(xs, ys, 1)

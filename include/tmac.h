@@ -289,6 +289,14 @@ tmac_status tmac_mpgemv_fused_ex(const tmac_wdesc* desc, const void* packed_dev,
 tmac_status tmac_stream_read(const void* src_dev, size_t bytes, void* sink_dev, int32_t per_thread,
                              int32_t nontemporal, void* stream);
 
+/* Measurement helper, not part of the mpGEMM path (Section 3.2 wants the tables in the fastest
+ * on-chip memory because they are read at random: this measures how fast that memory serves such
+ * reads).  `workgroups` workgroups of 256 lanes each hold 32 KB of tables in LDS and issue
+ * `rounds` x 16 reads of 16 bytes per lane at data-dependent offsets, with the address arithmetic
+ * of the batched lookup kernels and no other work; sink_dev needs 256 writable bytes.
+ * Errors: TMAC_EINVAL, TMAC_EHIP. */
+tmac_status tmac_lds_lookup_probe(int32_t workgroups, int32_t rounds, void* sink_dev, void* stream);
+
 const char* tmac_status_str(tmac_status s);
 
 /* Text of the last HIP error this thread met inside the library ("" if none); diagnostics

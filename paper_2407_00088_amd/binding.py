@@ -27,7 +27,7 @@ TMAC_LAYOUT_R64K32 = 3    # batched lookup kernel, lane = weight row (many activ
 EXPORTS = [
     "tmac_packed_bytes", "tmac_pack_weights", "tmac_lut_bytes", "tmac_precompute_lut",
     "tmac_workspace_bytes", "tmac_mpgemm", "tmac_mpgemm_ex", "tmac_status_str", "tmac_version",
-    "tmac_last_error_detail", "tmac_stream_read", "tmac_mpgemv_fused", "tmac_mpgemv_fused_ex",
+    "tmac_last_error_detail", "tmac_stream_read", "tmac_lds_lookup_probe", "tmac_mpgemv_fused", "tmac_mpgemv_fused_ex",
     "tmac_fused_workspace_bytes", "tmac_mpgemm_fused",
 ]
 
@@ -85,6 +85,8 @@ def _load() -> C.CDLL:
     lib.tmac_last_error_detail.restype, lib.tmac_last_error_detail.argtypes = C.c_char_p, []
     lib.tmac_stream_read.restype = C.c_int
     lib.tmac_stream_read.argtypes = [P, SZ, P, I32, I32, P]
+    lib.tmac_lds_lookup_probe.restype = C.c_int
+    lib.tmac_lds_lookup_probe.argtypes = [I32, I32, P, P]
     return lib
 
 
@@ -137,6 +139,12 @@ def tmac_pack_weights(desc: tmac_wdesc, q: np.ndarray, scales: Optional[np.ndarr
     _check(lib.tmac_pack_weights(C.byref(desc), _np_ptr(q), _np_ptr(s16), _np_ptr(z16),
                                  _np_ptr(blob), nbytes), "tmac_pack_weights")
     return blob
+
+
+def tmac_lds_lookup_probe(workgroups: int, rounds: int, sink, stream=None) -> None:
+    """LDS lookup-rate probe (measurement helper): workgroups x 256 lanes x rounds x 16 reads of 16 bytes."""
+    _check(lib.tmac_lds_lookup_probe(workgroups, rounds, C.c_void_p(sink.data_ptr()), _stream_ptr(stream)),
+           "tmac_lds_lookup_probe")
 
 
 def tmac_stream_read(src, sink, per_thread: int = 4, nontemporal: bool = False, nbytes: Optional[int] = None,

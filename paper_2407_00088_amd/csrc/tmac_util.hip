@@ -1,6 +1,6 @@
-// Measurement helper: a plain streaming-read kernel.  It is the "what can a read-only kernel
-// reach on this chip" reference that the benchmark prints next to the lookup kernels; it takes
-// no part in the mpGEMM path.
+// Measurement helpers: a plain streaming-read kernel, the "what can a read-only kernel reach on
+// this chip" reference that the benchmark prints next to the lookup kernels, and a probe of the
+// LDS lookup rate; neither takes part in the mpGEMM path.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -32,9 +32,56 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const ru32x4* __restri
   if (acc == 0x9E3779B9u) sink[blockIdx.x & 63] = acc;
 }
 
+// Measurement helper: the lookup rate of LDS alone.  A workgroup holds 32 KB of tables laid out as
+// the batched kernels keep them (256-byte tables of sixteen 16-byte entries: eight activation
+// rows side by side) and every lane reads entries at data-dependent offsets, sixteen reads in
+// flight, with the address arithmetic of those kernels (one byte permute per read) and nothing
+// done with the values.  One read of a wavefront serves 64 lanes x 8 rows = 512 lookups.
+typedef __attribute__((address_space(3))) ru32x4 probe_lds_u32x4;
+__global__ __launch_bounds__(256) void lds_lookup_probe_kernel(int rounds, uint32_t* __restrict__ sink) {
+  __shared__ __attribute__((aligned(2048))) char tab[32768];
+  for (int i = threadIdx.x; i < 32768 / 16; i += 256)
+    reinterpret_cast<ru32x4*>(tab)[i] = ru32x4{(uint32_t)i, (uint32_t)i * 3u, (uint32_t)i * 5u, (uint32_t)i * 7u};
+  __syncthreads();
+  const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)tab);
+  uint32_t x = (threadIdx.x * 2654435761u) ^ (blockIdx.x * 40503u);
+  uint32_t keep = 0;
+  for (int r = 0; r < rounds; ++r) {
+    x = x * 1664525u + 1013904223u;                       // two index dwords (two bit planes): eight 4-bit indices each
+    const uint32_t x2 = x * 22695477u + 1u;
+    const uint32_t cbase = lds0 + (uint32_t)(r & 15) * 2048u;  // the chunk's eight tables
+    const uint32_t off[4] = {(x << 4) & 0xF0F0F0F0u, x & 0xF0F0F0F0u, (x2 << 4) & 0xF0F0F0F0u, x2 & 0xF0F0F0F0u};
+    ru32x4 e[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      // address = {0, cbase byte 2, cbase byte 1, one byte of the offsets}; table j % 8 of the chunk
+      const uint32_t a = __builtin_amdgcn_perm(off[2 * (j >> 3) + (j & 1)], cbase, 0x0C020100u + 4u + (uint32_t)((j >> 1) & 3));
+      e[j] = *reinterpret_cast<probe_lds_u32x4*>(a + (j & 7) * 256);
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) asm volatile("" ::"v"(e[j]));  // the values are "used": no instruction
+    keep += x >> 31;
+  }
+  if (keep == 0xFFFFFFFFu) sink[blockIdx.x & 63] = keep;  // practically never; keeps the loop alive
+}
+
 }  // namespace tmac
 
 using namespace tmac;
+
+extern "C" tmac_status tmac_lds_lookup_probe(int32_t workgroups, int32_t rounds, void* sink_dev, void* stream) {
+  if (!sink_dev || workgroups <= 0 || rounds <= 0 || rounds > (1 << 24)) return TMAC_EINVAL;
+  uint32_t* sink = static_cast<uint32_t*>(sink_dev);
+  int r = rounds;
+  void* args[] = {&r, &sink};
+  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(lds_lookup_probe_kernel), dim3((unsigned)workgroups),
+                                       dim3(256), args, 0, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) {
+    note_hip_error((int)e);
+    return TMAC_EHIP;
+  }
+  return TMAC_OK;
+}
 
 extern "C" tmac_status tmac_stream_read(const void* src_dev, size_t bytes, void* sink_dev, int32_t per_thread,
                                         int32_t nontemporal, void* stream) {
