@@ -827,3 +827,25 @@ def test_precompute_tables_against_the_oracle(T, torch, g, int_act):
     else:
         S = raw[s_off: s_off + N * 4].view(np.float32)
         assert np.allclose(S, a.astype(np.float64).sum(axis=1), rtol=1e-5, atol=1e-4)
+
+
+# ------------------------------------------------------ measurement helpers ----
+
+def test_measurement_helpers_run_and_check_their_arguments(T, torch):
+    """tmac_stream_read and tmac_lds_lookup_probe take no part in the path; they must launch, finish,
+    leave the sink alone (their stores practically never happen) and refuse bad arguments."""
+    from paper_2407_00088_amd import binding as B
+    src = torch.arange(1 << 16, dtype=torch.int32, device="cuda")
+    sink = torch.zeros(256, dtype=torch.uint8, device="cuda")
+    for per_thread in (1, 4, 8):
+        for nt in (False, True):
+            B.tmac_stream_read(src, sink, per_thread, nt)
+    B.tmac_lds_lookup_probe(64, 8, sink)
+    torch.cuda.synchronize()
+    assert not sink.cpu().numpy().any()
+    with pytest.raises(B.TmacError):
+        B.tmac_stream_read(src, sink, 3, False)
+    with pytest.raises(B.TmacError):
+        B.tmac_lds_lookup_probe(0, 8, sink)
+    with pytest.raises(B.TmacError):
+        B.tmac_lds_lookup_probe(64, 0, sink)
