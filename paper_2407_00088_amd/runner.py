@@ -38,8 +38,10 @@ class LinearLUT:
         blob = packed_host if packed_host is not None else B.tmac_pack_weights(self.desc, q, scales, zeros)
         self.packed_bytes = int(blob.size)
         self.packed = torch.from_numpy(blob).to(device)
-        self.lut = torch.empty(B.tmac_lut_bytes(max_N, K, group, self.lut_t, g=g), dtype=torch.uint8, device=device)
-        # the split of a call (and with it the workspace) depends on N: size for every N up to max_N
+        # the regions of the LUT buffer, the split of a call and with it the workspace depend on N:
+        # size both for every N up to max_N
+        lut_bytes = max(B.tmac_lut_bytes(n, K, group, self.lut_t, g=g) for n in range(1, max_N + 1))
+        self.lut = torch.empty(max(lut_bytes, 256), dtype=torch.uint8, device=device)
         ws = max(B.tmac_workspace_bytes(self.desc, n) for n in range(1, max_N + 1))
         self.workspace = torch.zeros(max(ws, 256), dtype=torch.uint8, device=device)
 

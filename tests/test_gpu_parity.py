@@ -849,3 +849,18 @@ def test_measurement_helpers_run_and_check_their_arguments(T, torch):
         B.tmac_lds_lookup_probe(0, 8, sink)
     with pytest.raises(B.TmacError):
         B.tmac_lds_lookup_probe(64, 0, sink)
+
+
+def test_one_holder_serves_every_row_count_up_to_its_maximum(T, torch):
+    """The LUT buffer's regions and the split of a call depend on N (64 rows need a larger LUT buffer
+    than 65): a holder sized for 100 rows must serve any smaller call."""
+    from paper_2407_00088_amd.runner import from_problem
+    p = wl.make_grouped(0, 1200, 100, 130, 1280, 4, 128, name="holder")
+    lin = from_problem(p, layout=L3)
+    ref = oracle_fp(p)
+    for N in (100, 64, 65, 3, 1):
+        out = lin.forward(torch.from_numpy(p.act[:N]).cuda())
+        one = lin.forward_one_call(torch.from_numpy(p.act[:N]).cuda())
+        torch.cuda.synchronize()
+        assert orc.rel_frobenius(out.cpu().numpy(), ref[:N]) <= FP_TOL, N
+        assert orc.rel_frobenius(one.cpu().numpy(), ref[:N]) <= FP_TOL, N
