@@ -179,7 +179,9 @@ tmac_status tmac_pack_weights(const tmac_wdesc* desc, const uint8_t* q_host,
  * the mirror-consolidated byte-split half tables of the register-table kernel, each region
  * 256-byte aligned.  The three regions of the register-table kernel exist up to N = 64 (beyond
  * that tmac_mpgemm returns TMAC_EUNSUPPORTED for layout 2; its fused call takes any N).
- * 0 on bad arguments. */
+ * The size is therefore not monotonic in N (64 rows need more than 65): a buffer shared by calls
+ * of different N takes the largest of their sizes.  The layout inside the buffer belongs to the
+ * N it was filled for.  0 on bad arguments. */
 size_t tmac_lut_bytes(int32_t N, int32_t K, int32_t g, int32_t group, tmac_lut_t lut);
 
 /* Online table precompute (Algorithm 1 Precompute; Section 3.1; mirror consolidation of
