@@ -108,8 +108,11 @@ typedef struct {
  *            share (lane & 7) cover one chunk.
  *            Stored 4-bit code of an index p:  p < 8 ? p : 8 | (15 - p)   (bit 3 = negate,
  *            bits 0..2 = entry of the stored half table, because T[p] = -T[15-p]).
- *            Byte y of a dword holds two codes of the same table, the low nibble for the
- *            "low" row and the high nibble for the "high" row (r = row in tile):
+ *            Byte y of a dword holds two codes of the same table, one for the "low" row and
+ *            one for the "high" row: bits 0..2 = entry of the low row's code, bit 7 = its negate
+ *            bit; bits 4..6 = entry of the high row's code, whose negate bit sits in bit 3 of
+ *            byte (y + 1) mod 4 of the same dword (rotated right by four bits, the dword shows
+ *            the high rows' codes as it shows the low rows' unrotated).  With r = row in tile:
  *              bits = 4: dword d = 0..3:  low = (r = 2d, plane y), high = (r = 2d+1, plane y)
  *              bits = 2: dword d = 0..1:  low = (r = 4d + y/2, plane y%2),
  *                                         high = (r = 4d + 2 + y/2, plane y%2)

@@ -96,6 +96,23 @@ static void pack_indices_layout3(const tmac_wdesc* d, const Geometry& ge, const 
       }
 }
 
+// Bit order of a layout-2 dword of eight folded codes.  In: byte y = {code of the "high" row in the
+// high nibble, code of the "low" row in the low nibble}, a code being {negate, 3-bit entry}.  Out:
+// byte y = {negate_low(y), entry_high(y), negate_high(y - 1 mod 4), entry_low(y)}: the low rows' negate
+// bits sit at bit 7 of their own byte, and after a rotation of the dword by four bits (which brings
+// the high rows' entries to bits 0..2) so do the high rows'.  The lookup kernel then needs no shift
+// of its own for either sign.
+static inline uint32_t place_negate_bits(uint32_t w) {
+  uint32_t out = 0;
+  for (int y = 0; y < 4; ++y) {
+    const uint32_t byte = (w >> (8 * y)) & 0xffu;
+    const uint32_t e_lo = byte & 7u, n_lo = (byte >> 3) & 1u, e_hi = (byte >> 4) & 7u, n_hi = byte >> 7;
+    out |= (e_lo | (e_hi << 4) | (n_lo << 7)) << (8 * y);
+    out |= (n_hi << 3) << (8 * ((y + 1) & 3));
+  }
+  return out;
+}
+
 // Layout 2: per (8-row tile, 16-k unit) four tables, each with `bits` dwords.  Byte y of a dword
 // carries two indices of the same table: the low nibble belongs to the "low" row set and the
 // high nibble to the "high" row set; which (row, plane) a byte stands for depends on how many
@@ -140,6 +157,7 @@ static void pack_indices_layout2(const tmac_wdesc* d, const Geometry& ge, const 
         else if (b == 2) { dst[nd++] = pair(0, 0); dst[nd++] = pair(1, 0); }
         else if (b == 1) { dst[nd++] = single(0); }
         else { dst[nd++] = pair(0, 0); dst[nd++] = pair(1, 0); dst[nd++] = single(2); }
+        for (int i = 0; i < nd; ++i) dst[i] = place_negate_bits(dst[i]);
       }
       // 16-byte piece i of the record goes to (piece i, slot of the unit's lane) of the block, so
       // that the lanes of a wavefront read one contiguous run per load instruction
@@ -220,4 +238,4 @@ extern "C" const char* tmac_status_str(tmac_status s) {
   return "unknown status";
 }
 
-extern "C" int32_t tmac_version(void) { return 1000 * 0 + 6; }
+extern "C" int32_t tmac_version(void) { return 1000 * 0 + 7; }

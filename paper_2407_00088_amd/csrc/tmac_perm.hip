@@ -7,7 +7,9 @@
 //
 //   * Mirror consolidation (Section 3.3): only entries 0..7 of a table are kept, 8 fp16 values =
 //     16 bytes.  A stored 4-bit code is {negate, 3-bit entry}; negation is an XOR of the fp16
-//     sign bit, which the packer has placed so that one shift-and-mask aligns it.
+//     sign bit, which the packer has placed at bit 7 of a byte: of the code's own byte for the
+//     "low" rows, and of the byte that the code's entry reaches when the dword is rotated by
+//     four bits for the "high" rows, so that neither needs a shift of its own.
 //   * fp16 entries as two 8-bit tables (Section 4: "split float16 into two 8-bit LUTs"): the low
 //     bytes and the high bytes of the 8 entries form two 8-byte sources (the precompute kernel
 //     stores them already split); two permutes fetch both halves of 4 entries, two more permutes
@@ -353,10 +355,11 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
             // v_and_or_b32 (a VOP3 instruction takes a single literal or scalar operand)
             uint32_t pv;
             asm("v_mov_b32 %0, %1" : "=v"(pv) : "s"(planes));
+            const uint32_t xh = __builtin_amdgcn_alignbit(x, x, 4);  // the "high" rows: entries in bits 0..2, negate in bit 7
             vA = lookq(x & 0x07070707u);
-            wA = bperm(WHI, WLO, ((x >> 3) & 0x01010101u) | pv);
-            vB = lookq((x >> 4) & 0x07070707u);
-            wB = bperm(WHI, WLO, ((x >> 7) & 0x01010101u) | pv);
+            wA = bperm(WHI, WLO, ((x >> 7) & 0x01010101u) | pv);
+            vB = lookq(xh & 0x07070707u);
+            wB = bperm(WHI, WLO, ((xh >> 7) & 0x01010101u) | pv);
           };
           auto dot4 = [&](uint32_t v, uint32_t w, int a) { return __builtin_amdgcn_sdot4((int)v, (int)w, a, false); };
           auto quadq = [&](uint32_t x, int& a_lo, int& a_hi) {  // 4 planes of one row (low nibbles), one (high)
@@ -412,33 +415,36 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
           p01 = bperm(hi, lo, 0x05010400u);  // fp16 pair of bytes 0 and 1
           p23 = bperm(hi, lo, 0x07030602u);  // fp16 pair of bytes 2 and 3
         };
+        // the "high" rows of a dword: rotated by four bits their entries sit in bits 0..2 and their
+        // negate bits (stored in bit 3 of the following byte) in bit 7 of each byte
+        auto hi_set = [](uint32_t x) { return __builtin_amdgcn_alignbit(x, x, 4); };
         auto quad = [&](uint32_t x, float& a_lo, float& a_hi) {  // 4 planes of one row (low nibbles), one (high)
           uint32_t a, b;
-          look(x & 0x07070707u, (x << 4) & 0x80808080u, a, b);
+          look(x & 0x07070707u, x & 0x80808080u, a, b);
           a_lo = dot2(a, W01, a_lo);
           a_lo = dot2(b, W23, a_lo);
-          look((x >> 4) & 0x07070707u, x & 0x80808080u, a, b);
+          look(hi_set(x) & 0x07070707u, hi_set(x) & 0x80808080u, a, b);
           a_hi = dot2(a, W01, a_hi);
           a_hi = dot2(b, W23, a_hi);
         };
         auto pair = [&](uint32_t x, float* a4) {  // planes 0,1 of rows 0,1 (low) and 2,3 (high) of a4
           uint32_t a, b;
-          look(x & 0x07070707u, (x << 4) & 0x80808080u, a, b);
+          look(x & 0x07070707u, x & 0x80808080u, a, b);
           a4[0] = dot2(a, W01, a4[0]);
           a4[1] = dot2(b, W01, a4[1]);
-          look((x >> 4) & 0x07070707u, x & 0x80808080u, a, b);
+          look(hi_set(x) & 0x07070707u, hi_set(x) & 0x80808080u, a, b);
           a4[2] = dot2(a, W01, a4[2]);
           a4[3] = dot2(b, W01, a4[3]);
         };
         auto single = [&](uint32_t x, uint16_t wgt, float* a8) {  // one plane of rows 0..3 (low), 4..7 (high)
           const uint32_t wl = h2pack(wgt, H_0), wh = h2pack(H_0, wgt);
           uint32_t a, b;
-          look(x & 0x07070707u, (x << 4) & 0x80808080u, a, b);
+          look(x & 0x07070707u, x & 0x80808080u, a, b);
           a8[0] = dot2(a, wl, a8[0]);
           a8[1] = dot2(a, wh, a8[1]);
           a8[2] = dot2(b, wl, a8[2]);
           a8[3] = dot2(b, wh, a8[3]);
-          look((x >> 4) & 0x07070707u, x & 0x80808080u, a, b);
+          look(hi_set(x) & 0x07070707u, hi_set(x) & 0x80808080u, a, b);
           a8[4] = dot2(a, wl, a8[4]);
           a8[5] = dot2(a, wh, a8[5]);
           a8[6] = dot2(b, wl, a8[6]);

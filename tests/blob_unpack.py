@@ -52,8 +52,13 @@ def unpack_layout2(blob: np.ndarray):
         for d in range(bits):
             for y in range(4):
                 r_lo, r_hi, plane = byte_meaning(bits, d, y)
-                byte = (idx[:, :, tb, d] >> (8 * y)) & 0xFF            # [tiles, units]
-                for code, r in ((byte & 15, r_lo), (byte >> 4, r_hi)):
+                word = idx[:, :, tb, d]
+                byte = (word >> (8 * y)) & 0xFF                        # [tiles, units]
+                nxt = (word >> (8 * ((y + 1) % 4))) & 0xFF
+                # byte y = {negate_low, entry_high (3 bits), negate_high of byte y - 1, entry_low (3 bits)}
+                code_lo = (byte & 7) | ((byte >> 7) << 3)
+                code_hi = ((byte >> 4) & 7) | (((nxt >> 3) & 1) << 3)
+                for code, r in ((code_lo, r_lo), (code_hi, r_hi)):
                     p = unfold(code.astype(np.int64))
                     for e in range(4):
                         bit = ((p >> e) & 1).astype(np.uint8)

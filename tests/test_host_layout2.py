@@ -47,8 +47,8 @@ def test_layout2_special_matrices(bits):
     for q in (np.zeros((M, K), np.uint8), np.full((M, K), top, np.uint8)):
         _, q2, _, _ = unpack_layout2(T.tmac_pack_weights(d, q))
         assert np.array_equal(q2, q)
-    # all-max codes: every index is 15, stored as {negate, entry 0} = 8 -> exactly one bit per
-    # stored nibble inside the matrix, none in the padding
+    # all-max codes: every index is 15, stored as {negate, entry 0} -> exactly one bit per stored
+    # code inside the matrix, none in the padding
     blob = T.tmac_pack_weights(d, np.full((M, K), top, np.uint8))
     idx_off, idx_bytes = struct.unpack_from("<2Q", blob.tobytes(), 56)
     ones = int(np.unpackbits(blob[idx_off: idx_off + idx_bytes]).sum())
@@ -78,7 +78,10 @@ def test_mirror_fold_matches_table_symmetry():
         tile, r = divmod(p, 8)
         word = int(idx[tile, 0, 0, 0])
         y = r % 4
-        code = (word >> (8 * y + (4 if r >= 4 else 0))) & 15
+        byte, nxt = (word >> (8 * y)) & 0xFF, (word >> (8 * ((y + 1) % 4))) & 0xFF
+        # rows 0..3: entry in bits 0..2, negate in bit 7; rows 4..7: entry in bits 4..6, negate in bit 3
+        # of the following byte
+        code = ((byte >> 4) & 7) | (((nxt >> 3) & 1) << 3) if r >= 4 else (byte & 7) | ((byte >> 7) << 3)
         val = -half[code & 7] if code & 8 else half[code & 7]
         assert val == lut[p]
 
