@@ -295,6 +295,9 @@ __device__ __forceinline__ void rows_chunk(const uint32_t (&x)[BITS], uint32_t c
   }
 }
 
+// Scale of activation row n (int8 activations quantised per token), 1 where there is none.
+__device__ __forceinline__ float rows_act_scale(const RowsParams& p, int n) { return p.act_scale ? p.act_scale[n] : 1.0f; }
+
 // Sum of activation row n from the LUT buffer (one scale per row or per tensor: nq = 1).
 template <bool IS_INT>
 __device__ __forceinline__ void rows_row_sum(const RowsParams& p, int n, float& Sf, int& Si) {
@@ -310,8 +313,7 @@ __device__ __forceinline__ void rows_row_sum(const RowsParams& p, int n, float& 
 // scale per row or per tensor; Sf / Si = the sum of activation row n in that case.
 template <bool IS_INT>
 __device__ __forceinline__ void rows_finish(const RowsParams& p, int n, int m, float vf, int vi, float s, float z,
-                                            float Sf, int Si) {
-  const float as = p.act_scale ? p.act_scale[n] : 1.0f;
+                                            float Sf, int Si, float as) {
   float res;
   int ires = 0;
   if (p.grouped) {
@@ -439,7 +441,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
     float Sf;
     int Si;
     rows_row_sum<IS_INT>(p, n, Sf, Si);
-    rows_finish<IS_INT>(p, n, m, vf, vi, s, z, Sf, Si);
+    rows_finish<IS_INT>(p, n, m, vf, vi, s, z, Sf, Si, rows_act_scale(p, n));
   };
   constexpr bool RAW_INT = IS_INT;  // ungrouped integer tables: partial sums are exact integers
   const int nz = gridDim.z;
@@ -718,7 +720,8 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows8_kernel(const Row
       float Sf;
       int Si;
       rows_row_sum<IS_INT>(p, n0 + t, Sf, Si);
-      rows_finish<IS_INT>(p, n0 + t, m, p.grouped ? acc[t] : (float)L[t], IS_INT ? (int)L[t] : 0, s, z, Sf, Si);
+      rows_finish<IS_INT>(p, n0 + t, m, p.grouped ? acc[t] : (float)L[t], IS_INT ? (int)L[t] : 0, s, z, Sf, Si,
+                          rows_act_scale(p, n0 + t));
     }
     return;
   }
@@ -735,7 +738,9 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows8_kernel(const Row
 }
 
 // Adds the partial sums [nz][N][Mp] of the K slices in slice order and finishes: one thread per
-// output, sixteen loads in flight.
+// output.  Everything the thread needs is requested before the first wait (scale and zero, the
+// activation scale, the row sum or its per-slice parts, sixteen partial sums per round), so that a
+// call pays one round trip to memory, not one per operand.
 template <bool IS_INT>
 __global__ __launch_bounds__(64) void rows_sum_kernel(const RowsParams p, int nz) {
   const int m = blockIdx.x * 64 + threadIdx.x, n = blockIdx.y;
@@ -743,40 +748,40 @@ __global__ __launch_bounds__(64) void rows_sum_kernel(const RowsParams p, int nz
   const bool raw_int = IS_INT && !p.grouped;
   const float* src = p.ws_part + (size_t)n * p.Mp + m;
   const size_t stride = (size_t)p.N * p.Mp;
+  const bool own_sz = !p.grouped && !p.per_tensor;
+  const uint32_t szv = own_sz ? p.sz[(size_t)(m >> 6) * p.nq * 64 + (m & 63)] : 0u;
+  const float as = rows_act_scale(p, n);
+  // fused table build: the row sum is the sum of the slices' sums, taken in slice order below
+  const bool slice_sums = !p.grouped && p.ws_srow != nullptr;
+  float Sf = 0.f;
+  int Si = 0;
+  if (!p.grouped && !slice_sums) rows_row_sum<IS_INT>(p, n, Sf, Si);
   float sf = 0.f;
   int si = 0;
   for (int sl0 = 0; sl0 < nz; sl0 += 16) {
-    float v[16];
+    float v[16], r[16];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) v[u] = src[(size_t)min(sl0 + u, nz - 1) * stride];
+    for (int u = 0; u < 16; ++u) {
+      const int sl = min(sl0 + u, nz - 1);
+      v[u] = src[(size_t)sl * stride];
+      r[u] = slice_sums ? p.ws_srow[(size_t)sl * p.N + n] : 0.f;
+    }
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
       if (sl0 + u < nz) {
         if (raw_int) si += __float_as_int(v[u]);
         else sf += v[u];
+        if constexpr (IS_INT) Si += slice_sums ? __float_as_int(r[u]) : 0;
+        else Sf += r[u];
       }
     }
   }
   float s = p.wscale, z = p.zero_point;
-  if (!p.grouped && !p.per_tensor) {
-    const uint32_t v = p.sz[(size_t)(m >> 6) * p.nq * 64 + (m & 63)];
-    s = __half2float(__ushort_as_half((uint16_t)(v & 0xffffu)));
-    z = __half2float(__ushort_as_half((uint16_t)(v >> 16)));
+  if (own_sz) {
+    s = __half2float(__ushort_as_half((uint16_t)(szv & 0xffffu)));
+    z = __half2float(__ushort_as_half((uint16_t)(szv >> 16)));
   }
-  float Sf = 0.f;
-  int Si = 0;
-  if (!p.grouped) {
-    if (p.ws_srow) {  // fused table build: the row sum is the sum of the slices' sums, in slice order
-      for (int sl = 0; sl < nz; ++sl) {
-        const float v = p.ws_srow[(size_t)sl * p.N + n];
-        if constexpr (IS_INT) Si += __float_as_int(v);
-        else Sf += v;
-      }
-    } else {
-      rows_row_sum<IS_INT>(p, n, Sf, Si);
-    }
-  }
-  rows_finish<IS_INT>(p, n, m, sf, si, s, z, Sf, Si);
+  rows_finish<IS_INT>(p, n, m, sf, si, s, z, Sf, Si, as);
 }
 
 template <bool IS_INT, int BITS, int NT, bool FUSED>
