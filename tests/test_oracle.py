@@ -487,3 +487,28 @@ def test_fp16_tree_tables_route_error():
     e_tree = orc.rel_frobenius(orc.lut_mpgemm(p.act, p.q, 4, p.scales, p.zeros, p.group, table_dtype="fp16_tree"), ref)
     print(f"fp16 tables: once-rounded {e_once:.2e}, built by fp16 additions {e_tree:.2e}")
     assert 5e-5 < e_once < e_tree < 6e-4
+
+
+def test_fp16_routes_keep_their_error_on_heavy_tailed_activations():
+    """The roundings of the fp16 routes (tables built by fp16 additions, narrow chunk sums) scale with
+    the entries themselves: outlier channels 50 or 300 times the rest, Student-t tails or an all-positive
+    offset leave the relative error where it is on Gaussian data, a fifth of the 2e-3 bar."""
+    rng = np.random.default_rng(95)
+    M, K, G, b = 32, 2048, 128, 4
+    q = rng.integers(0, 16, size=(M, K), dtype=np.uint8)
+    s = rng.uniform(0.01, 0.1, size=(M, K // G)).astype(np.float16)
+    z = rng.uniform(0, 15, size=(M, K // G)).astype(np.float16)
+    base = rng.standard_normal((2, K))
+    cases = {
+        "gauss": base,
+        "1% x50": base * np.where(rng.random((2, K)) < 0.01, 50.0, 1.0),
+        "0.2% x300": base * np.where(rng.random((2, K)) < 0.002, 300.0, 1.0),
+        "student t3": rng.standard_t(3, size=(2, K)),
+        "positive": np.abs(base) + 3.0,
+    }
+    for name, a in cases.items():
+        a = a.astype(np.float16)
+        ref = orc.mpgemm_definition(a, q, s, z, group=G)
+        e_tree = orc.rel_frobenius(orc.lut_mpgemm(a, q, b, s, z, group=G, table_dtype="fp16_tree"), ref)
+        e_narrow = orc.rel_frobenius(orc.lut_mpgemm_narrow(a, q, b, s, z, G), ref)
+        assert e_tree < 5e-4 and e_narrow < 7e-4, (name, e_tree, e_narrow)
