@@ -192,6 +192,21 @@ def test_small_magnitude_activations(T, torch, layout):
     check_fp(T, torch, p, layout=layout)
 
 
+@pytest.mark.parametrize("N", [1, 16])
+def test_heavy_tailed_activations(T, torch, layout, N):
+    """Outlier channels (0.2 % of the activations 300 times the rest, magnitudes up to about 1000): the
+    fp16 tables and chunk sums stay finite and the error stays where it is on Gaussian data."""
+    if N > 8 and layout != L3:
+        pytest.skip("the register-table kernel serves at most 8 rows here")
+    p = wl.make_grouped(0, 88 + N, N, 96, 4096, 4, 128, name="heavy_tail")
+    rng = np.random.default_rng(88)
+    boost = np.where(rng.random(p.act.shape) < 0.002, 300.0, 1.0)
+    p.act = (p.act.astype(np.float64) * boost).astype(np.float16)
+    assert np.abs(p.act.astype(np.float64)).max() > 100
+    err = check_fp(T, torch, p, layout=layout)
+    assert err <= 8e-4
+
+
 # ------------------------------------------------------------ integer path ----
 
 @pytest.mark.parametrize("M,K,N", [(48, 256, 1), (100, 192, 3), (16, 8640, 1), (130, 3200, 5)])
