@@ -20,6 +20,11 @@
 //   * Bit-plane shift-accumulate (Eq. 1): the widening v_fma_mix_f32 takes the fp16 chunk sum and
 //     multiplies by 2^i.
 //   * Scale, zero and bias once per quantisation group (Section 4, bit-serial linear transform).
+//     In the many-row kernel with fp16 tables the group's scale rides on the plane weights
+//     (s/2 * 2^i, four multiplies when a group starts) and the bias term s * (mid - z) * S is
+//     added at the same moment, so a group costs 12 instructions instead of 32 and the finished
+//     group sums need no registers of their own; integer tables keep exact integer group sums
+//     and convert once per group.
 //   * Axis order (Section 3.2 "axis reordering"): K is walked slice by slice inside the
 //     workgroup, so only a 32 KB slice of the tables is live in LDS; the sums of a row stay
 //     in the lane's registers: fixed order.
@@ -357,10 +362,14 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
   const uint32_t* my_sz = p.sz + (size_t)tile * p.nq * 64 + lane;
   const uint32_t lds0 = (uint32_t)(uintptr_t)((rows_lds_char*)tab);  // a multiple of 1024
 
-  float acc[NT];   // finished group sums (grouped mode)
-  AccT L[NT];      // look-up sums of the current quantisation group (or of the whole row)
+  // fp tables: L is the running result, the plane weights w carry half the current group's scale and
+  // the group's bias term is added when the group starts; integer tables (and one scale per row or
+  // tensor): L is the raw look-up sum of the group (row), finished in acc at the group's end
+  float acc[NT];
+  AccT L[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) { acc[t] = 0.f; L[t] = 0; }
+  float w[4] = {p.pw[0], p.pw[1], p.pw[2], p.pw[3]};
 
   auto load_idx = [&](int c, uint32_t (&x)[BITS]) {
     const uint32_t* src = my_idx + (size_t)c * 64 * BITS;
@@ -380,10 +389,22 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
   const int cz0 = blockIdx.z * p.cps, cz1 = min(cz0 + p.cps, p.n_chunks);
   const int kg_end = min(cz1 * TPC, p.KG);  // tables beyond it are read as zero
   int gq = p.grouped ? cz0 / p.cpg : 0, cg = 0;  // current quantisation group, chunks done in it (wave-uniform)
-  uint32_t szv = 0;          // {scale, zero} of the lane's row for the current group
-  float Sg[NT];
+  // {scale, zero} of the lane's row and the activation sums of a group, requested one group ahead
+  uint32_t szv = 0, szv_next = 0;
+  float Sg[NT], Sg_next[NT];
+  auto load_group = [&](int g) {
+    const int gc = min(g, p.nq - 1);
+    szv_next = my_sz[(size_t)gc * 64];
 #pragma unroll
-  for (int t = 0; t < NT; ++t) Sg[t] = 0.f;
+    for (int t = 0; t < NT; ++t) {
+      const int n = min(n0 + t, p.N - 1);
+      if constexpr (IS_INT) Sg_next[t] = (float)static_cast<const int*>(p.S)[(size_t)n * p.nq + gc];
+      else Sg_next[t] = static_cast<const float*>(p.S)[(size_t)n * p.nq + gc];
+    }
+  };
+#pragma unroll
+  for (int t = 0; t < NT; ++t) Sg[t] = Sg_next[t] = 0.f;
+  if (p.grouped) load_group(gq);
   uint32_t xn[BITS];
   load_idx(cz0, xn);
 
@@ -404,23 +425,31 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
       for (int b = 0; b < BITS; ++b) x[b] = xn[b];
       if (c + 1 < cz1) load_idx(c + 1, xn);  // next chunk's indices, one chunk ahead
       if (p.grouped && cg == 0 && gq < p.nq) {  // (chunks in the K padding belong to no group)
-        // scale/zero of the group that starts here and the activation sums its bias term needs
-        szv = my_sz[(size_t)gq * 64];
+        // a group starts: its scale/zero and activation sums have been requested a group ago
+        szv = szv_next;
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          const int n = min(n0 + t, p.N - 1);
-          if constexpr (IS_INT) Sg[t] = (float)static_cast<const int*>(p.S)[(size_t)n * p.nq + gq];
-          else Sg[t] = static_cast<const float*>(p.S)[(size_t)n * p.nq + gq];
+        for (int t = 0; t < NT; ++t) Sg[t] = Sg_next[t];
+        load_group(gq + 1);
+        if constexpr (!IS_INT) {
+          const float s = __half2float(__ushort_as_half((uint16_t)(szv & 0xffffu)));
+          const float z = __half2float(__ushort_as_half((uint16_t)(szv >> 16)));
+          const float hs = 0.5f * s, bz = s * (p.mid - z);
+#pragma unroll
+          for (int b = 0; b < 4; ++b) w[b] = hs * p.pw[b];
+#pragma unroll
+          for (int t = 0; t < NT; ++t) L[t] = fmaf(bz, Sg[t], L[t]);  // bias term of Section 4's linear transform
         }
       }
-      rows_chunk<IS_INT, BITS, NT, G>(x, lds0 + (uint32_t)(c - c0) * (uint32_t)CB, L, p.pw);
+      rows_chunk<IS_INT, BITS, NT, G>(x, lds0 + (uint32_t)(c - c0) * (uint32_t)CB, L, w);
       if (p.grouped && gq < p.nq && ++cg == p.cpg) {
-        const float s = __half2float(__ushort_as_half((uint16_t)(szv & 0xffffu)));
-        const float z = __half2float(__ushort_as_half((uint16_t)(szv >> 16)));
+        if constexpr (IS_INT) {
+          const float s = __half2float(__ushort_as_half((uint16_t)(szv & 0xffffu)));
+          const float z = __half2float(__ushort_as_half((uint16_t)(szv >> 16)));
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          acc[t] = fmaf(s, fmaf(p.mid - z, Sg[t], 0.5f * (float)L[t]), acc[t]);
-          L[t] = 0;
+          for (int t = 0; t < NT; ++t) {
+            acc[t] = fmaf(s, fmaf(p.mid - z, Sg[t], 0.5f * (float)L[t]), acc[t]);
+            L[t] = 0;
+          }
         }
         cg = 0;
         ++gq;
@@ -450,7 +479,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       if (n0 + t >= p.N) break;
-      finish(n0 + t, p.grouped ? acc[t] : (float)L[t], IS_INT ? (int)L[t] : 0);
+      finish(n0 + t, (IS_INT && p.grouped) ? acc[t] : (float)L[t], IS_INT ? (int)L[t] : 0);
     }
     return;
   }
@@ -468,7 +497,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
       const int n = n0 + t;
       if (n < p.N) {
         const size_t o = ((size_t)blockIdx.z * p.N + n) * p.Mp + (size_t)tile_raw * 64 + lane;
-        const float v = p.grouped ? acc[t] : (raw_int ? __int_as_float((int)L[t]) : (float)L[t]);
+        const float v = (IS_INT && p.grouped) ? acc[t] : (raw_int ? __int_as_float((int)L[t]) : (float)L[t]);
         __hip_atomic_store(p.ws_part + o, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
