@@ -429,7 +429,6 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
         szv = szv_next;
 #pragma unroll
         for (int t = 0; t < NT; ++t) Sg[t] = Sg_next[t];
-        load_group(gq + 1);
         if constexpr (!IS_INT) {
           const float s = __half2float(__ushort_as_half((uint16_t)(szv & 0xffffu)));
           const float z = __half2float(__ushort_as_half((uint16_t)(szv >> 16)));
@@ -439,6 +438,10 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
 #pragma unroll
           for (int t = 0; t < NT; ++t) L[t] = fmaf(bz, Sg[t], L[t]);  // bias term of Section 4's linear transform
         }
+        // (the requests for the next group come after the last use of this group's values, so that they
+        // can land in the same registers and nobody has to wait for them before the next group starts)
+        __builtin_amdgcn_sched_barrier(0);
+        load_group(gq + 1);
       }
       rows_chunk<IS_INT, BITS, NT, G>(x, lds0 + (uint32_t)(c - c0) * (uint32_t)CB, L, w);
       if (p.grouped && gq < p.nq && ++cg == p.cpg) {
