@@ -385,6 +385,19 @@ def main():
             del c
             torch.cuda.empty_cache()
         detail["stacked_projections"] = stacked
+        # the same kernel on Llama-2-70B-shaped matrices (34-125 MB per call): how the fraction of the
+        # roofline grows once the fixed cost of a launch is spread over more bytes
+        larger = []
+        for M, K in ((8192, 8192), (28672, 8192), (8192, 28672)):
+            c = Case(wl.make_grouped(3, 40 + M // 1000 + K // 4000, 1, M, K, 4, 128, name=f"llama2_70b_{M}x{K}_w4_n1"))
+            fu = measure_kernel(c, max(200, args.steps // 4), c.fused)
+            ru = measure_kernel(c, max(200, args.steps // 4), c.stream_read)
+            larger.append({"name": c.p.name, "fused_us": round(fu, 3), "plain_read_of_same_bytes_us": round(ru, 3),
+                           "bytes": c.bytes, "GBps": round(c.bytes / fu / 1e3, 1),
+                           "frac_hbm_peak": round(c.bytes / fu / 1e3 / HBM_PEAK_GBPS, 4)})
+            del c
+            torch.cuda.empty_cache()
+        detail["larger_matrices"] = larger
         # one Llama-2-7B decoder block, N = 1: its seven projections as seven fused launches, and with
         # Q,K,V and gate,up stacked along M (four launches); weights of every launch from its own ring
         blk = {}
