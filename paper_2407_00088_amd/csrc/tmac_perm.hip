@@ -684,9 +684,12 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
     const int passes = (p.bs.nB + NW - 1) / NW;
     if ((double)508.0 * ((1 << desc->bits) - 1) * 256.0 * passes >= 16777216.0) return TMAC_EUNSUPPORTED;
   }
-  // two row tiles per workgroup halve the table traffic but also the number of waves; one tile
-  // per workgroup measured faster on every decode shape, so it is the default
-  const int rt = rows_per_group == 16 ? 2 : 1;
+  // Two row tiles per workgroup share one set of tables (built or loaded once for 16 rows) but
+  // halve the number of wavefronts.  Measured: worth 3-6 % once a call has more than about 8000
+  // wavefronts, eight per SIMD (22016 x 4096, 8192 x 8192, 28672 x 8192), a loss of 2-5 % below
+  // (4096 x 4096 up to 12288 x 4096): the default follows the wavefront count.
+  int rt = rows_per_group == 16 ? 2 : 1;
+  if (rows_per_group == 0 && !q8 && (int64_t)ge.n_tiles * NW >= 8192) rt = 2;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int gm = one_group ? 0 : (desc->group % 128 == 0 ? 2 : 1);
   {

@@ -844,6 +844,26 @@ def test_precompute_tables_against_the_oracle(T, torch, g, int_act):
         assert np.allclose(S, a.astype(np.float64).sum(axis=1), rtol=1e-5, atol=1e-4)
 
 
+def test_large_call_takes_two_row_tiles_per_workgroup_by_default(T, torch):
+    """From about 8000 wavefronts on (here 8192 x 8192: 1024 row tiles x 8 waves) the register-table
+    kernel serves 16 rows per workgroup unless told otherwise: the default call, the call with 8 rows
+    per workgroup and the fused call agree with the oracle on sampled rows (the oracle takes them one
+    at a time at this size) and, the order of additions per row being the same, with each other."""
+    from paper_2407_00088_amd.binding import tmac_tuning
+    p = wl.make_grouped(0, 1300, 1, 8192, 8192, 4, 128, name="rt_auto")
+    lin = make_lin(p, L2)
+    A = torch.from_numpy(p.act).cuda()
+    auto = lin.forward(A).cpu().numpy()
+    rows8 = lin.forward(A, tuning=tmac_tuning(8)).cpu().numpy()
+    fused = lin.forward_fused(A).cpu().numpy()
+    rows = np.random.default_rng(1300).choice(p.M, size=96, replace=False)
+    ref = orc.mpgemm_definition(p.act, p.q[rows], p.scales[rows], p.zeros[rows], p.group)
+    for got in (auto, rows8, fused):
+        assert orc.rel_frobenius(got[:, rows], ref) <= FP_TOL
+    assert np.array_equal(auto.view(np.uint32), rows8.view(np.uint32))
+    assert np.array_equal(auto.view(np.uint32), fused.view(np.uint32))
+
+
 # ------------------------------------------------------ measurement helpers ----
 
 def test_measurement_helpers_run_and_check_their_arguments(T, torch):
