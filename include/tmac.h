@@ -268,7 +268,7 @@ tmac_status tmac_mpgemm_fused(const tmac_wdesc* desc, const void* packed_dev, co
 /* Launch-shape knobs for benchmarking sweeps; 0 = library default.
  *   rows_per_group   register-table kernel (layout 2): weight rows per workgroup, 8 or 16
  *                    (default: 8, and 16 once a call has more than about 8000 wavefronts, i.e.
- *                    M / 8 * ceil(K / 1024) >= 8192, where sharing one set of tables between two
+ *                    N * M / 8 * ceil(K / 1024) >= 8192, where sharing one set of tables between two
  *                    row tiles pays); must be 0 for layout 3 (TMAC_EUNSUPPORTED otherwise) */
 typedef struct {
   int32_t rows_per_group, reserved[7];

@@ -687,9 +687,10 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
   // Two row tiles per workgroup share one set of tables (built or loaded once for 16 rows) but
   // halve the number of wavefronts.  Measured: worth 3-6 % once a call has more than about 8000
   // wavefronts, eight per SIMD (22016 x 4096, 8192 x 8192, 28672 x 8192), a loss of 2-5 % below
-  // (4096 x 4096 up to 12288 x 4096): the default follows the wavefront count.
+  // (4096 x 4096 up to 12288 x 4096); with several activation rows (one GEMV each in one launch)
+  // the same count decides (4096 x 4096: from four rows on).  The default follows it.
   int rt = rows_per_group == 16 ? 2 : 1;
-  if (rows_per_group == 0 && !q8 && (int64_t)ge.n_tiles * NW >= 8192) rt = 2;
+  if (rows_per_group == 0 && !q8 && (int64_t)ge.n_tiles * NW * N >= 8192) rt = 2;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int gm = one_group ? 0 : (desc->group % 128 == 0 ? 2 : 1);
   {
