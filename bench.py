@@ -30,7 +30,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 ALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9   # one vector instruction per lane and cycle on every CU
-ALU_OPS_PER_LOOKUP_ADD = 46.0 / 64.0   # batched kernel, eight activation rows per workgroup
+ALU_OPS_PER_LOOKUP_ADD = 83.0 / 128.0  # batched kernel, sixteen activation rows per workgroup (N >= 128)
 RING_MB = 576  # > 2 x 256 MB Infinity Cache
 
 # HBM bytes of the three launches of one step (default configuration: fused kernel, 8 rows per
@@ -240,10 +240,11 @@ def main():
                              "precompute_us": round(pu, 2),
                              "TOPS_equiv": round(flops / us / 1e6, 2),
                              "lookups_per_s": round(lookup_adds / us * 1e6, -6),
-                             # plain-ALU roofline of the batched kernel: 46 vector instructions per 64
-                             # lookup-adds of a lane is what the method needs in this kernel (2 offset masks,
-                             # 8 address permutes, 28 packed adds, 8 widening multiply-adds per chunk and
-                             # plane of eight activation rows); peak = 256 CUs x 64 lanes x 2.4 GHz
+                             # plain-ALU roofline of the batched kernel: 83 vector instructions per 128
+                             # lookup-adds of a lane is what the method needs in this kernel (3 offset
+                             # instructions, 8 address permutes, 56 packed adds, 16 widening multiply-adds
+                             # per chunk and plane of sixteen activation rows); peak = 256 CUs x 64 lanes
+                             # x 2.4 GHz
                              "roofline": {"bound": "alu", "unit": "lane-op/s", "peak": ALU_PEAK_LANE_OPS,
                                           "achieved": round(lookup_adds * ALU_OPS_PER_LOOKUP_ADD / (us - pu) * 1e6, -9),
                                           "frac": round(lookup_adds * ALU_OPS_PER_LOOKUP_ADD / (us - pu) * 1e6

@@ -161,8 +161,9 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
 
 // Batched lookup kernel (layout 3); defined in tmac_rows.hip.
 struct RowsPlan {
-  int nt;                     // activation rows per workgroup (4 or 8)
-  int n_tiles_n, row_blocks;  // workgroups along N (nt activation rows each) and M (256 weight rows each)
+  int nt;                     // activation rows per n tile of the LUT buffer (4 or 8)
+  int oct;                    // n tiles per workgroup (2 for many rows at g = 4, else 1)
+  int n_tiles_n, row_blocks;  // workgroups along N (nt * oct activation rows each) and M (256 weight rows each)
   int cps, slices;            // 32-k chunks per K slice, number of K slices (gridDim.z)
   bool eight;                 // slices of eight chunks: the kernel pair for few activation rows serves the call
   size_t part_bytes, ctr_bytes;  // workspace: partial sums and arrival counters (0 when slices == 1)

@@ -217,16 +217,20 @@ __device__ __forceinline__ void rows_stage_item(const RowsParams& p, char* tab, 
 // The lookups of one 32-k chunk: x = the lane's `BITS` index dwords, cbase = LDS byte address of
 // the chunk's first table (low byte zero); L += sum over planes of 2^plane * (sum of the looked-up
 // entries), per activation row.
-template <bool IS_INT, int BITS, int NT, int G, typename AccT>
-__device__ __forceinline__ void rows_chunk(const uint32_t (&x)[BITS], uint32_t cbase, AccT (&L)[NT], const float (&pw)[4]) {
+// With OCT = 2 the workgroup serves two sets of NT activation rows whose tables sit OSTRIDE bytes
+// apart in LDS: one address (one permute) then feeds two reads, and L holds 2 NT sums.
+template <bool IS_INT, int BITS, int NT, int G, typename AccT, int OCT = 1, int OSTRIDE = 0>
+__device__ __forceinline__ void rows_chunk(const uint32_t (&x)[BITS], uint32_t cbase, AccT (&L)[NT * OCT],
+                                           const float (&pw)[4]) {
   using Sh = RowsShape<NT, G>;
   constexpr int TPC = Sh::TPC, HD = Sh::HD, TB = Sh::TB;
+  static_assert(OCT == 1 || (OCT == 2 && NT == 8 && TPC * OCT <= 16), "two row sets: eight rows each, g = 4");
   // rounds of 16 LDS reads (one, two or four planes at g = 2, 4, 8): the hardware counts at
   // most 15 outstanding LDS operations exactly, so a round's reads can be consumed as they return
-  constexpr int PL = 16 / TPC;
+  constexpr int PL = 16 / (TPC * OCT);
 #pragma unroll
   for (int b0 = 0; b0 < BITS; b0 += PL) {
-    uint32_t e[PL][TPC][HD];
+    uint32_t e[PL][TPC][OCT * HD];
 #pragma unroll
     for (int bb = 0; bb < PL; ++bb) {
       const int b = b0 + bb;
@@ -261,8 +265,11 @@ __device__ __forceinline__ void rows_chunk(const uint32_t (&x)[BITS], uint32_t c
           const ru32x2v r = *reinterpret_cast<rows_lds_u32x2*>(a + j * TB);
           e[bb][j][0] = r.x; e[bb][j][1] = r.y;
         } else {
-          const ru32x4v r = *reinterpret_cast<rows_lds_u32x4*>(a + j * TB);
-          e[bb][j][0] = r.x; e[bb][j][1] = r.y; e[bb][j][2] = r.z; e[bb][j][3] = r.w;
+#pragma unroll
+          for (int o = 0; o < OCT; ++o) {
+            const ru32x4v r = *reinterpret_cast<rows_lds_u32x4*>(a + j * TB + o * OSTRIDE);
+            e[bb][j][4 * o + 0] = r.x; e[bb][j][4 * o + 1] = r.y; e[bb][j][4 * o + 2] = r.z; e[bb][j][4 * o + 3] = r.w;
+          }
         }
       }
     }
@@ -277,7 +284,7 @@ __device__ __forceinline__ void rows_chunk(const uint32_t (&x)[BITS], uint32_t c
       const int b = b0 + bb;
       if (b >= BITS) break;
 #pragma unroll
-      for (int u = 0; u < HD; ++u) {
+      for (int u = 0; u < OCT * HD; ++u) {
         if constexpr (IS_INT) {
           rs2v q[TPC];
 #pragma unroll
@@ -342,11 +349,16 @@ __device__ __forceinline__ void rows_finish(const RowsParams& p, int n, int m, f
 }
 
 
-template <bool IS_INT, int BITS, int NT, int G>
+// OCT = 2: the workgroup serves two n tiles of NT = 8 activation rows (their tables side by side in
+// the two halves of the LDS slice), so that one address permute feeds two reads; the LUT buffer's
+// n tiles stay eight rows wide.
+template <bool IS_INT, int BITS, int NT, int G, int OCT>
 __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const RowsParams p) {
   using Sh = RowsShape<NT, G>;
   constexpr int TPC = Sh::TPC, CB = Sh::CB;
-  constexpr int CPS = rows_lds_chunks(G, NT);  // 32-k chunks per slice
+  constexpr int CPS = rows_lds_chunks(G, NT) / OCT;  // 32-k chunks per slice
+  constexpr int NTT = NT * OCT;                      // activation rows of the workgroup
+  constexpr int OSTRIDE = ROWS_LDS / OCT;            // bytes between the two row sets' tables
   static_assert(CPS >= 1 && CB % 256 == 0, "chunk bases must keep a zero low byte");
   __shared__ __attribute__((aligned(2048))) char tab[ROWS_LDS];  // byte-permuted addresses need the alignment
   __shared__ int s_last;
@@ -354,7 +366,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int n0 = blockIdx.x * NT;                       // activation rows of this workgroup
+  const int n0 = blockIdx.x * NTT;                      // activation rows of this workgroup
   const int tile_raw = blockIdx.y * ROWS_WAVES + wave;  // 64-row tile of this wave
   const bool tile_ok = tile_raw < p.n_tiles;
   const int tile = tile_ok ? tile_raw : p.n_tiles - 1;  // clamped: loads stay in range, stores are masked
@@ -365,10 +377,10 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
   // fp tables: L is the running result, the plane weights w carry half the current group's scale and
   // the group's bias term is added when the group starts; integer tables (and one scale per row or
   // tensor): L is the raw look-up sum of the group (row), finished in acc at the group's end
-  float acc[NT];
-  AccT L[NT];
+  float acc[NTT];
+  AccT L[NTT];
 #pragma unroll
-  for (int t = 0; t < NT; ++t) { acc[t] = 0.f; L[t] = 0; }
+  for (int t = 0; t < NTT; ++t) { acc[t] = 0.f; L[t] = 0; }
   float w[4] = {p.pw[0], p.pw[1], p.pw[2], p.pw[3]};
 
   auto load_idx = [&](int c, uint32_t (&x)[BITS]) {
@@ -391,19 +403,19 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
   int gq = p.grouped ? cz0 / p.cpg : 0, cg = 0;  // current quantisation group, chunks done in it (wave-uniform)
   // {scale, zero} of the lane's row and the activation sums of a group, requested one group ahead
   uint32_t szv = 0, szv_next = 0;
-  float Sg[NT], Sg_next[NT];
+  float Sg[NTT], Sg_next[NTT];
   auto load_group = [&](int g) {
     const int gc = min(g, p.nq - 1);
     szv_next = my_sz[(size_t)gc * 64];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
+    for (int t = 0; t < NTT; ++t) {
       const int n = min(n0 + t, p.N - 1);
       if constexpr (IS_INT) Sg_next[t] = (float)static_cast<const int*>(p.S)[(size_t)n * p.nq + gc];
       else Sg_next[t] = static_cast<const float*>(p.S)[(size_t)n * p.nq + gc];
     }
   };
 #pragma unroll
-  for (int t = 0; t < NT; ++t) Sg[t] = Sg_next[t] = 0.f;
+  for (int t = 0; t < NTT; ++t) Sg[t] = Sg_next[t] = 0.f;
   if (p.grouped) load_group(gq);
   uint32_t xn[BITS];
   load_idx(cz0, xn);
@@ -412,7 +424,12 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
     // stage the tables of this K-slice for the NT activation rows: item = (table, half) reads the
     // 8 entries of the four rows and writes them entry-major
     __syncthreads();
-    rows_stage_copy<NT, G, ROWS_LDS>(p, tab, blockIdx.x, c0 * TPC, kg_end);
+    {
+      const int last8 = (p.N + NT - 1) / NT - 1;  // last n tile of the LUT buffer (a second row set past it repeats it)
+#pragma unroll
+      for (int o = 0; o < OCT; ++o)
+        rows_stage_copy<NT, G, OSTRIDE>(p, tab + o * OSTRIDE, min((int)blockIdx.x * OCT + o, last8), c0 * TPC, kg_end);
+    }
     __syncthreads();
 
     const int c_end = min(c0 + CPS, cz1);
@@ -428,7 +445,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
         // a group starts: its scale/zero and activation sums have been requested a group ago
         szv = szv_next;
 #pragma unroll
-        for (int t = 0; t < NT; ++t) Sg[t] = Sg_next[t];
+        for (int t = 0; t < NTT; ++t) Sg[t] = Sg_next[t];
         if constexpr (!IS_INT) {
           const float s = __half2float(__ushort_as_half((uint16_t)(szv & 0xffffu)));
           const float z = __half2float(__ushort_as_half((uint16_t)(szv >> 16)));
@@ -436,20 +453,20 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
 #pragma unroll
           for (int b = 0; b < 4; ++b) w[b] = hs * p.pw[b];
 #pragma unroll
-          for (int t = 0; t < NT; ++t) L[t] = fmaf(bz, Sg[t], L[t]);  // bias term of Section 4's linear transform
+          for (int t = 0; t < NTT; ++t) L[t] = fmaf(bz, Sg[t], L[t]);  // bias term of Section 4's linear transform
         }
         // (the requests for the next group come after the last use of this group's values, so that they
         // can land in the same registers and nobody has to wait for them before the next group starts)
         __builtin_amdgcn_sched_barrier(0);
         load_group(gq + 1);
       }
-      rows_chunk<IS_INT, BITS, NT, G>(x, lds0 + (uint32_t)(c - c0) * (uint32_t)CB, L, w);
+      rows_chunk<IS_INT, BITS, NT, G, AccT, OCT, OSTRIDE>(x, lds0 + (uint32_t)(c - c0) * (uint32_t)CB, L, w);
       if (p.grouped && gq < p.nq && ++cg == p.cpg) {
         if constexpr (IS_INT) {
           const float s = __half2float(__ushort_as_half((uint16_t)(szv & 0xffffu)));
           const float z = __half2float(__ushort_as_half((uint16_t)(szv >> 16)));
 #pragma unroll
-          for (int t = 0; t < NT; ++t) {
+          for (int t = 0; t < NTT; ++t) {
             acc[t] = fmaf(s, fmaf(p.mid - z, Sg[t], 0.5f * (float)L[t]), acc[t]);
             L[t] = 0;
           }
@@ -480,7 +497,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
   if (nz == 1) {
     if (!row_ok) return;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
+    for (int t = 0; t < NTT; ++t) {
       if (n0 + t >= p.N) break;
       finish(n0 + t, (IS_INT && p.grouped) ? acc[t] : (float)L[t], IS_INT ? (int)L[t] : 0);
     }
@@ -496,7 +513,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
   const bool raw_int = RAW_INT && !p.grouped;
   if (tile_ok) {
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
+    for (int t = 0; t < NTT; ++t) {
       const int n = n0 + t;
       if (n < p.N) {
         const size_t o = ((size_t)blockIdx.z * p.N + n) * p.Mp + (size_t)tile_raw * 64 + lane;
@@ -517,18 +534,18 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
   __syncthreads();
   if (!s_last || !row_ok) return;
   // four slices x NT rows of loads in flight per round trip; sums taken in slice order
-  float sf[NT];
-  int si[NT];
+  float sf[NTT];
+  int si[NTT];
 #pragma unroll
-  for (int t = 0; t < NT; ++t) { sf[t] = 0.f; si[t] = 0; }
+  for (int t = 0; t < NTT; ++t) { sf[t] = 0.f; si[t] = 0; }
   const size_t mrow = (size_t)tile_raw * 64 + lane;
   for (int sl0 = 0; sl0 < nz; sl0 += 4) {
-    float v[4][NT];
+    float v[4][NTT];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int sl = min(sl0 + u, nz - 1);
 #pragma unroll
-      for (int t = 0; t < NT; ++t) {
+      for (int t = 0; t < NTT; ++t) {
         const int n = min(n0 + t, p.N - 1);
         v[u][t] = __hip_atomic_load(p.ws_part + ((size_t)sl * p.N + n) * p.Mp + mrow, __ATOMIC_RELAXED,
                                     __HIP_MEMORY_SCOPE_AGENT);
@@ -538,7 +555,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
     for (int u = 0; u < 4; ++u) {
       if (sl0 + u < nz) {
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
+        for (int t = 0; t < NTT; ++t) {
           if (raw_int) si[t] += __float_as_int(v[u][t]);
           else sf[t] += v[u][t];
         }
@@ -546,38 +563,41 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
     }
   }
 #pragma unroll
-  for (int t = 0; t < NT; ++t) {
+  for (int t = 0; t < NTT; ++t) {
     if (n0 + t >= p.N) break;
     finish(n0 + t, sf[t], si[t]);
   }
 }
 
-template <bool IS_INT, int BITS, int NT, int G>
+template <bool IS_INT, int BITS, int NT, int G, int OCT>
 static hipError_t launch_rows_one(const RowsParams& p, hipStream_t st) {
   RowsParams local = p;
   void* args[] = {&local};
-  const dim3 grid((p.N + NT - 1) / NT, (p.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES, (p.n_chunks + p.cps - 1) / p.cps);
-  return hipLaunchKernel(reinterpret_cast<const void*>(mpgemm_rows_kernel<IS_INT, BITS, NT, G>), grid,
+  const dim3 grid((p.N + NT * OCT - 1) / (NT * OCT), (p.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES,
+                  (p.n_chunks + p.cps - 1) / p.cps);
+  return hipLaunchKernel(reinterpret_cast<const void*>(mpgemm_rows_kernel<IS_INT, BITS, NT, G, OCT>), grid,
                          dim3(64 * ROWS_WAVES), args, 0, st);
 }
 
-template <bool IS_INT, int NT, int G>
+template <bool IS_INT, int NT, int G, int OCT = 1>
 static hipError_t launch_rows_bits(const RowsParams& p, int bits, hipStream_t st) {
   switch (bits) {
-    case 1: return launch_rows_one<IS_INT, 1, NT, G>(p, st);
-    case 2: return launch_rows_one<IS_INT, 2, NT, G>(p, st);
-    case 3: return launch_rows_one<IS_INT, 3, NT, G>(p, st);
-    case 4: return launch_rows_one<IS_INT, 4, NT, G>(p, st);
+    case 1: return launch_rows_one<IS_INT, 1, NT, G, OCT>(p, st);
+    case 2: return launch_rows_one<IS_INT, 2, NT, G, OCT>(p, st);
+    case 3: return launch_rows_one<IS_INT, 3, NT, G, OCT>(p, st);
+    case 4: return launch_rows_one<IS_INT, 4, NT, G, OCT>(p, st);
   }
   return hipErrorInvalidValue;
 }
 
+// oct: n tiles per workgroup (2 only with g = 4 and eight-row n tiles)
 template <bool IS_INT>
-static hipError_t launch_rows_nt(const RowsParams& p, int g, int nt, int bits, hipStream_t st) {
+static hipError_t launch_rows_nt(const RowsParams& p, int g, int nt, int oct, int bits, hipStream_t st) {
   if (g == 8) return launch_rows_bits<IS_INT, ROWS_NT_NARROW, 8>(p, bits, st);  // (rows_nt: always narrow)
   if (g == 2)
     return nt == ROWS_NT_WIDE ? launch_rows_bits<IS_INT, ROWS_NT_WIDE, 2>(p, bits, st)
                               : launch_rows_bits<IS_INT, ROWS_NT_NARROW, 2>(p, bits, st);
+  if (oct == 2) return launch_rows_bits<IS_INT, ROWS_NT_WIDE, 4, 2>(p, bits, st);
   return nt == ROWS_NT_WIDE ? launch_rows_bits<IS_INT, ROWS_NT_WIDE, 4>(p, bits, st)
                             : launch_rows_bits<IS_INT, ROWS_NT_NARROW, 4>(p, bits, st);
 }
@@ -850,12 +870,14 @@ static hipError_t launch_rows8_nt(const RowsParams& p, int nt, int bits, hipStre
 // How a call is split: workgroups along N and M, and the number of K slices (1 when the (row block,
 // n tile) pairs alone fill the chip; otherwise enough slices of at least 256 k, whole quantisation
 // groups each, to give about two workgroups per CU).
-RowsPlan rows_plan(const tmac_wdesc* desc, int N) {
+// The plan with `oct` n tiles per workgroup.
+static RowsPlan rows_plan_oct(const tmac_wdesc* desc, int N, int oct) {
   const Geometry ge = geometry(desc);
   RowsPlan pl;
   pl.row_blocks = (ge.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES;
   pl.nt = rows_nt(N, desc->g);
-  pl.n_tiles_n = (N + pl.nt - 1) / pl.nt;
+  pl.oct = oct;
+  pl.n_tiles_n = (N + pl.nt * pl.oct - 1) / (pl.nt * pl.oct);
   const bool one_group = (desc->group == 0 || desc->group == desc->K);
   const int cpg = (one_group || desc->group < 32) ? 1 : desc->group / 32;  // (sizes below 32 are rejected at launch)
   const int min_cps = (8 + cpg - 1) / cpg * cpg;  // at least 256 k, whole groups
@@ -865,7 +887,7 @@ RowsPlan rows_plan(const tmac_wdesc* desc, int N) {
   if (want > max_slices) want = max_slices;
   int cps = (int)((ge.n_chunks + want - 1) / want);
   // whole LDS slices where a workgroup gets at least one (nothing staged in vain), whole groups always
-  const int lds_chunks = rows_lds_chunks(desc->g, pl.nt);
+  const int lds_chunks = rows_lds_chunks(desc->g, pl.nt) / pl.oct;
   int unit = cpg;
   if (want > 1 && cps >= lds_chunks) {
     unit = lds_chunks;
@@ -876,12 +898,23 @@ RowsPlan rows_plan(const tmac_wdesc* desc, int N) {
   pl.cps = cps;
   // eight-chunk slices, several of them, g = 4, a group size that divides 256 (or no groups):
   // the kernel pair for few activation rows
-  pl.eight = desc->g == 4 && cps == R8_CH && ge.n_chunks > R8_CH && (one_group || R8_CH % cpg == 0);
+  pl.eight = pl.oct == 1 && desc->g == 4 && cps == R8_CH && ge.n_chunks > R8_CH && (one_group || R8_CH % cpg == 0);
   pl.slices = (ge.n_chunks + cps - 1) / cps;
   pl.part_bytes = pl.slices > 1 ? ((size_t)pl.slices * N * ge.Mp * 4 + 255) / 256 * 256 : 0;
   pl.ctr_bytes = pl.slices > 1 ? ((size_t)pairs * 4 + 255) / 256 * 256 : 0;
   pl.srow_bytes = pl.eight ? ((size_t)pl.slices * N * 4 + 255) / 256 * 256 : 0;
   return pl;
+}
+
+// Many activation rows at g = 4: a workgroup takes two n tiles (16 rows), one address permute per two
+// reads.  Measured against one n tile per workgroup (precompute + lookup, 4 bit): 13824 x 5120 even
+// at 48 rows, 7 % ahead at 64, 9 % at 96, 6 % at 128 and beyond; 4096 x 4096, where the eight-chunk
+// kernel pair serves up to 192 rows, behind below 96 rows, even at 96, 4 % ahead at 128.
+RowsPlan rows_plan(const tmac_wdesc* desc, int N) {
+  const RowsPlan one = rows_plan_oct(desc, N, 1);
+  const bool can = desc->g == 4 && one.nt == ROWS_NT_WIDE;
+  if (can && (N >= 128 || (N >= 64 && !one.eight))) return rows_plan_oct(desc, N, 2);
+  return one;
 }
 
 // Whether a call builds its tables inside the lookup kernel when it is given activations instead
@@ -957,7 +990,7 @@ int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void*
   hipError_t e;
   if (fused) e = is_int ? launch_rows8_nt<true, true>(p, pl.nt, desc->bits, st) : launch_rows8_nt<false, true>(p, pl.nt, desc->bits, st);
   else if (pl.eight) e = is_int ? launch_rows8_nt<true>(p, pl.nt, desc->bits, st) : launch_rows8_nt<false>(p, pl.nt, desc->bits, st);
-  else e = is_int ? launch_rows_nt<true>(p, desc->g, pl.nt, desc->bits, st) : launch_rows_nt<false>(p, desc->g, pl.nt, desc->bits, st);
+  else e = is_int ? launch_rows_nt<true>(p, desc->g, pl.nt, pl.oct, desc->bits, st) : launch_rows_nt<false>(p, desc->g, pl.nt, pl.oct, desc->bits, st);
   if (e != hipSuccess) {
     note_hip_error((int)e);
     return TMAC_EHIP;

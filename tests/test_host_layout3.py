@@ -49,9 +49,10 @@ def test_layout3_sizes_and_group_rules():
     d = desc3(5120, 5120, 4, 128)
     assert T.tmac_packed_bytes(d) == 256 + 5120 * 5120 // 2 + 5120 * 40 * 4
     assert T.tmac_workspace_bytes(d, 4096) == 256            # enough (row block, n tile) pairs: K is not split
-    # 256 rows: 32 n tiles x 20 row blocks; K is split in 5 slices of two LDS slices each:
-    # partial sums [5][256][5120] fp32, one counter per (row block, n tile), 256 spare bytes
-    assert T.tmac_workspace_bytes(d, 256) == 5 * 256 * 5120 * 4 + 640 * 4 + 256
+    # 256 rows: a workgroup takes two n tiles of 8 rows: 16 x 20 (n tile pair, row block) pairs; K is
+    # split in 10 slices of 16 chunks (two LDS slices) each: partial sums [10][256][5120] fp32, one
+    # counter per pair, 256 spare bytes
+    assert T.tmac_workspace_bytes(d, 256) == 10 * 256 * 5120 * 4 + 320 * 4 + 256
     assert T.tmac_workspace_bytes(d, 4) > 4 * 5120 * 4        # few rows: partial sums of the K slices
     assert T.tmac_packed_bytes(desc3(100, 48, 2, 16)) > 0     # packs; the kernel rejects the group size
 
