@@ -844,6 +844,26 @@ def test_precompute_tables_against_the_oracle(T, torch, g, int_act):
         assert np.allclose(S, a.astype(np.float64).sum(axis=1), rtol=1e-5, atol=1e-4)
 
 
+@pytest.mark.parametrize("N", [71, 129, 200])
+@pytest.mark.parametrize("bits,group", [(4, 128), (2, 64), (3, -1), (4, 0)])
+def test_many_rows_two_n_tiles_per_workgroup(T, torch, N, bits, group):
+    """From 64 activation rows on a workgroup of the many-row kernel serves two n tiles of eight rows
+    (one address for two LDS reads).  Row counts that are no multiple of 16 leave the last workgroup a
+    second n tile that repeats the first or is only partly filled; group scales, one scale per row and
+    one per tensor; fp16 and exact integer tables."""
+    from paper_2407_00088_amd.runner import from_problem
+    M, K = 150, 1536
+    if group == 0:
+        rng = np.random.default_rng(1400 + N + bits)
+        p = wl.Problem("oct", 0, N, M, K, bits, 0, wl.uniform_codes(rng, M, K, bits), None, None,
+                       weight_scale=0.05, zero_point=3.0, act=wl.gaussian_act(rng, N, K))
+    else:
+        p = wl.make_grouped(0, 1400 + N + bits, N, M, K, bits, K if group < 0 else group, name="oct")
+    check_fp(T, torch, p, layout=L3)
+    pt = wl.make_ternary(0, 1450 + N, N, M, K, name="oct_int")
+    check_int(T, torch, pt, layout=L3)
+
+
 def test_large_call_takes_two_row_tiles_per_workgroup_by_default(T, torch):
     """From about 8000 wavefronts on (here 8192 x 8192: 1024 row tiles x 8 waves) the register-table
     kernel serves 16 rows per workgroup unless told otherwise: the default call, the call with 8 rows
