@@ -1,24 +1,31 @@
 #!/usr/bin/env python3
-"""Benchmark of the LUT mpGEMV hot path on one MI355X.
+"""Benchmark of the LUT mpGEMV/mpGEMM hot path on one MI355X.
 
 A step = one pass of the whole hot path (table precompute, lookup, bit-plane accumulate, scale
 and zero, reduce, store) over the three Llama-2-7B-shaped W4A16 decode GEMVs (N=1; M x K =
-4096x4096, 11008x4096, 4096x11008; group 128), inputs resident in HBM.  By default every GEMV
-is ONE launch of tmac_mpgemv_fused (tables built inside the lookup kernel); --two-call times
-tmac_precompute_lut + tmac_mpgemm instead.  Every shape cycles through a ring of distinct
-packed weight copies larger than twice the 256 MB Infinity Cache, so weights come from HBM.
+4096x4096, 11008x4096, 4096x11008; group 128), inputs resident in HBM.  By default the three
+GEMVs are ONE launch of tmac_mpgemv_fused_multi (tables built inside the lookup kernel, the
+workgroups of one grid dealt out over the three matrices); --separate times one
+tmac_mpgemv_fused launch per GEMV, --two-call tmac_precompute_lut + tmac_mpgemm per GEMV.  Every
+shape cycles through a ring of distinct packed weight copies larger than twice the 256 MB
+Infinity Cache, so weights come from HBM.
 
 Launches are replayed from HIP graphs (captured once, outside the timed region) so that the
-host-side cost of issuing ~3 us kernels from Python does not hide the GPU time; the timed
-region is bracketed by HIP events on the launching stream and by synchronize().
+host-side cost of issuing microsecond kernels from Python does not hide the GPU time; the timed
+region is bracketed by HIP events on the launching stream and by synchronize().  Before the
+warm-up an untimed pre-roll of PREROLL_STEPS steps brings the clocks up, so that a short timed
+region (20 steps) reads like a long one.
 
 Prints ONE JSON line: whole-step throughput (algorithmic GB/s), the roofline of the dominant
-kernel (the lookup kernel: back-to-back launches over the weight ring, HIP events) and the CPU
-oracle timed on the host cores as a reported baseline.
+kernel, the CPU oracle timed on the host cores as a reported baseline, and under `detail` the rest
+of the metric: time per call at 1-4 bit on two shapes with the linear fit, the BitNet-shaped
+ternary GEMVs, one decoder block, and TOPS-equivalent at N = 256 against the measured lookup
+ceiling.  Every per-kernel figure takes at least MIN_LAUNCHES launches whatever --steps says.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -29,15 +36,28 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-ALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9   # one vector instruction per lane and cycle on every CU
-ALU_OPS_PER_LOOKUP_ADD = 83.0 / 128.0  # batched kernel, sixteen activation rows per workgroup (N >= 128)
-RING_MB = 576  # > 2 x 256 MB Infinity Cache
+RING_MB = 576        # > 2 x 256 MB Infinity Cache
+PREROLL_STEPS = 400  # untimed steps before the warm-up (clock ramp), independent of --steps
+MIN_LAUNCHES = 300   # launches behind every per-kernel figure, independent of --steps
 
-# HBM bytes of the three launches of one step (default configuration: fused kernel, 8 rows per
-# workgroup), from two rocprofv3 --pmc passes (FETCH_SIZE, then WRITE_SIZE), each dispatch's
-# counter scaled by what the same counter reads for the plain read kernel on a blob of the same
-# size (2093 / 2051 bytes per count); summary under profiles/.
-MEASURED_TRAFFIC_BYTES = {"fetch": [9.26e6, 24.14e6, 24.28e6], "write": [16384, 44032, 16384]}
+# HBM bytes of one step's launch(es) from two rocprofv3 --pmc passes (FETCH_SIZE, then WRITE_SIZE),
+# each dispatch's counter scaled by what the same counter reads for the plain read kernel on a blob
+# of known size; summary under profiles/.  The figures belong to the kernel sources they were taken
+# with: they are emitted only while the hash of those sources is unchanged.
+MEASURED_TRAFFIC = {
+    "sources_sha256_16": None,
+    "multi": None,      # bytes per step, one launch
+    "separate": None,   # bytes per step, three launches
+}
+KERNEL_SOURCES = ["paper_2407_00088_amd/csrc/tmac_perm.hip", "paper_2407_00088_amd/csrc/tmac_internal.h"]
+
+
+def kernel_sources_hash():
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
 
 
 def algorithmic_bytes(M, K, bits, group, N=1, act_bytes=2, out_bytes=4):
@@ -45,6 +65,16 @@ def algorithmic_bytes(M, K, bits, group, N=1, act_bytes=2, out_bytes=4):
     w = M * K * bits // 8
     sz = 0 if group == 0 else M * (K // group) * 4
     return w + sz + N * K * act_bytes + N * M * out_bytes
+
+
+def linear_fit(xs, ys):
+    import numpy as np
+    xs, ys = np.asarray(xs, dtype=np.float64), np.asarray(ys, dtype=np.float64)
+    c, t0 = np.polyfit(xs, ys, 1)
+    ss_res = float(((ys - (c * xs + t0)) ** 2).sum())
+    ss_tot = float(((ys - ys.mean()) ** 2).sum())
+    return {"us_per_bit": round(float(c), 4), "t0_us": round(float(t0), 4),
+            "r2": round(1 - ss_res / ss_tot, 5) if ss_tot > 0 else None}
 
 
 def main():
@@ -56,14 +86,18 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--ring-mb", type=int, default=RING_MB)
     ap.add_argument("--rows", type=int, default=0, help="tmac_tuning.rows_per_group override (8 or 16)")
-    ap.add_argument("--sweep", action="store_true", help="also time the W1..W4 and BitNet shapes")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also: eager one-copy protocol, int8 tables, stacked and 70B-sized matrices, small batches, g sweep")
+    ap.add_argument("--headline-only", action="store_true", help="skip the detail rows (for profiling the step)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead of graph replay")
     ap.add_argument("--prefill-only", action="store_true",
-                    help="time only the N=256 rows of the sweep and print them (for profiling that kernel)")
+                    help="time only the N=256 rows and print them (for profiling that kernel)")
     ap.add_argument("--small-batch-only", action="store_true",
-                    help="time only the N = 2..64 rows of the sweep and print them (for profiling those kernels)")
+                    help="time only the N = 2..64 rows and print them (for profiling those kernels)")
+    ap.add_argument("--separate", action="store_true",
+                    help="step = one tmac_mpgemv_fused launch per GEMV instead of one launch for the three")
     ap.add_argument("--two-call", action="store_true",
-                    help="step = tmac_precompute_lut + tmac_mpgemm (two launches per GEMV) instead of the fused call")
+                    help="step = tmac_precompute_lut + tmac_mpgemm (two launches per GEMV)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -75,6 +109,7 @@ def main():
 
     import paper_2407_00088_amd as T
     import tmac_workloads as wl
+    from paper_2407_00088_amd import bench_helpers as H
     from paper_2407_00088_amd.binding import tmac_tuning
     from paper_2407_00088_amd.runner import from_problem
 
@@ -100,30 +135,37 @@ def main():
             # the launch-shape knob belongs to the register-table kernel with 16-bit tables
             self.tuning = tuning if (self.lin.layout == 2 and self.lin.lut_t != T.TMAC_LUT_I8Q) else None
 
+        def next_packed(self):
+            packed = self.ring[self.i % len(self.ring)]
+            self.i += 1
+            return packed
+
         def precompute(self):
             self.lin.precompute(self.A)
 
         def mpgemm(self):
-            packed = self.ring[self.i % len(self.ring)]
-            self.i += 1
-            self.lin.mpgemm(self.p.N, self.out, T.TMAC_OUT_F32, act_scale=self.s_a, tuning=self.tuning, packed=packed)
+            self.lin.mpgemm(self.p.N, self.out, T.TMAC_OUT_F32, act_scale=self.s_a, tuning=self.tuning,
+                            packed=self.next_packed())
 
         def fused(self):
-            packed = self.ring[self.i % len(self.ring)]
-            self.i += 1
-            self.lin.mpgemv_fused(self.A, self.p.N, self.out, T.TMAC_OUT_F32, act_scale=self.s_a, packed=packed,
-                                  tuning=self.tuning)
+            self.lin.mpgemv_fused(self.A, self.p.N, self.out, T.TMAC_OUT_F32, act_scale=self.s_a,
+                                  packed=self.next_packed(), tuning=self.tuning)
 
         def one_call(self):
-            packed = self.ring[self.i % len(self.ring)]
-            self.i += 1
-            self.lin.mpgemm_fused(self.A, self.p.N, self.out, T.TMAC_OUT_F32, act_scale=self.s_a, packed=packed)
+            self.lin.mpgemm_fused(self.A, self.p.N, self.out, T.TMAC_OUT_F32, act_scale=self.s_a,
+                                  packed=self.next_packed())
+
+        def item(self):
+            """This matrix as an item of tmac_mpgemv_fused_multi, on the ring's next copy."""
+            return (self.lin.desc, self.next_packed(), self.A, self.out, self.s_a, self.lin.weight_scale)
 
         def stream_read(self):
             """Plain read of the same packed bytes: what a read-only kernel reaches on this ring."""
-            packed = self.ring[self.i % len(self.ring)]
-            self.i += 1
-            T.tmac_stream_read(packed, sink, 1, True)
+            H.stream_read(self.next_packed(), sink, 1, True)
+
+    def multi(cases_):
+        """One launch for several matrices (tmac_mpgemv_fused_multi)."""
+        T.tmac_mpgemv_fused_multi([c.item() for c in cases_], cases_[0].p.N, T.TMAC_OUT_F32, tuning=tuning)
 
     class Replay:
         """`body` issued `reps` times per launch, either eagerly or as one captured HIP graph."""
@@ -160,9 +202,9 @@ def main():
             stream.synchronize()
         return t0.elapsed_time(t1) * 1e3 / (launches * replay.reps)
 
-    def timed_exact(body, reps, steps, warm_steps):
-        """Exactly `warm_steps` untimed and `steps` timed executions of `body`: whole replays of `reps`
-        executions plus one shorter replay for the remainder.  Returns microseconds per execution."""
+    def timed_exact(body, reps, steps, warm_steps, preroll):
+        """`preroll` + `warm_steps` untimed and exactly `steps` timed executions of `body`: whole replays of
+        `reps` executions plus one shorter replay for the remainder.  Returns microseconds per execution."""
         full = Replay(body, reps)
         tails = {}
 
@@ -174,9 +216,9 @@ def main():
                 seq.append(tails[n % reps])
             return seq
 
-        warm_seq, timed_seq = plan(warm_steps), plan(steps)
+        pre_seq, warm_seq, timed_seq = plan(preroll), plan(warm_steps), plan(steps)
         with torch.cuda.stream(stream):
-            for r in warm_seq:
+            for r in pre_seq + warm_seq:
                 r.run()
             stream.synchronize()
             t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -187,13 +229,29 @@ def main():
             stream.synchronize()
         return t0.elapsed_time(t1) * 1e3 / steps
 
+    def per_launch(body, reps, min_launches=MIN_LAUNCHES):
+        """Microseconds per execution of `body`, over at least `min_launches` executions (graphs of `reps`
+        executions, one warm replay first): the same answer whatever --steps says."""
+        replays = max(2, -(-min_launches // reps))
+        return timed(Replay(body, reps), replays, 1)
+
     def ring_len(c):
         return len(c.ring)
 
-    def measure_kernel(c, total, body=None):
-        reps = ring_len(c)
-        launches = max(1, total // reps)
-        return timed(Replay(body or c.mpgemm, reps), launches, max(1, launches // 10))
+    def measure_kernel(c, body=None, min_launches=MIN_LAUNCHES):
+        return per_launch(body or c.mpgemm, ring_len(c), min_launches)
+
+    def gemv_row(c, name=None, with_two_call=False):
+        """One decode GEMV shape: the fused launch, the plain read of the same bytes, rates."""
+        fu = measure_kernel(c, c.fused)
+        ru = measure_kernel(c, c.stream_read)
+        row = {"name": name or c.p.name, "M": c.p.M, "K": c.p.K, "bits": c.p.bits, "fused_us": round(fu, 3),
+               "plain_read_of_same_bytes_us": round(ru, 3), "bytes": c.bytes, "GBps": round(c.bytes / fu / 1e3, 1),
+               "frac_hbm_peak": round(c.bytes / fu / 1e3 / HBM_PEAK_GBPS, 4)}
+        if with_two_call:
+            row["mpgemm_us"] = round(measure_kernel(c), 3)
+            row["precompute_us"] = round(per_launch(c.precompute, 50), 3)
+        return row
 
     def small_batch_rows():
         """Small batches (N = 2..64) on the 4096 x 4096 W4 shape: precompute + lookup per call, in both
@@ -210,19 +268,33 @@ def main():
                 def both(c=c):
                     c.precompute()
                     c.mpgemm()
-                us = timed(Replay(both, ring_len(c)), max(1, args.steps // ring_len(c)), 2)
+                us = per_launch(both, ring_len(c))
                 row[key + "_call_us"] = round(us, 3)
                 row[key + "_TOPS_equiv"] = round(2.0 * N * p.M * p.K / us / 1e6, 3)
                 # the same rows through the one-call entry point (tables built in the lookup kernel)
-                fu = measure_kernel(c, args.steps, c.one_call)
-                row[key + "_one_call_us"] = round(fu, 3)
+                row[key + "_one_call_us"] = round(measure_kernel(c, c.one_call), 3)
                 del c
                 torch.cuda.empty_cache()
             small.append(row)
         return small
 
-    def prefill_rows():
-        """Prefill mpGEMM, N = 256 (batched lookup kernel): precompute + mpgemm per call."""
+    def lds_lookup_ceiling():
+        """Lookup rate of LDS alone (LDS probe of libtmac_bench.so): the ceiling of the batched kernels'
+        lookups.  One 16-byte read of a wavefront serves 64 lanes x 8 activation rows = 512 lookups."""
+        wgs, rounds = 256 * 5 * 4, 2000
+
+        def probe():
+            H.lds_lookup_probe(wgs, rounds, sink)
+        us = timed(Replay(probe, 1), 5, 2)
+        wave_reads = wgs * 4 * rounds * 16
+        return {"workgroups": wgs, "rounds": rounds, "us": round(us, 1),
+                "wave_reads_per_s": round(wave_reads / us * 1e6, -6),
+                "lookups_per_s": round(wave_reads * 512 / us * 1e6, -9)}
+
+    def prefill_rows(ceiling_lookups_per_s):
+        """Prefill mpGEMM, N = 256 (batched lookup kernel): precompute + mpgemm per call.  The roofline
+        of this path is the lookup rate (lookup-and-add, no dense contraction): lookups per second
+        against what LDS alone delivers with the same table layout and addressing, measured in this run."""
         rows = []
         for bits in (2, 4):
             for i in range(3):
@@ -236,36 +308,17 @@ def main():
                 pu = timed(Replay(c.precompute, 2), 10, 2)
                 flops = 2.0 * p.N * p.M * p.K
                 lookup_adds = p.N * p.M * (p.K / 4) * bits
+                rate = lookup_adds / us * 1e6
                 rows.append({"name": p.name, "bits": bits, "N": p.N, "call_us": round(us, 2),
                              "precompute_us": round(pu, 2),
                              "TOPS_equiv": round(flops / us / 1e6, 2),
-                             "lookups_per_s": round(lookup_adds / us * 1e6, -6),
-                             # plain-ALU roofline of the batched kernel: 83 vector instructions per 128
-                             # lookup-adds of a lane is what the method needs in this kernel (3 offset
-                             # instructions, 8 address permutes, 56 packed adds, 16 widening multiply-adds
-                             # per chunk and plane of sixteen activation rows); peak = 256 CUs x 64 lanes
-                             # x 2.4 GHz
-                             "roofline": {"bound": "alu", "unit": "lane-op/s", "peak": ALU_PEAK_LANE_OPS,
-                                          "achieved": round(lookup_adds * ALU_OPS_PER_LOOKUP_ADD / (us - pu) * 1e6, -9),
-                                          "frac": round(lookup_adds * ALU_OPS_PER_LOOKUP_ADD / (us - pu) * 1e6
-                                                        / ALU_PEAK_LANE_OPS, 4)}})
+                             "lookups_per_s": round(rate, -6),
+                             "roofline": {"bound": "lds lookup rate", "unit": "lookups/s",
+                                          "peak": ceiling_lookups_per_s, "achieved": round(rate, -6),
+                                          "frac": round(rate / ceiling_lookups_per_s, 4)}})
                 del c
                 torch.cuda.empty_cache()
         return rows
-
-    def lds_lookup_ceiling():
-        """Lookup rate of LDS alone (tmac_lds_lookup_probe): the ceiling of the batched kernels' lookups.
-        One 16-byte read of a wavefront serves 64 lanes x 8 activation rows = 512 lookups."""
-        wgs, rounds = 256 * 5 * 4, 2000
-
-        def probe():
-            T.tmac_lds_lookup_probe(wgs, rounds, sink)
-        us = timed(Replay(probe, 1), 5, 2)
-        wave_reads = wgs * 4 * rounds * 16
-        return {"workgroups": wgs, "rounds": rounds, "us": round(us, 1),
-                "wave_reads_per_s": round(wave_reads / us * 1e6, -6),
-                "bytes_per_clk_per_cu_at_2.4GHz": round(wave_reads * 1024 / us * 1e6 / 256 / 2.4e9, 1),
-                "lookups_per_s": round(wave_reads * 512 / us * 1e6, -9)}
 
     def isolated_rows(cases_):
         """The paper's own protocol (Section 5.1: warm-up, then the mean of 100 runs) on ONE copy of the
@@ -297,130 +350,162 @@ def main():
         return
 
     if args.prefill_only:
-        print(json.dumps({"prefill_n256": prefill_rows(), "lds_lookup_ceiling": lds_lookup_ceiling()}))
+        ceil = lds_lookup_ceiling()
+        print(json.dumps({"prefill_n256": prefill_rows(ceil["lookups_per_s"]), "lds_lookup_ceiling": ceil}))
         return
 
+    # ------------------------------------------------------------------ the step ----
     cases = [Case(wl.config2(i)) for i in range(3)]
     step_bytes = sum(c.bytes for c in cases)
+    mode = "two_call" if args.two_call else ("separate" if args.separate else "multi")
 
-    fused = not args.two_call
+    def step_multi():
+        multi(cases)
 
-    def step():
+    def step_separate():
         for c in cases:
-            if fused:
-                c.fused()
-            else:
-                c.precompute()
-                c.mpgemm()
+            c.fused()
 
+    def step_two_call():
+        for c in cases:
+            c.precompute()
+            c.mpgemm()
+
+    step = {"multi": step_multi, "separate": step_separate, "two_call": step_two_call}[mode]
     reps = max(ring_len(c) for c in cases)
-    step_us = timed_exact(step, reps, max(1, args.steps), max(0, args.warmup))
     steps_done = max(1, args.steps)
+    step_us = timed_exact(step, reps, steps_done, max(0, args.warmup), PREROLL_STEPS)
     ms_per_step = step_us * 1e-3
     value = step_bytes / (step_us * 1e-6) / 1e9
 
-    # dominant kernel: the lookup kernel alone (the fused one when the step uses it), back-to-back
-    # over the weight ring
-    mp_us = [measure_kernel(c, args.steps) for c in cases]
-    fu_us = [measure_kernel(c, args.steps, c.fused) for c in cases]
-    per_us = fu_us if fused else mp_us
-    if fused:
-        # the timed region consists of launches of the dominant kernel only (one per shape): its average
-        # launch duration over that region is step_us / 3, for step_bytes / 3 bytes per launch
-        achieved, how = value, "HIP events over the timed region: three launches of this kernel per step"
-    else:
-        achieved = sum(c.bytes for c in cases) / (sum(per_us) * 1e-6) / 1e9
+    detail = {}
+    launches_per_step = {"multi": 1, "separate": 3, "two_call": 6}[mode]
+    if mode == "two_call":
+        # the step also launches the precompute kernel: the lookup kernel alone, back to back over the ring
+        mp_us = [measure_kernel(c) for c in cases]
+        achieved = step_bytes / (sum(mp_us) * 1e-6) / 1e9
         how = "HIP events over back-to-back launches of this kernel alone (the step also launches the precompute kernel)"
-    pre_us = [timed(Replay(c.precompute, 50), max(1, args.steps // 50), 2) for c in cases]
-    read_us = [measure_kernel(c, args.steps, c.stream_read) for c in cases]
-    detail = {"shapes": []}
-    for c, us, fu, pu, ru in zip(cases, mp_us, fu_us, pre_us, read_us):
-        dom = fu if fused else us
-        detail["shapes"].append({"M": c.p.M, "K": c.p.K, "bits": c.p.bits, "mpgemm_us": round(us, 3),
-                                 "fused_us": None if fu is None else round(fu, 3),
-                                 "precompute_us": round(pu, 3), "bytes": c.bytes,
-                                 "GBps": round(c.bytes / dom / 1e3, 1),
-                                 "frac_hbm_peak": round(c.bytes / dom / 1e3 / HBM_PEAK_GBPS, 4),
-                                 "plain_read_of_same_bytes_us": round(ru, 3)})
+        avg_launch_us, launch_us = sum(mp_us) / 3, mp_us
+    else:
+        # the timed region consists of launches of the dominant kernel only
+        achieved = value
+        how = (f"HIP events over the timed region: {launches_per_step} launch(es) of this kernel per step, "
+               f"{step_bytes // launches_per_step} algorithmic bytes per launch on average")
+        avg_launch_us, launch_us = step_us / launches_per_step, None
+    traffic = None
+    if mode in ("multi", "separate") and not args.rows and MEASURED_TRAFFIC["sources_sha256_16"] == kernel_sources_hash():
+        traffic = MEASURED_TRAFFIC[mode]
+
+    if not args.headline_only:
+        # the same step the other ways, each over at least MIN_LAUNCHES steps
+        variants = {}
+        for key, fn in (("one_launch_for_the_three_us", step_multi), ("three_fused_launches_us", step_separate),
+                        ("precompute_plus_lookup_six_launches_us", step_two_call)):
+            us = per_launch(fn, reps)
+            variants[key] = round(us, 3)
+            variants[key.replace("_us", "_frac_hbm_peak")] = round(step_bytes / us / 1e3 / HBM_PEAK_GBPS, 4)
+
+        def step_read():
+            for c in cases:
+                c.stream_read()
+        variants["plain_read_of_the_same_bytes_three_launches_us"] = round(per_launch(step_read, reps), 3)
+        variants["empty_kernel_us"] = round(per_launch(H.empty_kernel, 100), 3)
+        detail["step_variants"] = variants
+        detail["shapes"] = [gemv_row(c, with_two_call=True) for c in cases]
+        if launch_us is None:
+            launch_us = [r["fused_us"] for r in detail["shapes"]]
+
+        # one Llama-2-7B decoder block, N = 1 (seven projections, 107.7 MB of packed weights), weights of
+        # every projection from its own ring: Q,K,V in one launch, O, gate and up in one launch, down
+        blk_shapes = [("q", 4096, 4096), ("k", 4096, 4096), ("v", 4096, 4096), ("o", 4096, 4096),
+                      ("gate", 11008, 4096), ("up", 11008, 4096), ("down", 4096, 11008)]
+        cs = {k: Case(wl.make_grouped(3, 90 + i, 1, M, K, 4, 128, name=f"block_{k}"), ring_mb=args.ring_mb // 2)
+              for i, (k, M, K) in enumerate(blk_shapes)}
+        nbytes = sum(c.bytes for c in cs.values())
+
+        def block_multi():
+            multi([cs["q"], cs["k"], cs["v"]])
+            cs["o"].fused()
+            multi([cs["gate"], cs["up"]])
+            cs["down"].fused()
+
+        def block_separate():
+            for k, _, _ in blk_shapes:
+                cs[k].fused()
+        breps = max(ring_len(c) for c in cs.values())
+        blk = {}
+        for key, fn in (("four_launches_qkv_and_gate_up_grouped", block_multi), ("seven_launches", block_separate)):
+            us = per_launch(fn, breps)
+            blk[key] = {"us": round(us, 3), "bytes": nbytes, "GBps": round(nbytes / us / 1e3, 1),
+                        "frac_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)}
+        del cs
+        torch.cuda.empty_cache()
+        detail["decoder_block_llama2_7b"] = blk
+        keep = cases if args.sweep else []
+        if not args.sweep:
+            del cases[:]
+            torch.cuda.empty_cache()
+
+        # W1..W4 at N = 1 on two shapes (config 3 and its 11008 x 4096 sibling): time per call, rate,
+        # and the fit t(b) = t0 + c b
+        sweep = {}
+        for M, K in ((4096, 4096), (11008, 4096)):
+            rows = []
+            for b in (1, 2, 3, 4):
+                p = wl.config3(b) if (M, K) == (4096, 4096) else wl.make_grouped(3, 10 + b, 1, M, K, b, 128)
+                c = Case(p)
+                rows.append(gemv_row(c, with_two_call=(M == 4096)))
+                del c
+                torch.cuda.empty_cache()
+            sweep[f"{M}x{K}"] = {"rows": rows,
+                                 "fit_fused": linear_fit([r["bits"] for r in rows], [r["fused_us"] for r in rows]),
+                                 "fit_plain_read": linear_fit([r["bits"] for r in rows],
+                                                              [r["plain_read_of_same_bytes_us"] for r in rows])}
+        detail["bit_sweep_n1"] = sweep
+
+        # BitNet-b1.58-3B-shaped ternary GEMVs (config 4): int8 activations, exact integers
+        bn = [Case(wl.config4(i)) for i in range(3)]
+        bn_rows = [gemv_row(c) for c in bn]
+        bn_bytes = sum(c.bytes for c in bn)
+        us = per_launch(lambda: multi(bn), max(ring_len(c) for c in bn))
+        detail["bitnet_ternary_n1"] = {"rows": bn_rows,
+                                       "one_launch_for_the_three": {"us": round(us, 3), "bytes": bn_bytes,
+                                                                    "GBps": round(bn_bytes / us / 1e3, 1),
+                                                                    "frac_hbm_peak": round(bn_bytes / us / 1e3 / HBM_PEAK_GBPS, 4)}}
+        del bn
+        torch.cuda.empty_cache()
+
+        # N = 256 (config 5)
+        ceil = lds_lookup_ceiling()
+        detail["lds_lookup_ceiling"] = ceil
+        detail["prefill_n256"] = prefill_rows(ceil["lookups_per_s"])
+        cases = keep
 
     if args.sweep:
         detail["isolated_one_copy_eager"] = isolated_rows(cases)
-        sweep = []
-        del cases[1:]
+        del cases[:]
         torch.cuda.empty_cache()
-        extra = [wl.config3(b) for b in (1, 2, 3, 4)] + [wl.config4(i) for i in range(3)]
-        for p in extra:
-            c = Case(p)
-            us = measure_kernel(c, args.steps)
-            fu = measure_kernel(c, args.steps, c.fused)
-            pu = timed(Replay(c.precompute, 50), max(1, args.steps // 50), 2)
-            ru = measure_kernel(c, args.steps, c.stream_read)
-            sweep.append({"name": p.name, "bits": p.bits, "mpgemm_us": round(us, 3),
-                          "fused_us": None if fu is None else round(fu, 3), "precompute_us": round(pu, 3),
-                          "plain_read_of_same_bytes_us": round(ru, 3),
-                          "bytes": c.bytes, "GBps": round(c.bytes / us / 1e3, 1),
-                          "frac_hbm_peak": round(c.bytes / us / 1e3 / HBM_PEAK_GBPS, 4)})
-            del c
-            torch.cuda.empty_cache()
-        detail["sweep"] = sweep
         # int8 table quantisation (Section 3.3): lookup kernel with int8 tables, two-call path
         tq = []
         for i in range(3):
             c = Case(wl.config2(i), lut_t=T.TMAC_LUT_I8Q)
-            us = measure_kernel(c, args.steps)
-            pu = timed(Replay(c.precompute, 50), max(1, args.steps // 50), 2)
+            us = measure_kernel(c)
+            pu = per_launch(c.precompute, 50)
             tq.append({"name": c.p.name + "_int8_tables", "mpgemm_us": round(us, 3), "precompute_us": round(pu, 3),
                        "bytes": c.bytes, "GBps": round(c.bytes / us / 1e3, 1),
                        "frac_hbm_peak": round(c.bytes / us / 1e3 / HBM_PEAK_GBPS, 4)})
             del c
             torch.cuda.empty_cache()
         detail["table_quantisation"] = tq
-        # stacked projections in one call (Q,K,V and gate,up of Llama-2-7B stacked along M): the
-        # fraction of the roofline the same kernel reaches once a call moves more bytes
-        stacked = []
-        for M, K in ((12288, 4096), (22016, 4096)):
-            c = Case(wl.make_grouped(3, 50 + M // 1000, 1, M, K, 4, 128, name=f"stacked_{M}x{K}_w4_n1"))
-            fu = measure_kernel(c, args.steps, c.fused)
-            ru = measure_kernel(c, args.steps, c.stream_read)
-            stacked.append({"name": c.p.name, "fused_us": round(fu, 3), "plain_read_of_same_bytes_us": round(ru, 3),
-                            "bytes": c.bytes, "GBps": round(c.bytes / fu / 1e3, 1),
-                            "frac_hbm_peak": round(c.bytes / fu / 1e3 / HBM_PEAK_GBPS, 4)})
+        # one bigger matrix per call: stacked projections (Q,K,V and gate,up stacked along M by the caller)
+        # and Llama-2-70B-shaped matrices (34-125 MB per call)
+        big = []
+        for M, K in ((12288, 4096), (22016, 4096), (8192, 8192), (28672, 8192), (8192, 28672)):
+            c = Case(wl.make_grouped(3, 40 + M // 1000 + K // 4000, 1, M, K, 4, 128, name=f"{M}x{K}_w4_n1"))
+            big.append(gemv_row(c))
             del c
             torch.cuda.empty_cache()
-        detail["stacked_projections"] = stacked
-        # the same kernel on Llama-2-70B-shaped matrices (34-125 MB per call): how the fraction of the
-        # roofline grows once the fixed cost of a launch is spread over more bytes
-        larger = []
-        for M, K in ((8192, 8192), (28672, 8192), (8192, 28672)):
-            c = Case(wl.make_grouped(3, 40 + M // 1000 + K // 4000, 1, M, K, 4, 128, name=f"llama2_70b_{M}x{K}_w4_n1"))
-            fu = measure_kernel(c, max(200, args.steps // 4), c.fused)
-            ru = measure_kernel(c, max(200, args.steps // 4), c.stream_read)
-            larger.append({"name": c.p.name, "fused_us": round(fu, 3), "plain_read_of_same_bytes_us": round(ru, 3),
-                           "bytes": c.bytes, "GBps": round(c.bytes / fu / 1e3, 1),
-                           "frac_hbm_peak": round(c.bytes / fu / 1e3 / HBM_PEAK_GBPS, 4)})
-            del c
-            torch.cuda.empty_cache()
-        detail["larger_matrices"] = larger
-        # one Llama-2-7B decoder block, N = 1: its seven projections as seven fused launches, and with
-        # Q,K,V and gate,up stacked along M (four launches); weights of every launch from its own ring
-        blk = {}
-        shapes = {"qkv": (12288, 4096), "o": (4096, 4096), "gate_up": (22016, 4096), "down": (4096, 11008),
-                  "gate": (11008, 4096)}
-        cs = {k: Case(wl.make_grouped(3, 90 + i, 1, M, K, 4, 128, name=f"block_{k}"), ring_mb=args.ring_mb // 2)
-              for i, (k, (M, K)) in enumerate(shapes.items())}
-        for key, seq in (("stacked_4_launches", ["qkv", "o", "gate_up", "down"]),
-                         ("separate_7_launches", ["o", "o", "o", "o", "gate", "gate", "down"])):
-            def block_step(seq=seq):
-                for k in seq:
-                    cs[k].fused()
-            reps = max(ring_len(cs[k]) for k in seq)
-            us = timed(Replay(block_step, reps), max(1, args.steps // reps), 2)
-            nbytes = sum(cs[k].bytes for k in seq)
-            blk[key] = {"us": round(us, 3), "bytes": nbytes, "GBps": round(nbytes / us / 1e3, 1),
-                        "frac_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)}
-        del cs
-        torch.cuda.empty_cache()
-        detail["decoder_block_llama2_7b"] = blk
+        detail["larger_matrices"] = big
         detail["small_batch"] = small_batch_rows()
         # LUT group size g = 2, 4, 8 in the batched kernel (Section 4 on the choice of g): fewer,
         # larger tables against more look-ups; precompute + lookup per call
@@ -433,8 +518,7 @@ def main():
                 def both(c=c):
                     c.precompute()
                     c.mpgemm()
-                reps = ring_len(c) if p.N <= 16 else 2
-                us = timed(Replay(both, reps), max(2, args.steps // (4 * reps)) if p.N <= 16 else 10, 2)
+                us = per_launch(both, ring_len(c)) if p.N <= 16 else timed(Replay(both, 2), 10, 2)
                 pu = timed(Replay(c.precompute, 20), 5, 1)
                 gs.append({"name": p.name, "N": p.N, "g": g, "call_us": round(us, 2), "precompute_us": round(pu, 2),
                            "lut_bytes": int(c.lin.lut.numel()),
@@ -442,15 +526,6 @@ def main():
                 del c
                 torch.cuda.empty_cache()
         detail["g_sweep"] = gs
-        detail["prefill_n256"] = prefill_rows()
-        detail["lds_lookup_ceiling"] = lds_lookup_ceiling()
-        xs = np.array([s["bits"] for s in sweep[:4]], dtype=np.float64)
-        ys = np.array([s["mpgemm_us"] for s in sweep[:4]], dtype=np.float64)
-        cfit, t0fit = np.polyfit(xs, ys, 1)
-        ss_res = float(((ys - (cfit * xs + t0fit)) ** 2).sum())
-        ss_tot = float(((ys - ys.mean()) ** 2).sum())
-        detail["bit_linearity"] = {"us_per_bit": round(float(cfit), 4), "t0_us": round(float(t0fit), 4),
-                                   "r2": round(1 - ss_res / ss_tot, 5) if ss_tot > 0 else None}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -467,36 +542,16 @@ def main():
             t_used += time.perf_counter() - t0
             done_bytes += pbytes[calls % 3]
             calls += 1
-        # per shape: median of five oracle calls with the BLAS pool at one thread and at all threads
-        def oracle_medians():
-            out = []
-            for p in ps:
-                ts = []
-                for _ in range(5):
-                    t0 = time.perf_counter()
-                    orc.mpgemm_definition(p.act, p.q, p.scales, p.zeros, p.group)
-                    ts.append(time.perf_counter() - t0)
-                out.append(round(sorted(ts)[2] * 1e6, 1))
-            return out
-        used, note = n_threads, ""
-        try:
-            from threadpoolctl import threadpool_limits
-            with threadpool_limits(limits=1):
-                one = oracle_medians()
-            many = oracle_medians()
-            detail["cpu_oracle_us_per_call"] = {"shapes": [p.name for p in ps], "threads_1": one,
-                                                f"threads_{n_threads}": many}
-            if sum(one) < 1.15 * sum(many):
-                # numpy's element-wise de-quantisation dominates and runs on one thread: the BLAS pool
-                # of the matvec makes no difference to the time
-                used, note = 1, f"; same time with the BLAS pool at 1 and at {n_threads} threads"
-        except ImportError:
-            pass
-        cpu = {"value": round(done_bytes / t_used / 1e9, 4), "unit": "GB/s", "cores": used,
-               "kind": "oracle",
+        # numpy's element-wise de-quantisation dominates the oracle and runs on one thread whatever
+        # the BLAS pool of the matvec is set to: one core is what it uses
+        cpu = {"value": round(done_bytes / t_used / 1e9, 4), "unit": "GB/s", "cores": 1,
+               "kind": "oracle", "host_threads_available": n_threads,
                "sample": f"{calls} oracle calls (dequantise to fp64 + fp64 matvec) cycling the three "
-                         f"config-2 shapes, {t_used:.1f} s{note}"}
+                         f"config-2 shapes, {t_used:.1f} s"}
 
+    how_step = {"multi": "ONE launch of tmac_mpgemv_fused_multi for the three shapes (table precompute + lookup in the kernel)",
+                "separate": "one fused launch (table precompute + lookup) per shape",
+                "two_call": "precompute_lut + mpgemm per shape"}[mode]
     line = {
         "metric": "mpgemv_w4a16_llama2_7b_decode_algorithmic_GBps",
         "value": round(value, 2),
@@ -512,22 +567,21 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[1]: Llama-2-7B-shaped W4A16 decode GEMV, N=1, "
                                "(M,K) in {(4096,4096),(11008,4096),(4096,11008)}, group 128; step = "
-                               + ("one fused launch (table precompute + lookup) per shape"
-                                  if fused else "precompute_lut + mpgemm per shape")
-                               + f" for the three shapes, weights cycled through a {args.ring_mb} MiB ring per shape",
+                               + how_step + f", weights cycled through a {args.ring_mb} MiB ring per shape",
                    "launch": "eager" if args.no_graph else "hip graph replay",
+                   "untimed_preroll_steps": PREROLL_STEPS,
                    "frac_hbm_peak_whole_step": round(value / HBM_PEAK_GBPS, 4)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": (sum(MEASURED_TRAFFIC_BYTES["fetch"]) + sum(MEASURED_TRAFFIC_BYTES["write"])
-                                 if (fused and not args.rows) else None),
-                     "traffic_unit": "bytes per step (three launches), rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated",
+                     "traffic": traffic,
+                     "traffic_unit": "bytes per step, rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated; null when the "
+                                     "kernel sources changed since the counters were read",
                      "algorithmic_bytes": step_bytes,
-                     "kernel": ("mpgemv_perm_kernel<f16 tables, 4 bit, chunk scales, 8 rows, "
-                                + ("fused table build>" if fused else "tables from the LUT buffer>")),
+                     "kernel": "mpgemv_perm_kernel<f16 tables, 4 bit, chunk scales, "
+                               + ("fused table build>" if mode != "two_call" else "tables from the LUT buffer>"),
                      "measured": how,
-                     "avg_launch_us": round(step_us / 3, 3) if fused else round(sum(per_us) / 3, 3),
-                     "launch_us": [round(u, 3) for u in per_us]},
+                     "avg_launch_us": round(avg_launch_us, 3),
+                     "launch_us_one_shape_at_a_time": None if launch_us is None else [round(u, 3) for u in launch_us]},
         "cpu_baseline": cpu,
         "detail": detail,
     }

@@ -20,8 +20,8 @@
  *   S[n,G]     = sum of the activations of quantisation group G.
  *
  * General rules
- *   - The library allocates no memory and keeps no mutable global state; the caller owns
- *     every buffer.  Pointers named *_host are host memory, *_dev are device memory of the
+ *   - The library allocates no memory; the caller owns every buffer.  The only state it keeps is
+ *     the text of the last HIP error of the calling thread (tmac_last_error_detail).  Pointers named *_host are host memory, *_dev are device memory of the
  *     current HIP device.  Device pointers must be 16-byte aligned (256 recommended).
  *   - Device entry points only enqueue work on `stream` (a hipStream_t passed as void*,
  *     NULL = the default stream) and never synchronise.
@@ -162,8 +162,8 @@ size_t tmac_packed_bytes(const tmac_wdesc* desc);
  *                levels, the bias term vanishes); ignored when group == 0 (the zero of
  *                the whole tensor is desc->zero_point)
  *   packed_host  output, packed_bytes >= tmac_packed_bytes(desc)
- * The blob cannot be checked against `desc` once it is in device memory: passing a blob
- * packed for a different desc to tmac_mpgemm is undefined.
+ * The device entry points do not read the blob on the host: passing a blob packed for a different
+ * desc to them is undefined; tmac_blob_check compares a host copy of the header with a desc.
  * Errors: TMAC_EINVAL (null pointer, bad desc, code out of range), TMAC_ESIZE. */
 tmac_status tmac_pack_weights(const tmac_wdesc* desc, const uint8_t* q_host,
                               const uint16_t* scales_host, const uint16_t* zeros_host,
@@ -265,13 +265,19 @@ tmac_status tmac_mpgemm_fused(const tmac_wdesc* desc, const void* packed_dev, co
                               float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
                               void* workspace_dev, size_t workspace_bytes, void* stream);
 
-/* Launch-shape knobs for benchmarking sweeps; 0 = library default.
- *   rows_per_group   register-table kernel (layout 2): weight rows per workgroup, 8 or 16
- *                    (default: 8, and 16 once a call has more than about 8000 wavefronts, i.e.
- *                    N * M / 8 * ceil(K / 1024) >= 8192, where sharing one set of tables between two
- *                    row tiles pays); must be 0 for layout 3 (TMAC_EUNSUPPORTED otherwise) */
+/* Launch-shape knobs of the register-table kernel (layout 2) for benchmarking sweeps; 0 = library
+ * default; all must be 0 for layout 3 (TMAC_EUNSUPPORTED otherwise).  Results do not depend on
+ * rows_per_group or workgroup_waves; group_waves changes the order in which partial sums over K are
+ * added (every setting is deterministic and within the same error bound).
+ *   rows_per_group   weight rows that share one set of tables: 8 or 16 (default: 8, and 16 once a
+ *                    call has more than about 8000 wavefronts, where sharing the tables pays)
+ *   group_waves      most wavefronts that split the K of one group of rows, 1..16; a row of K
+ *                    elements has ceil(K / 1024) blocks, dealt round-robin to the group's waves
+ *   workgroup_waves  wavefronts per workgroup, 1..16, rounded down to whole groups (at least one)
+ *   workgroups_per_cu  most workgroups resident on one compute unit, 2..8 (enforced by asking for
+ *                    LDS that nobody uses; default: whatever registers and wave slots allow) */
 typedef struct {
-  int32_t rows_per_group, reserved[7];
+  int32_t rows_per_group, group_waves, workgroup_waves, workgroups_per_cu, reserved[4];
 } tmac_tuning;
 
 /* Same as tmac_mpgemm with explicit launch-shape knobs (NULL = defaults). */
@@ -288,21 +294,51 @@ tmac_status tmac_mpgemv_fused_ex(const tmac_wdesc* desc, const void* packed_dev,
                                  float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
                                  void* stream, const tmac_tuning* tuning);
 
-/* Measurement helper, not part of the mpGEMM path (Section 5.2 notes that multi-threaded mpGEMV
- * is bound by memory bandwidth: this is the plain streaming read the lookup kernels are compared
- * with).  Reads `bytes` bytes from src_dev with 16-byte loads, `per_thread` (1, 4 or 8) loads in
- * flight per lane, optionally non-temporal; sink_dev needs 256 writable bytes.
- * Errors: TMAC_EINVAL, TMAC_EUNSUPPORTED, TMAC_EHIP. */
-tmac_status tmac_stream_read(const void* src_dev, size_t bytes, void* sink_dev, int32_t per_thread,
-                             int32_t nontemporal, void* stream);
+/* Several independent decode GEMVs in ONE launch (the paper's end-to-end section, 5.3, shows that
+ * what surrounds the kernels eats their gains: a decode GEMV of a few megabytes costs about as
+ * much to launch as to run).  Item i is the call tmac_mpgemv_fused(desc, packed_dev, A_dev, act, N,
+ * lda, act_scale_dev, weight_scale, out_dev, out, ldo, stream); the workgroups of one grid are
+ * dealt out over the row tiles of all matrices, tables are built inside the kernel as in the single
+ * call, and the result of every item equals that single call's bit for bit (the summation order of
+ * a matrix does not depend on what else is in the launch).
+ *   items   host array of `count` items, 1 <= count <= TMAC_MULTI_MAX; read before the call returns
+ *   every desc: layout 2, K % 16 == 0, the same bits; the scales of all matrices must be grouped
+ *   the same way (all per row or per tensor, or all with group sizes that are multiples of 128, or
+ *   all with other multiples of 16); M, K, group size, pointers and leading dimensions are per item.
+ *   act, N, out are common to the items.  Items must not alias each other's outputs.
+ *   tuning  NULL = defaults (only rows_per_group applies)
+ * Errors: TMAC_EINVAL (null or misaligned pointer, bad desc or leading dimension),
+ * TMAC_EUNSUPPORTED (count out of range, mixed bit-widths or grouping modes, what
+ * tmac_mpgemv_fused rejects), TMAC_EHIP. */
+enum { TMAC_MULTI_MAX = 8 };
+typedef struct {
+  const tmac_wdesc* desc;
+  const void* packed_dev;
+  const void* A_dev;
+  int64_t lda;
+  const float* act_scale_dev;
+  float weight_scale;
+  void* out_dev;
+  int64_t ldo;
+} tmac_gemv_item;
+tmac_status tmac_mpgemv_fused_multi(const tmac_gemv_item* items, int32_t count, tmac_act_t act, int32_t N,
+                                    tmac_out_t out, void* stream, const tmac_tuning* tuning);
 
-/* Measurement helper, not part of the mpGEMM path (Section 3.2 wants the tables in the fastest
- * on-chip memory because they are read at random: this measures how fast that memory serves such
- * reads).  `workgroups` workgroups of 256 lanes each hold 32 KB of tables in LDS and issue
- * `rounds` x 16 reads of 16 bytes per lane at data-dependent offsets, with the address arithmetic
- * of the batched lookup kernels and no other work; sink_dev needs 256 writable bytes.
- * Errors: TMAC_EINVAL, TMAC_EHIP. */
-tmac_status tmac_lds_lookup_probe(int32_t workgroups, int32_t rounds, void* sink_dev, void* stream);
+/* Host-side check of a packed blob against a desc (the blob header is the first 256 bytes of what
+ * tmac_pack_weights wrote; pass the host copy, or those bytes copied back from the device):
+ * TMAC_OK when magic, layout, M, K, bits, g, group, the per-tensor zero point and the sizes in the
+ * header are those tmac_pack_weights writes for `desc`; TMAC_EINVAL otherwise (or on a null
+ * pointer or an invalid desc).  The device entry points cannot make this check themselves: they
+ * never read device memory on the host. */
+tmac_status tmac_blob_check(const tmac_wdesc* desc, const void* header_host);
+
+/* Largest tmac_lut_bytes / tmac_workspace_bytes / tmac_fused_workspace_bytes over 1..N_max
+ * activation rows: the size of a buffer that serves every call with at most N_max rows (the sizes
+ * are not monotonic in N).  0 on bad arguments, or when any N in the range is unsupported for the
+ * fused workspace. */
+size_t tmac_lut_bytes_max(int32_t N_max, int32_t K, int32_t g, int32_t group, tmac_lut_t lut);
+size_t tmac_workspace_bytes_max(const tmac_wdesc* desc, int32_t N_max);
+size_t tmac_fused_workspace_bytes_max(const tmac_wdesc* desc, int32_t N_max, tmac_act_t act);
 
 const char* tmac_status_str(tmac_status s);
 

@@ -145,31 +145,6 @@ def precompute_lut(act, g=4, dtype=np.float64):
     return lut.astype(dtype)
 
 
-def precompute_lut_fp16_tree(act, g=4):
-    """Precompute in the activations' own precision (reading of Section 3.1 for
-    fp16 activations: the table is built with adds and subtracts of the same
-    type as its entries).  The g signed terms +-a_j are added pairwise,
-    ((+-a0 +- a1) + (+-a2 +- a3)) + ..., and every addition is rounded to fp16
-    (round to nearest even).  Returns a float16 array of shape (N, K/g, 2^g).
-    With g = 2 there is one addition and the result equals the once-rounded
-    exact sum; from g = 4 on entries can differ from it by the roundings of the
-    partial sums."""
-    A = np.asarray(act)
-    assert A.dtype == np.float16 and g & (g - 1) == 0
-    N, K = A.shape
-    assert K % g == 0
-    Ag = A.reshape(N, K // g, g).astype(np.float64)
-    lut = np.zeros((N, K // g, 1 << g), dtype=np.float16)
-    for p in range(1 << g):
-        terms = [Ag[:, :, j] if (p >> j) & 1 else -Ag[:, :, j] for j in range(g)]
-        while len(terms) > 1:
-            # the fp64 sum of two fp16 numbers is exact, so this is one rounding per addition
-            terms = [(terms[i] + terms[i + 1]).astype(np.float16).astype(np.float64)
-                     for i in range(0, len(terms), 2)]
-        lut[:, :, p] = terms[0].astype(np.float16)
-    return lut
-
-
 def mirror_half(lut):
     """Mirror consolidation (Section 3.3): keep entries 0..2^(g-1)-1 only."""
     return lut[..., : lut.shape[-1] // 2]
@@ -197,53 +172,6 @@ def lookup_sum(lut, idx, lut_groups_per_qgroup):
     return out
 
 
-def lookup_sum_narrow(lut16, idx, lut_groups_per_qgroup, tables_per_sum=8):
-    """Look-up + aggregation for one bit plane with a narrow running sum
-    (Section 3.3 / Section 4, "fast aggregation": look-up results are added in
-    the tables' own precision and converted to a higher precision now and
-    then).  Reading for 16-bit float tables: the entries of ``tables_per_sum``
-    consecutive LUT groups are added pairwise in fp16,
-    ((e0+e1)+(e2+e3))+((e4+e5)+(e6+e7)), every add rounded to fp16; these short
-    sums are then added in fp64.  ``lut16`` must be a float16 table."""
-    assert lut16.dtype == np.float16
-    N, KG, _ = lut16.shape
-    M, KG2 = idx.shape
-    T = tables_per_sum
-    assert KG == KG2 and KG % lut_groups_per_qgroup == 0 and lut_groups_per_qgroup % T == 0
-    assert T & (T - 1) == 0
-    nq = KG // lut_groups_per_qgroup
-    out = np.zeros((N, M, nq), dtype=np.float64)
-    kg_range = np.arange(KG)
-    for n in range(N):
-        v = lut16[n][kg_range[None, :], idx].reshape(M, KG // T, T)      # fp16
-        while v.shape[-1] > 1:
-            v = (v[..., 0::2] + v[..., 1::2]).astype(np.float16)          # one rounding per add
-        short = v[..., 0].astype(np.float64)                              # [M, KG/T]
-        out[n] = short.reshape(M, nq, lut_groups_per_qgroup // T).sum(axis=2)
-    return out
-
-
-def lut_mpgemm_narrow(act, q, bits, scales, zeros, group, g=4, tables_per_sum=8):
-    """The LUT route with fp16 tables built by fp16 additions
-    (``precompute_lut_fp16_tree``) and the narrow running sum of
-    ``lookup_sum_narrow`` (group scales only); everything else as ``lut_mpgemm``."""
-    q = np.asarray(q)
-    M, K = q.shape
-    nq = K // group
-    s = np.asarray(scales).astype(np.float64)
-    z = np.asarray(zeros).astype(np.float64)
-    lut = precompute_lut_fp16_tree(act, g)
-    S = group_sums(act, group).astype(np.float64)
-    mid = (2.0 ** bits - 1.0) / 2.0
-    Lsum = np.zeros((lut.shape[0], M, nq), dtype=np.float64)
-    for i, plane in enumerate(bit_planes(q, bits)):
-        Lsum += (2.0 ** i) * lookup_sum_narrow(lut, group_indices(plane, g), group // g, tables_per_sum)
-    R = np.zeros((lut.shape[0], M), dtype=np.float64)
-    for gq in range(nq):
-        R += s[None, :, gq] * (0.5 * Lsum[:, :, gq] + (mid - z[None, :, gq]) * S[:, gq][:, None])
-    return R
-
-
 def group_sums(act, group):
     """S[n, G] = sum of the activations of quantisation group G (the product of
     A with the all-ones matrix J of Section 4, per group)."""
@@ -265,9 +193,8 @@ def lut_mpgemm(act, q, bits, scales=None, zeros=None, group=0, weight_scale=1.0,
 
     The first term is Algorithm 1's sum_i alpha_i R_i, the second is its R_beta
     with the zero point folded into the constant matrix B.
-    ``table_dtype=np.float16`` rounds every table entry to fp16 once;
-    ``table_dtype="fp16_tree"`` builds the tables with fp16 additions
-    (``precompute_lut_fp16_tree``); the sums over looked-up entries stay in fp64.
+    ``table_dtype=np.float16`` rounds every table entry to fp16 once; the sums
+    over looked-up entries stay in fp64.
     """
     q = np.asarray(q)
     M, K = q.shape
@@ -280,7 +207,7 @@ def lut_mpgemm(act, q, bits, scales=None, zeros=None, group=0, weight_scale=1.0,
     else:
         s = np.asarray(scales).astype(np.float64)
         z = np.asarray(zeros).astype(np.float64)
-    lut = precompute_lut_fp16_tree(act, g) if table_dtype == "fp16_tree" else precompute_lut(act, g, dtype=table_dtype)
+    lut = precompute_lut(act, g, dtype=table_dtype)
     S = group_sums(act, G).astype(np.float64)                     # [N, nq]
     mid = (2.0 ** bits - 1.0) / 2.0
     N = lut.shape[0]
@@ -330,22 +257,10 @@ def algorithm1_unscaled(act, q, bits, g=4):
 
 
 # ----------------------------------------------------------------------------
-# Table quantisation (Section 3.3) -- reading: one scale per quantisation group,
-# shared by all tables that are aggregated together before conversion
+# Table quantisation (Section 3.3) -- reading: one scale per unit of four tables
+# (16 activations), shared by the tables whose look-ups are added as integers
+# before the single conversion
 # ----------------------------------------------------------------------------
-
-
-def quantize_tables_int8(lut, lut_groups_per_qgroup):
-    """int8 table quantisation with a dynamic scale per (n, quantisation group):
-    scale = max|T| / 127 over the tables of the group, entries rint(T/scale)
-    clipped to +-127.  Returns (int8 tables as int64, scales fp64 [N, nq])."""
-    N, KG, P = lut.shape
-    nq = KG // lut_groups_per_qgroup
-    t = lut.astype(np.float64).reshape(N, nq, lut_groups_per_qgroup * P)
-    amax = np.abs(t).max(axis=2)
-    scale = np.where(amax > 0, amax / 127.0, 1.0)
-    qt = np.clip(np.rint(t / scale[:, :, None]), -127, 127).astype(np.int64)
-    return qt.reshape(N, KG, P), scale
 
 
 def quantize_tables_int8_per_unit(lut, tables_per_unit=4):

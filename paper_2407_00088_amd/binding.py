@@ -24,11 +24,14 @@ TMAC_OUT_F32, TMAC_OUT_F16, TMAC_OUT_I32 = 0, 1, 2
 TMAC_LAYOUT_R8U16 = 2     # register-table decode kernel (small N)
 TMAC_LAYOUT_R64K32 = 3    # batched lookup kernel, lane = weight row (many activation rows)
 
+TMAC_MULTI_MAX = 8
+
 EXPORTS = [
     "tmac_packed_bytes", "tmac_pack_weights", "tmac_lut_bytes", "tmac_precompute_lut",
     "tmac_workspace_bytes", "tmac_mpgemm", "tmac_mpgemm_ex", "tmac_status_str", "tmac_version",
-    "tmac_last_error_detail", "tmac_stream_read", "tmac_lds_lookup_probe", "tmac_mpgemv_fused", "tmac_mpgemv_fused_ex",
-    "tmac_fused_workspace_bytes", "tmac_mpgemm_fused",
+    "tmac_last_error_detail", "tmac_mpgemv_fused", "tmac_mpgemv_fused_ex",
+    "tmac_fused_workspace_bytes", "tmac_mpgemm_fused", "tmac_mpgemv_fused_multi", "tmac_blob_check",
+    "tmac_lut_bytes_max", "tmac_workspace_bytes_max", "tmac_fused_workspace_bytes_max",
 ]
 
 
@@ -39,7 +42,14 @@ class tmac_wdesc(C.Structure):
 
 
 class tmac_tuning(C.Structure):
-    _fields_ = [("rows_per_group", C.c_int32), ("reserved", C.c_int32 * 7)]
+    _fields_ = [("rows_per_group", C.c_int32), ("group_waves", C.c_int32), ("workgroup_waves", C.c_int32),
+                ("workgroups_per_cu", C.c_int32), ("reserved", C.c_int32 * 4)]
+
+
+class tmac_gemv_item(C.Structure):
+    _fields_ = [("desc", C.POINTER(tmac_wdesc)), ("packed_dev", C.c_void_p), ("A_dev", C.c_void_p),
+                ("lda", C.c_int64), ("act_scale_dev", C.c_void_p), ("weight_scale", C.c_float),
+                ("out_dev", C.c_void_p), ("ldo", C.c_int64)]
 
 
 class TmacError(RuntimeError):
@@ -83,10 +93,14 @@ def _load() -> C.CDLL:
     lib.tmac_status_str.restype, lib.tmac_status_str.argtypes = C.c_char_p, [C.c_int]
     lib.tmac_version.restype, lib.tmac_version.argtypes = I32, []
     lib.tmac_last_error_detail.restype, lib.tmac_last_error_detail.argtypes = C.c_char_p, []
-    lib.tmac_stream_read.restype = C.c_int
-    lib.tmac_stream_read.argtypes = [P, SZ, P, I32, I32, P]
-    lib.tmac_lds_lookup_probe.restype = C.c_int
-    lib.tmac_lds_lookup_probe.argtypes = [I32, I32, P, P]
+    lib.tmac_mpgemv_fused_multi.restype = C.c_int
+    lib.tmac_mpgemv_fused_multi.argtypes = [C.POINTER(tmac_gemv_item), I32, C.c_int, I32, C.c_int, P,
+                                            C.POINTER(tmac_tuning)]
+    lib.tmac_blob_check.restype, lib.tmac_blob_check.argtypes = C.c_int, [D, P]
+    lib.tmac_lut_bytes_max.restype, lib.tmac_lut_bytes_max.argtypes = SZ, [I32, I32, I32, I32, C.c_int]
+    lib.tmac_workspace_bytes_max.restype, lib.tmac_workspace_bytes_max.argtypes = SZ, [D, I32]
+    lib.tmac_fused_workspace_bytes_max.restype = SZ
+    lib.tmac_fused_workspace_bytes_max.argtypes = [D, I32, C.c_int]
     return lib
 
 
@@ -141,26 +155,33 @@ def tmac_pack_weights(desc: tmac_wdesc, q: np.ndarray, scales: Optional[np.ndarr
     return blob
 
 
-def tmac_lds_lookup_probe(workgroups: int, rounds: int, sink, stream=None) -> None:
-    """LDS lookup-rate probe (measurement helper): workgroups x 256 lanes x rounds x 16 reads of 16 bytes."""
-    _check(lib.tmac_lds_lookup_probe(workgroups, rounds, C.c_void_p(sink.data_ptr()), _stream_ptr(stream)),
-           "tmac_lds_lookup_probe")
-
-
-def tmac_stream_read(src, sink, per_thread: int = 4, nontemporal: bool = False, nbytes: Optional[int] = None,
-                     stream=None) -> None:
-    """Plain streaming read of a device tensor (measurement helper)."""
-    n = src.numel() * src.element_size() if nbytes is None else nbytes
-    _check(lib.tmac_stream_read(C.c_void_p(src.data_ptr()), n, C.c_void_p(sink.data_ptr()), per_thread,
-                                1 if nontemporal else 0, _stream_ptr(stream)), "tmac_stream_read")
-
-
 def tmac_lut_bytes(N: int, K: int, group: int, lut: int, g: int = 4) -> int:
     return int(lib.tmac_lut_bytes(N, K, g, group, lut))
 
 
+def tmac_lut_bytes_max(N_max: int, K: int, group: int, lut: int, g: int = 4) -> int:
+    return int(lib.tmac_lut_bytes_max(N_max, K, g, group, lut))
+
+
 def tmac_workspace_bytes(desc: tmac_wdesc, N: int) -> int:
     return int(lib.tmac_workspace_bytes(C.byref(desc), N))
+
+
+def tmac_workspace_bytes_max(desc: tmac_wdesc, N_max: int) -> int:
+    return int(lib.tmac_workspace_bytes_max(C.byref(desc), N_max))
+
+
+def tmac_fused_workspace_bytes_max(desc: tmac_wdesc, N_max: int, act: int) -> int:
+    return int(lib.tmac_fused_workspace_bytes_max(C.byref(desc), N_max, act))
+
+
+def tmac_blob_check(desc: tmac_wdesc, header: np.ndarray) -> int:
+    """Status of the host-side header check (TMAC_OK or TMAC_EINVAL); `header`: at least the first
+    256 bytes of a packed blob, as a uint8 numpy array."""
+    h = np.ascontiguousarray(header, dtype=np.uint8)
+    if h.size < 256:
+        raise ValueError("the blob header is 256 bytes")
+    return int(lib.tmac_blob_check(C.byref(desc), _np_ptr(h)))
 
 
 def _stream_ptr(stream) -> Optional[int]:
@@ -219,6 +240,28 @@ def tmac_mpgemv_fused(desc: tmac_wdesc, packed, A, N: int, out, out_t: int, act:
         _check(lib.tmac_mpgemv_fused(*args), "tmac_mpgemv_fused")
     else:
         _check(lib.tmac_mpgemv_fused_ex(*args, C.byref(tuning)), "tmac_mpgemv_fused_ex")
+
+
+def tmac_mpgemv_fused_multi(items, N: int, out_t: int, act: Optional[int] = None, stream=None,
+                            tuning: Optional[tmac_tuning] = None) -> None:
+    """items: sequence of (desc, packed, A, out[, act_scale[, weight_scale]]) with device tensors;
+    one launch serves them all."""
+    import torch
+    n = len(items)
+    arr = (tmac_gemv_item * max(n, 1))()
+    for i, it in enumerate(items):
+        desc, packed, A, out = it[:4]
+        act_scale = it[4] if len(it) > 4 else None
+        wscale = it[5] if len(it) > 5 else 1.0
+        a_act = TMAC_ACT_I8 if A.dtype == torch.int8 else TMAC_ACT_F16
+        if act is None:
+            act = a_act
+        arr[i] = tmac_gemv_item(C.pointer(desc), packed.data_ptr(), A.data_ptr(),
+                                A.stride(0) if A.dim() == 2 else desc.K,
+                                act_scale.data_ptr() if act_scale is not None else None, float(wscale),
+                                out.data_ptr(), out.stride(0) if out.dim() == 2 else desc.M)
+    _check(lib.tmac_mpgemv_fused_multi(arr, n, TMAC_ACT_F16 if act is None else act, N, out_t, _stream_ptr(stream),
+                                       C.byref(tuning) if tuning is not None else None), "tmac_mpgemv_fused_multi")
 
 
 def tmac_fused_workspace_bytes(desc: tmac_wdesc, N: int, act: int) -> int:

@@ -9,7 +9,10 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libtmac_hip.so")
-SOURCES = ["tmac_kernels.hip", "tmac_perm.hip", "tmac_rows.hip", "tmac_util.hip", "tmac_pack.cpp"]
+SOURCES = ["tmac_kernels.hip", "tmac_perm.hip", "tmac_rows.hip", "tmac_pack.cpp"]
+# measurement helpers (plain read, LDS probe, empty kernel): a library of their own, not the product's ABI
+BENCH_LIB_PATH = os.path.join(PKG_DIR, "libtmac_bench.so")
+BENCH_SOURCES = ["tmac_bench.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -19,15 +22,20 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = True, extra_flags=()) -> str:
+def _compile(out: str, sources, verbose: bool, extra_flags=()) -> None:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-o", LIB_PATH]
-    for s in SOURCES:
+    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-o", out]
+    for s in sources:
         path = os.path.join(CSRC, s)
         cmd += ["-x", "hip", path] if s.endswith(".cpp") else [path]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
+
+
+def build(verbose: bool = True, extra_flags=()) -> str:
+    _compile(LIB_PATH, SOURCES, verbose, extra_flags)
+    _compile(BENCH_LIB_PATH, BENCH_SOURCES, verbose, extra_flags)
     return LIB_PATH
 
 

@@ -1,14 +1,14 @@
 // Measurement helpers: a plain streaming-read kernel, the "what can a read-only kernel reach on
 // this chip" reference that the benchmark prints next to the lookup kernels, and a probe of the
-// LDS lookup rate; neither takes part in the mpGEMM path.
+// LDS lookup rate, and an empty kernel; none takes part in the mpGEMM path (they are built into a
+// library of their own, libtmac_bench.so).
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
 
-#include "tmac.h"
-#include "tmac_internal.h"
+#include "tmac_bench.h"
 
-namespace tmac {
+namespace tmac_bench {
 
 typedef uint32_t ru32x4 __attribute__((ext_vector_type(4)));
 
@@ -65,27 +65,28 @@ __global__ __launch_bounds__(256) void lds_lookup_probe_kernel(int rounds, uint3
   if (keep == 0xFFFFFFFFu) sink[blockIdx.x & 63] = keep;  // practically never; keeps the loop alive
 }
 
-}  // namespace tmac
+__global__ void empty_kernel() {}
 
-using namespace tmac;
+}  // namespace tmac_bench
 
-extern "C" tmac_status tmac_lds_lookup_probe(int32_t workgroups, int32_t rounds, void* sink_dev, void* stream) {
-  if (!sink_dev || workgroups <= 0 || rounds <= 0 || rounds > (1 << 24)) return TMAC_EINVAL;
+using namespace tmac_bench;
+
+extern "C" int tmac_bench_lds_lookup_probe(int32_t workgroups, int32_t rounds, void* sink_dev, void* stream) {
+  if (!sink_dev || workgroups <= 0 || rounds <= 0 || rounds > (1 << 24)) return 1;
   uint32_t* sink = static_cast<uint32_t*>(sink_dev);
   int r = rounds;
   void* args[] = {&r, &sink};
   const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(lds_lookup_probe_kernel), dim3((unsigned)workgroups),
                                        dim3(256), args, 0, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) {
-    note_hip_error((int)e);
-    return TMAC_EHIP;
+    return 4;
   }
-  return TMAC_OK;
+  return 0;
 }
 
-extern "C" tmac_status tmac_stream_read(const void* src_dev, size_t bytes, void* sink_dev, int32_t per_thread,
+extern "C" int tmac_bench_stream_read(const void* src_dev, size_t bytes, void* sink_dev, int32_t per_thread,
                                         int32_t nontemporal, void* stream) {
-  if (!src_dev || !sink_dev || bytes < 16 || (reinterpret_cast<uintptr_t>(src_dev) & 15u)) return TMAC_EINVAL;
+  if (!src_dev || !sink_dev || bytes < 16 || (reinterpret_cast<uintptr_t>(src_dev) & 15u)) return 1;
   const size_t n16 = bytes / 16;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const ru32x4* src = static_cast<const ru32x4*>(src_dev);
@@ -100,15 +101,21 @@ extern "C" tmac_status tmac_stream_read(const void* src_dev, size_t bytes, void*
     case 9: fn = reinterpret_cast<const void*>(stream_read_kernel<4, true>); break;
     case 16: fn = reinterpret_cast<const void*>(stream_read_kernel<8, false>); break;
     case 17: fn = reinterpret_cast<const void*>(stream_read_kernel<8, true>); break;
-    default: return TMAC_EINVAL;
+    default: return 1;
   }
   const size_t per_block = (size_t)256 * pt;
   const size_t blocks = (n16 + per_block - 1) / per_block;
-  if (blocks > 0x7fffffffu) return TMAC_EUNSUPPORTED;
+  if (blocks > 0x7fffffffu) return 2;
   const hipError_t e = hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(256), args, 0, st);
   if (e != hipSuccess) {
-    note_hip_error((int)e);
-    return TMAC_EHIP;
+    return 4;
   }
-  return TMAC_OK;
+  return 0;
+}
+
+extern "C" int tmac_bench_empty_kernel(void* stream) {
+  void* args[] = {nullptr};  // no parameters
+  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(empty_kernel), dim3(1), dim3(64), args, 0,
+                                       static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? 0 : 4;
 }

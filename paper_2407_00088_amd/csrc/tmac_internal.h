@@ -157,7 +157,12 @@ __device__ inline __attribute__((always_inline)) float sum4_f16(uint32_t x01, ui
 // tmac_status value.
 int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, const void* A_dev,
                      int64_t lda, int lut_t, int N, const float* act_scale_dev, float weight_scale,
-                     void* out_dev, int out_t, int64_t ldo, void* stream, int rows_per_group);
+                     void* out_dev, int out_t, int64_t ldo, void* stream, const tmac_tuning* tuning);
+
+// Several matrices in one launch of the register-table kernel, tables built in the kernel (items
+// validated by the caller as for launch_perm_gemv with lut_dev == nullptr).
+int launch_perm_gemv_multi(const tmac_gemv_item* items, int count, int act_t, int N, int out_t, void* stream,
+                           const tmac_tuning* tuning);
 
 // Batched lookup kernel (layout 3); defined in tmac_rows.hip.
 struct RowsPlan {

@@ -7,6 +7,7 @@
 //                         of the decode kernel (Section 3.3, Section 4).
 //   precompute_q8_kernel  the same with table quantisation (Section 3.3): int8 entries and one
 //                         scale per 16 activations.
+//   precompute_g_kernel   tables for the LUT group sizes 2 and 8.
 //
 // The lookup kernels live in tmac_perm.hip (decode, packed layout 2) and tmac_rows.hip (many
 // activation rows, packed layout 3).
@@ -15,6 +16,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <cstring>
 #include <tuple>
 #include <utility>
 
@@ -358,6 +360,20 @@ __global__ __launch_bounds__(256) void precompute_q8_kernel(const __half* __rest
 // ------------------------------------------------------------------------------------------
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Launch-shape knobs: NULL or all zero = defaults.
+static bool tuning_valid(const tmac_tuning* t) {
+  if (!t) return true;
+  if (t->rows_per_group != 0 && t->rows_per_group != 8 && t->rows_per_group != 16) return false;
+  if (t->group_waves < 0 || t->group_waves > 16 || t->workgroup_waves < 0 || t->workgroup_waves > 16) return false;
+  if (t->workgroups_per_cu != 0 && (t->workgroups_per_cu < 2 || t->workgroups_per_cu > 8)) return false;
+  for (int r : t->reserved)
+    if (r != 0) return false;
+  return true;
+}
+static bool tuning_default(const tmac_tuning* t) {
+  return !t || (t->rows_per_group == 0 && t->group_waves == 0 && t->workgroup_waves == 0 && t->workgroups_per_cu == 0);
+}
+
 // Last HIP error seen by this thread while enqueuing (diagnostics only).
 static thread_local hipError_t g_last_hip_error = hipSuccess;
 void note_hip_error(int hip_error) { g_last_hip_error = static_cast<hipError_t>(hip_error); }
@@ -478,16 +494,15 @@ extern "C" tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed
   if (!aligned16(packed_dev) || !aligned16(lut_dev) || !aligned16(workspace_dev)) return TMAC_EINVAL;
   if (ldo < desc->M) return TMAC_EINVAL;
   if (!group_supported(desc)) return TMAC_EUNSUPPORTED;
-  const int rpg = tuning ? tuning->rows_per_group : 0;
-  if (rpg != 0 && rpg != 8 && rpg != 16) return TMAC_EINVAL;
+  if (!tuning_valid(tuning)) return TMAC_EINVAL;
   if (desc->layout == TMAC_LAYOUT_R8U16) {
     // register-table decode kernel; it needs no workspace
     return static_cast<tmac_status>(launch_perm_gemv(desc, packed_dev, lut_dev, nullptr, 0, (int)lut, N,
                                                       act_scale_dev, weight_scale, out_dev, (int)out, ldo,
-                                                      stream, rpg));
+                                                      stream, tuning));
   }
   // batched lookup kernel (lane = weight row); no launch-shape knobs
-  if (rpg != 0) return TMAC_EUNSUPPORTED;
+  if (!tuning_default(tuning)) return TMAC_EUNSUPPORTED;
   return static_cast<tmac_status>(launch_rows_gemm(desc, packed_dev, lut_dev, nullptr, 0, (int)lut, N, act_scale_dev,
                                                     weight_scale, out_dev, (int)out, ldo, workspace_dev,
                                                     workspace_bytes, stream));
@@ -507,12 +522,81 @@ extern "C" tmac_status tmac_mpgemv_fused_ex(const tmac_wdesc* desc, const void* 
   if (lda % row_elems_16B != 0) return TMAC_EINVAL;
   if (desc->layout != TMAC_LAYOUT_R8U16 || desc->K % 16 != 0) return TMAC_EUNSUPPORTED;
   if (!group_supported(desc)) return TMAC_EUNSUPPORTED;
-  const int rpg = tuning ? tuning->rows_per_group : 0;
-  if (rpg != 0 && rpg != 8 && rpg != 16) return TMAC_EINVAL;
+  if (!tuning_valid(tuning)) return TMAC_EINVAL;
   return static_cast<tmac_status>(launch_perm_gemv(desc, packed_dev, nullptr, A_dev, lda,
                                                     act == TMAC_ACT_I8 ? (int)TMAC_LUT_I16 : (int)TMAC_LUT_F16,
                                                     N, act_scale_dev, weight_scale, out_dev, (int)out, ldo,
-                                                    stream, rpg));
+                                                    stream, tuning));
+}
+
+extern "C" tmac_status tmac_mpgemv_fused_multi(const tmac_gemv_item* items, int32_t count, tmac_act_t act, int32_t N,
+                                               tmac_out_t out, void* stream, const tmac_tuning* tuning) {
+  if (!items || N <= 0) return TMAC_EINVAL;
+  if (count < 1 || count > TMAC_MULTI_MAX) return TMAC_EUNSUPPORTED;
+  if (act != TMAC_ACT_F16 && act != TMAC_ACT_I8) return TMAC_EINVAL;
+  if (out != TMAC_OUT_F32 && out != TMAC_OUT_F16 && out != TMAC_OUT_I32) return TMAC_EINVAL;
+  if (!tuning_valid(tuning)) return TMAC_EINVAL;
+  const int64_t row_elems_16B = (act == TMAC_ACT_F16) ? 8 : 16;
+  for (int i = 0; i < count; ++i) {
+    const tmac_gemv_item& it = items[i];
+    if (!desc_valid(it.desc) || !it.packed_dev || !it.A_dev || !it.out_dev) return TMAC_EINVAL;
+    if (!aligned16(it.packed_dev) || !aligned16(it.A_dev)) return TMAC_EINVAL;
+    if (it.ldo < it.desc->M || it.lda < it.desc->K || it.lda % row_elems_16B != 0) return TMAC_EINVAL;
+    if (it.desc->layout != TMAC_LAYOUT_R8U16 || it.desc->K % 16 != 0) return TMAC_EUNSUPPORTED;
+    if (!group_supported(it.desc)) return TMAC_EUNSUPPORTED;
+  }
+  return static_cast<tmac_status>(launch_perm_gemv_multi(items, count, (int)act, N, (int)out, stream, tuning));
+}
+
+extern "C" tmac_status tmac_blob_check(const tmac_wdesc* desc, const void* header_host) {
+  if (!desc_valid(desc) || !header_host) return TMAC_EINVAL;
+  tmac_blob_header h;
+  memcpy(&h, header_host, sizeof(h));
+  const Geometry ge = geometry(desc);
+  const float zp = desc->group == 0 ? desc->zero_point : 0.0f;
+  const bool same = h.magic == TMAC_MAGIC && h.layout == (uint32_t)desc->layout && h.M == desc->M && h.K == desc->K &&
+                    h.bits == desc->bits && h.g == desc->g && h.group == desc->group && h.Mp == ge.Mp &&
+                    h.Kp == ge.Kp && h.n_tiles == ge.n_tiles && h.n_chunks == ge.n_chunks &&
+                    h.n_qgroups == ge.n_qgroups && h.zero_point == zp && h.idx_off == ge.idx_off &&
+                    h.idx_bytes == ge.idx_bytes && h.sz_off == ge.sz_off && h.sz_bytes == ge.sz_bytes &&
+                    h.total_bytes == ge.total_bytes;
+  return same ? TMAC_OK : TMAC_EINVAL;
+}
+
+extern "C" size_t tmac_lut_bytes_max(int32_t N_max, int32_t K, int32_t g, int32_t group, tmac_lut_t lut) {
+  // every region grows with N (the padded row count of the table region is N rounded up to 4 or
+  // 8, never less than for N - 1), but the register-table kernel's regions exist only up to
+  // TMAC_DECODE_MAX_ROWS rows: the largest size is at N_max or at that row count
+  if (N_max <= 0) return 0;
+  size_t best = 0;
+  const int cand[] = {N_max, TMAC_DECODE_MAX_ROWS};
+  for (int n : cand) {
+    if (n > N_max) continue;
+    const size_t b = tmac_lut_bytes(n, K, g, group, lut);
+    if (b > best) best = b;
+  }
+  return best;
+}
+
+extern "C" size_t tmac_workspace_bytes_max(const tmac_wdesc* desc, int32_t N_max) {
+  if (!desc_valid(desc) || N_max <= 0) return 0;
+  size_t best = 0;
+  for (int n = 1; n <= N_max; ++n) {  // host arithmetic only; the split of a call changes with N in steps
+    const size_t b = tmac_workspace_bytes(desc, n);
+    if (b > best) best = b;
+  }
+  return best;
+}
+
+extern "C" size_t tmac_fused_workspace_bytes_max(const tmac_wdesc* desc, int32_t N_max, tmac_act_t act) {
+  if (!desc_valid(desc) || N_max <= 0) return 0;
+  size_t best = 0;
+  for (int n = 1; n <= N_max; ++n) {
+    const size_t b = tmac_fused_workspace_bytes(desc, n, act);
+    if (b == 0) return 0;
+    if (b > best) best = b;
+  }
+  return best;
 }
 
 extern "C" tmac_status tmac_mpgemv_fused(const tmac_wdesc* desc, const void* packed_dev, const void* A_dev,

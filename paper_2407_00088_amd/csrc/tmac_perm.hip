@@ -43,84 +43,13 @@
 
 #include <cmath>
 #include <cstdint>
+#include <cstring>
 
 #include "tmac.h"
 #include "tmac_internal.h"
+#include "tmac_perm_core.h"
 
 namespace tmac {
-
-typedef uint32_t pu32x4 __attribute__((ext_vector_type(4)));
-typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-
-struct PermParams {
-  const pu32x4* idx;       // packed indices, 16-byte slots (see layout 2 in tmac.h)
-  const pu32x4* sz;        // [n_tiles][nq] x 32 bytes: {fp16 scale, fp16 zero} of the 8 rows
-  const pu32x4* ht;        // split fp16 half tables, [N][U][4] 16-byte slots, piece-major per block
-  const void* S;           // [N][nq] fp32 / int32 group sums
-  const void* S16;         // [N][U]  fp32 / int32 unit sums
-  const void* S128;        // [N][U/8] fp32 / int32 sums of every 128 consecutive activations
-  const float* usc;        // int8 tables: [N][U] scale of the lane's four tables
-  const void* A;           // fused mode: activations [N][lda], fp16 or int8 (no LUT buffer is read)
-  int64_t lda;
-  void* out;
-  const float* act_scale;
-  int64_t ldo;
-  int M, N, K, U, n_tiles, nq;
-  int G;           // elements per quantisation group
-  uint32_t q_magic;  // ceil(2^32 / d), d = units (mode 1) or chunks (mode 2) per quantisation group; 0 if d = 1
-  BlockSplit bs;   // split of the U/8 chunks into blocks of at most 8
-  uint32_t ht_zero;  // slot index of the all-zero table
-  int per_tensor, int_exact, icoef;
-  float wscale, zero_point, mid;
-  int out_t;
-};
-
-__device__ __forceinline__ uint32_t bperm(uint32_t hi, uint32_t lo, uint32_t sel) {
-  return __builtin_amdgcn_perm(hi, lo, sel);  // bytes 0..3 of the source = lo, 4..7 = hi
-}
-
-__device__ __forceinline__ float dot2(uint32_t pair, uint32_t w, float acc) {
-  return __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, pair), __builtin_bit_cast(h2, w), acc, false);
-}
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_add_t(float v) {
-  return v + __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), CTRL, 0xf, 0xf, false));
-}
-
-// Sum 8 per-lane values over lane bits 5, 4, 3 with a transposing butterfly; afterwards every
-// lane holds row (lane >> 3), summed over the eight lanes with the same (lane & 7).
-//   v_permlane32_swap exchanges lanes 32..63 of its first operand with lanes 0..31 of the second,
-//   v_permlane16_swap does the same for the odd/even 16-lane rows; after each exchange the two
-//   operands hold, in every lane, two partial sums of the same row.
-__device__ __forceinline__ float reduce_hi3(const float* t, int lane) {
-  float v4[4], v2[2];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const auto rv = __builtin_amdgcn_permlane32_swap(__float_as_uint(t[i]), __float_as_uint(t[i + 4]), false, false);
-    v4[i] = __uint_as_float(rv[0]) + __uint_as_float(rv[1]);  // row i (lanes < 32) or i + 4
-  }
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const auto rv = __builtin_amdgcn_permlane16_swap(__float_as_uint(v4[i]), __float_as_uint(v4[i + 2]), false, false);
-    v2[i] = __uint_as_float(rv[0]) + __uint_as_float(rv[1]);  // row i + 2 * bit4(lane) + 4 * bit5(lane)
-  }
-  const bool up = (lane & 8) != 0;
-  const float keep = up ? v2[1] : v2[0], send = up ? v2[0] : v2[1];
-  return keep + __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(send), 0x128, 0xf, 0xf, false));  // row_ror:8
-}
-
-// Sum over lane bits 0, 1, 2 (all lanes of a group of 8 end with the total).
-__device__ __forceinline__ float reduce_lo3(float v) {
-  v = dpp_add_t<0xB1>(v);   // quad_perm [1,0,3,2]
-  v = dpp_add_t<0x4E>(v);   // quad_perm [2,3,0,1]
-  v = dpp_add_t<0x141>(v);  // row_half_mirror
-  return v;
-}
-
-// fp16 bit patterns of the plane weights
-constexpr uint32_t h2pack(uint16_t lo, uint16_t hi) { return (uint32_t)lo | ((uint32_t)hi << 16); }
-constexpr uint16_t H_0 = 0x0000, H_05 = 0x3800, H_1 = 0x3C00, H_2 = 0x4000, H_4 = 0x4400, H_8 = 0x4800;
 
 // GM: 0 = one scale per row or per tensor (raw sums, finished at the end), 1 = group scales applied
 // per (row, lane) (any group size that is a multiple of 16), 2 = group scales applied per
@@ -128,21 +57,40 @@ constexpr uint16_t H_0 = 0x0000, H_05 = 0x3800, H_1 = 0x3C00, H_2 = 0x4000, H_4 
 // FUSED: the lane builds the four tables of its unit from the activations itself (Algorithm 1
 // Precompute inside the lookup kernel), with the arithmetic of the stand-alone precompute kernel.
 // Q8: int8 tables with one scale per lane-unit (not with IS_INT or FUSED).
-template <bool IS_INT, int BITS, int GM, int RT, bool FUSED, bool Q8>
-__global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
+template <bool IS_INT, int BITS, int GM, int RT, bool FUSED, bool Q8, int NM>
+__global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParamsT<NM> pp) {
   static_assert(!(Q8 && (IS_INT || FUSED)), "int8 tables: fp16 activations, tables from the LUT buffer");
   constexpr int NR = 8 * RT;
   __shared__ float red[16 * NR];
   __shared__ float redS[16];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int NW = blockDim.x >> 6;
   const int n = blockIdx.y;
   const uint32_t jl = (uint32_t)lane & 7u, pos = (uint32_t)lane >> 3;  // chunk in block, unit in chunk
+  // the matrix this workgroup serves (all wave-uniform).  Its description is copied out of the
+  // kernel arguments in one go: every scalar load is requested before the first wait.
+  int mi = 0, wg0 = 0;
+  if constexpr (NM > 1) {
+#pragma unroll
+    for (int i = 0; i < NM - 1; ++i) {  // wg_end is non-decreasing, INT_MAX past the last matrix
+      const bool past = (int)blockIdx.x >= pp.wg_end[i];
+      mi += past ? 1 : 0;
+      wg0 = past ? pp.wg_end[i] : wg0;
+    }
+  }
+  const PermMat p = pp.m[mi];
+  // The waves of a workgroup form gpw groups of gsz waves; a group serves RT row tiles over the whole
+  // K, wave wig of it taking the blocks wig, wig + gsz, ...  Waves left over (blockDim is shared by
+  // the matrices of a launch) have no group: they skip the work and join the barrier.
+  const int NW = p.gsz;
+  const int grp = (int)(((uint32_t)wave * p.ginv) >> 8);
+  const int wig = wave - grp * NW;
+  const bool active = grp < p.gpw;
+  const uint32_t tg = (uint32_t)(((int)blockIdx.x - wg0) * p.gpw + (active ? grp : 0));  // group of row tiles
   uint32_t tile[RT];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
-    const uint32_t t = blockIdx.x * RT + rt;
+    const uint32_t t = tg * RT + rt;
     tile[rt] = t < (uint32_t)p.n_tiles ? t : (uint32_t)p.n_tiles - 1;  // clamped; stores are masked
   }
 
@@ -164,26 +112,19 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
       if (!p.per_tensor) fin_sz[rt] = reinterpret_cast<const uint32_t*>(p.sz)[(size_t)tile[rt] * 8 + jl];
   }
 
-  // plane weights: halved in the group-scale modes, where acc = bias + 1/2 * sum_i 2^i L_i
-  constexpr uint32_t W01 = GM ? h2pack(H_05, H_1) : h2pack(H_1, H_2);
-  constexpr uint32_t W23 = GM ? h2pack(H_2, H_4) : h2pack(H_4, H_8);
-  constexpr uint16_t WS0 = GM ? H_05 : H_1;  // single plane 0
-  constexpr uint16_t WS2 = GM ? H_2 : H_4;   // single plane 2
-
   // GM 0: raw sums, GM 1: scaled sums per (row, lane); GM 2: one scaled (row, chunk) sum per tile
   float tot[GM == 2 ? RT : NR];
 #pragma unroll
   for (int r = 0; r < (GM == 2 ? RT : NR); ++r) tot[r] = 0.f;
 
   float Stot = 0.f;  // fused mode, GM 0: this lane's share of the sum of all activations
-  for (int blk = wave; blk < p.bs.nB; blk += NW) {
-    const uint32_t c0 = (uint32_t)block_start(p.bs, blk);
-    const uint32_t ng = (uint32_t)(blk < p.bs.r ? p.bs.q + 1 : p.bs.q);
-    const uint32_t u0 = 8u * c0, nu = 8u * ng;
-    const bool valid = jl < ng;
-    const uint32_t l = valid ? pos * ng + jl : 0u;  // lanes without a unit re-read slot 0, with zero tables
-    const uint32_t c = valid ? c0 + jl : c0;        // 128-k chunk of this lane
-    const uint32_t u = 8u * c + pos;                // 16-k unit of this lane
+  for (int blk = active ? wig : p.bs.nB; blk < p.bs.nB; blk += NW) {
+    const LaneBlock lb = lane_block(p.bs, blk, lane);
+    const uint32_t u0 = lb.u0, nu = lb.nu;
+    const bool valid = lb.valid;
+    const uint32_t l = lb.l;  // lanes without a unit re-read slot 0, with zero tables
+    const uint32_t c = lb.c;  // 128-k chunk of this lane
+    const uint32_t u = lb.u;  // 16-k unit of this lane
 
     // 1. scale and zero, and (from the LUT buffer) the activation sum the bias term needs
     uint32_t szr[GM == 1 ? NR : RT];
@@ -218,25 +159,12 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
 
     // 1b. in fused mode: the lane's 16 activations (zero past the end of K and for idle lanes), raw;
     // they are unpacked only after the index loads have been requested
-    uint32_t araw[8];  // fp16: two per dword; int8: four per dword (one table each) in araw[0..3]
-    if constexpr (FUSED) {
-      const bool have = valid && 16u * u < (uint32_t)p.K;
-      pu32x4 v0 = {0u, 0u, 0u, 0u}, v1 = {0u, 0u, 0u, 0u};
-      if constexpr (IS_INT) {
-        if (have) v0 = *reinterpret_cast<const pu32x4*>(static_cast<const int8_t*>(p.A) + (size_t)n * p.lda + 16u * u);
-      } else {
-        if (have) {
-          const pu32x4* ap = reinterpret_cast<const pu32x4*>(static_cast<const __half*>(p.A) + (size_t)n * p.lda + 16u * u);
-          v0 = ap[0];
-          v1 = ap[1];
-        }
-      }
-      araw[0] = v0.x; araw[1] = v0.y; araw[2] = v0.z; araw[3] = v0.w;
-      araw[4] = v1.x; araw[5] = v1.y; araw[6] = v1.z; araw[7] = v1.w;
-    }
+    uint32_t araw[8];
+    if constexpr (FUSED) lane_load_act<IS_INT>(p.A, p.lda, n, p.K, lb, araw);
 
     // 2. tables from the LUT buffer (requested before the indices: they are needed first)
-    uint32_t lo0[4], lo1[4], hi0[4], hi1[4];
+    LaneTables T;
+    uint32_t (&lo0)[4] = T.lo0, (&lo1)[4] = T.lo1, (&hi0)[4] = T.hi0, (&hi1)[4] = T.hi1;
     float uscale = 0.f;
     if constexpr (Q8) {
       // two 16-byte pieces: tables 0,1 and 2,3, eight one-byte entries each (lo0 = entries 0..3,
@@ -275,51 +203,13 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
     // loads below the first lookups (or, in fused mode, the first use of the activations)
     __builtin_amdgcn_sched_barrier(0);
 
-    // 4. fused mode: the activation sum the bias term needs
+    // 4. fused mode: the activation sum the bias term needs, and the four tables, built while the
+    // indices are in flight
     if constexpr (FUSED) {
-      // sum of the lane's 16 activations, in the order of the precompute kernel's tree
-      if constexpr (IS_INT) {
-        int s16 = 0;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) s16 = __builtin_amdgcn_sdot4((int)araw[t], 0x01010101, s16, false);
-        Sl = (float)s16;  // |s16| <= 16 * 128
-      } else {
-        float t4[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) t4[t] = sum4_f16(araw[2 * t], araw[2 * t + 1]);
-        Sl = (t4[0] + t4[1]) + (t4[2] + t4[3]);
-      }
+      Sl = lane_act_sum<IS_INT>(araw);
       if constexpr (GM == 0) Stot += Sl;
-      if constexpr (GM == 2) {
-        // sum over the chunk's eight lanes (lane bits 3, 4, 5), pairing units as the precompute kernel does
-        Sl += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(Sl), 0x128, 0xf, 0xf, false));  // row_ror:8
-        Sl += __shfl_xor(Sl, 16);
-        Sl += __shfl_xor(Sl, 32);
-      }
-    }
-    // 4b. fused mode: build the four tables while the indices are in flight (mirror half: entries
-    // 0..7, i.e. the fourth activation subtracted), as low-byte and high-byte permute sources
-    if constexpr (FUSED) {
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        uint32_t pk[4];
-        if constexpr (IS_INT) {
-          // int8 activations are exact in fp16 and so is every sum of four of them (|T| <= 508): the
-          // fp16 additions of the fp16 path give the integer table
-          // (conversion: byte b + 128 under the high byte 0x64 is the fp16 number 1024 + 128 + b)
-          const uint32_t biased = araw[t] ^ 0x80808080u;
-          const h2 off = {(_Float16)1152.0f, (_Float16)1152.0f};
-          const h2 x01 = __builtin_bit_cast(h2, bperm(0x64646464u, biased, 0x04010400u)) - off;
-          const h2 x23 = __builtin_bit_cast(h2, bperm(0x64646464u, biased, 0x04030402u)) - off;
-          half_table_f16(__builtin_bit_cast(uint32_t, x01), __builtin_bit_cast(uint32_t, x23), pk);
-        } else {
-          half_table_f16(araw[2 * t], araw[2 * t + 1], pk);  // fp16 additions, as every table builder
-        }
-        lo0[t] = bperm(pk[1], pk[0], 0x06040200u);
-        lo1[t] = bperm(pk[3], pk[2], 0x06040200u);
-        hi0[t] = bperm(pk[1], pk[0], 0x07050301u);
-        hi1[t] = bperm(pk[3], pk[2], 0x07050301u);
-      }
+      if constexpr (GM == 2) Sl = chunk_sum(Sl);
+      lane_build_tables<IS_INT>(araw, T);
     }
 
 #pragma unroll
@@ -330,7 +220,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
       for (int r = 0; r < 8; ++r) {
         if constexpr (GM == 1) {
           const float z = __half2float(__ushort_as_half((uint16_t)(szr[8 * rt + r] >> 16)));
-          acc[r] = fmaf(-z, Sl, p.mid * Sl);
+          acc[r] = fmaf(-z, Sl, pp.mid * Sl);
         } else if constexpr (GM == 0) {
           acc[r] = tot[8 * rt + r];
         } else {
@@ -406,65 +296,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
 #pragma unroll
         for (int r = 0; r < 8; ++r) acc[r] = fmaf((float)ia[r], us, acc[r]);
       } else {
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        // four lookups of table t: selector bytes `sel` (0..7 each), sign bits `sgn` at bit 7 of each byte
-        auto look = [&](uint32_t sel, uint32_t sgn, uint32_t& p01, uint32_t& p23) {
-          const uint32_t lo = bperm(lo1[t], lo0[t], sel);
-          const uint32_t hi = bperm(hi1[t], hi0[t], sel) ^ sgn;
-          p01 = bperm(hi, lo, 0x05010400u);  // fp16 pair of bytes 0 and 1
-          p23 = bperm(hi, lo, 0x07030602u);  // fp16 pair of bytes 2 and 3
-        };
-        // the "high" rows of a dword: rotated by four bits their entries sit in bits 0..2 and their
-        // negate bits (stored in bit 3 of the following byte) in bit 7 of each byte
-        auto hi_set = [](uint32_t x) { return __builtin_amdgcn_alignbit(x, x, 4); };
-        auto quad = [&](uint32_t x, float& a_lo, float& a_hi) {  // 4 planes of one row (low nibbles), one (high)
-          uint32_t a, b;
-          look(x & 0x07070707u, x & 0x80808080u, a, b);
-          a_lo = dot2(a, W01, a_lo);
-          a_lo = dot2(b, W23, a_lo);
-          look(hi_set(x) & 0x07070707u, hi_set(x) & 0x80808080u, a, b);
-          a_hi = dot2(a, W01, a_hi);
-          a_hi = dot2(b, W23, a_hi);
-        };
-        auto pair = [&](uint32_t x, float* a4) {  // planes 0,1 of rows 0,1 (low) and 2,3 (high) of a4
-          uint32_t a, b;
-          look(x & 0x07070707u, x & 0x80808080u, a, b);
-          a4[0] = dot2(a, W01, a4[0]);
-          a4[1] = dot2(b, W01, a4[1]);
-          look(hi_set(x) & 0x07070707u, hi_set(x) & 0x80808080u, a, b);
-          a4[2] = dot2(a, W01, a4[2]);
-          a4[3] = dot2(b, W01, a4[3]);
-        };
-        auto single = [&](uint32_t x, uint16_t wgt, float* a8) {  // one plane of rows 0..3 (low), 4..7 (high)
-          const uint32_t wl = h2pack(wgt, H_0), wh = h2pack(H_0, wgt);
-          uint32_t a, b;
-          look(x & 0x07070707u, x & 0x80808080u, a, b);
-          a8[0] = dot2(a, wl, a8[0]);
-          a8[1] = dot2(a, wh, a8[1]);
-          a8[2] = dot2(b, wl, a8[2]);
-          a8[3] = dot2(b, wh, a8[3]);
-          look(hi_set(x) & 0x07070707u, hi_set(x) & 0x80808080u, a, b);
-          a8[4] = dot2(a, wl, a8[4]);
-          a8[5] = dot2(a, wh, a8[5]);
-          a8[6] = dot2(b, wl, a8[6]);
-          a8[7] = dot2(b, wh, a8[7]);
-        };
-        const uint32_t* wt = &w[rt][t * BITS];
-        if constexpr (BITS == 4) {
-#pragma unroll
-          for (int d = 0; d < 4; ++d) quad(wt[d], acc[2 * d], acc[2 * d + 1]);
-        } else if constexpr (BITS == 2) {
-          pair(wt[0], acc);
-          pair(wt[1], acc + 4);
-        } else if constexpr (BITS == 1) {
-          single(wt[0], WS0, acc);
-        } else {
-          pair(wt[0], acc);
-          pair(wt[1], acc + 4);
-          single(wt[2], WS2, acc);
-        }
-      }
+        lane_lookups<BITS, GM != 0>(w[rt], T, acc);
       }
 
       // 7. scale: once per (row, lane) in GM 1, once per (row, chunk) in GM 2
@@ -481,7 +313,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
         const float v = reduce_hi3(acc, lane);  // row pos, summed over the chunk (sums of this size are exact for ints)
         const float s = __half2float(__ushort_as_half((uint16_t)(szr[rt] & 0xffffu)));
         const float z = __half2float(__ushort_as_half((uint16_t)(szr[rt] >> 16)));
-        tot[rt] = fmaf(s, fmaf(p.mid - z, Sl, v), tot[rt]);
+        tot[rt] = fmaf(s, fmaf(pp.mid - z, Sl, v), tot[rt]);
       }
     }
   }
@@ -508,12 +340,13 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
   }
   __syncthreads();
 
-  // 9. wave 0 sums the waves with a fixed tree (lane = 8*slot + row: waves slot and slot + 8, then
-  // the slots), finishes and stores
-  if (wave != 0) return;
+  // 9. the first wave of every group sums the group's waves with a fixed tree (lane = 8*slot + row:
+  // waves slot and slot + 8, then the slots), finishes and stores
+  if (wig != 0 || !active) return;
+  const int w0 = grp * NW;  // first wave of the group
   if constexpr (FUSED && GM == 0) {
     float st = 0.f;
-    for (int wv = 0; wv < NW; ++wv) st += redS[wv];  // wave order
+    for (int wv = 0; wv < NW; ++wv) st += redS[w0 + wv];  // wave order
     fin_Sf = st;
     fin_Si = (int)st;
   }
@@ -524,19 +357,19 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
     float sf = 0.f;
     int si = 0;
     if constexpr (RAW_INT) {
-      si = ws < NW ? __float_as_int(red[ws * NR + r]) : 0;
-      if (ws + 8 < NW) si += __float_as_int(red[(ws + 8) * NR + r]);
+      si = ws < NW ? __float_as_int(red[(w0 + ws) * NR + r]) : 0;
+      if (ws + 8 < NW) si += __float_as_int(red[(w0 + ws + 8) * NR + r]);
       si += __builtin_amdgcn_update_dpp(0, si, 0x128, 0xf, 0xf, false);  // row_ror:8
       si += __shfl_xor(si, 16);
       si += __shfl_xor(si, 32);
     } else {
-      sf = ws < NW ? red[ws * NR + r] : 0.f;
-      if (ws + 8 < NW) sf += red[(ws + 8) * NR + r];
+      sf = ws < NW ? red[(w0 + ws) * NR + r] : 0.f;
+      if (ws + 8 < NW) sf += red[(w0 + ws + 8) * NR + r];
       sf += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(sf), 0x128, 0xf, 0xf, false));
       sf += __shfl_xor(sf, 16);
       sf += __shfl_xor(sf, 32);
     }
-    const uint32_t t = blockIdx.x * RT + rt;
+    const uint32_t t = tg * RT + rt;
     const int m = (int)t * 8 + (int)jl;
     if (lane < 8 && t < (uint32_t)p.n_tiles && m < p.M) {
       float res;
@@ -555,44 +388,61 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParams p) {
             ires = (si + p.icoef * St) >> 1;  // numerator is always even
             res = ((float)ires * as) * s;     // two roundings, left to right
           } else {
-            res = (fmaf(p.mid - z, (float)St, 0.5f * (float)si) * as) * s;  // explicit fma: same rounding in every instantiation
+            res = (fmaf(pp.mid - z, (float)St, 0.5f * (float)si) * as) * s;  // explicit fma: same rounding in every instantiation
           }
         } else {
           const float St = fin_Sf;
-          res = (s * fmaf(p.mid - z, St, 0.5f * sf)) * as;  // explicit fma: same rounding in every instantiation
+          res = (s * fmaf(pp.mid - z, St, 0.5f * sf)) * as;  // explicit fma: same rounding in every instantiation
         }
       }
       const size_t o = (size_t)n * p.ldo + m;
-      if (p.out_t == TMAC_OUT_F32) static_cast<float*>(p.out)[o] = res;
-      else if (p.out_t == TMAC_OUT_F16) static_cast<__half*>(p.out)[o] = __float2half_rn(res);
+      if (pp.out_t == TMAC_OUT_F32) static_cast<float*>(p.out)[o] = res;
+      else if (pp.out_t == TMAC_OUT_F16) static_cast<__half*>(p.out)[o] = __float2half_rn(res);
       else static_cast<int*>(p.out)[o] = ires;
     }
   }
 }
 
+// count == 1 launches the single-matrix instantiation (its arguments hold one matrix); only the
+// kernels that build their tables themselves have an instantiation for several matrices.
 template <bool IS_INT, int BITS, int GM, int RT, bool FUSED, bool Q8 = false>
-static hipError_t launch_one(const PermParams& p, int NW, hipStream_t st) {
-  PermParams local = p;
-  void* args[] = {&local};
-  return hipLaunchKernel(reinterpret_cast<const void*>(mpgemv_perm_kernel<IS_INT, BITS, GM, RT, FUSED, Q8>),
-                         dim3((p.n_tiles + RT - 1) / RT, p.N), dim3(NW * 64), args, 0, st);
+static hipError_t launch_one(const PermParams& p, int count, int NW, hipStream_t st) {
+  const dim3 grid(p.wg_end[count - 1], p.N), block(NW * 64);
+  const size_t lds = (size_t)p.pad;  // dynamic LDS nobody uses: caps the workgroups per CU (0: no cap)
+  if (count == 1) {
+    PermParamsT<1> one;
+    one.wg_end[0] = p.wg_end[0];
+    one.N = p.N; one.mid = p.mid; one.out_t = p.out_t; one.pad = 0;
+    one.m[0] = p.m[0];
+    void* args[] = {&one};
+    return hipLaunchKernel(reinterpret_cast<const void*>(mpgemv_perm_kernel<IS_INT, BITS, GM, RT, FUSED, Q8, 1>), grid,
+                           block, args, lds, st);
+  }
+  if constexpr (FUSED && !Q8) {
+    PermParams local = p;
+    void* args[] = {&local};
+    return hipLaunchKernel(
+        reinterpret_cast<const void*>(mpgemv_perm_kernel<IS_INT, BITS, GM, RT, FUSED, Q8, PERM_MAX_MATS>), grid, block,
+        args, lds, st);
+  }
+  return hipErrorInvalidValue;
 }
 
 // rt: row tiles per workgroup (1 or 2)
 template <bool IS_INT, int BITS, int GM>
-static hipError_t launch_rt(const PermParams& p, int rt, bool fused, int NW, hipStream_t st) {
+static hipError_t launch_rt(const PermParams& p, int count, int rt, bool fused, int NW, hipStream_t st) {
   if (fused)
-    return rt == 2 ? launch_one<IS_INT, BITS, GM, 2, true>(p, NW, st) : launch_one<IS_INT, BITS, GM, 1, true>(p, NW, st);
-  return rt == 2 ? launch_one<IS_INT, BITS, GM, 2, false>(p, NW, st) : launch_one<IS_INT, BITS, GM, 1, false>(p, NW, st);
+    return rt == 2 ? launch_one<IS_INT, BITS, GM, 2, true>(p, count, NW, st) : launch_one<IS_INT, BITS, GM, 1, true>(p, count, NW, st);
+  return rt == 2 ? launch_one<IS_INT, BITS, GM, 2, false>(p, count, NW, st) : launch_one<IS_INT, BITS, GM, 1, false>(p, count, NW, st);
 }
 
 // int8 tables: one row tile per workgroup, tables from the LUT buffer
 template <int BITS>
 static hipError_t launch_q8(const PermParams& p, int gm, int NW, hipStream_t st) {
   switch (gm) {
-    case 0: return launch_one<false, BITS, 0, 1, false, true>(p, NW, st);
-    case 1: return launch_one<false, BITS, 1, 1, false, true>(p, NW, st);
-    default: return launch_one<false, BITS, 2, 1, false, true>(p, NW, st);
+    case 0: return launch_one<false, BITS, 0, 1, false, true>(p, 1, NW, st);
+    case 1: return launch_one<false, BITS, 1, 1, false, true>(p, 1, NW, st);
+    default: return launch_one<false, BITS, 2, 1, false, true>(p, 1, NW, st);
   }
 }
 
@@ -607,32 +457,31 @@ static hipError_t launch_q8_bits(const PermParams& p, int bits, int gm, int NW, 
 }
 
 template <bool IS_INT, int BITS>
-static hipError_t launch_gm(const PermParams& p, int gm, int rt, bool fused, int NW, hipStream_t st) {
+static hipError_t launch_gm(const PermParams& p, int count, int gm, int rt, bool fused, int NW, hipStream_t st) {
   switch (gm) {
-    case 0: return launch_rt<IS_INT, BITS, 0>(p, rt, fused, NW, st);
-    case 1: return launch_rt<IS_INT, BITS, 1>(p, rt, fused, NW, st);
-    default: return launch_rt<IS_INT, BITS, 2>(p, rt, fused, NW, st);
+    case 0: return launch_rt<IS_INT, BITS, 0>(p, count, rt, fused, NW, st);
+    case 1: return launch_rt<IS_INT, BITS, 1>(p, count, rt, fused, NW, st);
+    default: return launch_rt<IS_INT, BITS, 2>(p, count, rt, fused, NW, st);
   }
 }
 
 template <bool IS_INT>
-static hipError_t launch_bits(const PermParams& p, int bits, int gm, int rt, bool fused, int NW, hipStream_t st) {
+static hipError_t launch_bits(const PermParams& p, int count, int bits, int gm, int rt, bool fused, int NW, hipStream_t st) {
   switch (bits) {
-    case 1: return launch_gm<IS_INT, 1>(p, gm, rt, fused, NW, st);
-    case 2: return launch_gm<IS_INT, 2>(p, gm, rt, fused, NW, st);
-    case 3: return launch_gm<IS_INT, 3>(p, gm, rt, fused, NW, st);
-    case 4: return launch_gm<IS_INT, 4>(p, gm, rt, fused, NW, st);
+    case 1: return launch_gm<IS_INT, 1>(p, count, gm, rt, fused, NW, st);
+    case 2: return launch_gm<IS_INT, 2>(p, count, gm, rt, fused, NW, st);
+    case 3: return launch_gm<IS_INT, 3>(p, count, gm, rt, fused, NW, st);
+    case 4: return launch_gm<IS_INT, 4>(p, count, gm, rt, fused, NW, st);
   }
   return hipErrorInvalidValue;
 }
 
-int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, const void* A_dev,
-                     int64_t lda, int lut_t, int N, const float* act_scale_dev, float weight_scale,
-                     void* out_dev, int out_t, int64_t ldo, void* stream, int rows_per_group) {
+int perm_fill(PermMat& p, const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, const void* A_dev,
+              int64_t lda, int lut_t, int N, const float* act_scale_dev, float weight_scale, void* out_dev,
+              int out_t, int64_t ldo, int group_waves, int* gm_out) {
   const bool fused = (lut_dev == nullptr);
   const bool q8 = (lut_t == TMAC_LUT_I8Q);
   const int lut_is_int = (lut_t == TMAC_LUT_I16);
-  if (q8 && (fused || rows_per_group == 16)) return TMAC_EUNSUPPORTED;
   const Geometry ge = geometry(desc);
   LutGeom lg;
   if (!lut_geom(N, desc->K, desc->g, desc->group, lut_t, &lg)) return TMAC_EINVAL;
@@ -643,7 +492,6 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
     return TMAC_EUNSUPPORTED;
   const bool one_group = (desc->group == 0 || desc->group == desc->K);
 
-  PermParams p;
   const char* blob = static_cast<const char*>(packed_dev);
   p.idx = reinterpret_cast<const pu32x4*>(blob + ge.idx_off);
   p.sz = reinterpret_cast<const pu32x4*>(blob + ge.sz_off);
@@ -660,16 +508,13 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
   p.out = out_dev;
   p.act_scale = act_scale_dev;
   p.ldo = ldo;
-  p.M = desc->M; p.N = N; p.U = lg.U; p.n_tiles = ge.n_tiles; p.nq = lg.nq;
-  p.G = lg.Geff;
+  p.M = desc->M; p.U = lg.U; p.n_tiles = ge.n_tiles; p.nq = lg.nq;
   p.bs = block_split(lg.U);
   p.per_tensor = (desc->group == 0);
   p.wscale = weight_scale;
-  p.mid = 0.5f * (float)((1 << desc->bits) - 1);
   p.zero_point = p.per_tensor ? desc->zero_point : 0.f;
   p.int_exact = 0;
   p.icoef = 0;
-  p.out_t = out_t;
   if (p.per_tensor && lut_is_int) {
     const float z = desc->zero_point;
     if (z == rintf(z) && fabsf(z) < 64.f) {
@@ -678,20 +523,17 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
     }
   }
   if (out_t == TMAC_OUT_I32 && !p.int_exact) return TMAC_EINVAL;
-  const int NW = p.bs.nB < 16 ? p.bs.nB : 16;
+  const int gcap = group_waves > 0 ? group_waves : PERM_GROUP_WAVES;
+  p.gsz = p.bs.nB < gcap ? p.bs.nB : gcap;
+  p.ginv = (256u + (uint32_t)p.gsz - 1u) / (uint32_t)p.gsz;
   if (lut_is_int) {
     // integer sums are carried in fp32 inside a wave: a wave's total must stay below 2^24
-    const int passes = (p.bs.nB + NW - 1) / NW;
+    const int passes = (p.bs.nB + p.gsz - 1) / p.gsz;
     if ((double)508.0 * ((1 << desc->bits) - 1) * 256.0 * passes >= 16777216.0) return TMAC_EUNSUPPORTED;
+    // fused call with one scale per row or tensor: the sum of an activation row (|sum| <= 128 K)
+    // is carried in fp32 across lanes and waves as well
+    if (fused && one_group && (double)128.0 * desc->K >= 16777216.0) return TMAC_EUNSUPPORTED;
   }
-  // Two row tiles per workgroup share one set of tables (built or loaded once for 16 rows) but
-  // halve the number of wavefronts.  Measured: worth 3-6 % once a call has more than about 8000
-  // wavefronts, eight per SIMD (22016 x 4096, 8192 x 8192, 28672 x 8192), a loss of 2-5 % below
-  // (4096 x 4096 up to 12288 x 4096); with several activation rows (one GEMV each in one launch)
-  // the same count decides (4096 x 4096: from four rows on).  The default follows it.
-  int rt = rows_per_group == 16 ? 2 : 1;
-  if (rows_per_group == 0 && !q8 && (int64_t)ge.n_tiles * NW * N >= 8192) rt = 2;
-  hipStream_t st = static_cast<hipStream_t>(stream);
   const int gm = one_group ? 0 : (desc->group % 128 == 0 ? 2 : 1);
   {
     // divisor of the lane's unit (mode 1) or chunk (mode 2) index that gives its quantisation group
@@ -699,9 +541,124 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
     if (d >= 65536u || lg.U >= 65536) return TMAC_EUNSUPPORTED;
     p.q_magic = d == 1 ? 0u : (uint32_t)((4294967296ull + d - 1) / d);
   }
-  const hipError_t e = q8 ? launch_q8_bits(p, desc->bits, gm, NW, st)
-                          : lut_is_int ? launch_bits<true>(p, desc->bits, gm, rt, fused, NW, st)
-                                       : launch_bits<false>(p, desc->bits, gm, rt, fused, NW, st);
+  *gm_out = gm;
+  return TMAC_OK;
+}
+
+// Bytes of unused dynamic LDS that let at most `wgs_per_cu` workgroups share a CU's 160 KB (0: no cap).
+// Fewer resident waves finish in a more staggered way, which evens out the end of a launch.
+static int perm_lds_cap(int wgs_per_cu) {
+  if (wgs_per_cu <= 0) return 0;
+  const int total = 160 * 1024, n = wgs_per_cu < 2 ? 2 : wgs_per_cu;  // (one per CU would exceed the 64 KB a workgroup may ask for)
+  return total / (n + 1) + 1024;  // n + 1 of these do not fit
+}
+
+// Launch shape of matrix i for W waves per workgroup and rt row tiles per group of waves; returns the
+// number of workgroups.
+static int64_t perm_shape(PermMat& p, int W, int rt) {
+  p.gpw = W / p.gsz;
+  const int64_t groups = ((int64_t)p.n_tiles + rt - 1) / rt;
+  return (groups + p.gpw - 1) / p.gpw;
+}
+
+int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev, const void* A_dev,
+                     int64_t lda, int lut_t, int N, const float* act_scale_dev, float weight_scale,
+                     void* out_dev, int out_t, int64_t ldo, void* stream, const tmac_tuning* tuning) {
+  const int rows_per_group = tuning ? tuning->rows_per_group : 0;
+  const int group_waves = tuning ? tuning->group_waves : 0;
+  const int wg_waves = tuning ? tuning->workgroup_waves : 0;
+  const bool fused = (lut_dev == nullptr);
+  const bool q8 = (lut_t == TMAC_LUT_I8Q);
+  const int lut_is_int = (lut_t == TMAC_LUT_I16);
+  if (q8 && (fused || rows_per_group == 16)) return TMAC_EUNSUPPORTED;
+  PermParams pp;
+  memset(&pp, 0, sizeof(pp));
+  PermMat& p = pp.m[0];
+  int gm = 0;
+  const int stt = perm_fill(p, desc, packed_dev, lut_dev, A_dev, lda, lut_t, N, act_scale_dev, weight_scale, out_dev,
+                            out_t, ldo, group_waves, &gm);
+  if (stt != TMAC_OK) return stt;
+  pp.N = N;
+  pp.mid = 0.5f * (float)((1 << desc->bits) - 1);
+  pp.out_t = out_t;
+  // waves per workgroup: one group of waves unless asked otherwise (then whole groups)
+  const int NW = wg_waves > 0 ? (wg_waves / p.gsz > 0 ? wg_waves / p.gsz * p.gsz : p.gsz) : p.gsz;
+  // Two row tiles per group of waves share one set of tables (built or loaded once for 16 rows) but
+  // halve the number of wavefronts.  Measured: worth 3-6 % once a call has more than about 8000
+  // wavefronts, eight per SIMD (22016 x 4096, 8192 x 8192, 28672 x 8192), a loss of 2-5 % below
+  // (4096 x 4096 up to 12288 x 4096); with several activation rows (one GEMV each in one launch)
+  // the same count decides (4096 x 4096: from four rows on).  The default follows it.
+  int rt = rows_per_group == 16 ? 2 : 1;
+  if (rows_per_group == 0 && !q8 && (int64_t)p.n_tiles * p.gsz * N >= 8192) rt = 2;
+  const int64_t wgs = perm_shape(p, NW, rt);
+  if (wgs > 0x7fffffff) return TMAC_EUNSUPPORTED;
+  pp.wg_end[0] = (int)wgs;
+  pp.pad = perm_lds_cap(tuning ? tuning->workgroups_per_cu : 0);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const hipError_t e = q8 ? launch_q8_bits(pp, desc->bits, gm, NW, st)
+                          : lut_is_int ? launch_bits<true>(pp, 1, desc->bits, gm, rt, fused, NW, st)
+                                       : launch_bits<false>(pp, 1, desc->bits, gm, rt, fused, NW, st);
+  if (e != hipSuccess) {
+    note_hip_error((int)e);
+    return TMAC_EHIP;
+  }
+  return TMAC_OK;
+}
+
+// Several matrices, one launch: the workgroups of the grid are dealt out over the matrices' groups of
+// row tiles.  All matrices share the code path (bit-width, how scales are grouped, activation type);
+// K, M and every pointer are per matrix.  The waves per workgroup W are common to the launch: each
+// matrix puts floor(W / gsz) groups of gsz waves into a workgroup, and W is chosen so that the fewest
+// wave slots stay idle.  The summation order of a matrix depends on its gsz alone, so results equal
+// those of the single-matrix call bit for bit.
+int launch_perm_gemv_multi(const tmac_gemv_item* items, int count, int act_t, int N, int out_t, void* stream,
+                           const tmac_tuning* tuning) {
+  const int rows_per_group = tuning ? tuning->rows_per_group : 0;
+  const int group_waves = tuning ? tuning->group_waves : 0;
+  const int wg_waves = tuning ? tuning->workgroup_waves : 0;
+  if (count < 1 || count > PERM_MAX_MATS) return TMAC_EUNSUPPORTED;
+  const int lut_t = act_t == TMAC_ACT_I8 ? (int)TMAC_LUT_I16 : (int)TMAC_LUT_F16;
+  PermParams pp;
+  memset(&pp, 0, sizeof(pp));
+  int gm0 = 0, max_gsz = 1;
+  int64_t waves = 0;
+  for (int i = 0; i < count; ++i) {
+    const tmac_gemv_item& it = items[i];
+    int gm = 0;
+    const int stt = perm_fill(pp.m[i], it.desc, it.packed_dev, nullptr, it.A_dev, it.lda, lut_t, N, it.act_scale_dev,
+                              it.weight_scale, it.out_dev, out_t, it.ldo, group_waves, &gm);
+    if (stt != TMAC_OK) return stt;
+    if (i == 0) gm0 = gm;
+    if (gm != gm0 || it.desc->bits != items[0].desc->bits) return TMAC_EUNSUPPORTED;
+    if (pp.m[i].gsz > max_gsz) max_gsz = pp.m[i].gsz;
+    waves += (int64_t)pp.m[i].n_tiles * pp.m[i].gsz;
+  }
+  pp.N = N;
+  pp.mid = 0.5f * (float)((1 << items[0].desc->bits) - 1);
+  pp.out_t = out_t;
+  int rt = rows_per_group == 16 ? 2 : 1;
+  if (rows_per_group == 0 && waves * N >= 8192) rt = 2;
+  // waves per workgroup: the W in [largest gsz, 16] that leaves the fewest wave slots idle
+  int W = max_gsz;
+  int64_t best = -1;
+  const int w_lo = wg_waves >= max_gsz ? wg_waves : max_gsz, w_hi = wg_waves >= max_gsz ? wg_waves : PERM_WG_WAVES_MAX;
+  for (int w = w_lo; w <= w_hi; ++w) {
+    int64_t slots = 0;
+    for (int i = 0; i < count; ++i) slots += perm_shape(pp.m[i], w, rt) * w;
+    if (best < 0 || slots < best) { best = slots; W = w; }
+  }
+  int64_t end = 0;
+  for (int i = 0; i < count; ++i) {
+    end += perm_shape(pp.m[i], W, rt);
+    if (end > 0x7fffffff) return TMAC_EUNSUPPORTED;
+    pp.wg_end[i] = (int)end;
+  }
+  for (int i = count; i < PERM_MAX_MATS; ++i) pp.wg_end[i] = 0x7fffffff;
+  pp.pad = perm_lds_cap(tuning ? tuning->workgroups_per_cu : 0);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int bits = items[0].desc->bits;
+  const hipError_t e = (lut_t == TMAC_LUT_I16) ? launch_bits<true>(pp, count, bits, gm0, rt, true, W, st)
+                                               : launch_bits<false>(pp, count, bits, gm0, rt, true, W, st);
   if (e != hipSuccess) {
     note_hip_error((int)e);
     return TMAC_EHIP;

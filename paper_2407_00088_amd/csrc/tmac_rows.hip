@@ -14,9 +14,11 @@
 //     row and of one 32-k chunk with one load (16 bytes at 4 bit); the eight nibbles of a dword are
 //     the indices of eight consecutive tables, and two mask-and-shift operations turn them into
 //     the byte offsets of the entries (even and odd tables) four at a time.
-//   * Aggregation (Section 3.3 keeps the running sum narrow and widens it now and then): the eight
-//     entries of a chunk and plane are added as packed 16-bit pairs, two activation rows per
-//     instruction (exact for integer tables; three fp16 roundings for fp16 tables), then widened.
+//   * Aggregation: the eight entries of a chunk and plane are added as packed 16-bit pairs, two
+//     activation rows per instruction, then widened.  Exact for integer tables.  For fp16 tables
+//     this is this library's own choice and it is lossy (three fp16 roundings per chunk sum: about
+//     1.5e-4 -> 3.4e-4 relative error, still a sixth of the 2e-3 bar); it is not the paper's "fast
+//     8-bit aggregation" (Section 4), an integer averaging trick that is not built here.
 //   * Bit-plane shift-accumulate (Eq. 1): the widening v_fma_mix_f32 takes the fp16 chunk sum and
 //     multiplies by 2^i.
 //   * Scale, zero and bias once per quantisation group (Section 4, bit-serial linear transform).
@@ -276,9 +278,9 @@ __device__ __forceinline__ void rows_chunk(const uint32_t (&x)[BITS], uint32_t c
     __builtin_amdgcn_sched_barrier(0);  // keep the reads above the accumulation
     // The entries of a plane (one per table of the chunk) are added pairwise as packed 16-bit
     // values, two activation rows per instruction: exact for the integer tables (|sum| <= 4096),
-    // log2(32/g) roundings to fp16 for the fp16 tables (the convert to "a higher precision" of
-    // Section 3.3 happens once per chunk and plane); the chunk sum then enters the 32-bit sum of
-    // the quantisation group times 2^plane.
+    // log2(32/g) roundings to fp16 for the fp16 tables (lossy, this library's choice: the widening
+    // happens once per chunk and plane); the chunk sum then enters the 32-bit sum of the
+    // quantisation group times 2^plane.
 #pragma unroll
     for (int bb = 0; bb < PL; ++bb) {
       const int b = b0 + bb;
@@ -505,11 +507,14 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
   }
 
   // Split K: publish the partial sums; the last workgroup to arrive for this (row block, n tile)
-  // adds the slices in slice order and writes the result.  Visibility across the chip's XCDs (one
-  // L2 each): partials are written with agent-scope atomic stores, every wave waits for its
-  // stores (workgroup-scope release), the barrier orders all waves before thread 0's agent-scope
-  // counter increment, and the reader uses agent-scope atomic loads, which do not hit stale
-  // lines of its own L2.
+  // adds the slices in slice order and writes the result.  Ordering across the chip's XCDs (one
+  // L2 each) by the memory model, not by how the stores happen to be issued: every wave ends its
+  // partial-sum stores with an agent-scope release fence (its stores have been performed for the
+  // whole device before it passes the fence), the barrier orders all waves of the workgroup before
+  // thread 0, thread 0 takes its ticket with an agent-scope acquire-release increment, and the
+  // last workgroup passes an agent-scope acquire fence before it reads the other slices' sums.
+  // The partial sums themselves are relaxed agent-scope atomics: no tearing and no stale line of
+  // the reader's own L2.
   const bool raw_int = RAW_INT && !p.grouped;
   if (tile_ok) {
 #pragma unroll
@@ -522,17 +527,18 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
       }
     }
   }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
   __syncthreads();
   if (threadIdx.x == 0) {
     int* ctr = p.ws_ctr + (size_t)blockIdx.y * gridDim.x + blockIdx.x;
-    const int ticket = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int ticket = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
     const int last = (ticket == nz - 1);
     if (last) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = last;
   }
   __syncthreads();
   if (!s_last || !row_ok) return;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
   // four slices x NT rows of loads in flight per round trip; sums taken in slice order
   float sf[NTT];
   int si[NTT];

@@ -39,10 +39,10 @@ class LinearLUT:
         self.packed_bytes = int(blob.size)
         self.packed = torch.from_numpy(blob).to(device)
         # the regions of the LUT buffer, the split of a call and with it the workspace depend on N:
-        # size both for every N up to max_N
-        lut_bytes = max(B.tmac_lut_bytes(n, K, group, self.lut_t, g=g) for n in range(1, max_N + 1))
+        # both are sized for every N up to max_N
+        lut_bytes = B.tmac_lut_bytes_max(max_N, K, group, self.lut_t, g=g)
         self.lut = torch.empty(max(lut_bytes, 256), dtype=torch.uint8, device=device)
-        ws = max(B.tmac_workspace_bytes(self.desc, n) for n in range(1, max_N + 1))
+        ws = B.tmac_workspace_bytes_max(self.desc, max_N)
         self.workspace = torch.zeros(max(ws, 256), dtype=torch.uint8, device=device)
 
     def precompute(self, A, N: Optional[int] = None, stream=None):
@@ -64,7 +64,9 @@ class LinearLUT:
     def mpgemm_fused(self, A, N: int, out, out_t: int = B.TMAC_OUT_F32, act_scale=None, stream=None, packed=None):
         """One call for either layout (tmac_mpgemm_fused); its workspace is allocated on first use."""
         act = B.TMAC_ACT_I8 if A.dtype == self.torch.int8 else B.TMAC_ACT_F16
-        need = max(B.tmac_fused_workspace_bytes(self.desc, n, act) for n in range(1, self.max_N + 1))
+        need = B.tmac_fused_workspace_bytes_max(self.desc, self.max_N, act)
+        if need == 0:
+            raise B.TmacError(B.TMAC_EUNSUPPORTED, "tmac_fused_workspace_bytes_max")
         if getattr(self, "fused_ws", None) is None or self.fused_ws.numel() < need:
             self.fused_ws = self.torch.zeros(max(need, 256), dtype=self.torch.uint8, device=self.device)
         B.tmac_mpgemm_fused(self.desc, self.packed if packed is None else packed, A, N, out, out_t, self.fused_ws,

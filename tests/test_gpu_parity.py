@@ -11,6 +11,7 @@ tmac_precompute_lut + tmac_mpgemm ("regs") or as the single fused launch tmac_mp
 import numpy as np
 import pytest
 
+import rounding_models as rm
 import tmac_workloads as wl
 from oracle import tmac_oracle as orc
 
@@ -65,13 +66,44 @@ def oracle_fp(p):
     return orc.mpgemm_definition(p.act, p.q, p.scales, p.zeros, p.group, p.weight_scale, p.zero_point)
 
 
+ELEM_TOL_UNITS = 6.0   # allowed |got - ref| of one output, in units of u * E (see assert_elementwise)
+
+
+def assert_elementwise(got, ref, p, what=""):
+    """Bound on the error of EVERY output, next to the Frobenius bar over all of them.
+
+    The error of an output is a sum of about K b / 4 independent fp16 roundings (u = 2^-11) of table
+    entries and chunk sums, each proportional to the activations it covers times the weight range of
+    the row: it behaves like a Gaussian of standard deviation c u E with
+    E[n,m] = sqrt(sum_k (a[n,k] s[m,k] (2^b - 1))^2), whatever the distribution of the activations
+    (outlier channels included: they enter E as they enter the error).  The CPU models of the kernels'
+    roundings (tests/rounding_models.py) give c = 0.2-0.5 and a largest |error| of 1.5 u E over
+    thousands of outputs at K = 256 ... 13824, 1-4 bit, Gaussian and heavy-tailed activations; 6 u E is
+    allowed.  A typical output is 600-800 u E in size, so one that is off by 1 % of its own value
+    already misses this bound, which the Frobenius bar alone would not see (one output in 4096 with a
+    10 % error moves the norm by 1.5e-3)."""
+    u = 2.0 ** -11
+    a2 = np.asarray(p.act, dtype=np.float64) ** 2
+    if p.group == 0:
+        s_full = np.full((p.M, p.K), float(p.weight_scale))
+    else:
+        s_full = np.repeat(np.asarray(p.scales, dtype=np.float64), p.group, axis=1)
+    E = np.sqrt(a2 @ ((s_full * (2 ** p.bits - 1)) ** 2).T)
+    ratio = np.abs(np.asarray(got, dtype=np.float64) - ref) / np.maximum(u * E, 1e-300)
+    worst = float(ratio.max())
+    assert worst <= ELEM_TOL_UNITS, (p.name, what, worst, np.unravel_index(ratio.argmax(), ratio.shape))
+    return worst
+
+
 def check_fp(T, torch, p, tuning=None, tol=FP_TOL, layout=L3):
     got = run_fp(T, torch, p, tuning=tuning, layout=layout)
     ref = oracle_fp(p)
     assert got.shape == ref.shape and got.dtype == np.float32
     assert np.all(np.isfinite(got))
     err = orc.rel_frobenius(got, ref)
-    print(f"{p.name} layout{layout}: rel_frobenius={err:.3e}", flush=True)
+    worst = assert_elementwise(got, ref, p, f"layout{layout}")
+    print(f"{p.name} layout{layout}: rel_frobenius={err:.3e} worst element {worst:.2f} u E "
+          f"(bound {ELEM_TOL_UNITS})", flush=True)
     assert err <= tol, (p.name, layout, err)
     return err
 
@@ -344,6 +376,113 @@ def test_fused_rejects_what_it_cannot_do(T, torch):
         with pytest.raises(T.TmacError) as e:
             B.tmac_mpgemv_fused(d, packed, A, 1, out, B.TMAC_OUT_F32, lda=K)
         assert e.value.status in (B.TMAC_EUNSUPPORTED, B.TMAC_EINVAL)
+
+
+# ------------------------------------------- several matrices in one launch ----
+
+def _multi_vs_single(T, torch, problems, N, out_t, tuning=None, int_path=False):
+    """Runs tmac_mpgemv_fused_multi over `problems` and tmac_mpgemv_fused on each; returns both lists."""
+    from paper_2407_00088_amd import binding as B
+    from paper_2407_00088_amd.runner import from_problem
+    dt = {B.TMAC_OUT_F32: torch.float32, B.TMAC_OUT_F16: torch.float16, B.TMAC_OUT_I32: torch.int32}[out_t]
+    lins = [from_problem(p, layout=L2) for p in problems]
+    As = [torch.from_numpy(p.act_q if int_path else p.act).cuda() for p in problems]
+    scs = [torch.from_numpy(p.act_scale).cuda() if int_path else None for p in problems]
+    single = []
+    for lin, A, sc in zip(lins, As, scs):
+        o = torch.full((N, lin.M), -7, dtype=dt, device="cuda")
+        lin.mpgemv_fused(A, N, o, out_t, act_scale=sc)
+        single.append(o)
+    multi = [torch.full((N, lin.M), -9, dtype=dt, device="cuda") for lin in lins]
+    items = [(lin.desc, lin.packed, A, o, sc, lin.weight_scale) for lin, A, o, sc in zip(lins, As, multi, scs)]
+    B.tmac_mpgemv_fused_multi(items, N, out_t, tuning=tuning)
+    torch.cuda.synchronize()
+    return [o.cpu().numpy() for o in multi], [o.cpu().numpy() for o in single]
+
+
+def test_multi_launch_config2_equals_three_separate_calls_bitwise(T, torch):
+    """The three Llama-2-7B shapes of config 2 (K = 4096, 4096, 11008: four and eleven waves per group
+    of row tiles) in ONE launch: every output equals the single fused call's bit for bit, and meets
+    the bar against the oracle."""
+    ps = [wl.config2(i) for i in range(3)]
+    multi, single = _multi_vs_single(T, torch, ps, 1, T.TMAC_OUT_F32)
+    for p, m, s1 in zip(ps, multi, single):
+        assert np.array_equal(m.view(np.uint32), s1.view(np.uint32)), p.name
+        ref = oracle_fp(p)
+        assert orc.rel_frobenius(m, ref) <= FP_TOL
+        assert_elementwise(m, ref, p, "multi")
+
+
+@pytest.mark.parametrize("bits,group,N,rows", [(4, 128, 1, 0), (2, 128, 3, 8), (3, 64, 1, 16), (1, 0, 2, 0), (4, -1, 1, 16),
+                                               (2, 256, 2, 0)])
+def test_multi_launch_mixed_shapes_equal_separate_calls_bitwise(T, torch, bits, group, N, rows):
+    """Matrices of unlike shape in one launch: K from one block (128) to seventeen blocks (more than the
+    sixteen waves of a workgroup: two passes), ragged M (a last row tile of one row), a matrix smaller
+    than one workgroup; every grouping mode, both rows-per-group settings, N > 1; up to the maximum of
+    eight matrices.  Bit-identical to the single calls."""
+    from paper_2407_00088_amd import binding as B
+    kmin = 2 * group if group > 0 else 128   # (K == group would be one scale per row: another grouping mode)
+    shapes = [(200, 4096), (8, kmin), (41, 1536 if group == 256 else 1408), (64, 11008),
+              (1, max(256, kmin)), (130, 17408), (24, 5120), (77, 1024)]
+    ps = []
+    for i, (M, K) in enumerate(shapes):
+        if group == 0:
+            rng = np.random.default_rng(700 + i + bits)
+            ps.append(wl.Problem(f"multi_pt{i}", 0, N, M, K, bits, 0, wl.uniform_codes(rng, M, K, bits), None, None,
+                                 weight_scale=0.02 + 0.01 * i, zero_point=0.5 * i, act=wl.gaussian_act(rng, N, K)))
+        else:
+            ps.append(wl.make_grouped(0, 700 + i + bits, N, M, K, bits, K if group < 0 else group, name=f"multi{i}"))
+    tuning = B.tmac_tuning(rows) if rows else None
+    for count in (8, 3, 1):
+        multi, single = _multi_vs_single(T, torch, ps[:count], N, T.TMAC_OUT_F32, tuning=tuning)
+        for p, m, s1 in zip(ps, multi, single):
+            assert np.array_equal(m.view(np.uint32), s1.view(np.uint32)), (p.name, count)
+            assert orc.rel_frobenius(m, oracle_fp(p)) <= FP_TOL, (p.name, count)
+
+
+def test_multi_launch_int_path_is_exact(T, torch):
+    """The three BitNet-shaped ternary matrices of config 4 in one launch: int32 results equal the
+    integer oracle, fp32 results its two-rounding output, bit for bit."""
+    ps = [wl.config4(i) for i in range(3)]
+    multi_i, _ = _multi_vs_single(T, torch, ps, 1, T.TMAC_OUT_I32, int_path=True)
+    multi_f, single_f = _multi_vs_single(T, torch, ps, 1, T.TMAC_OUT_F32, int_path=True)
+    for p, mi, mf, sf in zip(ps, multi_i, multi_f, single_f):
+        ref_i = orc.ternary_int_matmul(p.act_q, p.q, int(p.zero_point))
+        assert np.array_equal(mi.astype(np.int64), ref_i), p.name
+        ref_f = orc.int_path_output_f32(ref_i, p.act_scale, p.weight_scale)
+        assert np.array_equal(mf.view(np.uint32), ref_f.view(np.uint32)), p.name
+        assert np.array_equal(mf.view(np.uint32), sf.view(np.uint32)), p.name
+
+
+def test_multi_launch_in_graph_replay(T, torch):
+    """Captured in a HIP graph and replayed with eager work in between: every replay equals the eager
+    result (no state is kept between launches)."""
+    from paper_2407_00088_amd import binding as B
+    from paper_2407_00088_amd.runner import from_problem
+    ps = [wl.make_grouped(0, 760 + i, 1, M, K, 4, 128, name=f"multig{i}") for i, (M, K) in
+          enumerate([(300, 4096), (96, 11008), (520, 2048)])]
+    lins = [from_problem(p, layout=L2) for p in ps]
+    As = [torch.from_numpy(p.act).cuda() for p in ps]
+    outs = [torch.zeros((1, p.M), dtype=torch.float32, device="cuda") for p in ps]
+    items = [(lin.desc, lin.packed, A, o) for lin, A, o in zip(lins, As, outs)]
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        B.tmac_mpgemv_fused_multi(items, 1, B.TMAC_OUT_F32)
+    stream.synchronize()
+    eager = [o.clone() for o in outs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        B.tmac_mpgemv_fused_multi(items, 1, B.TMAC_OUT_F32)
+    for rep in range(3):
+        for o in outs:
+            o.fill_(float(rep))          # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, e, p in zip(outs, eager, ps):
+            assert torch.equal(o, e), (rep, p.name)
+    for e, p in zip(eager, ps):
+        assert orc.rel_frobenius(e.cpu().numpy(), oracle_fp(p)) <= FP_TOL
 
 
 # ------------------------------------------------- int8 table quantisation ----
@@ -656,11 +795,11 @@ def test_random_shapes_int_path_exact(T, torch, seed):
 @pytest.mark.parametrize("N,bits", [(16, 4), (48, 2), (3, 3)])
 def test_batched_kernel_matches_the_narrow_sum_route(T, torch, N, bits):
     """The batched kernel adds the eight entries of a 32-k chunk and plane pairwise in fp16 before
-    widening: against the oracle route that takes exactly these roundings (fp64 elsewhere) only the
+    widening: against the CPU model that takes exactly these roundings (tests/rounding_models.py) (fp64 elsewhere) only the
     fp32 accumulation is left, orders of magnitude below the distance to the exact product."""
     p = wl.make_grouped(0, 880 + N, N, 256, 2048, bits, 128, name=f"narrow_n{N}")
     got = run_fp(T, torch, p, layout=L3)
-    model = orc.lut_mpgemm_narrow(p.act, p.q, bits, p.scales, p.zeros, p.group)
+    model = rm.lut_mpgemm_narrow(p.act, p.q, bits, p.scales, p.zeros, p.group)
     exact = oracle_fp(p)
     e_model, e_exact = orc.rel_frobenius(got, model), orc.rel_frobenius(got, exact)
     print(f"{p.name}: vs narrow-sum route {e_model:.2e}, vs exact {e_exact:.2e}", flush=True)
@@ -671,7 +810,7 @@ def test_batched_kernel_matches_the_narrow_sum_route(T, torch, N, bits):
 @pytest.mark.parametrize("bits,group", [(4, 128), (2, 32), (3, 0), (1, -1)])
 def test_decode_kernel_matches_the_fp16_table_route(T, torch, lay, bits, group):
     """The register-table kernel builds its tables with fp16 additions and accumulates in fp32:
-    against the oracle route with tables of the same construction (fp64 elsewhere) only the fp32
+    against the CPU model with tables of the same construction (tests/rounding_models.py) (fp64 elsewhere) only the fp32
     accumulation is left."""
     M, K = 200, 4096
     if group == 0:
@@ -681,8 +820,7 @@ def test_decode_kernel_matches_the_fp16_table_route(T, torch, lay, bits, group):
     else:
         p = wl.make_grouped(0, 890 + bits, 1, M, K, bits, K if group < 0 else group, name="tabroute")
     got = run_fp(T, torch, p, layout=lay)
-    model = orc.lut_mpgemm(p.act, p.q, bits, p.scales, p.zeros, p.group, p.weight_scale, p.zero_point,
-                           table_dtype="fp16_tree")
+    model = rm.lut_mpgemm_fp16_tree(p.act, p.q, bits, p.scales, p.zeros, p.group, p.weight_scale, p.zero_point)
     e_model, e_exact = orc.rel_frobenius(got, model), orc.rel_frobenius(got, oracle_fp(p))
     print(f"tabroute b{bits} G{p.group} layout{lay}: vs fp16-table route {e_model:.2e}, vs exact {e_exact:.2e}", flush=True)
     assert e_model <= 2e-6 and e_exact <= FP_TOL
@@ -706,10 +844,29 @@ def test_tiny_k_all_lut_group_sizes(T, torch, g, K):
         got, ref = out.cpu().numpy().astype(np.float64), oracle_fp(p)
         if M * N > 1:
             assert orc.rel_frobenius(got, ref) <= FP_TOL, (g, K, M, N)
-        # a single output of a few dozen terms can cancel to a fraction of its terms: each output is
-        # also held against the sum of the magnitudes of its terms, which the rounding errors scale with
-        W = orc.dequantize(p.q, p.scales, p.zeros, p.group, p.weight_scale, p.zero_point)
-        assert np.all(np.abs(got - ref) <= FP_TOL * (np.abs(p.act.astype(np.float64)) @ np.abs(W).T)), (g, K, M, N)
+        # a single output of a few dozen terms can cancel to a fraction of its terms (the 1 x 1 case is
+        # held to the Frobenius bar together with its siblings in the next test): each output is also
+        # held against the sum of the magnitudes of its terms, which the rounding errors scale with
+        assert_elementwise(got, ref, p, f"g{g} K{K} M{M} N{N}")
+
+
+def test_tiny_k_single_outputs_meet_the_frobenius_bar_together(T, torch):
+    """The fifteen 1 x 1 cases of the test above (g = 2, 4, 8 times five short K) as one vector of
+    outputs: relative Frobenius error within the 2e-3 bar.  One output alone has no norm to be
+    relative to but its own value, which a cancelling sum of a few dozen terms makes arbitrarily
+    small; fifteen of them do not all cancel."""
+    from paper_2407_00088_amd.runner import from_problem
+    got, ref = [], []
+    for g in (2, 4, 8):
+        for K in (8, 16, 24, 40, 136):
+            p = wl.make_grouped(0, 950 + K + g + 1, 1, 1, K, 3, K, name="tinyk")
+            out = from_problem(p, layout=L3, g=g).forward(torch.from_numpy(p.act).cuda())
+            torch.cuda.synchronize()
+            got.append(float(out.cpu().numpy()[0, 0]))
+            ref.append(float(oracle_fp(p)[0, 0]))
+    err = orc.rel_frobenius(np.array(got), np.array(ref))
+    print(f"tiny K, fifteen single outputs: rel_frobenius={err:.3e}", flush=True)
+    assert err <= FP_TOL
 
 
 # ------------------------------------------------- one-call entry point ----
@@ -826,7 +983,7 @@ def test_precompute_tables_against_the_oracle(T, torch, g, int_act):
     if int_act:
         assert np.array_equal(tab[:, : K // g].astype(np.int64), ref)
     else:
-        want = orc.precompute_lut_fp16_tree(a, g)
+        want = rm.precompute_lut_fp16_tree(a, g)
         got = tab[:, : K // g]
         assert np.array_equal(got.astype(np.float64), want.astype(np.float64))     # (-0 == +0)
         # within the roundings of the exact table's partial sums: g - 1 additions, each off by at most
@@ -887,23 +1044,25 @@ def test_large_call_takes_two_row_tiles_per_workgroup_by_default(T, torch):
 # ------------------------------------------------------ measurement helpers ----
 
 def test_measurement_helpers_run_and_check_their_arguments(T, torch):
-    """tmac_stream_read and tmac_lds_lookup_probe take no part in the path; they must launch, finish,
-    leave the sink alone (their stores practically never happen) and refuse bad arguments."""
-    from paper_2407_00088_amd import binding as B
+    """The plain-read kernel, the LDS probe and the empty kernel (libtmac_bench.so) take no part in the
+    path; they must launch, finish, leave the sink alone (their stores practically never happen) and
+    refuse bad arguments."""
+    from paper_2407_00088_amd import bench_helpers as H
     src = torch.arange(1 << 16, dtype=torch.int32, device="cuda")
     sink = torch.zeros(256, dtype=torch.uint8, device="cuda")
     for per_thread in (1, 4, 8):
         for nt in (False, True):
-            B.tmac_stream_read(src, sink, per_thread, nt)
-    B.tmac_lds_lookup_probe(64, 8, sink)
+            H.stream_read(src, sink, per_thread, nt)
+    H.lds_lookup_probe(64, 8, sink)
+    H.empty_kernel()
     torch.cuda.synchronize()
     assert not sink.cpu().numpy().any()
-    with pytest.raises(B.TmacError):
-        B.tmac_stream_read(src, sink, 3, False)
-    with pytest.raises(B.TmacError):
-        B.tmac_lds_lookup_probe(0, 8, sink)
-    with pytest.raises(B.TmacError):
-        B.tmac_lds_lookup_probe(64, 0, sink)
+    with pytest.raises(RuntimeError):
+        H.stream_read(src, sink, 3, False)
+    with pytest.raises(RuntimeError):
+        H.lds_lookup_probe(0, 8, sink)
+    with pytest.raises(RuntimeError):
+        H.lds_lookup_probe(64, 0, sink)
 
 
 def test_one_holder_serves_every_row_count_up_to_its_maximum(T, torch):
