@@ -271,8 +271,8 @@ tmac_status tmac_mpgemm_fused(const tmac_wdesc* desc, const void* packed_dev, co
  * added (every setting is deterministic and within the same error bound).
  *   rows_per_group   weight rows that share one set of tables: 8 or 16 (default: 8, and 16 once a
  *                    call has more than about 8000 wavefronts, where sharing the tables pays)
- *   group_waves      most wavefronts that split the K of one group of rows, 1..16; a row of K
- *                    elements has ceil(K / 1024) blocks, dealt round-robin to the group's waves
+ *   group_waves      most wavefronts that split the K of one group of rows, 1..16 (default 8); a
+ *                    row of K elements has ceil(K / 1024) blocks, dealt round-robin to the group's waves
  *   workgroup_waves  wavefronts per workgroup, 1..16, rounded down to whole groups (at least one)
  *   workgroups_per_cu  most workgroups resident on one compute unit, 2..8 (enforced by asking for
  *                    LDS that nobody uses; default: whatever registers and wave slots allow) */

@@ -92,7 +92,8 @@ struct PermMat {
   uint32_t ginv;     // ceil(256 / gsz): wave / gsz == (wave * ginv) >> 8 for wave < 16
 };
 constexpr int PERM_MAX_MATS = TMAC_MULTI_MAX;
-constexpr int PERM_GROUP_WAVES = 16;   // default cap on the waves that split the K of one group of row tiles
+constexpr int PERM_GROUP_WAVES = 8;    // default cap on the waves that split the K of one group of row tiles
+                                       // (workgroups of eight waves finish closer together than larger ones)
 constexpr int PERM_WG_WAVES_MAX = 16;  // most waves per workgroup
 
 // NM = 1: the single-matrix entry points; NM = PERM_MAX_MATS: several matrices in one launch.
