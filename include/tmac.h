@@ -202,10 +202,10 @@ tmac_status tmac_precompute_lut(const void* A_dev, tmac_act_t act, int32_t N, in
                                 int64_t lda, int32_t g, int32_t group, tmac_lut_t lut,
                                 void* lut_dev, size_t lut_bytes, void* stream);
 
-/* Bytes of workspace tmac_mpgemm needs for exactly N activation rows (split-K partial sums and
- * arrival counters; how a call is split depends on N, so a buffer meant for several N must take
- * the largest).  The workspace must be zero-filled once before its first use; every call leaves
- * the counters at zero again.  Calls that share a workspace must not overlap in time. */
+/* Bytes of workspace tmac_mpgemm needs for exactly N activation rows (split-K partial sums; how
+ * a call is split depends on N, so a buffer meant for several N must take the largest).  Its
+ * contents need not be initialised and mean nothing between calls.  Calls that share a workspace
+ * must not overlap in time. */
 size_t tmac_workspace_bytes(const tmac_wdesc* desc, int32_t N);
 
 /* Look-up, bit-plane shift-accumulate, scale/zero, reduce (Algorithm 1 main loop, Eq. 1,
@@ -255,9 +255,9 @@ tmac_status tmac_mpgemv_fused(const tmac_wdesc* desc, const void* packed_dev, co
  *   A_dev          [N,K] fp16 or int8, 16-byte aligned; leading dimension lda a multiple of 8
  *                  where the tables are built in the kernel (16 for int8 with layout 2), else as
  *                  for tmac_precompute_lut
- *   workspace_dev  tmac_fused_workspace_bytes(desc, N, act) bytes, 16-byte aligned, zero-filled
- *                  once before its first use (its first region is tmac_mpgemm's workspace);
- *                  calls that share it must not overlap in time
+ *   workspace_dev  tmac_fused_workspace_bytes(desc, N, act) bytes, 16-byte aligned, contents
+ *                  arbitrary (its first region is tmac_mpgemm's workspace); calls that share it
+ *                  must not overlap in time
  * Errors: TMAC_EINVAL, TMAC_EUNSUPPORTED, TMAC_ESIZE, TMAC_EHIP. */
 size_t tmac_fused_workspace_bytes(const tmac_wdesc* desc, int32_t N, tmac_act_t act);
 tmac_status tmac_mpgemm_fused(const tmac_wdesc* desc, const void* packed_dev, const void* A_dev,

@@ -171,7 +171,7 @@ struct RowsPlan {
   int n_tiles_n, row_blocks;  // workgroups along N (nt * oct activation rows each) and M (256 weight rows each)
   int cps, slices;            // 32-k chunks per K slice, number of K slices (gridDim.z)
   bool eight;                 // slices of eight chunks: the kernel pair for few activation rows serves the call
-  size_t part_bytes, ctr_bytes;  // workspace: partial sums and arrival counters (0 when slices == 1)
+  size_t part_bytes, ctr_bytes;  // workspace: partial sums (0 when slices == 1); ctr_bytes is always 0
   size_t srow_bytes;             // ... and the slices' sums of every activation row (eight-chunk plans)
 };
 RowsPlan rows_plan(const tmac_wdesc* desc, int N);

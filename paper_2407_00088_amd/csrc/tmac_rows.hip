@@ -32,10 +32,9 @@
 //     in the lane's registers: fixed order.
 //   * Few activation rows (batched decode) leave too few (row block, n tile) pairs to fill the
 //     chip: K is then also split over gridDim.z workgroups, whose partial sums meet in the
-//     workspace; the last workgroup to arrive adds them in slice order (fixed order again) and
-//     writes the result.  Nobody waits for anybody: a counter per output block tells which
-//     workgroup is last.  When the slices are as short as eight chunks (a handful of activation
-//     rows), mpgemm_rows8_kernel and rows_sum_kernel further down take the call instead.
+//     workspace; rows_sum_kernel, the next kernel on the stream, adds them in slice order (fixed
+//     order again) and writes the result.  When the slices are as short as eight chunks (a handful
+//     of activation rows), mpgemm_rows8_kernel further down takes the call instead.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -83,7 +82,6 @@ struct RowsParams {
   int cps;                 // 32-k chunks per workgroup along K (a multiple of cpg); gridDim.z slices
   int Mp;                  // M rounded up to 64
   float* ws_part;          // split K: [slices][N][Mp] partial sums (fp32, or int32 bit patterns)
-  int* ws_ctr;             // split K: arrival counters, one per (row block, n tile), zero between calls
   float* ws_srow;          // fused table build, one scale per row or tensor: [slices][N] sums of the
                            // activations of a K slice (fp32, or int32 bit patterns)
   int grouped;             // 1: group scales, 0: one scale per row or per tensor
@@ -363,7 +361,6 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
   constexpr int OSTRIDE = ROWS_LDS / OCT;            // bytes between the two row sets' tables
   static_assert(CPS >= 1 && CB % 256 == 0, "chunk bases must keep a zero low byte");
   __shared__ __attribute__((aligned(2048))) char tab[ROWS_LDS];  // byte-permuted addresses need the alignment
-  __shared__ int s_last;
   using AccT = typename std::conditional<IS_INT, int, float>::type;
 
   const int lane = threadIdx.x & 63;
@@ -506,15 +503,11 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
     return;
   }
 
-  // Split K: publish the partial sums; the last workgroup to arrive for this (row block, n tile)
-  // adds the slices in slice order and writes the result.  Ordering across the chip's XCDs (one
-  // L2 each) by the memory model, not by how the stores happen to be issued: every wave ends its
-  // partial-sum stores with an agent-scope release fence (its stores have been performed for the
-  // whole device before it passes the fence), the barrier orders all waves of the workgroup before
-  // thread 0, thread 0 takes its ticket with an agent-scope acquire-release increment, and the
-  // last workgroup passes an agent-scope acquire fence before it reads the other slices' sums.
-  // The partial sums themselves are relaxed agent-scope atomics: no tearing and no stale line of
-  // the reader's own L2.
+  // Split K: publish the partial sums with plain stores; rows_sum_kernel, launched behind this
+  // kernel on the same stream, adds the slices in slice order and finishes.  The kernel boundary
+  // orders the stores before the loads on every XCD (one L2 each); handing over inside the kernel
+  // instead (release fence, arrival counter, acquire fence in the last workgroup) makes every
+  // workgroup write back its L2, which cost more than the second launch at every size tried.
   const bool raw_int = RAW_INT && !p.grouped;
   if (tile_ok) {
 #pragma unroll
@@ -522,58 +515,14 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void mpgemm_rows_kernel(const Rows
       const int n = n0 + t;
       if (n < p.N) {
         const size_t o = ((size_t)blockIdx.z * p.N + n) * p.Mp + (size_t)tile_raw * 64 + lane;
-        const float v = (IS_INT && p.grouped) ? acc[t] : (raw_int ? __int_as_float((int)L[t]) : (float)L[t]);
-        __hip_atomic_store(p.ws_part + o, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        p.ws_part[o] = (IS_INT && p.grouped) ? acc[t] : (raw_int ? __int_as_float((int)L[t]) : (float)L[t]);
       }
     }
-  }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int* ctr = p.ws_ctr + (size_t)blockIdx.y * gridDim.x + blockIdx.x;
-    const int ticket = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    const int last = (ticket == nz - 1);
-    if (last) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    s_last = last;
-  }
-  __syncthreads();
-  if (!s_last || !row_ok) return;
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-  // four slices x NT rows of loads in flight per round trip; sums taken in slice order
-  float sf[NTT];
-  int si[NTT];
-#pragma unroll
-  for (int t = 0; t < NTT; ++t) { sf[t] = 0.f; si[t] = 0; }
-  const size_t mrow = (size_t)tile_raw * 64 + lane;
-  for (int sl0 = 0; sl0 < nz; sl0 += 4) {
-    float v[4][NTT];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int sl = min(sl0 + u, nz - 1);
-#pragma unroll
-      for (int t = 0; t < NTT; ++t) {
-        const int n = min(n0 + t, p.N - 1);
-        v[u][t] = __hip_atomic_load(p.ws_part + ((size_t)sl * p.N + n) * p.Mp + mrow, __ATOMIC_RELAXED,
-                                    __HIP_MEMORY_SCOPE_AGENT);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (sl0 + u < nz) {
-#pragma unroll
-        for (int t = 0; t < NTT; ++t) {
-          if (raw_int) si[t] += __float_as_int(v[u][t]);
-          else sf[t] += v[u][t];
-        }
-      }
-    }
-  }
-#pragma unroll
-  for (int t = 0; t < NTT; ++t) {
-    if (n0 + t >= p.N) break;
-    finish(n0 + t, sf[t], si[t]);
   }
 }
+
+template <bool IS_INT>
+__global__ void rows_sum_kernel(const RowsParams p, int nz);
 
 template <bool IS_INT, int BITS, int NT, int G, int OCT>
 static hipError_t launch_rows_one(const RowsParams& p, hipStream_t st) {
@@ -581,8 +530,13 @@ static hipError_t launch_rows_one(const RowsParams& p, hipStream_t st) {
   void* args[] = {&local};
   const dim3 grid((p.N + NT * OCT - 1) / (NT * OCT), (p.n_tiles + ROWS_WAVES - 1) / ROWS_WAVES,
                   (p.n_chunks + p.cps - 1) / p.cps);
-  return hipLaunchKernel(reinterpret_cast<const void*>(mpgemm_rows_kernel<IS_INT, BITS, NT, G, OCT>), grid,
-                         dim3(64 * ROWS_WAVES), args, 0, st);
+  hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(mpgemm_rows_kernel<IS_INT, BITS, NT, G, OCT>), grid,
+                                 dim3(64 * ROWS_WAVES), args, 0, st);
+  int nz = (int)grid.z;
+  if (e != hipSuccess || nz == 1) return e;
+  void* args2[] = {&local, &nz};
+  return hipLaunchKernel(reinterpret_cast<const void*>(rows_sum_kernel<IS_INT>), dim3((p.M + 63) / 64, p.N),
+                         dim3(64), args2, 0, st);
 }
 
 template <bool IS_INT, int NT, int G, int OCT = 1>
@@ -613,8 +567,7 @@ static hipError_t launch_rows_nt(const RowsParams& p, int g, int nt, int oct, in
 // Few activation rows: one slice of eight chunks per workgroup, sums finished by a second kernel
 // ------------------------------------------------------------------------------------------
 // With few activation rows a call is a chain of latencies, not a stream: the general kernel above
-// asks for a chunk's indices one chunk ahead and meets the other slices of K through counters in
-// memory (store, wait, count, wait, load).  Here the share of a workgroup is fixed at eight
+// asks for a chunk's indices one chunk ahead.  Here the share of a workgroup is fixed at eight
 // chunks (256 k, g = 4), so that every global load it will ever need (indices of all eight chunks,
 // scales and zeros, tables, group sums) is requested in one go at the start, the chunk loop is
 // straight-line code, and the partial sums are written with plain stores; rows_sum_kernel, the
@@ -907,7 +860,7 @@ static RowsPlan rows_plan_oct(const tmac_wdesc* desc, int N, int oct) {
   pl.eight = pl.oct == 1 && desc->g == 4 && cps == R8_CH && ge.n_chunks > R8_CH && (one_group || R8_CH % cpg == 0);
   pl.slices = (ge.n_chunks + cps - 1) / cps;
   pl.part_bytes = pl.slices > 1 ? ((size_t)pl.slices * N * ge.Mp * 4 + 255) / 256 * 256 : 0;
-  pl.ctr_bytes = pl.slices > 1 ? ((size_t)pairs * 4 + 255) / 256 * 256 : 0;
+  pl.ctr_bytes = 0;  // (no arrival counters: the slices meet in rows_sum_kernel)
   pl.srow_bytes = pl.eight ? ((size_t)pl.slices * N * 4 + 255) / 256 * 256 : 0;
   return pl;
 }
@@ -973,7 +926,6 @@ int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void*
   p.cps = pl.cps;
   p.Mp = ge.Mp;
   p.ws_part = static_cast<float*>(workspace_dev);
-  p.ws_ctr = workspace_dev ? reinterpret_cast<int*>(static_cast<char*>(workspace_dev) + pl.part_bytes) : nullptr;
   p.ws_srow = (fused && one_group) ? reinterpret_cast<float*>(static_cast<char*>(workspace_dev) + pl.part_bytes + pl.ctr_bytes)
                                    : nullptr;
   p.per_tensor = (desc->group == 0);

@@ -43,7 +43,8 @@ class LinearLUT:
         lut_bytes = B.tmac_lut_bytes_max(max_N, K, group, self.lut_t, g=g)
         self.lut = torch.empty(max(lut_bytes, 256), dtype=torch.uint8, device=device)
         ws = B.tmac_workspace_bytes_max(self.desc, max_N)
-        self.workspace = torch.zeros(max(ws, 256), dtype=torch.uint8, device=device)
+        # (left with a non-zero pattern on purpose: the library must not rely on its contents)
+        self.workspace = torch.full((max(ws, 256),), 0xA5, dtype=torch.uint8, device=device)
 
     def precompute(self, A, N: Optional[int] = None, stream=None):
         N = A.shape[0] if N is None else N
@@ -68,7 +69,7 @@ class LinearLUT:
         if need == 0:
             raise B.TmacError(B.TMAC_EUNSUPPORTED, "tmac_fused_workspace_bytes_max")
         if getattr(self, "fused_ws", None) is None or self.fused_ws.numel() < need:
-            self.fused_ws = self.torch.zeros(max(need, 256), dtype=self.torch.uint8, device=self.device)
+            self.fused_ws = self.torch.full((max(need, 256),), 0xA5, dtype=self.torch.uint8, device=self.device)
         B.tmac_mpgemm_fused(self.desc, self.packed if packed is None else packed, A, N, out, out_t, self.fused_ws,
                             act_scale=act_scale, weight_scale=self.weight_scale, stream=stream)
 

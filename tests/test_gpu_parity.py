@@ -689,9 +689,9 @@ def test_other_lut_group_sizes_are_layout3_only(T, torch):
 @pytest.mark.parametrize("N,M,K,group", [(16, 1024, 2048, 128), (16, 1024, 2304, 96), (256, 512, 1024, 128)])
 def test_batched_calls_in_graph_replay(T, torch, N, M, K, group):
     """precompute + lookup of the batched layout captured in a HIP graph and replayed, as bench.py
-    times them: K slices summed by the second kernel (group 128), by the last workgroup to arrive
-    through the counters in the workspace (group 96: the counters must be back at zero after every
-    call), and no split at all.  Every replay must give the eager result bit for bit."""
+    times them: K slices of eight chunks summed by the second kernel (group 128), longer slices of
+    the general kernel summed by the same second kernel (group 96), and no split at all.  The
+    workspace starts with arbitrary contents.  Every replay must give the eager result bit for bit."""
     from paper_2407_00088_amd.runner import from_problem
     p = wl.make_grouped(0, 860 + N + group, N, M, K, 4, group, name="graph_rows")
     lin = from_problem(p, layout=L3)

@@ -52,7 +52,7 @@ def test_layout3_sizes_and_group_rules():
     # 256 rows: a workgroup takes two n tiles of 8 rows: 16 x 20 (n tile pair, row block) pairs; K is
     # split in 10 slices of 16 chunks (two LDS slices) each: partial sums [10][256][5120] fp32, one
     # counter per pair, 256 spare bytes
-    assert T.tmac_workspace_bytes(d, 256) == 10 * 256 * 5120 * 4 + 320 * 4 + 256
+    assert T.tmac_workspace_bytes(d, 256) == 10 * 256 * 5120 * 4 + 256   # ten K slices of partial sums, nothing else
     assert T.tmac_workspace_bytes(d, 4) > 4 * 5120 * 4        # few rows: partial sums of the K slices
     assert T.tmac_packed_bytes(desc3(100, 48, 2, 16)) > 0     # packs; the kernel rejects the group size
 
