@@ -340,10 +340,28 @@ size_t tmac_lut_bytes_max(int32_t N_max, int32_t K, int32_t g, int32_t group, tm
 size_t tmac_workspace_bytes_max(const tmac_wdesc* desc, int32_t N_max);
 size_t tmac_fused_workspace_bytes_max(const tmac_wdesc* desc, int32_t N_max, tmac_act_t act);
 
+/* tmac_mpgemm for callers that cannot allocate device memory or bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks and
+ * results (bit for bit) as tmac_mpgemm, without the workspace: the split-K partial sums of the
+ * batched kernel (layout 3, few activation rows) go to a fixed array of
+ * TMAC_NOALLOC_MAX_WORKSPACE bytes inside the library, which every GPU the library runs on holds
+ * until the process ends.  The call allocates and frees nothing.
+ *   - A call whose partial sums need more (tmac_workspace_bytes(desc, N) - 256 bytes) returns
+ *     TMAC_ESIZE before anything is enqueued; tmac_last_error_detail() says so.
+ *   - The first call on a GPU looks up that GPU's address of the array (hipGetSymbolAddress): make
+ *     it outside stream capture.
+ *   - All calls on one GPU share the array: calls that overlap in time on one GPU (two streams)
+ *     race.  Its contents mean nothing between calls; nothing in it needs to start at zero. */
+#define TMAC_NOALLOC_MAX_WORKSPACE (8u << 20)
+tmac_status tmac_mpgemm_noalloc(const tmac_wdesc* desc, const void* packed_dev, const void* lut_dev,
+                                tmac_lut_t lut, int32_t N, const float* act_scale_dev,
+                                float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
+                                void* stream);
+
 const char* tmac_status_str(tmac_status s);
 
-/* Text of the last HIP error this thread met inside the library ("" if none); diagnostics
- * for a TMAC_EHIP return. */
+/* Text of the last HIP error this thread met inside the library, or of the last refusal that
+ * carries an explanation ("" if none); diagnostics for a TMAC_EHIP or TMAC_ESIZE return. */
 const char* tmac_last_error_detail(void);
 
 /* Library version: 1000*major + minor. */

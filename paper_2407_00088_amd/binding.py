@@ -31,7 +31,7 @@ EXPORTS = [
     "tmac_workspace_bytes", "tmac_mpgemm", "tmac_mpgemm_ex", "tmac_status_str", "tmac_version",
     "tmac_last_error_detail", "tmac_mpgemv_fused", "tmac_mpgemv_fused_ex",
     "tmac_fused_workspace_bytes", "tmac_mpgemm_fused", "tmac_mpgemv_fused_multi", "tmac_blob_check",
-    "tmac_lut_bytes_max", "tmac_workspace_bytes_max", "tmac_fused_workspace_bytes_max",
+    "tmac_lut_bytes_max", "tmac_workspace_bytes_max", "tmac_fused_workspace_bytes_max", "tmac_mpgemm_noalloc",
 ]
 
 
@@ -55,7 +55,7 @@ class tmac_gemv_item(C.Structure):
 class TmacError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        detail = lib.tmac_last_error_detail().decode() if status == TMAC_EHIP else ""
+        detail = lib.tmac_last_error_detail().decode() if status in (TMAC_EHIP, TMAC_ESIZE) else ""
         super().__init__(f"{where}: {status_str(status)} (status {status}) {detail}".rstrip())
 
 
@@ -83,6 +83,8 @@ def _load() -> C.CDLL:
     lib.tmac_mpgemm_ex.restype = C.c_int
     lib.tmac_mpgemm_ex.argtypes = [D, P, P, C.c_int, I32, P, F, P, C.c_int, I64, P, SZ, P,
                                    C.POINTER(tmac_tuning)]
+    lib.tmac_mpgemm_noalloc.restype = C.c_int
+    lib.tmac_mpgemm_noalloc.argtypes = [D, P, P, C.c_int, I32, P, F, P, C.c_int, I64, P]
     lib.tmac_mpgemv_fused.restype = C.c_int
     lib.tmac_mpgemv_fused.argtypes = [D, P, P, C.c_int, I32, I64, P, F, P, C.c_int, I64, P]
     lib.tmac_mpgemv_fused_ex.restype = C.c_int
@@ -220,6 +222,17 @@ def tmac_mpgemm(desc: tmac_wdesc, packed, lut_buf, lut: int, N: int, out, out_t:
         _check(lib.tmac_mpgemm(*args), "tmac_mpgemm")
     else:
         _check(lib.tmac_mpgemm_ex(*args, C.byref(tuning)), "tmac_mpgemm_ex")
+
+
+def tmac_mpgemm_noalloc(desc: tmac_wdesc, packed, lut_buf, lut: int, N: int, out, out_t: int,
+                        act_scale=None, weight_scale: float = 1.0, ldo: Optional[int] = None, stream=None) -> None:
+    """tmac_mpgemm without a workspace (the library's own fixed array takes the partial sums)."""
+    if ldo is None:
+        ldo = out.stride(0) if out.dim() == 2 else desc.M
+    as_ptr = C.c_void_p(act_scale.data_ptr()) if act_scale is not None else None
+    _check(lib.tmac_mpgemm_noalloc(C.byref(desc), C.c_void_p(packed.data_ptr()), C.c_void_p(lut_buf.data_ptr()), lut,
+                                   N, as_ptr, C.c_float(weight_scale), C.c_void_p(out.data_ptr()), out_t, ldo,
+                                   _stream_ptr(stream)), "tmac_mpgemm_noalloc")
 
 
 def tmac_mpgemv_fused(desc: tmac_wdesc, packed, A, N: int, out, out_t: int, act: Optional[int] = None,

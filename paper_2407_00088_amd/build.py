@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libtmac_hip.so")
-SOURCES = ["tmac_kernels.hip", "tmac_perm.hip", "tmac_rows.hip", "tmac_pack.cpp"]
+SOURCES = ["tmac_kernels.hip", "tmac_perm.hip", "tmac_rows.hip", "tmac_noalloc.hip", "tmac_pack.cpp"]
 # measurement helpers (plain read, LDS probe, empty kernel): a library of their own, not the product's ABI
 BENCH_LIB_PATH = os.path.join(PKG_DIR, "libtmac_bench.so")
 BENCH_SOURCES = ["tmac_bench.hip"]

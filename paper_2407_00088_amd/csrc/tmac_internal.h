@@ -184,6 +184,8 @@ int launch_rows_gemm(const tmac_wdesc* desc, const void* packed_dev, const void*
 
 // Records the last HIP error of this thread (diagnostics for TMAC_EHIP).
 void note_hip_error(int hip_error);
+// Explanation of a refusal (a string literal) for tmac_last_error_detail.
+void note_detail(const char* text);
 
 }  // namespace tmac
 #endif

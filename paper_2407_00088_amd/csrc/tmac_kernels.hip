@@ -376,7 +376,12 @@ static bool tuning_default(const tmac_tuning* t) {
 
 // Last HIP error seen by this thread while enqueuing (diagnostics only).
 static thread_local hipError_t g_last_hip_error = hipSuccess;
-void note_hip_error(int hip_error) { g_last_hip_error = static_cast<hipError_t>(hip_error); }
+static thread_local const char* g_last_detail = nullptr;  // a refusal's explanation (a string literal), newer than the error
+void note_hip_error(int hip_error) {
+  g_last_hip_error = static_cast<hipError_t>(hip_error);
+  g_last_detail = nullptr;
+}
+void note_detail(const char* text) { g_last_detail = text; }
 
 // Launch through hipLaunchKernel so that the status is this launch's own and not a stale
 // error left behind by some other user of the runtime in the same process.
@@ -387,7 +392,7 @@ static hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t
   void* ptrs[sizeof...(KArgs)];
   fill_ptrs(store, ptrs, std::index_sequence_for<KArgs...>{});
   const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds_bytes, st);
-  if (e != hipSuccess) g_last_hip_error = e;
+  if (e != hipSuccess) note_hip_error((int)e);
   return e;
 }
 
@@ -665,5 +670,6 @@ extern "C" tmac_status tmac_mpgemm(const tmac_wdesc* desc, const void* packed_de
 }
 
 extern "C" const char* tmac_last_error_detail(void) {
+  if (g_last_detail) return g_last_detail;
   return g_last_hip_error == hipSuccess ? "" : hipGetErrorString(g_last_hip_error);
 }
