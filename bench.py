@@ -49,7 +49,8 @@ MEASURED_TRAFFIC = {
     "multi": None,      # bytes per step, one launch
     "separate": None,   # bytes per step, three launches
 }
-KERNEL_SOURCES = ["paper_2407_00088_amd/csrc/tmac_perm.hip", "paper_2407_00088_amd/csrc/tmac_internal.h"]
+KERNEL_SOURCES = ["paper_2407_00088_amd/csrc/tmac_perm.hip", "paper_2407_00088_amd/csrc/tmac_perm_core.h",
+                  "paper_2407_00088_amd/csrc/tmac_internal.h"]
 
 
 def kernel_sources_hash():
@@ -396,7 +397,15 @@ def main():
     if mode in ("multi", "separate") and not args.rows and MEASURED_TRAFFIC["sources_sha256_16"] == kernel_sources_hash():
         traffic = MEASURED_TRAFFIC[mode]
 
-    if not args.headline_only:
+    if args.headline_only:
+        # a few plain reads of the same blobs: a kernel of known size in the same trace (it calibrates
+        # the byte counters of a profiler run)
+        with torch.cuda.stream(stream):
+            for _ in range(20):
+                for c in cases:
+                    c.stream_read()
+        stream.synchronize()
+    else:
         # the same step the other ways, each over at least MIN_LAUNCHES steps
         variants = {}
         for key, fn in (("one_launch_for_the_three_us", step_multi), ("three_fused_launches_us", step_separate),
@@ -461,6 +470,29 @@ def main():
                                  "fit_fused": linear_fit([r["bits"] for r in rows], [r["fused_us"] for r in rows]),
                                  "fit_plain_read": linear_fit([r["bits"] for r in rows],
                                                               [r["plain_read_of_same_bytes_us"] for r in rows])}
+        # the whole step (the three config-2 shapes in one launch) at 1..4 bit: with three matrices behind
+        # one launch the fixed cost of a launch weighs less and the line through the four points shows
+        # how time follows the bit-width
+        srows = []
+        for b in (1, 2, 3, 4):
+            cs3 = [Case(wl.make_grouped(3, 20 + 4 * i + b, 1, M, K, b, 128, name=f"step_{M}x{K}_w{b}"), ring_mb=args.ring_mb // 2)
+                   for i, (M, K) in enumerate(((4096, 4096), (11008, 4096), (4096, 11008)))]
+            nb = sum(c.bytes for c in cs3)
+            r3 = max(ring_len(c) for c in cs3)
+            us = per_launch(lambda: multi(cs3), r3)
+
+            def read3():
+                for c in cs3:
+                    c.stream_read()
+            ru = per_launch(read3, r3)
+            srows.append({"bits": b, "one_launch_us": round(us, 3), "bytes": nb, "GBps": round(nb / us / 1e3, 1),
+                          "frac_hbm_peak": round(nb / us / 1e3 / HBM_PEAK_GBPS, 4),
+                          "plain_read_three_launches_us": round(ru, 3)})
+            del cs3
+            torch.cuda.empty_cache()
+        sweep["three_shapes_one_launch"] = {"rows": srows,
+                                            "fit_one_launch": linear_fit([r["bits"] for r in srows],
+                                                                         [r["one_launch_us"] for r in srows])}
         detail["bit_sweep_n1"] = sweep
 
         # BitNet-b1.58-3B-shaped ternary GEMVs (config 4): int8 activations, exact integers

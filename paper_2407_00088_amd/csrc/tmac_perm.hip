@@ -58,7 +58,8 @@ namespace tmac {
 // Precompute inside the lookup kernel), with the arithmetic of the stand-alone precompute kernel.
 // Q8: int8 tables with one scale per lane-unit (not with IS_INT or FUSED).
 template <bool IS_INT, int BITS, int GM, int RT, bool FUSED, bool Q8, int NM>
-__global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParamsT<NM> pp) {
+__global__ __launch_bounds__(1024) void mpgemv_perm_kernel(int e0, int e1, int e2, int e3, int e4, int e5, int e6,
+                                                           const PermParamsT<NM> pp) {
   static_assert(!(Q8 && (IS_INT || FUSED)), "int8 tables: fp16 activations, tables from the LUT buffer");
   constexpr int NR = 8 * RT;
   __shared__ float red[16 * NR];
@@ -71,11 +72,15 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(const PermParamsT<NM>
   // kernel arguments in one go: every scalar load is requested before the first wait.
   int mi = 0, wg0 = 0;
   if constexpr (NM > 1) {
+    // (the first seven entries of wg_end travel as arguments of their own, ahead of the struct: the
+    // first dwords of the kernel arguments can be handed to a wave in registers at its start, so the
+    // matrix is known without a trip to memory)
+    const int ends[7] = {e0, e1, e2, e3, e4, e5, e6};
 #pragma unroll
     for (int i = 0; i < NM - 1; ++i) {  // wg_end is non-decreasing, INT_MAX past the last matrix
-      const bool past = (int)blockIdx.x >= pp.wg_end[i];
+      const bool past = (int)blockIdx.x >= ends[i];
       mi += past ? 1 : 0;
-      wg0 = past ? pp.wg_end[i] : wg0;
+      wg0 = past ? ends[i] : wg0;
     }
   }
   const PermMat p = pp.m[mi];
@@ -414,13 +419,17 @@ static hipError_t launch_one(const PermParams& p, int count, int NW, hipStream_t
     one.wg_end[0] = p.wg_end[0];
     one.N = p.N; one.mid = p.mid; one.out_t = p.out_t; one.pad = 0;
     one.m[0] = p.m[0];
-    void* args[] = {&one};
+    int e[7] = {0, 0, 0, 0, 0, 0, 0};
+    void* args[] = {&e[0], &e[1], &e[2], &e[3], &e[4], &e[5], &e[6], &one};
     return hipLaunchKernel(reinterpret_cast<const void*>(mpgemv_perm_kernel<IS_INT, BITS, GM, RT, FUSED, Q8, 1>), grid,
                            block, args, lds, st);
   }
   if constexpr (FUSED && !Q8) {
     PermParams local = p;
-    void* args[] = {&local};
+    static_assert(PERM_MAX_MATS == 8, "seven workgroup bounds travel as arguments of their own");
+    int e[7];
+    for (int i = 0; i < 7; ++i) e[i] = p.wg_end[i];
+    void* args[] = {&e[0], &e[1], &e[2], &e[3], &e[4], &e[5], &e[6], &local};
     return hipLaunchKernel(
         reinterpret_cast<const void*>(mpgemv_perm_kernel<IS_INT, BITS, GM, RT, FUSED, Q8, PERM_MAX_MATS>), grid, block,
         args, lds, st);
