@@ -78,8 +78,9 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(int e0, int e1, int e
     const int ends[7] = {e0, e1, e2, e3, e4, e5, e6};
 #pragma unroll
     for (int i = 0; i < NM - 1; ++i) {  // wg_end is non-decreasing, INT_MAX past the last matrix
-      const bool past = (int)blockIdx.x >= ends[i];
-      mi += past ? 1 : 0;
+      // (sign bit of end - 1 - id as an integer: keeps the count in scalar registers)
+      const int past = (int)((uint32_t)(ends[i] - 1 - (int)blockIdx.x) >> 31);
+      mi += past;
       wg0 = past ? ends[i] : wg0;
     }
   }
@@ -152,9 +153,10 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(int e0, int e1, int e
     } else if constexpr (GM == 2) {
       // one {scale, zero} per lane: row pos of the tile, quantisation group of chunk c
       const uint32_t gq = p.q_magic ? __umulhi(c, p.q_magic) : c;  // c / (chunks per group), exact for c < 2^16
-      const uint32_t* szw = reinterpret_cast<const uint32_t*>(p.sz);
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) szr[rt] = szw[(tile[rt] * (uint32_t)p.nq + gq) * 8 + pos];
+      for (int rt = 0; rt < RT; ++rt)
+        szr[rt] = load_at<uint32_t>(scalar_base(reinterpret_cast<const char*>(p.sz) + (size_t)(tile[rt] * (uint32_t)p.nq) * 32),
+                                    (gq * 8 + pos) * 4);
       if constexpr (!FUSED) {
         if constexpr (IS_INT) Sl = (float)static_cast<const int*>(p.S128)[(uint32_t)n * ((uint32_t)p.U >> 3) + c];
         else Sl = static_cast<const float*>(p.S128)[(uint32_t)n * ((uint32_t)p.U >> 3) + c];
@@ -196,10 +198,14 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(int e0, int e1, int e
     uint32_t w[RT][4 * BITS];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      const pu32x4* src = p.idx + (tile[rt] * (uint32_t)p.U + u0) * BITS + l;
+      // wave-uniform 64-bit base (scalar registers) plus the lane's 32-bit byte offset: the loads
+      // take the base from scalar registers and need no address arithmetic in the vector ALU
+      const char* base = reinterpret_cast<const char*>(p.idx) + (size_t)((tile[rt] * (uint32_t)p.U + u0) * BITS) * 16;
+      const uint32_t voff = l * 16u;
 #pragma unroll
       for (int i = 0; i < BITS; ++i) {
-        const pu32x4 v = __builtin_nontemporal_load(src + i * nu);
+        const gbase_t bi = scalar_base(base + (size_t)(i * nu) * 16);
+        const pu32x4 v = __builtin_nontemporal_load(reinterpret_cast<const __attribute__((address_space(1))) pu32x4*>(bi + voff));
         w[rt][4 * i + 0] = v.x; w[rt][4 * i + 1] = v.y; w[rt][4 * i + 2] = v.z; w[rt][4 * i + 3] = v.w;
       }
     }
@@ -301,7 +307,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(int e0, int e1, int e
 #pragma unroll
         for (int r = 0; r < 8; ++r) acc[r] = fmaf((float)ia[r], us, acc[r]);
       } else {
-        lane_lookups<BITS, GM != 0>(w[rt], T, acc);
+        lane_lookups<BITS, GM != 0, GM == 2>(w[rt], T, acc);
       }
 
       // 7. scale: once per (row, lane) in GM 1, once per (row, chunk) in GM 2

@@ -26,6 +26,15 @@ __device__ __forceinline__ float dot2(uint32_t pair, uint32_t w, float acc) {
   return __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, pair), __builtin_bit_cast(h2, w), acc, false);
 }
 
+// The same dot product for a sum that starts at zero: the three-operand form with the constant 0 as
+// addend (the compiler only picks the accumulate-in-place form, which needs a zeroed register first).
+// The plane weights come in a scalar register: this encoding takes no literal.
+__device__ __forceinline__ float dot2_from_zero(uint32_t pair, uint32_t w_sgpr) {
+  float r;
+  asm("v_dot2_f32_f16 %0, %1, %2, 0" : "=v"(r) : "v"(pair), "s"(w_sgpr));
+  return r;
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_add_t(float v) {
   return v + __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), CTRL, 0xf, 0xf, false));
@@ -145,6 +154,20 @@ __device__ __forceinline__ LaneBlock lane_block(const BlockSplit& bs, int blk, i
   return b;
 }
 
+// A wave-uniform global pointer pinned whole in scalar registers, so that a load from it plus a
+// lane's 32-bit byte offset takes the base from scalar registers (no 64-bit address arithmetic in
+// the vector ALU; left alone the compiler folds the lane's offset into the pointer first).
+typedef const __attribute__((address_space(1))) char* gbase_t;
+__device__ __forceinline__ gbase_t scalar_base(const void* uniform_ptr) {
+  gbase_t b = (gbase_t)uniform_ptr;
+  asm("" : "+s"(b));
+  return b;
+}
+template <typename T>
+__device__ __forceinline__ T load_at(gbase_t base, uint32_t byte_off) {
+  return *reinterpret_cast<const __attribute__((address_space(1))) T*>(base + byte_off);
+}
+
 // The lane's 16 activations, raw (zero past the end of K and for lanes without a unit): fp16 two per
 // dword in araw[0..7]; int8 four per dword (one table each) in araw[0..3].
 template <bool IS_INT>
@@ -153,12 +176,13 @@ __device__ __forceinline__ void lane_load_act(const void* A, int64_t lda, int n,
   const bool have = b.valid && 16u * b.u < (uint32_t)K;
   pu32x4 v0 = {0u, 0u, 0u, 0u}, v1 = {0u, 0u, 0u, 0u};
   if constexpr (IS_INT) {
-    if (have) v0 = *reinterpret_cast<const pu32x4*>(static_cast<const int8_t*>(A) + (size_t)n * lda + 16u * b.u);
+    const gbase_t row = scalar_base(static_cast<const int8_t*>(A) + (size_t)n * lda);
+    if (have) v0 = load_at<pu32x4>(row, 16u * b.u);
   } else {
+    const gbase_t row = scalar_base(static_cast<const __half*>(A) + (size_t)n * lda);
     if (have) {
-      const pu32x4* ap = reinterpret_cast<const pu32x4*>(static_cast<const __half*>(A) + (size_t)n * lda + 16u * b.u);
-      v0 = ap[0];
-      v1 = ap[1];
+      v0 = load_at<pu32x4>(row, 32u * b.u);
+      v1 = load_at<pu32x4>(row, 32u * b.u + 16u);
     }
   }
   araw[0] = v0.x; araw[1] = v0.y; araw[2] = v0.z; araw[3] = v0.w;
@@ -219,7 +243,8 @@ __device__ __forceinline__ void lane_build_tables(const uint32_t (&araw)[8], Lan
 // The lookups of one row tile and one unit: w = the lane's 4 * BITS index dwords (table t in dwords
 // t * BITS ..), acc[r] += sum over the unit's tables and planes of 2^plane (halved when HALF) times the
 // looked-up entry, for the eight rows r of the tile (Eq. 1).
-template <int BITS, bool HALF>
+// ZERO: the sums start at zero (what acc holds on entry is ignored).
+template <int BITS, bool HALF, bool ZERO = false>
 __device__ __forceinline__ void lane_lookups(uint32_t* w, const LaneTables& T, float (&acc)[8]) {
   // plane weights: halved in the group-scale modes, where acc = bias + 1/2 * sum_i 2^i L_i
   constexpr uint32_t W01 = HALF ? h2pack(H_05, H_1) : h2pack(H_1, H_2);
@@ -241,34 +266,41 @@ __device__ __forceinline__ void lane_lookups(uint32_t* w, const LaneTables& T, f
     auto quad = [&](uint32_t x, float& a_lo, float& a_hi) {  // 4 planes of one row (low nibbles), one (high)
       uint32_t a, b;
       look(x & 0x07070707u, x & 0x80808080u, a, b);
-      a_lo = dot2(a, W01, a_lo);
+      a_lo = (ZERO && t == 0) ? dot2_from_zero(a, W01) : dot2(a, W01, a_lo);
       a_lo = dot2(b, W23, a_lo);
       look(hi_set(x) & 0x07070707u, hi_set(x) & 0x80808080u, a, b);
-      a_hi = dot2(a, W01, a_hi);
+      a_hi = (ZERO && t == 0) ? dot2_from_zero(a, W01) : dot2(a, W01, a_hi);
       a_hi = dot2(b, W23, a_hi);
     };
-    auto pair = [&](uint32_t x, float* a4) {  // planes 0,1 of rows 0,1 (low) and 2,3 (high) of a4
-      uint32_t a, b;
-      look(x & 0x07070707u, x & 0x80808080u, a, b);
-      a4[0] = dot2(a, W01, a4[0]);
-      a4[1] = dot2(b, W01, a4[1]);
-      look(hi_set(x) & 0x07070707u, hi_set(x) & 0x80808080u, a, b);
-      a4[2] = dot2(a, W01, a4[2]);
-      a4[3] = dot2(b, W01, a4[3]);
+    // first: these sums start here (the first table of a call whose sums start at zero)
+    auto acc2 = [&](uint32_t pr, uint32_t wgt, float c, bool first) {
+      return first ? dot2_from_zero(pr, wgt) : dot2(pr, wgt, c);
     };
-    auto single = [&](uint32_t x, uint16_t wgt, float* a8) {  // one plane of rows 0..3 (low), 4..7 (high)
-      const uint32_t wl = h2pack(wgt, H_0), wh = h2pack(H_0, wgt);
+    auto pair = [&](uint32_t x, float* a4) {  // planes 0,1 of rows 0,1 (low) and 2,3 (high) of a4
+      constexpr bool F = ZERO;
+      const bool first = F && t == 0;
       uint32_t a, b;
       look(x & 0x07070707u, x & 0x80808080u, a, b);
-      a8[0] = dot2(a, wl, a8[0]);
-      a8[1] = dot2(a, wh, a8[1]);
-      a8[2] = dot2(b, wl, a8[2]);
-      a8[3] = dot2(b, wh, a8[3]);
+      a4[0] = acc2(a, W01, a4[0], first);
+      a4[1] = acc2(b, W01, a4[1], first);
       look(hi_set(x) & 0x07070707u, hi_set(x) & 0x80808080u, a, b);
-      a8[4] = dot2(a, wl, a8[4]);
-      a8[5] = dot2(a, wh, a8[5]);
-      a8[6] = dot2(b, wl, a8[6]);
-      a8[7] = dot2(b, wh, a8[7]);
+      a4[2] = acc2(a, W01, a4[2], first);
+      a4[3] = acc2(b, W01, a4[3], first);
+    };
+    auto single = [&](uint32_t x, uint16_t wgt, float* a8, bool may_be_first) {  // one plane of rows 0..3 (low), 4..7 (high)
+      const uint32_t wl = h2pack(wgt, H_0), wh = h2pack(H_0, wgt);
+      const bool first = ZERO && may_be_first && t == 0;
+      uint32_t a, b;
+      look(x & 0x07070707u, x & 0x80808080u, a, b);
+      a8[0] = acc2(a, wl, a8[0], first);
+      a8[1] = acc2(a, wh, a8[1], first);
+      a8[2] = acc2(b, wl, a8[2], first);
+      a8[3] = acc2(b, wh, a8[3], first);
+      look(hi_set(x) & 0x07070707u, hi_set(x) & 0x80808080u, a, b);
+      a8[4] = acc2(a, wl, a8[4], first);
+      a8[5] = acc2(a, wh, a8[5], first);
+      a8[6] = acc2(b, wl, a8[6], first);
+      a8[7] = acc2(b, wh, a8[7], first);
     };
     const uint32_t* wt = &w[t * BITS];
     if constexpr (BITS == 4) {
@@ -278,11 +310,11 @@ __device__ __forceinline__ void lane_lookups(uint32_t* w, const LaneTables& T, f
       pair(wt[0], acc);
       pair(wt[1], acc + 4);
     } else if constexpr (BITS == 1) {
-      single(wt[0], WS0, acc);
+      single(wt[0], WS0, acc, true);
     } else {
       pair(wt[0], acc);
       pair(wt[1], acc + 4);
-      single(wt[2], WS2, acc);
+      single(wt[2], WS2, acc, false);
     }
     // Table by table, in the order the index pieces were requested: the lookups of table t run while
     // the pieces of the later tables are still in flight, and few registers are live at a time.  An
