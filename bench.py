@@ -93,6 +93,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead of graph replay")
     ap.add_argument("--prefill-only", action="store_true",
                     help="time only the N=256 rows and print them (for profiling that kernel)")
+    ap.add_argument("--valu-rates-only", action="store_true",
+                    help="run only the probe of the vector-instruction issue rates and print it")
     ap.add_argument("--small-batch-only", action="store_true",
                     help="time only the N = 2..64 rows and print them (for profiling those kernels)")
     ap.add_argument("--separate", action="store_true",
@@ -292,6 +294,24 @@ def main():
                 "wave_reads_per_s": round(wave_reads / us * 1e6, -6),
                 "lookups_per_s": round(wave_reads * 512 / us * 1e6, -9)}
 
+    def valu_issue_rates():
+        """Issue rate of the vector instructions the register-table lookups consist of (probe of
+        libtmac_bench.so): nanoseconds per wavefront instruction and SIMD, for 1, 2 and 4 wavefronts per SIMD."""
+        rows = []
+        n_simd = torch.cuda.get_device_properties(0).multi_processor_count * 4
+        for kind, name, per_iter in ((0, "v_and_b32", 64), (1, "v_perm_b32", 64), (2, "v_dot2c_f32_f16", 64),
+                                     (3, "lookup sequence of one index dword (17 instructions)", 8 * 17)):
+            row = {"instruction": name}
+            for wps in (1, 2, 4):
+                wgs, iters = n_simd * wps // 4, 2000
+
+                def probe(kind=kind, wgs=wgs, iters=iters):
+                    H.valu_rate_probe(kind, wgs, iters, sink)
+                us = timed(Replay(probe, 1), 5, 2)
+                row[f"ns_per_wave_instr_per_simd_at_{wps}_waves"] = round(us * 1e3 / (iters * per_iter * wps), 3)
+            rows.append(row)
+        return rows
+
     def prefill_rows(ceiling_lookups_per_s):
         """Prefill mpGEMM, N = 256 (batched lookup kernel): precompute + mpgemm per call.  The roofline
         of this path is the lookup rate (lookup-and-add, no dense contraction): lookups per second
@@ -345,6 +365,10 @@ def main():
                 row[key] = {"mean": round(sum(ts) / len(ts), 2), "median": round(ts[len(ts) // 2], 2)}
             rows.append(row)
         return rows
+
+    if args.valu_rates_only:
+        print(json.dumps({"valu_issue_rates": valu_issue_rates()}))
+        return
 
     if args.small_batch_only:
         print(json.dumps({"small_batch": small_batch_rows()}))
@@ -514,6 +538,7 @@ def main():
         cases = keep
 
     if args.sweep:
+        detail["valu_issue_rates"] = valu_issue_rates()
         detail["isolated_one_copy_eager"] = isolated_rows(cases)
         del cases[:]
         torch.cuda.empty_cache()

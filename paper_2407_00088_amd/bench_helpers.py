@@ -8,7 +8,8 @@ from typing import Optional
 
 _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 BENCH_LIB_PATH = os.path.join(_PKG_DIR, "libtmac_bench.so")
-EXPORTS = ["tmac_bench_stream_read", "tmac_bench_lds_lookup_probe", "tmac_bench_empty_kernel"]
+EXPORTS = ["tmac_bench_stream_read", "tmac_bench_lds_lookup_probe", "tmac_bench_empty_kernel",
+           "tmac_bench_valu_rate_probe"]
 
 
 def _load() -> C.CDLL:
@@ -20,6 +21,8 @@ def _load() -> C.CDLL:
     lib.tmac_bench_stream_read.restype, lib.tmac_bench_stream_read.argtypes = C.c_int, [P, SZ, P, I32, I32, P]
     lib.tmac_bench_lds_lookup_probe.restype, lib.tmac_bench_lds_lookup_probe.argtypes = C.c_int, [I32, I32, P, P]
     lib.tmac_bench_empty_kernel.restype, lib.tmac_bench_empty_kernel.argtypes = C.c_int, [P]
+    lib.tmac_bench_valu_rate_probe.restype = C.c_int
+    lib.tmac_bench_valu_rate_probe.argtypes = [I32, I32, I32, P, P]
     return lib
 
 
@@ -54,3 +57,10 @@ def lds_lookup_probe(workgroups: int, rounds: int, sink, stream=None) -> None:
 
 def empty_kernel(stream=None) -> None:
     _check(lib.tmac_bench_empty_kernel(_stream_ptr(stream)), "tmac_bench_empty_kernel")
+
+
+def valu_rate_probe(kind: int, workgroups: int, iters: int, sink, stream=None) -> None:
+    """kind 0 v_and_b32, 1 v_perm_b32, 2 v_dot2c_f32_f16 (iters x 64 instructions per lane), 3 the lookup
+    sequence of one index dword (iters x 8 x 17 instructions per lane)."""
+    _check(lib.tmac_bench_valu_rate_probe(kind, workgroups, iters, C.c_void_p(sink.data_ptr()), _stream_ptr(stream)),
+           "tmac_bench_valu_rate_probe")

@@ -1,6 +1,6 @@
 // Measurement helpers: a plain streaming-read kernel, the "what can a read-only kernel reach on
 // this chip" reference that the benchmark prints next to the lookup kernels, and a probe of the
-// LDS lookup rate, and an empty kernel; none takes part in the mpGEMM path (they are built into a
+// LDS lookup rate, a probe of the vector-instruction issue rate, and an empty kernel; none takes part in the mpGEMM path (they are built into a
 // library of their own, libtmac_bench.so).
 #include <hip/hip_runtime.h>
 
@@ -67,6 +67,54 @@ __global__ __launch_bounds__(256) void lds_lookup_probe_kernel(int rounds, uint3
 
 __global__ void empty_kernel() {}
 
+// Measurement helper: how fast a SIMD issues the vector instructions the register-table lookups are
+// made of.  Every lane runs `iters` x 64 instructions of one kind on eight independent registers
+// (KIND 0: v_and_b32, 1: v_perm_b32, 2: v_dot2c_f32_f16), or `iters` x 8 times the lookup sequence
+// of one index dword (KIND 3: 17 instructions: rotation, two masks, two sign XORs, four lookup
+// permutes, four re-interleave permutes, four dot products, in the order the compiler emits them).
+// The caller picks the number of workgroups of 256 lanes, i.e. wavefronts per SIMD.
+template <int KIND>
+__global__ __launch_bounds__(256) void valu_rate_probe_kernel(int iters, uint32_t* __restrict__ sink) {
+  uint32_t a[8];
+  float f[8];
+  const uint32_t t = threadIdx.x * 2654435761u + blockIdx.x;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { a[i] = t + (uint32_t)i * 0x01020304u; f[i] = (float)i; }
+  const uint32_t lo0 = t ^ 0x55aa55aau, lo1 = t * 3u, hi0 = t * 5u, hi1 = t * 7u;
+  uint32_t c78 = 0x80808080u, c1 = 0x05010400u, c2 = 0x07030602u;
+  asm volatile("" : "+s"(c78), "+s"(c1), "+s"(c2));
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      if constexpr (KIND == 3) {
+        uint32_t x = a[r], s, l, h, p, q, xr;
+        asm volatile(
+            "v_and_b32 %1, 0x7070707, %0\n v_perm_b32 %2, %8, %7, %1\n v_perm_b32 %3, %10, %9, %1\n"
+            "v_bitop3_b32 %3, %3, %0, %11 bitop3:0x78\n v_perm_b32 %4, %3, %2, %12\n v_perm_b32 %5, %3, %2, %13\n"
+            "v_dot2c_f32_f16 %14, %4, %16\n v_dot2c_f32_f16 %14, %5, %17\n"
+            "v_alignbit_b32 %6, %0, %0, 4\n"
+            "v_and_b32 %1, 0x7070707, %6\n v_perm_b32 %2, %8, %7, %1\n v_perm_b32 %3, %10, %9, %1\n"
+            "v_bitop3_b32 %3, %3, %6, %11 bitop3:0x78\n v_perm_b32 %4, %3, %2, %12\n v_perm_b32 %5, %3, %2, %13\n"
+            "v_dot2c_f32_f16 %15, %4, %16\n v_dot2c_f32_f16 %15, %5, %17\n"
+            : "+v"(x), "=&v"(s), "=&v"(l), "=&v"(h), "=&v"(p), "=&v"(q), "=&v"(xr)
+            : "v"(lo0), "v"(lo1), "v"(hi0), "v"(hi1), "s"(c78), "s"(c1), "s"(c2), "v"(f[r]), "v"(f[(r + 1) & 7]), "v"(lo0),
+              "v"(hi1));
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          if constexpr (KIND == 0) asm volatile("v_and_b32 %0, %0, %1" : "+v"(a[i]) : "v"(lo1));
+          else if constexpr (KIND == 1) asm volatile("v_perm_b32 %0, %1, %0, %2" : "+v"(a[i]) : "v"(lo0), "v"(lo1));
+          else asm volatile("v_dot2c_f32_f16 %0, %1, %2" : "+v"(f[i]) : "v"(lo1), "v"(lo0));
+        }
+      }
+    }
+  }
+  uint32_t acc = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc ^= a[i] ^ __float_as_uint(f[i]);
+  if (acc == 0x12345678u) sink[blockIdx.x & 63] = acc;  // practically never; keeps the loop alive
+}
+
 }  // namespace tmac_bench
 
 using namespace tmac_bench;
@@ -111,6 +159,19 @@ extern "C" int tmac_bench_stream_read(const void* src_dev, size_t bytes, void* s
     return 4;
   }
   return 0;
+}
+
+extern "C" int tmac_bench_valu_rate_probe(int32_t kind, int32_t workgroups, int32_t iters, void* sink_dev, void* stream) {
+  if (!sink_dev || workgroups <= 0 || iters <= 0 || iters > (1 << 24) || kind < 0 || kind > 3) return 1;
+  uint32_t* sink = static_cast<uint32_t*>(sink_dev);
+  int it = iters;
+  void* args[] = {&it, &sink};
+  const void* fn = kind == 0   ? reinterpret_cast<const void*>(valu_rate_probe_kernel<0>)
+                   : kind == 1 ? reinterpret_cast<const void*>(valu_rate_probe_kernel<1>)
+                   : kind == 2 ? reinterpret_cast<const void*>(valu_rate_probe_kernel<2>)
+                               : reinterpret_cast<const void*>(valu_rate_probe_kernel<3>);
+  const hipError_t e = hipLaunchKernel(fn, dim3((unsigned)workgroups), dim3(256), args, 0, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? 0 : 4;
 }
 
 extern "C" int tmac_bench_empty_kernel(void* stream) {
