@@ -47,7 +47,11 @@ typedef enum {
   TMAC_EHIP = 4           /* the HIP runtime reported an error while enqueuing               */
 } tmac_status;
 
-typedef enum { TMAC_ACT_F16 = 0, TMAC_ACT_I8 = 1 } tmac_act_t;
+/* Activation type.  TMAC_ACT_F16_TQ is accepted by the calls that build their tables inside the
+ * lookup kernel (tmac_mpgemv_fused, tmac_mpgemv_fused_ex, tmac_mpgemv_fused_multi, and
+ * tmac_mpgemm_fused where it is one of those): fp16 activations whose tables are quantised to int8
+ * in the kernel, i.e. the arithmetic of TMAC_LUT_I8Q without a LUT buffer. */
+typedef enum { TMAC_ACT_F16 = 0, TMAC_ACT_I8 = 1, TMAC_ACT_F16_TQ = 2 } tmac_act_t;
 
 /* Table entry type.
  *   TMAC_LUT_F16: entries are signed sums of fp16 activations formed with fp16 additions (see
@@ -59,7 +63,9 @@ typedef enum { TMAC_ACT_F16 = 0, TMAC_ACT_I8 = 1 } tmac_act_t;
  *                 to int8 with one dynamic scale per 16 activations (four tables),
  *                 scale = max|T| / 127; the look-ups of those four tables are added as
  *                 integers and multiplied by the scale once.  Lossy (about 4e-3 relative
- *                 error on Gaussian data); packed layout 2 only. */
+ *                 error on Gaussian data); packed layout 2 only.  With a LUT buffer for at most
+ *                 64 activation rows; the fused calls quantise the tables in the kernel
+ *                 (TMAC_ACT_F16_TQ) for any N. */
 typedef enum { TMAC_LUT_F16 = 0, TMAC_LUT_I16 = 1, TMAC_LUT_I8Q = 2 } tmac_lut_t;
 
 /* TMAC_OUT_I32 (raw integer dot products) is available with TMAC_LUT_I16 and a
@@ -232,8 +238,11 @@ tmac_status tmac_mpgemm(const tmac_wdesc* desc, const void* packed_dev, const vo
  * entries, chunk sums and summation order are identical for group sizes that are multiples
  * of 16.
  *   packed_dev  layout-2 (TMAC_LAYOUT_R8U16) blob; K must be a multiple of 16
- *   A_dev       [N,K] fp16 (TMAC_ACT_F16: fp16 tables) or int8 (TMAC_ACT_I8: exact integer
- *               tables), 16-byte aligned, leading dimension lda a multiple of 8 (fp16) or 16 (int8)
+ *   A_dev       [N,K] fp16 (TMAC_ACT_F16: fp16 tables; TMAC_ACT_F16_TQ: int8 tables quantised in
+ *               the kernel, Section 3.3, the same entries and scales as tmac_precompute_lut with
+ *               TMAC_LUT_I8Q up to the last bit of the fp32 sums they are rounded from) or int8
+ *               (TMAC_ACT_I8: exact integer tables), 16-byte aligned, leading dimension lda a
+ *               multiple of 8 (fp16) or 16 (int8)
  *   other arguments as tmac_mpgemm; no LUT buffer and no workspace.
  * Errors: TMAC_EINVAL, TMAC_EUNSUPPORTED (layout 3, K % 16 != 0, unsupported group), TMAC_EHIP. */
 tmac_status tmac_mpgemv_fused(const tmac_wdesc* desc, const void* packed_dev, const void* A_dev,

@@ -18,7 +18,7 @@ _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG_DIR, "libtmac_hip.so")
 
 TMAC_OK, TMAC_EINVAL, TMAC_EUNSUPPORTED, TMAC_ESIZE, TMAC_EHIP = range(5)
-TMAC_ACT_F16, TMAC_ACT_I8 = 0, 1
+TMAC_ACT_F16, TMAC_ACT_I8, TMAC_ACT_F16_TQ = 0, 1, 2
 TMAC_LUT_F16, TMAC_LUT_I16, TMAC_LUT_I8Q = 0, 1, 2
 TMAC_OUT_F32, TMAC_OUT_F16, TMAC_OUT_I32 = 0, 1, 2
 TMAC_LAYOUT_R8U16 = 2     # register-table decode kernel (small N)
@@ -199,6 +199,7 @@ def tmac_precompute_lut(A, N: int, K: int, group: int, lut: int, lut_buf, act: O
     import torch
     if act is None:
         act = TMAC_ACT_I8 if A.dtype == torch.int8 else TMAC_ACT_F16
+    _check_act_dtype(A, act)
     if lda is None:
         lda = A.stride(0) if A.dim() == 2 else K
     _check(lib.tmac_precompute_lut(C.c_void_p(A.data_ptr()), act, N, K, lda, g, group, lut,
@@ -235,6 +236,15 @@ def tmac_mpgemm_noalloc(desc: tmac_wdesc, packed, lut_buf, lut: int, N: int, out
                                    _stream_ptr(stream)), "tmac_mpgemm_noalloc")
 
 
+def _check_act_dtype(A, act: int) -> None:
+    """The C ABI takes the activation type on trust; a tensor of another element size would be read
+    out of range."""
+    import torch
+    want = torch.int8 if act == TMAC_ACT_I8 else torch.float16
+    if A.dtype != want:
+        raise ValueError(f"activation type {act} needs a {want} tensor, got {A.dtype}")
+
+
 def tmac_mpgemv_fused(desc: tmac_wdesc, packed, A, N: int, out, out_t: int, act: Optional[int] = None,
                       lda: Optional[int] = None, act_scale=None, weight_scale: float = 1.0,
                       ldo: Optional[int] = None, stream=None, tuning: Optional[tmac_tuning] = None) -> None:
@@ -242,6 +252,7 @@ def tmac_mpgemv_fused(desc: tmac_wdesc, packed, A, N: int, out, out_t: int, act:
     import torch
     if act is None:
         act = TMAC_ACT_I8 if A.dtype == torch.int8 else TMAC_ACT_F16
+    _check_act_dtype(A, act)
     if lda is None:
         lda = A.stride(0) if A.dim() == 2 else desc.K
     if ldo is None:
@@ -269,6 +280,7 @@ def tmac_mpgemv_fused_multi(items, N: int, out_t: int, act: Optional[int] = None
         a_act = TMAC_ACT_I8 if A.dtype == torch.int8 else TMAC_ACT_F16
         if act is None:
             act = a_act
+        _check_act_dtype(A, act)
         arr[i] = tmac_gemv_item(C.pointer(desc), packed.data_ptr(), A.data_ptr(),
                                 A.stride(0) if A.dim() == 2 else desc.K,
                                 act_scale.data_ptr() if act_scale is not None else None, float(wscale),
@@ -288,6 +300,7 @@ def tmac_mpgemm_fused(desc: tmac_wdesc, packed, A, N: int, out, out_t: int, work
     import torch
     if act is None:
         act = TMAC_ACT_I8 if A.dtype == torch.int8 else TMAC_ACT_F16
+    _check_act_dtype(A, act)
     if lda is None:
         lda = A.stride(0) if A.dim() == 2 else desc.K
     if ldo is None:

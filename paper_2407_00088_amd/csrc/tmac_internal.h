@@ -147,7 +147,9 @@ __device__ inline __attribute__((always_inline)) void half_table_f16(uint32_t x0
 __device__ inline __attribute__((always_inline)) float sum4_f16(uint32_t x01, uint32_t x23) {
   const tmac_h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
   // (the first product in the three-operand form with the constant 0 as addend: the compiler would
-  // zero a register and accumulate in place)
+  // zero a register and accumulate in place; its result feeds only the addend of the second dot
+  // product, which may follow at once -- an instruction of another kind would need three wait states
+  // that the compiler does not keep after an assembly statement)
   float s;
   asm("v_dot2_f32_f16 %0, %1, %2, 0" : "=v"(s) : "v"(x01), "s"(0x3C003C00u));
   return __builtin_amdgcn_fdot2(__builtin_bit_cast(tmac_h2, x23), ones, s, false);

@@ -518,18 +518,20 @@ extern "C" tmac_status tmac_mpgemv_fused_ex(const tmac_wdesc* desc, const void* 
                                             float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
                                             void* stream, const tmac_tuning* tuning) {
   if (!desc_valid(desc) || !packed_dev || !A_dev || !out_dev || N <= 0) return TMAC_EINVAL;
-  if (act != TMAC_ACT_F16 && act != TMAC_ACT_I8) return TMAC_EINVAL;
+  if (act != TMAC_ACT_F16 && act != TMAC_ACT_I8 && act != TMAC_ACT_F16_TQ) return TMAC_EINVAL;
   if (out != TMAC_OUT_F32 && out != TMAC_OUT_F16 && out != TMAC_OUT_I32) return TMAC_EINVAL;
   if (!aligned16(packed_dev) || !aligned16(A_dev)) return TMAC_EINVAL;
   if (ldo < desc->M || lda < desc->K) return TMAC_EINVAL;
   // every lane reads the 16 activations of its unit with 16-byte loads
-  const int64_t row_elems_16B = (act == TMAC_ACT_F16) ? 8 : 16;
+  const int64_t row_elems_16B = (act == TMAC_ACT_I8) ? 16 : 8;
   if (lda % row_elems_16B != 0) return TMAC_EINVAL;
   if (desc->layout != TMAC_LAYOUT_R8U16 || desc->K % 16 != 0) return TMAC_EUNSUPPORTED;
   if (!group_supported(desc)) return TMAC_EUNSUPPORTED;
   if (!tuning_valid(tuning)) return TMAC_EINVAL;
   return static_cast<tmac_status>(launch_perm_gemv(desc, packed_dev, nullptr, A_dev, lda,
-                                                    act == TMAC_ACT_I8 ? (int)TMAC_LUT_I16 : (int)TMAC_LUT_F16,
+                                                    act == TMAC_ACT_I8       ? (int)TMAC_LUT_I16
+                                                    : act == TMAC_ACT_F16_TQ ? (int)TMAC_LUT_I8Q
+                                                                             : (int)TMAC_LUT_F16,
                                                     N, act_scale_dev, weight_scale, out_dev, (int)out, ldo,
                                                     stream, tuning));
 }
@@ -538,10 +540,10 @@ extern "C" tmac_status tmac_mpgemv_fused_multi(const tmac_gemv_item* items, int3
                                                tmac_out_t out, void* stream, const tmac_tuning* tuning) {
   if (!items || N <= 0) return TMAC_EINVAL;
   if (count < 1 || count > TMAC_MULTI_MAX) return TMAC_EUNSUPPORTED;
-  if (act != TMAC_ACT_F16 && act != TMAC_ACT_I8) return TMAC_EINVAL;
+  if (act != TMAC_ACT_F16 && act != TMAC_ACT_I8 && act != TMAC_ACT_F16_TQ) return TMAC_EINVAL;
   if (out != TMAC_OUT_F32 && out != TMAC_OUT_F16 && out != TMAC_OUT_I32) return TMAC_EINVAL;
   if (!tuning_valid(tuning)) return TMAC_EINVAL;
-  const int64_t row_elems_16B = (act == TMAC_ACT_F16) ? 8 : 16;
+  const int64_t row_elems_16B = (act == TMAC_ACT_I8) ? 16 : 8;
   for (int i = 0; i < count; ++i) {
     const tmac_gemv_item& it = items[i];
     if (!desc_valid(it.desc) || !it.packed_dev || !it.A_dev || !it.out_dev) return TMAC_EINVAL;
@@ -615,11 +617,13 @@ extern "C" tmac_status tmac_mpgemv_fused(const tmac_wdesc* desc, const void* pac
 // Bytes of the two regions of the workspace of tmac_mpgemm_fused: the split-K workspace of
 // tmac_mpgemm, then (only where the tables are not built inside the lookup kernel) a LUT buffer.
 static bool fused_regions(const tmac_wdesc* desc, int N, tmac_act_t act, size_t* ws, size_t* lut) {
-  if (!desc_valid(desc) || N <= 0 || (act != TMAC_ACT_F16 && act != TMAC_ACT_I8)) return false;
+  if (!desc_valid(desc) || N <= 0 || (act != TMAC_ACT_F16 && act != TMAC_ACT_I8 && act != TMAC_ACT_F16_TQ)) return false;
   const tmac_lut_t lt = (act == TMAC_ACT_I8) ? TMAC_LUT_I16 : TMAC_LUT_F16;
   *ws = (tmac_workspace_bytes(desc, N) + 255) / 256 * 256;
   const bool in_kernel = (desc->layout == TMAC_LAYOUT_R8U16) ? (desc->K % 16 == 0 && group_supported(desc))
                                                              : (group_supported(desc) && rows_builds_tables(desc, N));
+  // (int8 tables are quantised inside the register-table kernel only)
+  if (act == TMAC_ACT_F16_TQ && !(in_kernel && desc->layout == TMAC_LAYOUT_R8U16)) return false;
   // (the register-table kernel reads its tables from a LUT buffer for at most TMAC_DECODE_MAX_ROWS rows)
   if (!in_kernel && desc->layout == TMAC_LAYOUT_R8U16 && N > TMAC_DECODE_MAX_ROWS) return false;
   *lut = in_kernel ? 0 : tmac_lut_bytes(N, desc->K, desc->g, desc->group, lt);
@@ -637,7 +641,8 @@ extern "C" tmac_status tmac_mpgemm_fused(const tmac_wdesc* desc, const void* pac
                                          float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
                                          void* workspace_dev, size_t workspace_bytes, void* stream) {
   size_t ws, lutb;
-  if (!desc_valid(desc) || N <= 0 || (act != TMAC_ACT_F16 && act != TMAC_ACT_I8)) return TMAC_EINVAL;
+  if (!desc_valid(desc) || N <= 0 || (act != TMAC_ACT_F16 && act != TMAC_ACT_I8 && act != TMAC_ACT_F16_TQ))
+    return TMAC_EINVAL;
   if (!fused_regions(desc, N, act, &ws, &lutb)) return TMAC_EUNSUPPORTED;
   if (!packed_dev || !A_dev || !out_dev || !workspace_dev) return TMAC_EINVAL;
   if (out != TMAC_OUT_F32 && out != TMAC_OUT_F16 && out != TMAC_OUT_I32) return TMAC_EINVAL;

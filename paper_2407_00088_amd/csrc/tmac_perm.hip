@@ -60,7 +60,7 @@ namespace tmac {
 template <bool IS_INT, int BITS, int GM, int RT, bool FUSED, bool Q8, int NM>
 __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(int e0, int e1, int e2, int e3, int e4, int e5, int e6,
                                                            const PermParamsT<NM> pp) {
-  static_assert(!(Q8 && (IS_INT || FUSED)), "int8 tables: fp16 activations, tables from the LUT buffer");
+  static_assert(!(Q8 && IS_INT), "int8 tables: fp16 activations");
   constexpr int NR = 8 * RT;
   __shared__ float red[16 * NR];
   __shared__ float redS[16];
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(int e0, int e1, int e
     LaneTables T;
     uint32_t (&lo0)[4] = T.lo0, (&lo1)[4] = T.lo1, (&hi0)[4] = T.hi0, (&hi1)[4] = T.hi1;
     float uscale = 0.f;
-    if constexpr (Q8) {
+    if constexpr (Q8 && !FUSED) {
       // two 16-byte pieces: tables 0,1 and 2,3, eight one-byte entries each (lo0 = entries 0..3,
       // lo1 = entries 4..7); plus the unit's scale
 #pragma unroll
@@ -220,7 +220,8 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(int e0, int e1, int e
       Sl = lane_act_sum<IS_INT>(araw);
       if constexpr (GM == 0) Stot += Sl;
       if constexpr (GM == 2) Sl = chunk_sum(Sl);
-      lane_build_tables<IS_INT>(araw, T);
+      if constexpr (Q8) lane_build_tables_q8(araw, T, uscale);
+      else lane_build_tables<IS_INT>(araw, T);
     }
 
 #pragma unroll
@@ -262,7 +263,17 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(int e0, int e1, int e
             vB = lookq(xh & 0x07070707u);
             wB = bperm(WHI, WLO, ((xh >> 7) & 0x01010101u) | pv);
           };
-          auto dot4 = [&](uint32_t v, uint32_t w, int a) { return __builtin_amdgcn_sdot4((int)v, (int)w, a, false); };
+          // (the sums of the first table start at zero: the three-operand form with the constant 0
+          // as addend instead of a zeroed register; the result feeds the addend of the next table's
+          // dot product, see dot2_from_zero)
+          auto dot4 = [&](uint32_t v, uint32_t w, int a, bool first = true) {
+            if (t == 0 && first) {
+              int r;
+              asm("v_dot4_i32_i8 %0, %1, %2, 0" : "=v"(r) : "v"(v), "v"(w));
+              return r;
+            }
+            return __builtin_amdgcn_sdot4((int)v, (int)w, a, false);
+          };
           auto quadq = [&](uint32_t x, int& a_lo, int& a_hi) {  // 4 planes of one row (low nibbles), one (high)
             uint32_t vA, wA, vB, wB;
             both(x, 0x06040200u, vA, wA, vB, wB);
@@ -277,13 +288,14 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(int e0, int e1, int e
             a4[2] = dot4(vB, wB & 0x0000FFFFu, a4[2]);
             a4[3] = dot4(vB, wB & 0xFFFF0000u, a4[3]);
           };
-          auto singleq = [&](uint32_t x, uint32_t planes, int* a8) {  // one plane of rows 0..3 (low), 4..7 (high)
+          // first: these are the first terms of the sums (false for the third plane at three bits)
+          auto singleq = [&](uint32_t x, uint32_t planes, int* a8, bool first) {  // one plane of rows 0..3 (low), 4..7 (high)
             uint32_t vA, wA, vB, wB;
             both(x, planes, vA, wA, vB, wB);
 #pragma unroll
             for (int y = 0; y < 4; ++y) {
-              a8[y] = dot4(vA, wA & (0xFFu << (8 * y)), a8[y]);
-              a8[4 + y] = dot4(vB, wB & (0xFFu << (8 * y)), a8[4 + y]);
+              a8[y] = dot4(vA, wA & (0xFFu << (8 * y)), a8[y], first);
+              a8[4 + y] = dot4(vB, wB & (0xFFu << (8 * y)), a8[4 + y], first);
             }
           };
           const uint32_t* wt = &w[rt][t * BITS];
@@ -294,11 +306,11 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(int e0, int e1, int e
             pairq(wt[0], ia);
             pairq(wt[1], ia + 4);
           } else if constexpr (BITS == 1) {
-            singleq(wt[0], 0x00000000u, ia);
+            singleq(wt[0], 0x00000000u, ia, true);
           } else {
             pairq(wt[0], ia);
             pairq(wt[1], ia + 4);
-            singleq(wt[2], 0x04040404u, ia);
+            singleq(wt[2], 0x04040404u, ia, false);
           }
         }
         // integer sum of the unit's four tables, converted once and scaled (the scale is halved
@@ -430,7 +442,7 @@ static hipError_t launch_one(const PermParams& p, int count, int NW, hipStream_t
     return hipLaunchKernel(reinterpret_cast<const void*>(mpgemv_perm_kernel<IS_INT, BITS, GM, RT, FUSED, Q8, 1>), grid,
                            block, args, lds, st);
   }
-  if constexpr (FUSED && !Q8) {
+  if constexpr (FUSED) {
     PermParams local = p;
     static_assert(PERM_MAX_MATS == 8, "seven workgroup bounds travel as arguments of their own");
     int e[7];
@@ -451,22 +463,31 @@ static hipError_t launch_rt(const PermParams& p, int count, int rt, bool fused, 
   return rt == 2 ? launch_one<IS_INT, BITS, GM, 2, false>(p, count, NW, st) : launch_one<IS_INT, BITS, GM, 1, false>(p, count, NW, st);
 }
 
-// int8 tables: one row tile per workgroup, tables from the LUT buffer
+// int8 tables, from the LUT buffer or quantised inside the kernel (one or several matrices): one row
+// tile per group of waves (with two, the kernel needs 90-120 vector registers and a CU holds too few
+// waves; the int8 lookups save 4 of 17 instructions per index dword, the table build costs 50 more
+// per unit, so a second tile would be needed to come out ahead of the fp16 tables)
+template <int BITS, int GM>
+static hipError_t launch_q8_gm(const PermParams& p, int count, bool fused, int NW, hipStream_t st) {
+  if (fused) return launch_one<false, BITS, GM, 1, true, true>(p, count, NW, st);
+  return launch_one<false, BITS, GM, 1, false, true>(p, 1, NW, st);
+}
+
 template <int BITS>
-static hipError_t launch_q8(const PermParams& p, int gm, int NW, hipStream_t st) {
+static hipError_t launch_q8(const PermParams& p, int count, int gm, bool fused, int NW, hipStream_t st) {
   switch (gm) {
-    case 0: return launch_one<false, BITS, 0, 1, false, true>(p, 1, NW, st);
-    case 1: return launch_one<false, BITS, 1, 1, false, true>(p, 1, NW, st);
-    default: return launch_one<false, BITS, 2, 1, false, true>(p, 1, NW, st);
+    case 0: return launch_q8_gm<BITS, 0>(p, count, fused, NW, st);
+    case 1: return launch_q8_gm<BITS, 1>(p, count, fused, NW, st);
+    default: return launch_q8_gm<BITS, 2>(p, count, fused, NW, st);
   }
 }
 
-static hipError_t launch_q8_bits(const PermParams& p, int bits, int gm, int NW, hipStream_t st) {
+static hipError_t launch_q8_bits(const PermParams& p, int count, int bits, int gm, bool fused, int NW, hipStream_t st) {
   switch (bits) {
-    case 1: return launch_q8<1>(p, gm, NW, st);
-    case 2: return launch_q8<2>(p, gm, NW, st);
-    case 3: return launch_q8<3>(p, gm, NW, st);
-    case 4: return launch_q8<4>(p, gm, NW, st);
+    case 1: return launch_q8<1>(p, count, gm, fused, NW, st);
+    case 2: return launch_q8<2>(p, count, gm, fused, NW, st);
+    case 3: return launch_q8<3>(p, count, gm, fused, NW, st);
+    case 4: return launch_q8<4>(p, count, gm, fused, NW, st);
   }
   return hipErrorInvalidValue;
 }
@@ -499,7 +520,9 @@ int perm_fill(PermMat& p, const tmac_wdesc* desc, const void* packed_dev, const 
   const int lut_is_int = (lut_t == TMAC_LUT_I16);
   const Geometry ge = geometry(desc);
   LutGeom lg;
-  if (!lut_geom(N, desc->K, desc->g, desc->group, lut_t, &lg)) return TMAC_EINVAL;
+  // (tables quantised inside the kernel need no LUT buffer: the geometry of the fp16 type gives K's padding
+  // and the groups without the buffer's limit on N)
+  if (!lut_geom(N, desc->K, desc->g, desc->group, fused && q8 ? (int)TMAC_LUT_F16 : lut_t, &lg)) return TMAC_EINVAL;
   if (N > 65535) return TMAC_EUNSUPPORTED;
   if (!fused && !lg.decode_parts) return TMAC_EUNSUPPORTED;  // a LUT buffer for this many rows has no half tables
   // 32-bit slot arithmetic inside the kernel
@@ -585,7 +608,7 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
   const bool fused = (lut_dev == nullptr);
   const bool q8 = (lut_t == TMAC_LUT_I8Q);
   const int lut_is_int = (lut_t == TMAC_LUT_I16);
-  if (q8 && (fused || rows_per_group == 16)) return TMAC_EUNSUPPORTED;
+  if (q8 && rows_per_group == 16) return TMAC_EUNSUPPORTED;
   PermParams pp;
   memset(&pp, 0, sizeof(pp));
   PermMat& p = pp.m[0];
@@ -610,7 +633,7 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
   pp.wg_end[0] = (int)wgs;
   pp.pad = perm_lds_cap(tuning ? tuning->workgroups_per_cu : 0);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const hipError_t e = q8 ? launch_q8_bits(pp, desc->bits, gm, NW, st)
+  const hipError_t e = q8 ? launch_q8_bits(pp, 1, desc->bits, gm, fused, NW, st)
                           : lut_is_int ? launch_bits<true>(pp, 1, desc->bits, gm, rt, fused, NW, st)
                                        : launch_bits<false>(pp, 1, desc->bits, gm, rt, fused, NW, st);
   if (e != hipSuccess) {
@@ -632,7 +655,7 @@ int launch_perm_gemv_multi(const tmac_gemv_item* items, int count, int act_t, in
   const int group_waves = tuning ? tuning->group_waves : 0;
   const int wg_waves = tuning ? tuning->workgroup_waves : 0;
   if (count < 1 || count > PERM_MAX_MATS) return TMAC_EUNSUPPORTED;
-  const int lut_t = act_t == TMAC_ACT_I8 ? (int)TMAC_LUT_I16 : (int)TMAC_LUT_F16;
+  const int lut_t = act_t == TMAC_ACT_I8 ? (int)TMAC_LUT_I16 : act_t == TMAC_ACT_F16_TQ ? (int)TMAC_LUT_I8Q : (int)TMAC_LUT_F16;
   PermParams pp;
   memset(&pp, 0, sizeof(pp));
   int gm0 = 0, max_gsz = 1;
@@ -651,8 +674,10 @@ int launch_perm_gemv_multi(const tmac_gemv_item* items, int count, int act_t, in
   pp.N = N;
   pp.mid = 0.5f * (float)((1 << items[0].desc->bits) - 1);
   pp.out_t = out_t;
+  const bool q8 = (lut_t == TMAC_LUT_I8Q);
+  if (q8 && rows_per_group == 16) return TMAC_EUNSUPPORTED;
   int rt = rows_per_group == 16 ? 2 : 1;
-  if (rows_per_group == 0 && waves * N >= 8192) rt = 2;
+  if (rows_per_group == 0 && !q8 && waves * N >= 8192) rt = 2;
   // waves per workgroup: the W in [largest gsz, 8] (up to 16 when asked) that leaves the fewest wave
   // slots idle; measured on the three Llama-2-7B shapes in one launch: 14.2 us with workgroups of
   // eight waves, 17-19 us with sixteen
@@ -675,8 +700,9 @@ int launch_perm_gemv_multi(const tmac_gemv_item* items, int count, int act_t, in
   pp.pad = perm_lds_cap(tuning ? tuning->workgroups_per_cu : 0);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int bits = items[0].desc->bits;
-  const hipError_t e = (lut_t == TMAC_LUT_I16) ? launch_bits<true>(pp, count, bits, gm0, rt, true, W, st)
-                                               : launch_bits<false>(pp, count, bits, gm0, rt, true, W, st);
+  const hipError_t e = q8                        ? launch_q8_bits(pp, count, bits, gm0, true, W, st)
+                       : (lut_t == TMAC_LUT_I16) ? launch_bits<true>(pp, count, bits, gm0, rt, true, W, st)
+                                                 : launch_bits<false>(pp, count, bits, gm0, rt, true, W, st);
   if (e != hipSuccess) {
     note_hip_error((int)e);
     return TMAC_EHIP;

@@ -29,6 +29,10 @@ __device__ __forceinline__ float dot2(uint32_t pair, uint32_t w, float acc) {
 // The same dot product for a sum that starts at zero: the three-operand form with the constant 0 as
 // addend (the compiler only picks the accumulate-in-place form, which needs a zeroed register first).
 // The plane weights come in a scalar register: this encoding takes no literal.
+// The result may only be used as the addend of another dot product: the compiler cannot see inside
+// an assembly statement, so it does not keep the three wait states this chip wants between a dot
+// product and an instruction of another kind that reads its result (a dot product that takes the
+// result as its addend may follow at once).
 __device__ __forceinline__ float dot2_from_zero(uint32_t pair, uint32_t w_sgpr) {
   float r;
   asm("v_dot2_f32_f16 %0, %1, %2, 0" : "=v"(r) : "v"(pair), "s"(w_sgpr));
@@ -237,6 +241,76 @@ __device__ __forceinline__ void lane_build_tables(const uint32_t (&araw)[8], Lan
     T.lo1[t] = bperm(pk[3], pk[2], 0x06040200u);
     T.hi0[t] = bperm(pk[1], pk[0], 0x07050301u);
     T.hi1[t] = bperm(pk[3], pk[2], 0x07050301u);
+  }
+}
+
+// Table quantisation inside a lane (Section 3.3): the four tables of the unit as int8 entries
+// rint(T * 127 / amax) with amax = the largest |entry| of the unit (the sum of its |activations| per
+// table, maximised over the four tables), and the scale amax / 127.  Entries are formed in fp32 from
+// the fp16 activations (dot products with +-1), so they equal the exact sums whenever those fit
+// fp32.  lo0[t] / lo1[t]: entries 0..3 / 4..7 of table t, one byte each.
+//
+// The dot products are written as assembly in the three-operand form (the accumulate-in-place form
+// the compiler picks would copy the addend first).  The compiler does not know what an assembly
+// statement holds, so it cannot keep the distance this chip wants between a dot product and an
+// instruction of another kind that reads its result (three wait states; a dot product that takes it
+// as its addend may follow at once): every statement below ends with s_nop 2.
+__device__ __forceinline__ void lane_build_tables_q8(const uint32_t (&araw)[8], LaneTables& T, float& uscale) {
+  constexpr uint16_t H_M1 = 0xBC00;
+  constexpr uint32_t PP = h2pack(H_1, H_1), PM = h2pack(H_1, H_M1), MP = h2pack(H_M1, H_1), MM = h2pack(H_M1, H_M1);
+  // the largest |entry| of a table is the sum of its |activations|
+  uint32_t ab[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ab[i] = araw[i] & 0x7fff7fffu;
+  float s0, s1, s2, s3;
+  asm("v_dot2_f32_f16 %0, %4, %12, 0\n\t"
+      "v_dot2_f32_f16 %1, %6, %12, 0\n\t"
+      "v_dot2_f32_f16 %2, %8, %12, 0\n\t"
+      "v_dot2_f32_f16 %3, %10, %12, 0\n\t"
+      "v_dot2_f32_f16 %0, %5, %12, %0\n\t"
+      "v_dot2_f32_f16 %1, %7, %12, %1\n\t"
+      "v_dot2_f32_f16 %2, %9, %12, %2\n\t"
+      "v_dot2_f32_f16 %3, %11, %12, %3\n\t"
+      "s_nop 2"
+      : "=&v"(s0), "=&v"(s1), "=&v"(s2), "=&v"(s3)
+      : "v"(ab[0]), "v"(ab[1]), "v"(ab[2]), "v"(ab[3]), "v"(ab[4]), "v"(ab[5]), "v"(ab[6]), "v"(ab[7]), "s"(PP));
+  const float amax = fmaxf(fmaxf(s0, s1), fmaxf(s2, s3));
+  // 127 / amax: the hardware reciprocal refined by one Newton step (the quotient then is within an
+  // ulp of the exact one: an entry changes only if its exact quotient is that close to a half-integer)
+  float inv = 0.f;
+  if (amax > 0.f) {
+    const float r0 = __builtin_amdgcn_rcpf(amax);
+    const float r1 = fmaf(fmaf(-amax, r0, 1.0f), r0, r0);
+    inv = 127.0f * r1;
+  }
+  uscale = amax * (1.0f / 127.0f);
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    // entry p = +-a0 +-a1 +-a2 - a3 (bit j of p set = +a_j): first -a2 - a3 and a2 - a3, then the four
+    // sign pairs of a0, a1 on top of each
+    float e[8], tqn, wq;
+    asm("v_dot2_f32_f16 %8, %11, %12, 0\n\t"
+        "v_dot2_f32_f16 %9, %11, %13, 0\n\t"
+        "v_dot2_f32_f16 %0, %10, %12, %8\n\t"
+        "v_dot2_f32_f16 %1, %10, %13, %8\n\t"
+        "v_dot2_f32_f16 %2, %10, %14, %8\n\t"
+        "v_dot2_f32_f16 %3, %10, %15, %8\n\t"
+        "v_dot2_f32_f16 %4, %10, %12, %9\n\t"
+        "v_dot2_f32_f16 %5, %10, %13, %9\n\t"
+        "v_dot2_f32_f16 %6, %10, %14, %9\n\t"
+        "v_dot2_f32_f16 %7, %10, %15, %9\n\t"
+        "s_nop 2"
+        : "=&v"(e[0]), "=&v"(e[1]), "=&v"(e[2]), "=&v"(e[3]), "=&v"(e[4]), "=&v"(e[5]), "=&v"(e[6]), "=&v"(e[7]),
+          "=&v"(tqn), "=&v"(wq)
+        : "v"(araw[2 * t]), "v"(araw[2 * t + 1]), "s"(MM), "s"(PM), "s"(MP), "s"(PP));
+    // adding 1.5 * 2^23 rounds e * inv to the nearest integer (ties to even) and leaves it, in two's
+    // complement, in the low mantissa bits: byte 0 of the sum is the int8 entry (|e * inv| <= 127
+    // up to an ulp: the entries are bounded by amax)
+    uint32_t r[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) r[q] = __float_as_uint(fmaf(e[q], inv, 12582912.0f));
+    T.lo0[t] = bperm(bperm(r[3], r[2], 0x0c0c0400u), bperm(r[1], r[0], 0x0c0c0400u), 0x05040100u);
+    T.lo1[t] = bperm(bperm(r[7], r[6], 0x0c0c0400u), bperm(r[5], r[4], 0x0c0c0400u), 0x05040100u);
   }
 }
 

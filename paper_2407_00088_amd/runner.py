@@ -57,9 +57,10 @@ class LinearLUT:
                       stream=stream, tuning=tuning)
 
     def mpgemv_fused(self, A, N: int, out, out_t: int = B.TMAC_OUT_F32, act_scale=None, stream=None, packed=None,
-                     tuning=None):
-        """One launch: tables built inside the lookup kernel (layout 2 only)."""
-        B.tmac_mpgemv_fused(self.desc, self.packed if packed is None else packed, A, N, out, out_t,
+                     tuning=None, act=None):
+        """One launch: tables built inside the lookup kernel (layout 2 only); act = B.TMAC_ACT_F16_TQ
+        quantises them to int8 there."""
+        B.tmac_mpgemv_fused(self.desc, self.packed if packed is None else packed, A, N, out, out_t, act=act,
                             act_scale=act_scale, weight_scale=self.weight_scale, stream=stream, tuning=tuning)
 
     def mpgemm_fused(self, A, N: int, out, out_t: int = B.TMAC_OUT_F32, act_scale=None, stream=None, packed=None):
@@ -82,12 +83,12 @@ class LinearLUT:
         self.mpgemm_fused(A, N, out, out_t, act_scale=act_scale)
         return out
 
-    def forward_fused(self, A, out_t: int = B.TMAC_OUT_F32, act_scale=None, tuning=None):
+    def forward_fused(self, A, out_t: int = B.TMAC_OUT_F32, act_scale=None, tuning=None, act=None):
         torch = self.torch
         N = A.shape[0]
         dt = {B.TMAC_OUT_F32: torch.float32, B.TMAC_OUT_F16: torch.float16, B.TMAC_OUT_I32: torch.int32}[out_t]
         out = torch.empty((N, self.M), dtype=dt, device=self.device)
-        self.mpgemv_fused(A, N, out, out_t, act_scale=act_scale, tuning=tuning)
+        self.mpgemv_fused(A, N, out, out_t, act_scale=act_scale, tuning=tuning, act=act)
         return out
 
     def forward(self, A, out_t: int = B.TMAC_OUT_F32, act_scale=None, tuning=None):
