@@ -472,9 +472,15 @@ def main():
         def block_separate():
             for k, _, _ in blk_shapes:
                 cs[k].fused()
+
+        def block_one():
+            # all seven in ONE launch: what the kernel does with 108 MB behind one start; a real block
+            # cannot do this (O needs the attention output, down needs gate and up)
+            multi([cs[k] for k, _, _ in blk_shapes])
         breps = max(ring_len(c) for c in cs.values())
         blk = {}
-        for key, fn in (("four_launches_qkv_and_gate_up_grouped", block_multi), ("seven_launches", block_separate)):
+        for key, fn in (("four_launches_qkv_and_gate_up_grouped", block_multi), ("seven_launches", block_separate),
+                        ("one_launch_ignoring_the_data_dependencies", block_one)):
             us = per_launch(fn, breps)
             blk[key] = {"us": round(us, 3), "bytes": nbytes, "GBps": round(nbytes / us / 1e3, 1),
                         "frac_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)}
