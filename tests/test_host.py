@@ -293,6 +293,32 @@ def test_multi_call_rejects_bad_arguments_before_launch():
     assert call([item(d), item(d3)]) == B.TMAC_EUNSUPPORTED
     assert call([item(d)], out=B.TMAC_OUT_I32) == B.TMAC_EINVAL    # raw integers from fp16 tables
     assert call([item(d)], tuning=C.byref(B.tmac_tuning(12))) == B.TMAC_EINVAL
+    # tables quantised in the kernel: fp results only, one row tile per group of waves
+    assert call([item(d)], act=B.TMAC_ACT_F16_TQ, out=B.TMAC_OUT_I32) == B.TMAC_EINVAL
+    assert call([item(d)], act=B.TMAC_ACT_F16_TQ, tuning=C.byref(B.tmac_tuning(16))) == B.TMAC_EUNSUPPORTED
+
+
+def test_fused_call_refuses_sizes_beyond_its_index_arithmetic_before_launch():
+    """The register-table kernel counts units in 16 bits, slots in 32 bits and activation rows in the
+    grid's y dimension: larger calls are refused on the host (fake pointers: nothing is launched)."""
+    lib = B.lib
+    fake = C.c_void_p(0x1000)
+    F = lib.tmac_mpgemv_fused
+
+    def call(desc, N=1, act=0, lda=None):
+        return F(C.byref(desc), fake, fake, act, N, desc.K if lda is None else lda, None, C.c_float(1.0), fake, 0,
+                 desc.M, None)
+    ok = T.wdesc(64, 256, 4, 128, layout=B.TMAC_LAYOUT_R8U16)
+    assert call(ok, N=65536) == B.TMAC_EUNSUPPORTED                       # grid y
+    assert call(ok, N=0) == B.TMAC_EINVAL
+    long_k = T.wdesc(8, 1 << 20, 4, 128, layout=B.TMAC_LAYOUT_R8U16)      # 65536 units of 16 k
+    assert call(long_k) == B.TMAC_EUNSUPPORTED
+    many = T.wdesc(1 << 22, 1 << 19, 4, 128, layout=B.TMAC_LAYOUT_R8U16)  # row tiles x units x bits >= 2^32
+    assert call(many) == B.TMAC_EUNSUPPORTED
+    assert call(ok, act=B.TMAC_ACT_F16_TQ, N=65536) == B.TMAC_EUNSUPPORTED
+    # int8 activations with one scale per row: the row sum travels in fp32 and must stay below 2^24
+    long_int = T.wdesc(8, 1 << 18, 2, 0, layout=B.TMAC_LAYOUT_R8U16)
+    assert call(long_int, act=B.TMAC_ACT_I8) == B.TMAC_EUNSUPPORTED
 
 
 def test_bench_refuses_more_than_one_gpu():
