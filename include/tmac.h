@@ -21,8 +21,10 @@
  *
  * General rules
  *   - The library allocates no memory; the caller owns every buffer.  The only state it keeps is
- *     the text of the last HIP error of the calling thread (tmac_last_error_detail).  Pointers named *_host are host memory, *_dev are device memory of the
- *     current HIP device.  Device pointers must be 16-byte aligned (256 recommended).
+ *     the text of the calling thread's last error (tmac_last_error_detail) and, once
+ *     tmac_mpgemm_noalloc has run on a GPU, that GPU's address of the library's scratch array.
+ *   - Pointers named *_host are host memory, *_dev are device memory of the current HIP device.
+ *     Device pointers must be 16-byte aligned (256 recommended).
  *   - Device entry points only enqueue work on `stream` (a hipStream_t passed as void*,
  *     NULL = the default stream) and never synchronise.
  *   - Every failure is reported through the returned tmac_status; arguments are checked on
@@ -297,7 +299,7 @@ tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed_dev, const
                            const tmac_tuning* tuning);
 
 /* Same as tmac_mpgemv_fused with explicit launch-shape knobs (NULL = defaults; only
- * rows_per_group applies). */
+ * rows_per_group applies, and with TMAC_ACT_F16_TQ it must be 0 or 8: TMAC_EUNSUPPORTED otherwise). */
 tmac_status tmac_mpgemv_fused_ex(const tmac_wdesc* desc, const void* packed_dev, const void* A_dev,
                                  tmac_act_t act, int32_t N, int64_t lda, const float* act_scale_dev,
                                  float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
@@ -315,7 +317,7 @@ tmac_status tmac_mpgemv_fused_ex(const tmac_wdesc* desc, const void* packed_dev,
  *   the same way (all per row or per tensor, or all with group sizes that are multiples of 128, or
  *   all with other multiples of 16); M, K, group size, pointers and leading dimensions are per item.
  *   act, N, out are common to the items.  Items must not alias each other's outputs.
- *   tuning  NULL = defaults (only rows_per_group applies)
+ *   tuning  NULL = defaults (only rows_per_group applies; TMAC_ACT_F16_TQ takes 0 or 8)
  * Errors: TMAC_EINVAL (null or misaligned pointer, bad desc or leading dimension),
  * TMAC_EUNSUPPORTED (count out of range, mixed bit-widths or grouping modes, what
  * tmac_mpgemv_fused rejects), TMAC_EHIP. */
