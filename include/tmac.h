@@ -299,7 +299,7 @@ tmac_status tmac_mpgemm_ex(const tmac_wdesc* desc, const void* packed_dev, const
                            const tmac_tuning* tuning);
 
 /* Same as tmac_mpgemv_fused with explicit launch-shape knobs (NULL = defaults; only
- * rows_per_group applies, and with TMAC_ACT_F16_TQ it must be 0 or 8: TMAC_EUNSUPPORTED otherwise). */
+ * rows_per_group applies). */
 tmac_status tmac_mpgemv_fused_ex(const tmac_wdesc* desc, const void* packed_dev, const void* A_dev,
                                  tmac_act_t act, int32_t N, int64_t lda, const float* act_scale_dev,
                                  float weight_scale, void* out_dev, tmac_out_t out, int64_t ldo,
@@ -317,7 +317,7 @@ tmac_status tmac_mpgemv_fused_ex(const tmac_wdesc* desc, const void* packed_dev,
  *   the same way (all per row or per tensor, or all with group sizes that are multiples of 128, or
  *   all with other multiples of 16); M, K, group size, pointers and leading dimensions are per item.
  *   act, N, out are common to the items.  Items must not alias each other's outputs.
- *   tuning  NULL = defaults (only rows_per_group applies; TMAC_ACT_F16_TQ takes 0 or 8)
+ *   tuning  NULL = defaults (only rows_per_group applies)
  * Errors: TMAC_EINVAL (null or misaligned pointer, bad desc or leading dimension),
  * TMAC_EUNSUPPORTED (count out of range, mixed bit-widths or grouping modes, what
  * tmac_mpgemv_fused rejects), TMAC_EHIP. */

@@ -312,6 +312,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(int e0, int e1, int e
             pairq(wt[1], ia + 4);
             singleq(wt[2], 0x04040404u, ia, false);
           }
+          __builtin_amdgcn_sched_barrier(0);  // table by table: few registers live at a time
         }
         // integer sum of the unit's four tables, converted once and scaled (the scale is halved
         // together with the plane weights in the group-scale modes)
@@ -463,31 +464,34 @@ static hipError_t launch_rt(const PermParams& p, int count, int rt, bool fused, 
   return rt == 2 ? launch_one<IS_INT, BITS, GM, 2, false>(p, count, NW, st) : launch_one<IS_INT, BITS, GM, 1, false>(p, count, NW, st);
 }
 
-// int8 tables, from the LUT buffer or quantised inside the kernel (one or several matrices): one row
-// tile per group of waves (with two, the kernel needs 90-120 vector registers and a CU holds too few
-// waves; the int8 lookups save 4 of 17 instructions per index dword, the table build costs 50 more
-// per unit, so a second tile would be needed to come out ahead of the fp16 tables)
+// int8 tables: from the LUT buffer (one row tile per group of waves) or quantised inside the kernel
+// (one or two row tiles, one or several matrices).  The int8 lookups save 4 of 17 instructions per
+// index dword and the table build costs 50 more per unit than fp16 tables: with two row tiles the
+// instruction counts are level (719 against 734 at 4 bit), with one the fp16 tables are ahead.
 template <int BITS, int GM>
-static hipError_t launch_q8_gm(const PermParams& p, int count, bool fused, int NW, hipStream_t st) {
-  if (fused) return launch_one<false, BITS, GM, 1, true, true>(p, count, NW, st);
+static hipError_t launch_q8_gm(const PermParams& p, int count, int rt, bool fused, int NW, hipStream_t st) {
+  if (fused)
+    return rt == 2 ? launch_one<false, BITS, GM, 2, true, true>(p, count, NW, st)
+                   : launch_one<false, BITS, GM, 1, true, true>(p, count, NW, st);
   return launch_one<false, BITS, GM, 1, false, true>(p, 1, NW, st);
 }
 
 template <int BITS>
-static hipError_t launch_q8(const PermParams& p, int count, int gm, bool fused, int NW, hipStream_t st) {
+static hipError_t launch_q8(const PermParams& p, int count, int gm, int rt, bool fused, int NW, hipStream_t st) {
   switch (gm) {
-    case 0: return launch_q8_gm<BITS, 0>(p, count, fused, NW, st);
-    case 1: return launch_q8_gm<BITS, 1>(p, count, fused, NW, st);
-    default: return launch_q8_gm<BITS, 2>(p, count, fused, NW, st);
+    case 0: return launch_q8_gm<BITS, 0>(p, count, rt, fused, NW, st);
+    case 1: return launch_q8_gm<BITS, 1>(p, count, rt, fused, NW, st);
+    default: return launch_q8_gm<BITS, 2>(p, count, rt, fused, NW, st);
   }
 }
 
-static hipError_t launch_q8_bits(const PermParams& p, int count, int bits, int gm, bool fused, int NW, hipStream_t st) {
+static hipError_t launch_q8_bits(const PermParams& p, int count, int bits, int gm, int rt, bool fused, int NW,
+                                 hipStream_t st) {
   switch (bits) {
-    case 1: return launch_q8<1>(p, count, gm, fused, NW, st);
-    case 2: return launch_q8<2>(p, count, gm, fused, NW, st);
-    case 3: return launch_q8<3>(p, count, gm, fused, NW, st);
-    case 4: return launch_q8<4>(p, count, gm, fused, NW, st);
+    case 1: return launch_q8<1>(p, count, gm, rt, fused, NW, st);
+    case 2: return launch_q8<2>(p, count, gm, rt, fused, NW, st);
+    case 3: return launch_q8<3>(p, count, gm, rt, fused, NW, st);
+    case 4: return launch_q8<4>(p, count, gm, rt, fused, NW, st);
   }
   return hipErrorInvalidValue;
 }
@@ -608,7 +612,7 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
   const bool fused = (lut_dev == nullptr);
   const bool q8 = (lut_t == TMAC_LUT_I8Q);
   const int lut_is_int = (lut_t == TMAC_LUT_I16);
-  if (q8 && rows_per_group == 16) return TMAC_EUNSUPPORTED;
+  if (q8 && !fused && rows_per_group == 16) return TMAC_EUNSUPPORTED;
   PermParams pp;
   memset(&pp, 0, sizeof(pp));
   PermMat& p = pp.m[0];
@@ -627,13 +631,13 @@ int launch_perm_gemv(const tmac_wdesc* desc, const void* packed_dev, const void*
   // (4096 x 4096 up to 12288 x 4096); with several activation rows (one GEMV each in one launch)
   // the same count decides (4096 x 4096: from four rows on).  The default follows it.
   int rt = rows_per_group == 16 ? 2 : 1;
-  if (rows_per_group == 0 && !q8 && (int64_t)p.n_tiles * p.gsz * N >= 8192) rt = 2;
+  if (rows_per_group == 0 && (fused || !q8) && (int64_t)p.n_tiles * p.gsz * N >= 8192) rt = 2;
   const int64_t wgs = perm_shape(p, NW, rt);
   if (wgs > 0x7fffffff) return TMAC_EUNSUPPORTED;
   pp.wg_end[0] = (int)wgs;
   pp.pad = perm_lds_cap(tuning ? tuning->workgroups_per_cu : 0);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const hipError_t e = q8 ? launch_q8_bits(pp, 1, desc->bits, gm, fused, NW, st)
+  const hipError_t e = q8 ? launch_q8_bits(pp, 1, desc->bits, gm, rt, fused, NW, st)
                           : lut_is_int ? launch_bits<true>(pp, 1, desc->bits, gm, rt, fused, NW, st)
                                        : launch_bits<false>(pp, 1, desc->bits, gm, rt, fused, NW, st);
   if (e != hipSuccess) {
@@ -675,9 +679,8 @@ int launch_perm_gemv_multi(const tmac_gemv_item* items, int count, int act_t, in
   pp.mid = 0.5f * (float)((1 << items[0].desc->bits) - 1);
   pp.out_t = out_t;
   const bool q8 = (lut_t == TMAC_LUT_I8Q);
-  if (q8 && rows_per_group == 16) return TMAC_EUNSUPPORTED;
   int rt = rows_per_group == 16 ? 2 : 1;
-  if (rows_per_group == 0 && !q8 && waves * N >= 8192) rt = 2;
+  if (rows_per_group == 0 && waves * N >= 8192) rt = 2;
   // waves per workgroup: the W in [largest gsz, 8] (up to 16 when asked) that leaves the fewest wave
   // slots idle; measured on the three Llama-2-7B shapes in one launch: 14.2 us with workgroups of
   // eight waves, 17-19 us with sixteen
@@ -700,7 +703,7 @@ int launch_perm_gemv_multi(const tmac_gemv_item* items, int count, int act_t, in
   pp.pad = perm_lds_cap(tuning ? tuning->workgroups_per_cu : 0);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int bits = items[0].desc->bits;
-  const hipError_t e = q8                        ? launch_q8_bits(pp, count, bits, gm0, true, W, st)
+  const hipError_t e = q8                        ? launch_q8_bits(pp, count, bits, gm0, rt, true, W, st)
                        : (lut_t == TMAC_LUT_I16) ? launch_bits<true>(pp, count, bits, gm0, rt, true, W, st)
                                                  : launch_bits<false>(pp, count, bits, gm0, rt, true, W, st);
   if (e != hipSuccess) {

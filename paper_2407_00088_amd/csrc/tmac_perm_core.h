@@ -258,23 +258,19 @@ __device__ __forceinline__ void lane_build_tables(const uint32_t (&araw)[8], Lan
 __device__ __forceinline__ void lane_build_tables_q8(const uint32_t (&araw)[8], LaneTables& T, float& uscale) {
   constexpr uint16_t H_M1 = 0xBC00;
   constexpr uint32_t PP = h2pack(H_1, H_1), PM = h2pack(H_1, H_M1), MP = h2pack(H_M1, H_1), MM = h2pack(H_M1, H_M1);
-  // the largest |entry| of a table is the sum of its |activations|
-  uint32_t ab[8];
+  // the largest |entry| of a table is the sum of its |activations| (one table at a time: few
+  // registers are live next to the index registers, whose loads are already in flight)
+  float amax = 0.f;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) ab[i] = araw[i] & 0x7fff7fffu;
-  float s0, s1, s2, s3;
-  asm("v_dot2_f32_f16 %0, %4, %12, 0\n\t"
-      "v_dot2_f32_f16 %1, %6, %12, 0\n\t"
-      "v_dot2_f32_f16 %2, %8, %12, 0\n\t"
-      "v_dot2_f32_f16 %3, %10, %12, 0\n\t"
-      "v_dot2_f32_f16 %0, %5, %12, %0\n\t"
-      "v_dot2_f32_f16 %1, %7, %12, %1\n\t"
-      "v_dot2_f32_f16 %2, %9, %12, %2\n\t"
-      "v_dot2_f32_f16 %3, %11, %12, %3\n\t"
-      "s_nop 2"
-      : "=&v"(s0), "=&v"(s1), "=&v"(s2), "=&v"(s3)
-      : "v"(ab[0]), "v"(ab[1]), "v"(ab[2]), "v"(ab[3]), "v"(ab[4]), "v"(ab[5]), "v"(ab[6]), "v"(ab[7]), "s"(PP));
-  const float amax = fmaxf(fmaxf(s0, s1), fmaxf(s2, s3));
+  for (int t = 0; t < 4; ++t) {
+    float sa;
+    asm("v_dot2_f32_f16 %0, %1, %3, 0\n\t"
+        "v_dot2_f32_f16 %0, %2, %3, %0\n\t"
+        "s_nop 2"
+        : "=&v"(sa)
+        : "v"(araw[2 * t] & 0x7fff7fffu), "v"(araw[2 * t + 1] & 0x7fff7fffu), "s"(PP));
+    amax = fmaxf(amax, sa);
+  }
   // 127 / amax: the hardware reciprocal refined by one Newton step (the quotient then is within an
   // ulp of the exact one: an entry changes only if its exact quotient is that close to a half-integer)
   float inv = 0.f;
@@ -286,31 +282,28 @@ __device__ __forceinline__ void lane_build_tables_q8(const uint32_t (&araw)[8], 
   uscale = amax * (1.0f / 127.0f);
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    // entry p = +-a0 +-a1 +-a2 - a3 (bit j of p set = +a_j): first -a2 - a3 and a2 - a3, then the four
-    // sign pairs of a0, a1 on top of each
-    float e[8], tqn, wq;
-    asm("v_dot2_f32_f16 %8, %11, %12, 0\n\t"
-        "v_dot2_f32_f16 %9, %11, %13, 0\n\t"
-        "v_dot2_f32_f16 %0, %10, %12, %8\n\t"
-        "v_dot2_f32_f16 %1, %10, %13, %8\n\t"
-        "v_dot2_f32_f16 %2, %10, %14, %8\n\t"
-        "v_dot2_f32_f16 %3, %10, %15, %8\n\t"
-        "v_dot2_f32_f16 %4, %10, %12, %9\n\t"
-        "v_dot2_f32_f16 %5, %10, %13, %9\n\t"
-        "v_dot2_f32_f16 %6, %10, %14, %9\n\t"
-        "v_dot2_f32_f16 %7, %10, %15, %9\n\t"
-        "s_nop 2"
-        : "=&v"(e[0]), "=&v"(e[1]), "=&v"(e[2]), "=&v"(e[3]), "=&v"(e[4]), "=&v"(e[5]), "=&v"(e[6]), "=&v"(e[7]),
-          "=&v"(tqn), "=&v"(wq)
-        : "v"(araw[2 * t]), "v"(araw[2 * t + 1]), "s"(MM), "s"(PM), "s"(MP), "s"(PP));
-    // adding 1.5 * 2^23 rounds e * inv to the nearest integer (ties to even) and leaves it, in two's
-    // complement, in the low mantissa bits: byte 0 of the sum is the int8 entry (|e * inv| <= 127
-    // up to an ulp: the entries are bounded by amax)
-    uint32_t r[8];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) r[q] = __float_as_uint(fmaf(e[q], inv, 12582912.0f));
-    T.lo0[t] = bperm(bperm(r[3], r[2], 0x0c0c0400u), bperm(r[1], r[0], 0x0c0c0400u), 0x05040100u);
-    T.lo1[t] = bperm(bperm(r[7], r[6], 0x0c0c0400u), bperm(r[5], r[4], 0x0c0c0400u), 0x05040100u);
+    for (int h = 0; h < 2; ++h) {
+      // entry p = +-a0 +-a1 +-a2 - a3 (bit j of p set = +a_j); h = bit 2: first -a2 - a3 (h = 0) or
+      // a2 - a3 (h = 1), then the four sign pairs of a0, a1 on top of it
+      float e0, e1, e2, e3, base;
+      asm("v_dot2_f32_f16 %4, %6, %7, 0\n\t"
+          "v_dot2_f32_f16 %0, %5, %8, %4\n\t"
+          "v_dot2_f32_f16 %1, %5, %9, %4\n\t"
+          "v_dot2_f32_f16 %2, %5, %10, %4\n\t"
+          "v_dot2_f32_f16 %3, %5, %11, %4\n\t"
+          "s_nop 2"
+          : "=&v"(e0), "=&v"(e1), "=&v"(e2), "=&v"(e3), "=&v"(base)
+          : "v"(araw[2 * t]), "v"(araw[2 * t + 1]), "s"(h ? PM : MM), "s"(MM), "s"(PM), "s"(MP), "s"(PP));
+      // adding 1.5 * 2^23 rounds e * inv to the nearest integer (ties to even) and leaves it, in two's
+      // complement, in the low mantissa bits: byte 0 of the sum is the int8 entry (|e * inv| <= 127
+      // up to an ulp: the entries are bounded by amax)
+      const uint32_t r0 = __float_as_uint(fmaf(e0, inv, 12582912.0f)), r1 = __float_as_uint(fmaf(e1, inv, 12582912.0f));
+      const uint32_t r2 = __float_as_uint(fmaf(e2, inv, 12582912.0f)), r3 = __float_as_uint(fmaf(e3, inv, 12582912.0f));
+      const uint32_t word = bperm(bperm(r3, r2, 0x0c0c0400u), bperm(r1, r0, 0x0c0c0400u), 0x05040100u);
+      if (h == 0) T.lo0[t] = word;
+      else T.lo1[t] = word;
+    }
   }
 }
 

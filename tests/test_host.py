@@ -293,9 +293,8 @@ def test_multi_call_rejects_bad_arguments_before_launch():
     assert call([item(d), item(d3)]) == B.TMAC_EUNSUPPORTED
     assert call([item(d)], out=B.TMAC_OUT_I32) == B.TMAC_EINVAL    # raw integers from fp16 tables
     assert call([item(d)], tuning=C.byref(B.tmac_tuning(12))) == B.TMAC_EINVAL
-    # tables quantised in the kernel: fp results only, one row tile per group of waves
+    # tables quantised in the kernel: fp results only
     assert call([item(d)], act=B.TMAC_ACT_F16_TQ, out=B.TMAC_OUT_I32) == B.TMAC_EINVAL
-    assert call([item(d)], act=B.TMAC_ACT_F16_TQ, tuning=C.byref(B.tmac_tuning(16))) == B.TMAC_EUNSUPPORTED
 
 
 def test_fused_call_refuses_sizes_beyond_its_index_arithmetic_before_launch():
