@@ -13,8 +13,10 @@ Infinity Cache, so weights come from HBM.
 Launches are replayed from HIP graphs (captured once, outside the timed region) so that the
 host-side cost of issuing microsecond kernels from Python does not hide the GPU time; the timed
 region is bracketed by HIP events on the launching stream and by synchronize().  Before the
-warm-up an untimed pre-roll of PREROLL_STEPS steps brings the clocks up, so that a short timed
-region (20 steps) reads like a long one.
+warm-up an untimed pre-roll of PREROLL_STEPS steps brings the clocks up, and the fixed cost of an
+event pair around a graph replay (25-45 us) is cancelled by bracketing twice, once around L
+calibration steps and once around L + K steps (see timed_exact), so that a short timed region
+(20 steps) reads like a long one.
 
 Prints ONE JSON line: whole-step throughput (algorithmic GB/s), the roofline of the dominant
 kernel, the CPU oracle timed on the host cores as a reported baseline, and under `detail` the rest
@@ -38,6 +40,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 RING_MB = 576        # > 2 x 256 MB Infinity Cache
 PREROLL_STEPS = 400  # untimed steps before the warm-up (clock ramp), independent of --steps
+LEAD_IN_STEPS = 600  # untimed steps in front of every event bracket (about 8 ms of continuous work)
 MIN_LAUNCHES = 300   # launches behind every per-kernel figure, independent of --steps
 
 # HBM bytes of one step's launch(es) from two rocprofv3 --pmc passes (FETCH_SIZE, then WRITE_SIZE),
@@ -199,6 +202,7 @@ def main():
             for _ in range(warm):
                 replay.run()
             stream.synchronize()
+            replay.run()  # untimed lead-in: the GPU is busy while the host enqueues the timed launches
             t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             t0.record(stream)
             for _ in range(launches):
@@ -207,38 +211,72 @@ def main():
             stream.synchronize()
         return t0.elapsed_time(t1) * 1e3 / (launches * replay.reps)
 
+    def steady_us(body, reps, steps):
+        """Time of exactly `steps` executions of `body` in steady state, in microseconds per execution.
+
+        A pair of HIP events around a graph replay carries a fixed cost of 25-45 us on this runtime (the
+        events' own packets and the start of a graph that did not run just before), which a region of
+        20 steps = 0.27 ms would show as +2 us per step.  So the region is bracketed twice, each time by
+        events on the launching stream with synchronize() on both sides: once around a calibration graph of
+        L executions (L = `reps`, one pass over the weight ring) and once around the timed sequence, whose
+        last graph holds L + r executions; the difference of the two brackets is the time of exactly
+        `steps` = q * 4 * reps + r executions with the fixed cost cancelled.  Each bracket is preceded by
+        untimed replays of its own first graph (the GPU is busy while the host enqueues, the bracket
+        starts with a graph that has just run, and the clocks have recovered from the idle gap of the
+        synchronize()).  The pair is measured three times and the median difference is returned."""
+        big = 4 * reps
+        cache = {}
+
+        def graph(n):
+            if n not in cache:
+                cache[n] = Replay(body, n)
+            return cache[n]
+
+        def bracket(seq):
+            # untimed lead-in: about LEAD_IN_STEPS executions of the bracket's own first graph
+            lead = max(2, -(-LEAD_IN_STEPS // seq[0].reps))
+            with torch.cuda.stream(stream):
+                for _ in range(lead):
+                    seq[0].run()
+                t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                t0.record(stream)
+                for g in seq:
+                    g.run()
+                t1.record(stream)
+                stream.synchronize()
+            return t0.elapsed_time(t1) * 1e3
+
+        q = (steps - 1) // big
+        r = steps - q * big                      # 1 .. big
+        cal_seq = [graph(reps)]
+        timed_seq = [graph(big)] * q + [graph(reps + r)]
+        diffs, dbg = [], []
+        for _ in range(3):
+            ca = bracket(cal_seq)
+            tb = bracket(timed_seq)
+            diffs.append(tb - ca)
+            dbg.append((round(ca, 1), round(tb, 1)))
+        if os.environ.get("TMAC_BENCH_DEBUG"):
+            print("DEBUG reps", reps, "steps", steps, "q", q, "r", r, "(calibration, timed) us:", dbg, file=sys.stderr, flush=True)
+        return sorted(diffs)[1] / steps
+
     def timed_exact(body, reps, steps, warm_steps, preroll):
-        """`preroll` + `warm_steps` untimed and exactly `steps` timed executions of `body`: whole replays of
-        `reps` executions plus one shorter replay for the remainder.  Returns microseconds per execution."""
-        full = Replay(body, reps)
-        tails = {}
-
-        def plan(n):
-            seq = [full] * (n // reps)
-            if n % reps:
-                if n % reps not in tails:
-                    tails[n % reps] = Replay(body, n % reps)
-                seq.append(tails[n % reps])
-            return seq
-
-        pre_seq, warm_seq, timed_seq = plan(preroll), plan(warm_steps), plan(steps)
-        with torch.cuda.stream(stream):
-            for r in pre_seq + warm_seq:
-                r.run()
-            stream.synchronize()
-            t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            t0.record(stream)
-            for r in timed_seq:
-                r.run()
-            t1.record(stream)
-            stream.synchronize()
-        return t0.elapsed_time(t1) * 1e3 / steps
+        """`preroll` + `warm_steps` untimed executions of `body`, then steady_us over exactly `steps`."""
+        n = preroll + warm_steps
+        if n > 0:
+            g = Replay(body, min(n, 4 * reps))
+            with torch.cuda.stream(stream):
+                done = 0
+                while done < n:   # whole replays: at least n executions
+                    g.run()
+                    done += g.reps
+                stream.synchronize()
+        return steady_us(body, reps, steps)
 
     def per_launch(body, reps, min_launches=MIN_LAUNCHES):
-        """Microseconds per execution of `body`, over at least `min_launches` executions (graphs of `reps`
-        executions, one warm replay first): the same answer whatever --steps says."""
-        replays = max(2, -(-min_launches // reps))
-        return timed(Replay(body, reps), replays, 3)
+        """Microseconds per execution of `body` in steady state over at least `min_launches` executions: the
+        same answer whatever --steps says."""
+        return steady_us(body, reps, max(min_launches, reps))
 
     def ring_len(c):
         return len(c.ring)
@@ -640,6 +678,9 @@ def main():
                                + how_step + f", weights cycled through a {args.ring_mb} MiB ring per shape",
                    "launch": "eager" if args.no_graph else "hip graph replay",
                    "untimed_preroll_steps": PREROLL_STEPS,
+                   "timing": "HIP events around a graph of L + K steps minus the same around a graph of L steps "
+                             "(L = one pass over the weight ring): the fixed cost of an event pair around a graph "
+                             "replay cancels; each bracket follows about 600 untimed steps of its first graph; median of three pairs",
                    "frac_hbm_peak_whole_step": round(value / HBM_PEAK_GBPS, 4)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
