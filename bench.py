@@ -211,6 +211,8 @@ def main():
             stream.synchronize()
         return t0.elapsed_time(t1) * 1e3 / (launches * replay.reps)
 
+    last_brackets = []  # the raw event brackets of the latest steady_us call
+
     def steady_us(body, reps, steps):
         """Time of exactly `steps` executions of `body` in steady state, in microseconds per execution.
 
@@ -256,8 +258,8 @@ def main():
             tb = bracket(timed_seq)
             diffs.append(tb - ca)
             dbg.append((round(ca, 1), round(tb, 1)))
-        if os.environ.get("TMAC_BENCH_DEBUG"):
-            print("DEBUG reps", reps, "steps", steps, "q", q, "r", r, "(calibration, timed) us:", dbg, file=sys.stderr, flush=True)
+        last_brackets[:] = [{"calibration_steps": reps, "bracket_steps": reps + steps, "calibration_us": c, "bracket_us": t}
+                            for c, t in dbg]
         return sorted(diffs)[1] / steps
 
     def timed_exact(body, reps, steps, warm_steps, preroll):
@@ -440,6 +442,7 @@ def main():
     reps = max(ring_len(c) for c in cases)
     steps_done = max(1, args.steps)
     step_us = timed_exact(step, reps, steps_done, max(0, args.warmup), PREROLL_STEPS)
+    headline_brackets = list(last_brackets)
     ms_per_step = step_us * 1e-3
     value = step_bytes / (step_us * 1e-6) / 1e9
 
@@ -681,6 +684,7 @@ def main():
                    "timing": "HIP events around a graph of L + K steps minus the same around a graph of L steps "
                              "(L = one pass over the weight ring): the fixed cost of an event pair around a graph "
                              "replay cancels; each bracket follows about 600 untimed steps of its first graph; median of three pairs",
+                   "event_brackets": headline_brackets,
                    "frac_hbm_peak_whole_step": round(value / HBM_PEAK_GBPS, 4)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
