@@ -320,7 +320,7 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(int e0, int e1, int e
 #pragma unroll
         for (int r = 0; r < 8; ++r) acc[r] = fmaf((float)ia[r], us, acc[r]);
       } else {
-        lane_lookups<BITS, GM != 0, GM == 2>(w[rt], T, acc);
+        lane_lookups<BITS, GM != 0, GM == 2, RT == 2>(w[rt], T, acc);
       }
 
       // 7. scale: once per (row, lane) in GM 1, once per (row, chunk) in GM 2

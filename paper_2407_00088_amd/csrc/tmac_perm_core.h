@@ -310,8 +310,8 @@ __device__ __forceinline__ void lane_build_tables_q8(const uint32_t (&araw)[8], 
 // The lookups of one row tile and one unit: w = the lane's 4 * BITS index dwords (table t in dwords
 // t * BITS ..), acc[r] += sum over the unit's tables and planes of 2^plane (halved when HALF) times the
 // looked-up entry, for the eight rows r of the tile (Eq. 1).
-// ZERO: the sums start at zero (what acc holds on entry is ignored).
-template <int BITS, bool HALF, bool ZERO = false>
+// ZERO: the sums start at zero (what acc holds on entry is ignored).  FENCE: see the end of the body.
+template <int BITS, bool HALF, bool ZERO = false, bool FENCE = false>
 __device__ __forceinline__ void lane_lookups(uint32_t* w, const LaneTables& T, float (&acc)[8]) {
   // plane weights: halved in the group-scale modes, where acc = bias + 1/2 * sum_i 2^i L_i
   constexpr uint32_t W01 = HALF ? h2pack(H_05, H_1) : h2pack(H_1, H_2);
@@ -384,11 +384,14 @@ __device__ __forceinline__ void lane_lookups(uint32_t* w, const LaneTables& T, f
       single(wt[2], WS2, acc, false);
     }
     // Table by table, in the order the index pieces were requested: the lookups of table t run while
-    // the pieces of the later tables are still in flight, and few registers are live at a time.  An
-    // empty asm statement that "rewrites" the sums of table t together with the index dwords of
-    // table t + 1 makes that order a data dependency (a scheduling barrier alone does not hold pure
-    // arithmetic in place: the instruction selector may emit it on either side).
-    if (t < 3) {
+    // the pieces of the later tables are still in flight, and few registers are live at a time.
+    // FENCE: a scheduling barrier between the tables.  With two row tiles per wave it takes the
+    // kernel from 77 to 69 vector registers and 1.5 % off the three-matrix step; with one row tile
+    // the same barrier costs 4.6 %, and the order is made a data dependency instead: an empty asm
+    // statement that "rewrites" the sums of table t together with the index dwords of table t + 1.
+    if constexpr (FENCE) {
+      if (t < 3) __builtin_amdgcn_sched_barrier(0);
+    } else if (t < 3) {
       uint32_t* wn = &w[(t + 1) * BITS];
       if constexpr (BITS == 4)
         asm volatile("" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "+v"(acc[4]), "+v"(acc[5]),
