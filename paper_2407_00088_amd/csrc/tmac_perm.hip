@@ -132,7 +132,14 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(int e0, int e1, int e
     const uint32_t c = lb.c;  // 128-k chunk of this lane
     const uint32_t u = lb.u;  // 16-k unit of this lane
 
-    // 1. scale and zero, and (from the LUT buffer) the activation sum the bias term needs
+    // 1. in fused mode: the lane's 16 activations (zero past the end of K and for idle lanes), raw;
+    // they are unpacked only after the index loads have been requested.  Requested first: the tables
+    // are built from them while the indices are in flight (ahead of the scale loads it is 1.3 % off a
+    // single-matrix launch)
+    uint32_t araw[8];
+    if constexpr (FUSED) lane_load_act<IS_INT>(p.A, p.lda, n, p.K, lb, araw);
+
+    // 1b. scale and zero, and (from the LUT buffer) the activation sum the bias term needs
     uint32_t szr[GM == 1 ? NR : RT];
     float Sl = 0.f;
     if constexpr (GM == 1) {
@@ -163,11 +170,6 @@ __global__ __launch_bounds__(1024) void mpgemv_perm_kernel(int e0, int e1, int e
         Sl = valid ? Sl : 0.f;
       }
     }
-
-    // 1b. in fused mode: the lane's 16 activations (zero past the end of K and for idle lanes), raw;
-    // they are unpacked only after the index loads have been requested
-    uint32_t araw[8];
-    if constexpr (FUSED) lane_load_act<IS_INT>(p.A, p.lda, n, p.K, lb, araw);
 
     // 2. tables from the LUT buffer (requested before the indices: they are needed first)
     LaneTables T;
