@@ -255,14 +255,17 @@ def main():
         cal_seq = [graph(reps)]
         timed_seq = [graph(big)] * q + [graph(reps + r)]
         diffs, dbg = [], []
-        for _ in range(3):
+        for _ in range(3 if steps >= 16 else 9):   # a handful of steps is within the noise of one pair
             ca = bracket(cal_seq)
             tb = bracket(timed_seq)
             diffs.append(tb - ca)
             dbg.append((round(ca, 1), round(tb, 1)))
         last_brackets[:] = [{"calibration_steps": reps, "bracket_steps": reps + steps, "calibration_us": c, "bracket_us": t}
                             for c, t in dbg]
-        return sorted(diffs)[1] / steps
+        d = sorted(diffs)[len(diffs) // 2]
+        if d <= 0:   # (cannot happen with more than a few steps) fall back to the whole bracket's average
+            return dbg[-1][1] / (reps + r + q * big)
+        return d / steps
 
     def timed_exact(body, reps, steps, warm_steps, preroll):
         """`preroll` + `warm_steps` untimed executions of `body`, then steady_us over exactly `steps`."""
